@@ -1,0 +1,438 @@
+/*
+ * CPU oracle for the QLoRA frozen-linear hot path -- see qlora_oracle.h.
+ * TEST INFRASTRUCTURE ONLY: never linked into, imported by, or used as a
+ * fallback for the HIP library.
+ *
+ * Build: g++ -O2 -std=c++17 -fopenmp -ffp-contract=off -shared -fPIC
+ * (no -ffast-math, no -march flags: every operation below must be a plain
+ * IEEE-754 binary32/binary64 operation).
+ */
+#include "qlora_oracle.h"
+
+#include <cfloat>
+#include <cmath>
+#include <cstring>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+/* ---- exactly rounded fp32 steps, evaluated through fp64 --------------------
+ * For binary32 operands the fp64 result of one +, * or / rounded again to
+ * binary32 equals the directly rounded binary32 result (53 >= 2*24 + 2). */
+inline float fl32_mul(float a, float b) { return (float)((double)a * (double)b); }
+inline float fl32_add(float a, float b) { return (float)((double)a + (double)b); }
+inline float fl32_sub(float a, float b) { return (float)((double)a - (double)b); }
+inline float fl32_div(float a, float b) { return (float)((double)a / (double)b); }
+
+inline uint32_t f32_bits(float v) { uint32_t u; std::memcpy(&u, &v, 4); return u; }
+inline float bits_f32(uint32_t u) { float v; std::memcpy(&v, &u, 4); return v; }
+inline double bf16_to_f64(uint16_t b) { return (double)bits_f32((uint32_t)b << 16); }
+
+/* Appendix E, index 0..15.  Each printed decimal is the shortest form of a
+ * binary64 number that is exactly representable in binary32, so the
+ * conversion to float loses nothing. */
+const float kNF4[16] = {
+    -1.0f,
+    -0.6961928009986877f,
+    -0.5250730514526367f,
+    -0.39491748809814453f,
+    -0.28444138169288635f,
+    -0.18477343022823334f,
+    -0.09105003625154495f,
+    0.0f,
+    0.07958029955625534f,
+    0.16093020141124725f,
+    0.24611230194568634f,
+    0.33791524171829224f,
+    0.44070982933044434f,
+    0.5626170039176941f,
+    0.7229568362236023f,
+    1.0f,
+};
+
+/* value of an E4M3 magnitude code 0..0x7e: exponent field e, mantissa field m */
+inline double e4m3_mag(int code7) {
+  const int e = (code7 >> 3) & 15, m = code7 & 7;
+  if (e == 0) return std::ldexp((double)m, -9);            /* subnormal: m/8 * 2^-6 */
+  return std::ldexp(1.0 + (double)m / 8.0, e - 7);
+}
+
+}  // namespace
+
+extern "C" {
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_nf4_table(float out[16]) {
+  for (int i = 0; i < 16; ++i) out[i] = kNF4[i];
+}
+
+double oracle_normal_quantile(double p) {
+  /* Phi(x) = erfc(-x / sqrt 2) / 2 is increasing; bisect Phi(x) = p. */
+  if (!(p > 0.0 && p < 1.0)) return p <= 0.0 ? -HUGE_VAL : HUGE_VAL;
+  double lo = -40.0, hi = 40.0;
+  for (int it = 0; it < 200; ++it) {
+    const double mid = 0.5 * (lo + hi);
+    const double cdf = 0.5 * std::erfc(-mid / std::sqrt(2.0));
+    if (cdf < p) lo = mid; else hi = mid;
+  }
+  return 0.5 * (lo + hi);
+}
+
+void oracle_nf4_derive(double p_max, double out[16]) {
+  const double top = oracle_normal_quantile(p_max);
+  /* negative half: 8 points, the first (p = 1/2) is the duplicate zero */
+  for (int i = 1; i < 8; ++i) {
+    const double p = 0.5 + (p_max - 0.5) * (double)i / 7.0;
+    out[7 - i] = -oracle_normal_quantile(p) / top;
+  }
+  /* positive half: 9 points including the kept zero */
+  for (int i = 0; i < 9; ++i) {
+    const double p = 0.5 + (p_max - 0.5) * (double)i / 8.0;
+    out[7 + i] = (i == 0) ? 0.0 : oracle_normal_quantile(p) / top;
+  }
+}
+
+int oracle_nf4_index(float xhat) {
+  int idx = 0;
+  for (int j = 0; j < 15; ++j) {
+    /* the midpoint of two binary32 numbers is exact in binary64 */
+    const double mid = ((double)kNF4[j] + (double)kNF4[j + 1]) * 0.5;
+    if ((double)xhat > mid) ++idx;
+  }
+  return idx;
+}
+
+uint16_t oracle_bf16_rne(float v) {
+  const uint32_t u = f32_bits(v);
+  const uint32_t keep = u >> 16, rest = u & 0xffffu;
+  uint32_t r = keep;
+  if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) r = keep + 1;  /* carry may bump the exponent */
+  return (uint16_t)r;
+}
+
+float oracle_e4m3_value(uint8_t code) {
+  const int mag = code & 0x7f;
+  if (mag == 0x7f) return NAN;
+  const double v = e4m3_mag(mag);
+  return (float)((code & 0x80) ? -v : v);
+}
+
+float oracle_e4m3_unit(uint8_t code) {
+  return fl32_div(oracle_e4m3_value(code), 448.0f);
+}
+
+uint8_t oracle_e4m3_encode(float z) {
+  const double a = std::fabs((double)z);
+  int best = 0;
+  if (a >= 448.0) {
+    best = 0x7e;                                   /* saturate */
+  } else {
+    double best_d = a;                             /* distance to code 0 */
+    for (int c = 1; c <= 0x7e; ++c) {
+      const double d = std::fabs(a - e4m3_mag(c));
+      /* codes are in value order; on an exact tie keep the even one */
+      if (d < best_d || (d == best_d && (c & 1) == 0)) { best_d = d; best = c; }
+    }
+  }
+  if (best == 0) return 0;
+  return (uint8_t)(best | (z < 0.0f ? 0x80 : 0));
+}
+
+/* ---- exact mean of n non-negative binary32 numbers -------------------------
+ * Sum held as an unsigned big integer in units of 2^-149 (the binary32
+ * subnormal spacing), then divided by n and rounded once to binary32. */
+static float exact_mean_f32(const float* v, int64_t n) {
+  const int L = 12;                                /* 384 bits >= 24 + 253 + 63 */
+  uint32_t acc[L] = {0};
+  for (int64_t i = 0; i < n; ++i) {
+    const uint32_t u = f32_bits(v[i]) & 0x7fffffffu;
+    uint32_t e = u >> 23;
+    uint64_t m = u & 0x7fffffu;
+    if (e == 0) e = 1; else m |= 0x800000u;
+    const int sh = (int)e - 1;                     /* value = m * 2^(sh - 149) */
+    const int limb = sh >> 5, off = sh & 31;
+    uint64_t part = m << off;                      /* < 2^55 */
+    uint64_t carry = 0;
+    for (int k = limb; k < L; ++k) {
+      const uint64_t t = (uint64_t)acc[k] + (part & 0xffffffffu) + carry;
+      acc[k] = (uint32_t)t;
+      carry = t >> 32;
+      part >>= 32;
+      if (part == 0 && carry == 0) break;
+    }
+  }
+  /* long division by n (< 2^32 enforced by the caller) */
+  uint32_t q[L];
+  uint64_t rem = 0;
+  for (int k = L - 1; k >= 0; --k) {
+    const uint64_t cur = (rem << 32) | acc[k];
+    q[k] = (uint32_t)(cur / (uint64_t)n);
+    rem = cur % (uint64_t)n;
+  }
+  int top = -1;                                    /* index of the highest set bit of q */
+  for (int k = L - 1; k >= 0 && top < 0; --k)
+    if (q[k]) for (int b = 31; b >= 0; --b) if (q[k] >> b & 1u) { top = k * 32 + b; break; }
+  auto bit = [&](int i) -> uint32_t { return i < 0 ? 0u : (q[i >> 5] >> (i & 31)) & 1u; };
+  const int drop = top >= 24 ? top - 23 : 0;       /* low bits of q that do not fit in 24 */
+  uint64_t kept = 0;
+  for (int i = top; i >= drop; --i) kept = (kept << 1) | bit(i);
+  /* discarded fraction = (low `drop` bits of q + rem/n) / 2^drop, compared with 1/2 */
+  bool half, sticky;
+  if (drop == 0) {
+    half = 2 * rem >= (uint64_t)n;
+    sticky = half ? (2 * rem > (uint64_t)n) : (rem != 0);
+  } else {
+    half = bit(drop - 1) != 0;
+    sticky = rem != 0;
+    for (int i = drop - 2; i >= 0 && !sticky; --i) sticky = bit(i) != 0;
+  }
+  if (half && (sticky || (kept & 1u))) ++kept;
+  return (float)std::ldexp((double)kept, drop - 149);
+}
+
+int oracle_nf4_quantize(const float* W, int64_t rows, int64_t cols,
+                        int32_t blocksize, int32_t dq_blocksize,
+                        uint8_t* packed, uint8_t* code, float* c1, float* mean,
+                        float* c2_out) {
+  if (!W || !packed || !code || !c1 || !mean) return -1;
+  if (rows <= 0 || cols <= 0 || blocksize <= 0 || dq_blocksize <= 0) return -2;
+  const int64_t P = rows * cols;
+  if (P % blocksize != 0 || P % 2 != 0) return -2;
+  const int64_t n = P / blocksize;
+  if (n >= ((int64_t)1 << 32)) return -2;
+  for (int64_t i = 0; i < P; ++i) if (!std::isfinite(W[i])) return -3;
+
+  std::vector<float> c2((size_t)n);
+  std::vector<uint8_t> idx((size_t)P);
+#pragma omp parallel for schedule(static)      /* blocks are independent */
+  for (int64_t b = 0; b < n; ++b) {
+    const float* w = W + b * blocksize;
+    float amax = 0.0f;
+    for (int i = 0; i < blocksize; ++i) amax = std::fmax(amax, std::fabs(w[i]));
+    c2[(size_t)b] = amax;
+    const float rc = (amax < FLT_MIN) ? 0.0f : fl32_div(1.0f, amax);   /* Eq. 1: c = range / absmax, range 1 */
+    for (int i = 0; i < blocksize; ++i)
+      idx[(size_t)(b * blocksize + i)] = (uint8_t)oracle_nf4_index(fl32_mul(w[i], rc));
+  }
+  for (int64_t i = 0; i < P / 2; ++i)
+    packed[i] = (uint8_t)(idx[(size_t)(2 * i)] | (idx[(size_t)(2 * i + 1)] << 4));
+
+  /* Double Quantization: the fp32 constants of the first step are the input */
+  const float mu = exact_mean_f32(c2.data(), n);
+  *mean = mu;
+  const int64_t n1 = (n + dq_blocksize - 1) / dq_blocksize;
+  for (int64_t B = 0; B < n1; ++B) {
+    const int64_t lo = B * dq_blocksize;
+    const int64_t hi = (lo + dq_blocksize < n) ? lo + dq_blocksize : n;
+    float amax = 0.0f;
+    for (int64_t b = lo; b < hi; ++b) amax = std::fmax(amax, std::fabs(fl32_sub(c2[(size_t)b], mu)));
+    c1[B] = amax;
+    float rc1 = (amax < FLT_MIN) ? 0.0f : fl32_div(448.0f, amax);
+    if (!std::isfinite(rc1)) rc1 = 0.0f;
+    for (int64_t b = lo; b < hi; ++b)
+      code[b] = oracle_e4m3_encode(fl32_mul(fl32_sub(c2[(size_t)b], mu), rc1));
+  }
+  if (c2_out) std::memcpy(c2_out, c2.data(), (size_t)n * sizeof(float));
+  return 0;
+}
+
+int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* c1,
+                       float mean, int64_t rows, int64_t cols,
+                       int32_t blocksize, int32_t dq_blocksize,
+                       uint16_t* W_bf16, float* c2hat_out) {
+  if (!packed || !code || !c1 || !W_bf16) return -1;
+  if (rows <= 0 || cols <= 0 || blocksize <= 0 || dq_blocksize <= 0) return -2;
+  const int64_t P = rows * cols;
+  if (P % blocksize != 0 || P % 2 != 0) return -2;
+  const int64_t n = P / blocksize;
+#pragma omp parallel for schedule(static)      /* blocks are independent */
+  for (int64_t b = 0; b < n; ++b) {
+    const float inner = fl32_mul(oracle_e4m3_unit(code[b]), c1[b / dq_blocksize]);   /* dequant(c1, c2) */
+    const float c2hat = fl32_add(inner, mean);
+    if (c2hat_out) c2hat_out[b] = c2hat;
+    for (int i = 0; i < blocksize; ++i) {
+      const int64_t e = b * blocksize + i;
+      const int id = (packed[e >> 1] >> ((e & 1) * 4)) & 15;
+      W_bf16[e] = oracle_bf16_rne(fl32_mul(kNF4[id], c2hat));                          /* dequant(c2, W) */
+    }
+  }
+  return 0;
+}
+
+/* ---- Eq. 5 / Eq. 3 and the backward products, fp64 triple loops ----------- */
+
+static int check_lin(const void* a, const void* b, const void* out, int64_t M, int64_t h,
+                     int64_t o, int64_t r, const uint16_t* L1, const uint16_t* L2) {
+  if (!a || !b || !out) return -1;
+  if (M <= 0 || h <= 0 || o <= 0 || r < 0) return -2;
+  if (r > 0 && (!L1 || !L2)) return -1;
+  return 0;
+}
+
+int oracle_linear_fwd(const uint16_t* X, const uint16_t* What,
+                      const uint16_t* L1, const uint16_t* L2, double s,
+                      int64_t M, int64_t h, int64_t o, int64_t r,
+                      const int64_t* row_sel, int64_t n_sel, double* Y) {
+  if (int e = check_lin(X, What, Y, M, h, o, r, L1, L2)) return e;
+  if (!row_sel) n_sel = M;
+  for (int64_t i = 0; i < n_sel; ++i) { const int64_t m = row_sel ? row_sel[i] : i; if (m < 0 || m >= M) return -2; }
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < n_sel; ++i) {
+    const int64_t m = row_sel ? row_sel[i] : i;
+    double* y = Y + i * o;
+    for (int64_t n = 0; n < o; ++n) y[n] = 0.0;
+    for (int64_t k = 0; k < h; ++k) {                       /* X What */
+      const double x = bf16_to_f64(X[m * h + k]);
+      const uint16_t* w = What + k * o;
+      for (int64_t n = 0; n < o; ++n) y[n] += x * bf16_to_f64(w[n]);
+    }
+    std::vector<double> t((size_t)r, 0.0);                  /* T = X L1 */
+    for (int64_t k = 0; k < h; ++k) {
+      const double x = bf16_to_f64(X[m * h + k]);
+      for (int64_t j = 0; j < r; ++j) t[(size_t)j] += x * bf16_to_f64(L1[k * r + j]);
+    }
+    for (int64_t n = 0; n < o; ++n) {                       /* + s (T L2) */
+      double acc = 0.0;
+      for (int64_t j = 0; j < r; ++j) acc += t[(size_t)j] * bf16_to_f64(L2[j * o + n]);
+      y[n] += s * acc;
+    }
+  }
+  return 0;
+}
+
+int oracle_linear_fwd_cols(const uint16_t* X, const uint16_t* What,
+                           const uint16_t* L1, const uint16_t* L2, double s,
+                           int64_t M, int64_t h, int64_t o, int64_t r,
+                           const int64_t* col_sel, int64_t n_sel, double* Y) {
+  if (int e = check_lin(X, What, Y, M, h, o, r, L1, L2)) return e;
+  if (!col_sel || n_sel <= 0) return -1;
+  for (int64_t c = 0; c < n_sel; ++c) if (col_sel[c] < 0 || col_sel[c] >= o) return -2;
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t m = 0; m < M; ++m) {
+    std::vector<double> t((size_t)r, 0.0);
+    for (int64_t k = 0; k < h; ++k) {
+      const double x = bf16_to_f64(X[m * h + k]);
+      for (int64_t j = 0; j < r; ++j) t[(size_t)j] += x * bf16_to_f64(L1[k * r + j]);
+    }
+    for (int64_t c = 0; c < n_sel; ++c) {
+      const int64_t n = col_sel[c];
+      double acc = 0.0;
+      for (int64_t k = 0; k < h; ++k) acc += bf16_to_f64(X[m * h + k]) * bf16_to_f64(What[k * o + n]);
+      double lora = 0.0;
+      for (int64_t j = 0; j < r; ++j) lora += t[(size_t)j] * bf16_to_f64(L2[j * o + n]);
+      Y[m * n_sel + c] = acc + s * lora;
+    }
+  }
+  return 0;
+}
+
+int oracle_linear_bwd_dx(const uint16_t* dY, const uint16_t* What,
+                         const uint16_t* L1, const uint16_t* L2, double s,
+                         int64_t M, int64_t h, int64_t o, int64_t r,
+                         const int64_t* row_sel, int64_t n_sel, double* dX) {
+  if (int e = check_lin(dY, What, dX, M, h, o, r, L1, L2)) return e;
+  if (!row_sel) n_sel = M;
+  for (int64_t i = 0; i < n_sel; ++i) { const int64_t m = row_sel ? row_sel[i] : i; if (m < 0 || m >= M) return -2; }
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < n_sel; ++i) {
+    const int64_t m = row_sel ? row_sel[i] : i;
+    const uint16_t* g = dY + m * o;
+    std::vector<double> u((size_t)r, 0.0);                  /* U = dY L2^T */
+    for (int64_t j = 0; j < r; ++j) {
+      double acc = 0.0;
+      for (int64_t n = 0; n < o; ++n) acc += bf16_to_f64(g[n]) * bf16_to_f64(L2[j * o + n]);
+      u[(size_t)j] = acc;
+    }
+    for (int64_t k = 0; k < h; ++k) {
+      const uint16_t* w = What + k * o;
+      double acc = 0.0;                                     /* dY What^T */
+      for (int64_t n = 0; n < o; ++n) acc += bf16_to_f64(g[n]) * bf16_to_f64(w[n]);
+      double lora = 0.0;                                    /* U L1^T */
+      for (int64_t j = 0; j < r; ++j) lora += u[(size_t)j] * bf16_to_f64(L1[k * r + j]);
+      dX[i * h + k] = acc + s * lora;
+    }
+  }
+  return 0;
+}
+
+int oracle_linear_bwd_dx_cols(const uint16_t* dY, const uint16_t* What,
+                              const uint16_t* L1, const uint16_t* L2, double s,
+                              int64_t M, int64_t h, int64_t o, int64_t r,
+                              const int64_t* col_sel, int64_t n_sel, double* dX) {
+  if (int e = check_lin(dY, What, dX, M, h, o, r, L1, L2)) return e;
+  if (!col_sel || n_sel <= 0) return -1;
+  for (int64_t c = 0; c < n_sel; ++c) if (col_sel[c] < 0 || col_sel[c] >= h) return -2;
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t m = 0; m < M; ++m) {
+    const uint16_t* g = dY + m * o;
+    std::vector<double> u((size_t)r, 0.0);
+    for (int64_t j = 0; j < r; ++j) {
+      double acc = 0.0;
+      for (int64_t n = 0; n < o; ++n) acc += bf16_to_f64(g[n]) * bf16_to_f64(L2[j * o + n]);
+      u[(size_t)j] = acc;
+    }
+    for (int64_t c = 0; c < n_sel; ++c) {
+      const int64_t k = col_sel[c];
+      const uint16_t* w = What + k * o;
+      double acc = 0.0;
+      for (int64_t n = 0; n < o; ++n) acc += bf16_to_f64(g[n]) * bf16_to_f64(w[n]);
+      double lora = 0.0;
+      for (int64_t j = 0; j < r; ++j) lora += u[(size_t)j] * bf16_to_f64(L1[k * r + j]);
+      dX[m * n_sel + c] = acc + s * lora;
+    }
+  }
+  return 0;
+}
+
+int oracle_linear_bwd_dl(const uint16_t* dY, const uint16_t* X,
+                         const uint16_t* L1, const uint16_t* L2, double s,
+                         int64_t M, int64_t h, int64_t o, int64_t r,
+                         double* dL1, double* dL2) {
+  if (!dY || !X || !L1 || !L2 || !dL1 || !dL2) return -1;
+  if (M <= 0 || h <= 0 || o <= 0 || r <= 0) return -2;
+  std::vector<double> U((size_t)(M * r)), T((size_t)(M * r));
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m) {
+    for (int64_t j = 0; j < r; ++j) {                       /* U = dY L2^T */
+      double acc = 0.0;
+      for (int64_t n = 0; n < o; ++n) acc += bf16_to_f64(dY[m * o + n]) * bf16_to_f64(L2[j * o + n]);
+      U[(size_t)(m * r + j)] = acc;
+    }
+    for (int64_t j = 0; j < r; ++j) T[(size_t)(m * r + j)] = 0.0;
+    for (int64_t k = 0; k < h; ++k) {                       /* T = X L1 */
+      const double x = bf16_to_f64(X[m * h + k]);
+      for (int64_t j = 0; j < r; ++j) T[(size_t)(m * r + j)] += x * bf16_to_f64(L1[k * r + j]);
+    }
+  }
+#pragma omp parallel for schedule(static)
+  for (int64_t k = 0; k < h; ++k) {                         /* dL1 = s X^T U */
+    std::vector<double> acc((size_t)r, 0.0);
+    for (int64_t m = 0; m < M; ++m) {
+      const double x = bf16_to_f64(X[m * h + k]);
+      for (int64_t j = 0; j < r; ++j) acc[(size_t)j] += x * U[(size_t)(m * r + j)];
+    }
+    for (int64_t j = 0; j < r; ++j) dL1[k * r + j] = s * acc[(size_t)j];
+  }
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < o; ++n) {                         /* dL2 = s T^T dY */
+    std::vector<double> acc((size_t)r, 0.0);
+    for (int64_t m = 0; m < M; ++m) {
+      const double g = bf16_to_f64(dY[m * o + n]);
+      for (int64_t j = 0; j < r; ++j) acc[(size_t)j] += T[(size_t)(m * r + j)] * g;
+    }
+    for (int64_t j = 0; j < r; ++j) dL2[j * o + n] = s * acc[(size_t)j];
+  }
+  return 0;
+}
+
+}  // extern "C"

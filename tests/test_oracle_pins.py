@@ -1,0 +1,447 @@
+"""Pins for the CPU oracle: everything here checks the oracle against something
+other than itself -- values the paper prints, closed forms, invariants, library
+routines on special cases, exact rational arithmetic, brute force on tiny inputs.
+No GPU needed."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_table():
+    vals = []
+    with open(os.path.join(GOLD, "nf4_appendix_e.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                vals.append(line)
+    return vals
+
+
+def _bf16_bits(a):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def _bf16_f64(b):
+    return (np.asarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------- codebook
+
+def test_nf4_table_is_the_printed_one(oracle):
+    printed = _read_table()
+    tab = oracle.nf4_table()
+    assert len(printed) == 16
+    for s, v in zip(printed, tab):
+        # the printed decimal is the shortest form of a double that is exactly the fp32 entry
+        assert float(s) == float(v) and repr(float(v)) == s, (s, v)
+
+
+def test_nf4_table_structure(oracle):
+    tab = oracle.nf4_table().astype(np.float64)
+    assert np.all(np.diff(tab) > 0)
+    assert tab[0] == -1.0 and tab[15] == 1.0 and tab[7] == 0.0
+    assert (tab < 0).sum() == 7 and (tab > 0).sum() == 8
+
+
+def test_nf4_table_from_normal_quantiles(oracle):
+    # Section 3: asymmetric construction from N(0,1) quantiles, normalised to [-1, 1].
+    p_max = 1.0 - 0.5 * (1.0 / 32.0 + 1.0 / 30.0)
+    derived = oracle.nf4_derive(p_max)
+    tab = oracle.nf4_table().astype(np.float64)
+    assert np.abs(derived - tab).max() <= 2e-7
+    assert derived[7] == 0.0 and derived[0] == -1.0 and derived[15] == 1.0
+    # a wrong split (8 negative / 7 positive steps) must not fit
+    wrong = -oracle.nf4_derive(p_max)[::-1]
+    assert np.abs(wrong - tab).max() > 1e-2
+
+
+def test_normal_quantile_against_library(oracle):
+    from scipy.stats import norm
+    for p in [1e-6, 0.01, 0.25, 0.5, 0.75, 0.9677083, 0.999]:
+        assert abs(oracle.normal_quantile(p) - norm.ppf(p)) < 1e-11
+
+
+# ----------------------------------------------------------------------------- index assignment
+
+def test_index_is_nearest_value_bruteforce(oracle):
+    tab = oracle.nf4_table()
+    rng = np.random.default_rng(1)
+    xs = np.concatenate([rng.uniform(-1, 1, 4000), tab.astype(np.float64),
+                         [0.0, -0.0, 1.0000001, -1.0000001, 1e-30, -1e-30]]).astype(np.float32)
+    for x in xs:
+        d = [abs(Fraction(float(x)) - Fraction(float(q))) for q in tab]
+        best = min(d)
+        winners = [j for j in range(16) if d[j] == best]
+        got = oracle.nf4_index(x)
+        assert got == winners[0], (x, got, winners)       # lower index on an exact tie
+
+
+def test_index_ties_and_monotone(oracle):
+    tab = oracle.nf4_table()
+    n_ties = 0
+    for j in range(15):
+        mid = (Fraction(float(tab[j])) + Fraction(float(tab[j + 1]))) / 2
+        m32 = np.float32(float(mid))
+        if Fraction(float(m32)) == mid:                     # representable midpoint: a real tie
+            n_ties += 1
+            assert oracle.nf4_index(m32) == j
+            assert oracle.nf4_index(np.nextafter(m32, np.float32(2))) == j + 1
+        else:
+            lo = m32 if Fraction(float(m32)) < mid else np.nextafter(m32, np.float32(-2))
+            assert oracle.nf4_index(lo) == j
+            assert oracle.nf4_index(np.nextafter(lo, np.float32(2))) == j + 1
+    assert n_ties == 6                                      # six of the 15 midpoints are fp32 numbers
+    xs = np.sort(np.random.default_rng(2).uniform(-1.1, 1.1, 2000).astype(np.float32))
+    idx = [oracle.nf4_index(x) for x in xs]
+    assert all(a <= b for a, b in zip(idx, idx[1:]))
+    assert oracle.nf4_index(np.float32(0.0)) == 7 and oracle.nf4_index(np.float32(-0.0)) == 7
+
+
+# ----------------------------------------------------------------------------- roundings
+
+def test_bf16_rne_against_library(oracle):
+    rng = np.random.default_rng(3)
+    vals = np.concatenate([
+        rng.standard_normal(3000).astype(np.float32),
+        (rng.standard_normal(500) * 1e-20).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 1.0 + 2**-8, 1.0 + 3 * 2**-8, 3.3895314e38,
+                  -2.5, 65280.0, 65408.0, 65535.9], np.float32)])
+    want = _bf16_bits(vals)
+    got = np.array([oracle.bf16_rne(v) for v in vals], np.uint16)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_e4m3_decode_against_library(oracle):
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    for c in range(256):
+        v = oracle.e4m3_value(c)
+        if c & 0x7F == 0x7F:
+            assert np.isnan(v) and np.isnan(lib[c])
+        else:
+            assert v == lib[c], (c, v, lib[c])
+    assert oracle.e4m3_value(0x7E) == 448.0 and oracle.e4m3_value(0x01) == 2.0 ** -9
+    finite = {oracle.e4m3_value(c) for c in range(256) if c & 0x7F != 0x7F}
+    assert len(finite) == 253                               # +0 and -0 coincide
+
+
+def test_e4m3_encode_against_library(oracle):
+    rng = np.random.default_rng(4)
+    mags = np.array([oracle.e4m3_value(c) for c in range(0x7F)], np.float64)
+    mids = (mags[:-1] + mags[1:]) / 2                       # every tie point of the format
+    zs = np.concatenate([rng.uniform(-448, 448, 4000), rng.uniform(-1, 1, 2000), rng.uniform(-0.02, 0.02, 2000),
+                         mags, -mags, mids, -mids, np.nextafter(mids.astype(np.float32), 0),
+                         np.nextafter(mids.astype(np.float32), 1000)]).astype(np.float32)
+    zs = zs[np.abs(zs) <= 448]
+    lib = torch.from_numpy(zs).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    for z, w in zip(zs, lib):
+        got = oracle.e4m3_encode(z)
+        if (w & 0x7F) == 0:
+            assert got == 0, (z, got)                       # zero is always 0x00, never 0x80
+        else:
+            assert got == w, (z, got, w)
+    # every finite value is a fixed point
+    for c in range(256):
+        if c & 0x7F not in (0x7F, 0):
+            assert oracle.e4m3_encode(oracle.e4m3_value(c)) == c
+
+
+def test_e4m3_saturates(oracle):
+    for z, want in [(448.0, 0x7E), (449.0, 0x7E), (1e9, 0x7E), (-448.00003, 0xFE), (-3e38, 0xFE), (463.9, 0x7E)]:
+        assert oracle.e4m3_encode(z) == want
+
+
+def test_e4m3_unit_table(oracle):
+    for c in range(256):
+        if c & 0x7F == 0x7F:
+            continue
+        exact = Fraction(oracle.e4m3_value(c)) / 448
+        u = oracle.e4m3_unit(c)
+        # correctly rounded fp32 quotient: no fp32 neighbour is closer
+        for nb in (np.nextafter(u, np.float32(-9)), np.nextafter(u, np.float32(9))):
+            assert abs(Fraction(float(u)) - exact) <= abs(Fraction(float(nb)) - exact)
+    assert oracle.e4m3_unit(0x7E) == 1.0 and oracle.e4m3_unit(0xFE) == -1.0 and oracle.e4m3_unit(0) == 0.0
+
+
+# ----------------------------------------------------------------------------- quantize invariants
+
+def _round_f32(fr: Fraction) -> np.float32:
+    c = np.float32(float(fr))
+    cands = [c, np.nextafter(c, np.float32(-np.inf)), np.nextafter(c, np.float32(np.inf))]
+    best = min(cands, key=lambda v: (abs(Fraction(float(v)) - fr), int(np.float32(v).view(np.uint32)) & 1))
+    return np.float32(best)
+
+
+def _unpack(packed):
+    out = np.empty(packed.size * 2, np.uint8)
+    out[0::2] = packed & 15
+    out[1::2] = packed >> 4
+    return out
+
+
+@pytest.fixture(scope="module")
+def small_q(oracle, synth):
+    W = synth.normal_f32((128, 512), 0.02, 77)
+    return W, oracle.nf4_quantize(W)
+
+
+def test_footprint_matches_paper(oracle, small_q):
+    gold = {}
+    with open(os.path.join(GOLD, "dq_footprint.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                gold[k] = float(v)
+    W, q = small_q
+    P = W.size
+    const_bits = (q["code"].nbytes * 8 + q["c1"].nbytes * 8) / P
+    assert const_bits == 8 / 64 + 32 / (64 * 256)
+    assert round(const_bits, 3) == gold["bits_double_quant"]
+    assert round(q["c2"].nbytes * 8 / P, 3) == gold["bits_fp32_constants"]
+    assert round(q["c2"].nbytes * 8 / P - const_bits, 3) == gold["bits_saved"]
+    assert (q["packed"].nbytes * 8) / P == 4.0
+    assert (q["packed"].nbytes + q["code"].nbytes + q["c1"].nbytes) * 8 / P == 4.126953125
+
+
+def test_blocks_are_contiguous_slices(oracle, small_q):
+    W, q = small_q
+    W2 = W.copy()
+    flat = W2.reshape(-1)
+    b = 37
+    flat[64 * b:64 * (b + 1)] *= 3.0                        # touch one block only
+    q2 = oracle.nf4_quantize(W2)
+    c2a, c2b = q["c2"], q2["c2"]
+    changed = np.nonzero(c2a != c2b)[0]
+    np.testing.assert_array_equal(changed, [b])
+    assert c2b[b] == np.abs(flat[64 * b:64 * (b + 1)]).max()
+    # scaling a block by a constant leaves its NF4 indices essentially unchanged
+    ia, ib = _unpack(q["packed"]), _unpack(q2["packed"])
+    other = np.ones(ia.size, bool)
+    other[64 * b:64 * (b + 1)] = False
+    np.testing.assert_array_equal(ia[other], ib[other])
+
+
+def test_absmax_and_zero_elements(oracle, small_q):
+    W, q = small_q
+    idx = _unpack(q["packed"]).reshape(-1, 64)
+    blocks = W.reshape(-1, 64)
+    np.testing.assert_array_equal(q["c2"], np.abs(blocks).max(axis=1))
+    am = np.abs(blocks).argmax(axis=1)
+    rows = np.arange(blocks.shape[0])
+    top = idx[rows, am]
+    sign = blocks[rows, am] > 0
+    np.testing.assert_array_equal(top, np.where(sign, 15, 0))
+    Z = W.copy()
+    Z.reshape(-1)[:64] = 0.0                                # an all-zero block
+    Z.reshape(-1)[100] = 0.0
+    qz = oracle.nf4_quantize(Z)
+    iz = _unpack(qz["packed"])
+    assert np.all(iz[:64] == 7) and iz[100] == 7 and qz["c2"][0] == 0.0
+
+
+def test_round_trip_error_bound(oracle, small_q):
+    W, q = small_q
+    tab = oracle.nf4_table().astype(np.float64)
+    idx = _unpack(q["packed"]).reshape(-1, 64)
+    xh = W.reshape(-1, 64).astype(np.float64) / q["c2"][:, None].astype(np.float64)
+    err = np.abs(xh - tab[idx])
+    half_gap = np.diff(tab).max() / 2
+    assert abs(half_gap - 0.1519036) < 1e-6                 # largest gap is -1 -> -0.696
+    assert err.max() <= half_gap + 1e-6
+    # idx is the nearest value wherever xh is not within rounding distance of a midpoint
+    near = np.abs(xh[..., None] - tab).argmin(-1)
+    mids = (tab[:-1] + tab[1:]) / 2
+    safe = np.abs(xh[..., None] - mids).min(-1) > 1e-6
+    np.testing.assert_array_equal(idx[safe], near[safe])
+    rel_rms = np.sqrt(((xh - tab[idx]) ** 2).mean() / (xh ** 2).mean())
+    assert 0.07 < rel_rms < 0.12                            # ~0.09 for normal data, statistical sanity
+
+
+def test_packing_low_nibble_first(oracle):
+    W = np.zeros((1, 64), np.float32)
+    W[0, 0] = -1.0      # idx 0 (absmax element, negative)
+    W[0, 1] = 1.0       # idx 15
+    W[0, 2] = 0.5       # xhat 0.5 -> between 0.4407 (12) and 0.5626 (13): nearest 12
+    q = oracle.nf4_quantize(W)
+    assert q["packed"][0] == (0 | (15 << 4))
+    assert q["packed"][1] == (12 | (7 << 4))
+
+
+def test_mean_is_exactly_rounded(oracle):
+    rng = np.random.default_rng(5)
+    cases = [np.abs(rng.standard_normal(64 * 300)).astype(np.float32) * 0.05]
+    wide = np.abs(rng.standard_normal(64 * 40)).astype(np.float32)
+    wide[::64] *= np.float32(2.0) ** rng.integers(-60, 60, wide[::64].size).astype(np.float32)
+    cases.append(wide)                                      # no fp64 running sum is exact here
+    tiny = (np.abs(rng.standard_normal(64 * 8)) * 1e-41).astype(np.float32)  # subnormal constants
+    cases.append(tiny)
+    for flat in cases:
+        W = flat.reshape(-1, 64)
+        q = oracle.nf4_quantize(W)
+        c2 = np.abs(W).max(axis=1)
+        exact = sum((Fraction(float(v)) for v in c2), Fraction(0)) / len(c2)
+        assert q["mean"] == _round_f32(exact), (q["mean"], float(exact))
+
+
+def test_double_quant_invariants(oracle, small_q):
+    W, q = small_q
+    c2, mean = q["c2"], q["mean"]
+    assert np.all(c2 > 0)
+    c2p = (c2 - mean).astype(np.float32)                    # fp32 subtraction
+    assert abs(c2p.astype(np.float64).sum()) < 1e-6 * len(c2)
+    nb = len(q["c1"])
+    for B in range(nb):
+        seg = c2p[256 * B:256 * (B + 1)]
+        assert q["c1"][B] == np.abs(seg).max()
+        codes = q["code"][256 * B:256 * (B + 1)]
+        assert np.any((codes & 0x7F) == 0x7E)               # the super-block maximum uses the full range
+        unit = np.array([oracle.e4m3_unit(c) for c in codes], np.float64)
+        y = seg.astype(np.float64) / q["c1"][B]
+        bound = np.maximum(np.abs(y) * 2.0 ** -4, 2.0 ** -10 / 448) + 1e-6
+        assert np.all(np.abs(y - unit) <= bound)
+
+
+def test_dequant_against_library_pieces(oracle, small_q):
+    W, q = small_q
+    bits, c2hat = oracle.nf4_dequant(q, return_c2hat=True)
+    # constants: library E4M3 decode, then the two fp32 steps in numpy float32 arithmetic
+    val = torch.from_numpy(q["code"].copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    unit = (val / np.float32(448.0)).astype(np.float32)
+    want_c2 = (unit * np.repeat(q["c1"], 256)[:len(unit)]).astype(np.float32) + np.float32(q["mean"])
+    np.testing.assert_array_equal(c2hat, want_c2.astype(np.float32))
+    # relative error of the reconstructed constants is at the 8-bit-float level
+    rel = np.abs(c2hat.astype(np.float64) - q["c2"]) / q["c2"]
+    assert rel.max() < 4e-2 and np.sqrt((rel ** 2).mean()) < 1e-2
+    # weights: table lookup, one fp32 product, library bf16 cast
+    tab = oracle.nf4_table()
+    idx = _unpack(q["packed"])
+    prod = (tab[idx] * np.repeat(want_c2, 64)).astype(np.float32)
+    np.testing.assert_array_equal(bits.reshape(-1), _bf16_bits(prod))
+    # end-to-end: dequantised weights stay within the NF4 + DQ + bf16 error of the source
+    back = _bf16_f64(bits).reshape(W.shape)
+    tol = np.repeat(q["c2"], 64).reshape(W.shape) * (0.1519036 + 0.04 + 2.0 ** -8)
+    assert np.all(np.abs(back - W) <= tol)
+
+
+def test_quantize_rejects_bad_arguments(oracle):
+    with pytest.raises(ValueError):
+        oracle.nf4_quantize(np.zeros((3, 21), np.float32))
+    bad = np.zeros((2, 64), np.float32)
+    bad[0, 3] = np.inf
+    with pytest.raises(ValueError):
+        oracle.nf4_quantize(bad)
+
+
+# ----------------------------------------------------------------------------- forward / backward
+
+def _rand_bf16(rng, shape, scale=1.0):
+    return _bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+@pytest.fixture(scope="module")
+def lin_case():
+    rng = np.random.default_rng(6)
+    M, h, o, r = 9, 24, 40, 5
+    return dict(M=M, h=h, o=o, r=r, s=0.75, X=_rand_bf16(rng, (M, h)), W=_rand_bf16(rng, (h, o), 0.05),
+                L1=_rand_bf16(rng, (h, r), 0.1), L2=_rand_bf16(rng, (r, o), 0.1), dY=_rand_bf16(rng, (M, o)))
+
+
+def test_forward_against_library_matmul(oracle, lin_case):
+    c = lin_case
+    X, W, L1, L2 = (_bf16_f64(c[k]) for k in ("X", "W", "L1", "L2"))
+    want = X @ W + c["s"] * ((X @ L1) @ L2)
+    got = oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], c["s"])
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+    # W is h x o and is NOT transposed; a transposed operand would fail here
+    assert np.abs(got - (X @ W[:, ::-1] + c["s"] * ((X @ L1) @ L2))).max() > 1e-3
+    rows = np.array([8, 0, 3], np.int64)
+    np.testing.assert_array_equal(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], c["s"], rows=rows), got[rows])
+    cols = np.array([39, 1, 17, 0], np.int64)
+    np.testing.assert_allclose(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], c["s"], cols=cols), got[:, cols],
+                               rtol=0, atol=1e-12)
+
+
+def test_forward_special_cases(oracle, lin_case):
+    c = lin_case
+    X, W = _bf16_f64(c["X"]), _bf16_f64(c["W"])
+    base = X @ W
+    np.testing.assert_allclose(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], 0.0), base, atol=1e-12)
+    np.testing.assert_allclose(oracle.linear_fwd(c["X"], c["W"], None, None, 1.0), base, atol=1e-12)
+    zero = np.zeros_like(c["L2"])
+    np.testing.assert_allclose(oracle.linear_fwd(c["X"], c["W"], c["L1"], zero, 2.0), base, atol=1e-12)
+
+
+def test_brute_force_tiny(oracle):
+    # hand-checkable 2x2x2 case with r = 1, all values exactly representable in bf16
+    X = _bf16_bits(np.array([[1, 2], [3, 4]], np.float32))
+    W = _bf16_bits(np.array([[1, -1], [0.5, 2]], np.float32))
+    L1 = _bf16_bits(np.array([[1], [1]], np.float32))
+    L2 = _bf16_bits(np.array([[2, -2]], np.float32))
+    Y = oracle.linear_fwd(X, W, L1, L2, 0.5)
+    np.testing.assert_array_equal(Y, [[1 + 1 + 3, -1 + 4 - 3], [3 + 2 + 7, -3 + 8 - 7]])
+    dY = _bf16_bits(np.array([[1, 0], [0, 1]], np.float32))
+    dX = oracle.linear_bwd_dx(dY, W, L1, L2, 0.5)
+    np.testing.assert_array_equal(dX, [[1 + 1, 0.5 + 1], [-1 - 1, 2 - 1]])
+    dL1, dL2 = oracle.linear_bwd_dl(dY, X, L1, L2, 0.5)
+    np.testing.assert_array_equal(dL1, [[0.5 * (1 * 2 + 3 * -2)], [0.5 * (2 * 2 + 4 * -2)]])
+    np.testing.assert_array_equal(dL2, [[0.5 * 3, 0.5 * 7]])
+
+
+def _energy(oracle, c, X=None, L1=None, L2=None):
+    Y = oracle.linear_fwd(c["X"] if X is None else X, c["W"], c["L1"] if L1 is None else L1,
+                          c["L2"] if L2 is None else L2, c["s"])
+    return float((Y * _bf16_f64(c["dY"])).sum())
+
+
+def test_backward_by_exact_central_differences(oracle):
+    # E = sum(Y * dY) is linear in X, in L1 and in L2, so a central difference with a
+    # bf16-representable step is exact up to fp64 rounding: small integers, step 1.
+    rng = np.random.default_rng(7)
+    M, h, o, r = 5, 12, 16, 3
+    ints = lambda shape, k: _bf16_bits(rng.integers(-k, k + 1, shape).astype(np.float32))
+    c = dict(M=M, h=h, o=o, r=r, s=0.25, X=ints((M, h), 6), W=ints((h, o), 4), L1=ints((h, r), 3),
+             L2=ints((r, o), 3), dY=ints((M, o), 5))
+    dX = oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], c["s"])
+    dL1, dL2 = oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], c["L2"], c["s"])
+
+    def bump(bits, i, j, d):
+        a = _bf16_f64(bits).astype(np.float32).copy()
+        a[i, j] += d
+        return _bf16_bits(a)
+
+    for (i, j) in [(0, 0), (4, 11), (2, 5), (3, 7)]:
+        num = (_energy(oracle, c, X=bump(c["X"], i, j, 1)) - _energy(oracle, c, X=bump(c["X"], i, j, -1))) / 2
+        assert abs(num - dX[i, j]) < 1e-9
+    for (i, j) in [(0, 0), (11, 2), (6, 1)]:
+        num = (_energy(oracle, c, L1=bump(c["L1"], i, j, 1)) - _energy(oracle, c, L1=bump(c["L1"], i, j, -1))) / 2
+        assert abs(num - dL1[i, j]) < 1e-9
+    for (i, j) in [(0, 0), (2, 15), (1, 8)]:
+        num = (_energy(oracle, c, L2=bump(c["L2"], i, j, 1)) - _energy(oracle, c, L2=bump(c["L2"], i, j, -1))) / 2
+        assert abs(num - dL2[i, j]) < 1e-9
+
+
+def test_backward_against_library_matmul(oracle, lin_case):
+    c = lin_case
+    X, W, L1, L2, dY = (_bf16_f64(c[k]) for k in ("X", "W", "L1", "L2", "dY"))
+    s = c["s"]
+    want_dx = dY @ W.T + s * ((dY @ L2.T) @ L1.T)
+    got_dx = oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], s)
+    np.testing.assert_allclose(got_dx, want_dx, rtol=0, atol=1e-12)
+    rows = np.array([2, 7], np.int64)
+    np.testing.assert_array_equal(oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], s, rows=rows), got_dx[rows])
+    cols = np.array([23, 0, 5], np.int64)
+    np.testing.assert_allclose(oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], s, cols=cols),
+                               got_dx[:, cols], rtol=0, atol=1e-12)
+    dL1, dL2 = oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], c["L2"], s)
+    np.testing.assert_allclose(dL1, s * (X.T @ (dY @ L2.T)), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dL2, s * ((X @ L1).T @ dY), rtol=0, atol=1e-12)
+    # L2 = 0 kills dL1; L1 = 0 kills dL2
+    z1, z2 = np.zeros_like(c["L1"]), np.zeros_like(c["L2"])
+    assert np.all(oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], z2, s)[0] == 0)
+    assert np.all(oracle.linear_bwd_dl(c["dY"], c["X"], z1, c["L2"], s)[1] == 0)
