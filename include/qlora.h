@@ -1,0 +1,141 @@
+/*
+ * qlora.h -- C ABI of the MI355X (gfx950) library for the QLoRA frozen linear
+ * layer (arXiv 2305.14314): blockwise NF4 quantisation with Double
+ * Quantization, doubleDequant, and the forward / backward products of one
+ * linear layer with a LoRA adapter.
+ *
+ * Notation follows the paper (Eq. 3, Eq. 5): X is M x h (tokens x in-features),
+ * W is h x o row-major (in x out), L1 is h x r, L2 is r x o, s is a scalar.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers (HIP global memory) owned by the
+ *     caller; the library allocates and frees nothing and keeps no state
+ *     between calls.  Buffers must be 16-byte aligned, must not overlap between
+ *     inputs and outputs, and must stay alive until the stream has executed the
+ *     call.  `const qlora_nf4_view*` itself is a HOST pointer to a small struct
+ *     of device pointers; it is read before the call returns.
+ *   - 16-bit tensors are bf16 bit patterns (uint16_t), row-major, dense.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Calls only enqueue work; they never synchronise.
+ *   - Return value: QLORA_OK or a negative qlora_status.  Arguments are checked
+ *     on the host before any HIP call is made; on an argument error nothing is
+ *     launched and no output is touched.  No exception or abort crosses the ABI.
+ *   - Outputs are overwritten, never accumulated into.  Inputs must be finite.
+ *   - Workspace / scratch contents are undefined on entry and on exit.  Two
+ *     calls that share a workspace must be ordered on one stream.
+ */
+#ifndef QLORA_H
+#define QLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t qlora_status;
+enum {
+  QLORA_OK = 0,
+  QLORA_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  QLORA_ERR_SHAPE = -2,       /* non-positive size, cols not a multiple of blocksize, ...    */
+  QLORA_ERR_UNSUPPORTED = -3, /* blocksize != 64, dq_blocksize != 256, r not supported, ...  */
+  QLORA_ERR_WORKSPACE = -4,   /* workspace / scratch smaller than the *_sizes call reports   */
+  QLORA_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                            */
+  QLORA_ERR_HIP = -6          /* a kernel launch failed; see qlora_last_hip_error()          */
+};
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* qlora_status_string(qlora_status st);
+
+/* hipError_t (as int) of the most recent failed launch on the calling thread, 0 if none. */
+int qlora_last_hip_error(void);
+
+/* A quantised weight: views onto caller-owned device buffers.
+ *
+ * Storage layout (Section 3; the paper fixes the types, the byte layout is this
+ * library's):  the h x o matrix is flattened row-major and cut into contiguous
+ * blocks of `blocksize` = 64 elements (Eq. 1 and the paragraph after Eq. 2).
+ *   packed  : rows*cols/2 bytes; byte i holds element 2i in bits 3:0 and element
+ *             2i+1 in bits 7:4, each a 4-bit index into the NF4 table (Appendix E).
+ *   c2_code : n = rows*cols/blocksize bytes, the 8-bit-float codes of the
+ *             mean-subtracted first-level constants (OCP E4M3 bit patterns),
+ *             quantised in runs of `dq_blocksize` = 256 (Double Quantization).
+ *   c1      : ceil(n / dq_blocksize) fp32 second-level constants.
+ *   c2_mean : one fp32, the mean that was subtracted from c2 (per tensor).
+ * cols must be a multiple of blocksize, so a block never straddles two rows.
+ */
+typedef struct {
+  const uint8_t* packed;
+  const uint8_t* c2_code;
+  const float* c1;
+  const float* c2_mean;
+  int64_t rows;          /* h, in-features  */
+  int64_t cols;          /* o, out-features */
+  int32_t blocksize;     /* 64  */
+  int32_t dq_blocksize;  /* 256 */
+} qlora_nf4_view;
+
+/* Byte sizes of the buffers of a quantised rows x cols tensor and of the scratch
+ * qlora_nf4_quantize needs.  Any out-pointer may be NULL.
+ * 4 + 8/64 + 32/(64*256) = 4.127 bits per parameter (Section 3). */
+qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
+                             size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
+                             size_t* scratch_bytes);
+
+/* Blockwise NF4 quantisation with Double Quantization (Eq. 1; Section 3,
+ * "4-bit NormalFloat Quantization" step (3) and "Double Quantization").
+ *   W (in, fp32, rows x cols) -> packed, c2_code, c1, c2_mean as laid out above.
+ * Per block: c2 = absmax; x = w * fl32(1/c2) (0 when c2 < FLT_MIN); index = the
+ * nearest NF4 value (the lower index on an exact tie).  Then, per tensor:
+ * mean = correctly rounded fp32 mean of all c2; per run of 256 constants
+ * c1 = absmax(c2 - mean) and code = E4M3(round-to-nearest-even, saturating)
+ * of (c2 - mean) * fl32(448 / c1).
+ * scratch: device buffer of at least the size qlora_nf4_sizes reports. */
+qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
+                                int32_t blocksize, int32_t dq_blocksize,
+                                uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
+                                void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* doubleDequant (Eq. 6, Eq. 2): W_bf16[rows x cols] =
+ *   bf16_rne( NF4[index] * fl32( fl32(E4M3(code)/448 * c1) + mean ) ). */
+qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void* hip_stream);
+
+/* Workspace (bytes) qlora_linear_fwd / qlora_linear_bwd need for this shape. */
+qlora_status qlora_linear_fwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes);
+qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes);
+
+/* Forward of one QLoRA linear layer (Eq. 5 with the scalar s of Eq. 3):
+ *   Y = X * doubleDequant(Wq) + s * (X * L1) * L2          (bf16 in, fp32 accumulate, bf16 out)
+ * X: M x h, L1: h x r, L2: r x o, Y: M x o, with h = Wq->rows and o = Wq->cols.
+ * r may be 0 (then L1, L2 may be NULL and the adapter term is skipped); otherwise
+ * r must be a multiple of 16 and at most 256.  T_save (M x r bf16, may be NULL)
+ * receives T = X * L1 for the backward pass.  Any M >= 1 is accepted: a few
+ * tokens (M <= 16) take a bandwidth-bound streaming path, larger M the MFMA
+ * GEMM path. */
+qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq,
+                              const uint16_t* L1, const uint16_t* L2, float s,
+                              int64_t M, int32_t r,
+                              uint16_t* Y, uint16_t* T_save,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward of the same layer (Section 3, after Eq. 6): gradients flow through
+ * the dequantised bf16 weight to the input and to the adapter only; dE/dW is
+ * never formed.
+ *   dX  = dY * doubleDequant(Wq)^T + s * (dY * L2^T) * L1^T     (M x h)
+ *   dL1 = s * X^T * (dY * L2^T)                                  (h x r)
+ *   dL2 = s * (X * L1)^T * dY                                    (r x o)
+ * Each of dX, dL1, dL2 may be NULL and is then not computed.  X is needed only
+ * for dL1 / dL2 (may be NULL when both are NULL).  T_saved is the T_save of the
+ * forward call or NULL, in which case X * L1 is recomputed (gradient
+ * checkpointing).  With r = 0 only dX is produced. */
+qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq,
+                              const uint16_t* L1, const uint16_t* L2, float s,
+                              int64_t M, int32_t r, const uint16_t* T_saved,
+                              uint16_t* dX, uint16_t* dL1, uint16_t* dL2,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,179 @@
+"""Thin ctypes binding over the C ABI in include/qlora.h.
+
+Argument marshalling only: every step of the path runs in the HIP library.  torch is
+used for device memory and for the current stream handle.  There is no CPU or eager
+fallback: if the shared library is missing the import of a function raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, byref, c_float, c_int32, c_int64, c_size_t, c_void_p
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libqlora_hip.so")
+
+EXPORTS = [
+    "qlora_status_string", "qlora_last_hip_error", "qlora_nf4_sizes", "qlora_nf4_quantize",
+    "qlora_nf4_dequant", "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd",
+    "qlora_linear_bwd",
+]
+
+
+class QloraError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{message} (status {status})")
+        self.status = status
+
+
+class qlora_nf4_view(Structure):
+    _fields_ = [("packed", c_void_p), ("c2_code", c_void_p), ("c1", c_void_p), ("c2_mean", c_void_p),
+                ("rows", c_int64), ("cols", c_int64), ("blocksize", c_int32), ("dq_blocksize", c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2305_14314_amd.build` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, sp = c_void_p, POINTER(c_size_t)
+    L.qlora_status_string.restype = ctypes.c_char_p
+    L.qlora_status_string.argtypes = [c_int32]
+    L.qlora_last_hip_error.restype = ctypes.c_int
+    L.qlora_nf4_sizes.argtypes = [c_int64, c_int64, c_int32, c_int32, sp, sp, sp, sp]
+    L.qlora_nf4_quantize.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_nf4_dequant.argtypes = [POINTER(qlora_nf4_view), vp, vp]
+    L.qlora_linear_fwd_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp]
+    L.qlora_linear_bwd_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp]
+    L.qlora_linear_fwd.argtypes = [vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp, vp,
+                                   vp, c_size_t, vp]
+    L.qlora_linear_bwd.argtypes = [vp, vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp,
+                                   vp, vp, vp, vp, c_size_t, vp]
+    for name in EXPORTS:
+        if name not in ("qlora_status_string", "qlora_last_hip_error"):
+            getattr(L, name).restype = c_int32
+    _lib = L
+    return L
+
+
+def _check(st: int):
+    if st != 0:
+        raise QloraError(st, lib().qlora_status_string(st).decode())
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return c_void_p(s.cuda_stream)
+
+
+class NF4Weight:
+    """Device buffers of one quantised h x o weight plus the view struct the C ABI takes."""
+
+    def __init__(self, rows, cols, packed, code, c1, mean, blocksize=64, dq_blocksize=256):
+        self.rows, self.cols = int(rows), int(cols)
+        self.blocksize, self.dq_blocksize = int(blocksize), int(dq_blocksize)
+        self.packed, self.code, self.c1, self.mean = packed, code, c1, mean
+
+    def view(self) -> qlora_nf4_view:
+        return qlora_nf4_view(self.packed.data_ptr(), self.code.data_ptr(), self.c1.data_ptr(),
+                              self.mean.data_ptr(), self.rows, self.cols, self.blocksize, self.dq_blocksize)
+
+    @property
+    def nbytes(self) -> int:
+        return self.packed.numel() + self.code.numel() + 4 * self.c1.numel() + 4
+
+
+def qlora_nf4_sizes(rows, cols, blocksize=64, dq_blocksize=256):
+    """(packed_bytes, code_bytes, c1_bytes, scratch_bytes)"""
+    out = [c_size_t(0) for _ in range(4)]
+    _check(lib().qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize, *[byref(x) for x in out]))
+    return tuple(int(x.value) for x in out)
+
+
+def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None) -> NF4Weight:
+    """W: fp32 device tensor (h, o).  Returns the quantised weight (new device buffers)."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
+    rows, cols = W.shape
+    pb, cb, c1b, sb = qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize)
+    dev = W.device
+    packed = torch.empty(pb, dtype=torch.uint8, device=dev)
+    code = torch.empty(cb, dtype=torch.uint8, device=dev)
+    c1 = torch.empty(c1b // 4, dtype=torch.float32, device=dev)
+    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    if scratch is None:
+        scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
+    _check(lib().qlora_nf4_quantize(_ptr(W), rows, cols, blocksize, dq_blocksize, _ptr(packed), _ptr(code),
+                                    _ptr(c1), _ptr(mean), _ptr(scratch), scratch.numel(), _stream(stream)))
+    return NF4Weight(rows, cols, packed, code, c1, mean, blocksize, dq_blocksize)
+
+
+def qlora_nf4_dequant(Wq: NF4Weight, out=None, stream=None):
+    """Returns the bf16 weight (h, o)."""
+    if out is None:
+        out = torch.empty((Wq.rows, Wq.cols), dtype=torch.bfloat16, device=Wq.packed.device)
+    v = Wq.view()
+    _check(lib().qlora_nf4_dequant(byref(v), _ptr(out), _stream(stream)))
+    return out
+
+
+def qlora_linear_fwd_sizes(M, h, o, r) -> int:
+    out = c_size_t(0)
+    _check(lib().qlora_linear_fwd_sizes(M, h, o, r, byref(out)))
+    return int(out.value)
+
+
+def qlora_linear_bwd_sizes(M, h, o, r) -> int:
+    out = c_size_t(0)
+    _check(lib().qlora_linear_bwd_sizes(M, h, o, r, byref(out)))
+    return int(out.value)
+
+
+def qlora_linear_fwd(X, Wq: NF4Weight, L1, L2, s, Y=None, T_save=None, workspace=None, stream=None):
+    """Y = X dequant(Wq) + s (X L1) L2.  X (M, h), L1 (h, r), L2 (r, o) bf16 device tensors."""
+    M, h = X.shape
+    o = Wq.cols
+    r = 0 if L1 is None else L1.shape[1]
+    if Y is None:
+        Y = torch.empty((M, o), dtype=torch.bfloat16, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, qlora_linear_fwd_sizes(M, h, o, r)), dtype=torch.uint8, device=X.device)
+    v = Wq.view()
+    _check(lib().qlora_linear_fwd(_ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(Y), _ptr(T_save),
+                                  _ptr(workspace), workspace.numel(), _stream(stream)))
+    return Y
+
+
+def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1=None, dL2=None,
+                     need_dX=True, need_dL=True, workspace=None, stream=None):
+    """dX, dL1, dL2 of the layer; adapter gradients only, never dW."""
+    M, o = dY.shape
+    h = Wq.rows
+    r = 0 if L1 is None else L1.shape[1]
+    dev = dY.device
+    if dX is None and need_dX:
+        dX = torch.empty((M, h), dtype=torch.bfloat16, device=dev)
+    if r > 0 and need_dL:
+        if dL1 is None:
+            dL1 = torch.empty((h, r), dtype=torch.bfloat16, device=dev)
+        if dL2 is None:
+            dL2 = torch.empty((r, o), dtype=torch.bfloat16, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(16, qlora_linear_bwd_sizes(M, h, o, r)), dtype=torch.uint8, device=dev)
+    v = Wq.view()
+    _check(lib().qlora_linear_bwd(_ptr(dY), _ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(T_saved),
+                                  _ptr(dX), _ptr(dL1), _ptr(dL2), _ptr(workspace), workspace.numel(),
+                                  _stream(stream)))
+    return dX, dL1, dL2

@@ -1,0 +1,275 @@
+// C ABI of the library (declared in include/qlora.h): argument validation on the host,
+// then kernel launches on the caller's stream.  No allocation, no synchronisation, no state
+// apart from the thread-local code of the last failed launch.
+#include "qlora.h"
+
+#include <hip/hip_runtime.h>
+
+#include "launch.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline qlora_status hip_status(hipError_t e) {
+  if (e == hipSuccess) return QLORA_OK;
+  g_last_hip_error = (int)e;
+  return QLORA_ERR_HIP;
+}
+
+// Shape rules common to everything that touches a quantised tensor.
+qlora_status check_quant_shape(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize) {
+  if (rows <= 0 || cols <= 0 || blocksize <= 0 || dq_blocksize <= 0) return QLORA_ERR_SHAPE;
+  if (blocksize != 64 || dq_blocksize != 256) return QLORA_ERR_UNSUPPORTED;
+  if (cols % blocksize != 0) return QLORA_ERR_SHAPE;       // a block never straddles two rows
+  if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31) return QLORA_ERR_SHAPE;
+  if ((rows * cols) / blocksize >= (int64_t)1 << 32) return QLORA_ERR_SHAPE;
+  return QLORA_OK;
+}
+
+qlora_status check_view(const qlora_nf4_view* v) {
+  if (!v) return QLORA_ERR_NULL;
+  if (!v->packed || !v->c2_code || !v->c1 || !v->c2_mean) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(v->rows, v->cols, v->blocksize, v->dq_blocksize)) return st;
+  if (!aligned16(v->packed) || !aligned16(v->c2_code) || !aligned16(v->c1) || ((uintptr_t)v->c2_mean & 3u))
+    return QLORA_ERR_ALIGN;
+  return QLORA_OK;
+}
+
+inline qlora::NF4Dev to_dev(const qlora_nf4_view* v) {
+  return qlora::NF4Dev{v->packed, v->c2_code, v->c1, v->c2_mean, v->rows, v->cols};
+}
+
+qlora_status check_linear(int64_t M, int64_t h, int64_t o, int32_t r) {
+  if (M <= 0 || h <= 0 || o <= 0 || r < 0) return QLORA_ERR_SHAPE;
+  if (M > (int64_t)1 << 30) return QLORA_ERR_SHAPE;
+  if (h % 64 != 0 || o % 64 != 0) return QLORA_ERR_UNSUPPORTED;
+  if (r % 16 != 0 || r > 256) return QLORA_ERR_UNSUPPORTED;
+  return QLORA_OK;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Bump allocator over the caller's workspace; the same walk computes the size query.
+struct Carver {
+  char* base; size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  template <class T> T* take(size_t count) {
+    T* p = base ? (T*)(base + off) : nullptr;
+    off = align_up(off + count * sizeof(T), 256);
+    return p;
+  }
+};
+
+struct FwdPlan {
+  uint16_t* Wt;      // o x h     dequantised weight, transposed (K-contiguous for the forward)
+  uint16_t* L2t;     // o x rp    L2^T, rank zero-padded to a multiple of 64
+  uint16_t* Ts;      // M x rp    bf16(s * X L1)
+  float* part;       // split-K partials of X L1
+  int rp, splits;
+  size_t bytes;
+};
+FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
+  FwdPlan p{};
+  Carver c(ws);
+  p.rp = (r + 63) / 64 * 64;
+  p.Wt = c.take<uint16_t>((size_t)h * o);
+  if (r > 0) {
+    p.splits = qlora::small_gemm_splits((int)M, r, (int)h);
+    p.L2t = c.take<uint16_t>((size_t)o * p.rp);
+    p.Ts = c.take<uint16_t>((size_t)M * p.rp);
+    p.part = c.take<float>((size_t)p.splits * M * r);
+  }
+  p.bytes = c.off;
+  return p;
+}
+
+struct BwdPlan {
+  uint16_t* Wd;      // h x o     dequantised weight (K-contiguous for the backward)
+  uint16_t* L1p;     // h x rp    L1 with the rank zero-padded (only when r % 64 != 0)
+  uint16_t* Us;      // M x rp    bf16(s * dY L2^T)
+  uint16_t* U16;     // M x r     bf16(dY L2^T)
+  uint16_t* T16;     // M x r     bf16(X L1), recomputed when the caller saved none
+  float* part;       // split-K partials, reused by the four skinny products
+  int rp, sU, sT, sL1, sL2;
+  size_t bytes;
+};
+BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
+  BwdPlan p{};
+  Carver c(ws);
+  p.rp = (r + 63) / 64 * 64;
+  p.Wd = c.take<uint16_t>((size_t)h * o);
+  if (r > 0) {
+    p.sU = qlora::small_gemm_splits((int)M, r, (int)o);
+    p.sT = qlora::small_gemm_splits((int)M, r, (int)h);
+    p.sL1 = qlora::small_gemm_splits((int)h, r, (int)M);
+    p.sL2 = qlora::small_gemm_splits(r, (int)o, (int)M);
+    size_t pe = (size_t)p.sU * M * r;
+    if ((size_t)p.sT * M * r > pe) pe = (size_t)p.sT * M * r;
+    if ((size_t)p.sL1 * h * r > pe) pe = (size_t)p.sL1 * h * r;
+    if ((size_t)p.sL2 * r * o > pe) pe = (size_t)p.sL2 * r * o;
+    p.L1p = (r % 64) ? c.take<uint16_t>((size_t)h * p.rp) : nullptr;
+    p.Us = c.take<uint16_t>((size_t)M * p.rp);
+    p.U16 = c.take<uint16_t>((size_t)M * r);
+    p.T16 = c.take<uint16_t>((size_t)M * r);
+    p.part = c.take<float>(pe);
+  }
+  p.bytes = c.off;
+  return p;
+}
+
+
+}  // namespace
+
+extern "C" {
+
+const char* qlora_status_string(qlora_status st) {
+  switch (st) {
+    case QLORA_OK: return "QLORA_OK";
+    case QLORA_ERR_NULL: return "QLORA_ERR_NULL: a required pointer is NULL";
+    case QLORA_ERR_SHAPE: return "QLORA_ERR_SHAPE: bad size (non-positive, or cols not a multiple of blocksize)";
+    case QLORA_ERR_UNSUPPORTED: return "QLORA_ERR_UNSUPPORTED: blocksize must be 64, dq_blocksize 256, r a multiple of 16 up to 256";
+    case QLORA_ERR_WORKSPACE: return "QLORA_ERR_WORKSPACE: workspace or scratch too small";
+    case QLORA_ERR_ALIGN: return "QLORA_ERR_ALIGN: pointer not 16-byte aligned";
+    case QLORA_ERR_HIP: return "QLORA_ERR_HIP: kernel launch failed";
+    default: return "QLORA: unknown status";
+  }
+}
+
+int qlora_last_hip_error(void) { return g_last_hip_error; }
+
+qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
+                             size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
+                             size_t* scratch_bytes) {
+  if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
+  const int64_t P = rows * cols, n = P / blocksize, n1 = (n + dq_blocksize - 1) / dq_blocksize;
+  if (packed_bytes) *packed_bytes = (size_t)(P / 2);
+  if (code_bytes) *code_bytes = (size_t)n;
+  if (c1_bytes) *c1_bytes = (size_t)n1 * sizeof(float);
+  if (scratch_bytes) *scratch_bytes = qlora::kQuantBinsBytes + (size_t)n * sizeof(float);
+  return QLORA_OK;
+}
+
+qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
+                                int32_t blocksize, int32_t dq_blocksize,
+                                uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
+                                void* scratch, size_t scratch_bytes, void* hip_stream) {
+  if (!W || !packed || !c2_code || !c1 || !c2_mean || !scratch) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
+  size_t need = 0;
+  qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize, nullptr, nullptr, nullptr, &need);
+  if (scratch_bytes < need) return QLORA_ERR_WORKSPACE;
+  if (!aligned16(W) || !aligned16(packed) || !aligned16(c2_code) || !aligned16(c1) || !aligned16(scratch) ||
+      ((uintptr_t)c2_mean & 3u))
+    return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_quantize(W, rows * cols, packed, c2_code, c1, c2_mean, scratch,
+                                           (hipStream_t)hip_stream));
+}
+
+qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void* hip_stream) {
+  if (qlora_status st = check_view(Wq)) return st;
+  if (!W_bf16) return QLORA_ERR_NULL;
+  if (!aligned16(W_bf16)) return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_dequant(to_dev(Wq), W_bf16, (hipStream_t)hip_stream));
+}
+
+// --- linear layer -----------------------------------------------------------------------------------
+qlora_status qlora_linear_fwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes) {
+  if (qlora_status st = check_linear(M, h, o, r)) return st;
+  if (!workspace_bytes) return QLORA_ERR_NULL;
+  *workspace_bytes = plan_fwd(nullptr, M, h, o, r).bytes;
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes) {
+  if (qlora_status st = check_linear(M, h, o, r)) return st;
+  if (!workspace_bytes) return QLORA_ERR_NULL;
+  *workspace_bytes = plan_bwd(nullptr, M, h, o, r).bytes;
+  return QLORA_OK;
+}
+
+#define QL_TRY(expr) do { if (hipError_t e_ = (expr)) return hip_status(e_); } while (0)
+
+qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1, const uint16_t* L2,
+                              float s, int64_t M, int32_t r, uint16_t* Y, uint16_t* T_save, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  if (qlora_status st = check_view(Wq)) return st;
+  const int64_t h = Wq->rows, o = Wq->cols;
+  if (qlora_status st = check_linear(M, h, o, r)) return st;
+  if (!X || !Y || !workspace) return QLORA_ERR_NULL;
+  if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
+  const FwdPlan p = plan_fwd(workspace, M, h, o, r);
+  if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
+  if (!aligned16(X) || !aligned16(Y) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
+      !aligned16(T_save))
+    return QLORA_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const qlora::NF4Dev W = to_dev(Wq);
+
+  QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
+  if (r > 0) {
+    // T = X L1 (Eq. 3): split-K partials, then T_save = bf16(T) and Ts = bf16(s T), rank zero-padded
+    QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.splits, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, r, r, 1.0f, st));
+    QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
+  }
+  // Y = X What + Ts L2 (Eq. 5): the adapter term is the second K segment of the same accumulators
+  QL_TRY(qlora::launch_gemm_nt(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
+                               st));
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
+                              const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved,
+                              uint16_t* dX, uint16_t* dL1, uint16_t* dL2, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  if (qlora_status st = check_view(Wq)) return st;
+  const int64_t h = Wq->rows, o = Wq->cols;
+  if (qlora_status st = check_linear(M, h, o, r)) return st;
+  if (!dY || !workspace) return QLORA_ERR_NULL;
+  if (r == 0) { dL1 = nullptr; dL2 = nullptr; }
+  if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
+  if ((dL1 || dL2) && !X) return QLORA_ERR_NULL;
+  const BwdPlan p = plan_bwd(workspace, M, h, o, r);
+  if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
+  if (!aligned16(dY) || !aligned16(X) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
+      !aligned16(T_saved) || !aligned16(dX) || !aligned16(dL1) || !aligned16(dL2))
+    return QLORA_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const qlora::NF4Dev W = to_dev(Wq);
+
+  if (r > 0 && (dX || dL1)) {
+    // U = dY L2^T: U16 = bf16(U) feeds dL1, Us = bf16(s U) feeds the adapter segment of dX
+    QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, (int)M, r, (int)o, p.part, p.sU, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, p.Us, p.rp, p.rp, s, p.U16, r, r, 1.0f, st));
+  }
+  if (dX) {
+    const uint16_t* B1 = L1;
+    if (r > 0 && p.L1p) { QL_TRY(qlora::launch_copy_pad(L1, (int)h, r, p.L1p, p.rp, st)); B1 = p.L1p; }
+    QL_TRY(qlora::launch_dequant(W, p.Wd, st));
+    // dX = dY What^T + Us L1^T
+    QL_TRY(qlora::launch_gemm_nt(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, r > 0 ? p.rp : 0, dX, h, (int)M, (int)h,
+                                 st));
+  }
+  if (dL1) {
+    // dL1 = s X^T U: contraction over the tokens, both operands stored token-major
+    QL_TRY(qlora::launch_small_gemm(X, h, true, p.U16, r, true, (int)h, r, (int)M, p.part, p.sL1, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, r, dL1, r, r, s, nullptr, 0, 0, 0.0f, st));
+  }
+  if (dL2) {
+    const uint16_t* T = T_saved;
+    if (!T) {                                               // gradient checkpointing: recompute T = X L1
+      QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.sT, st));
+      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, p.T16, r, r, 1.0f, nullptr, 0, 0, 0.0f, st));
+      T = p.T16;
+    }
+    // dL2 = s T^T dY
+    QL_TRY(qlora::launch_small_gemm(T, r, true, dY, o, true, r, (int)o, (int)M, p.part, p.sL2, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, r, (int)o, dL2, o, (int)o, s, nullptr, 0, 0, 0.0f, st));
+  }
+  return QLORA_OK;
+}
+
+}  // extern "C"

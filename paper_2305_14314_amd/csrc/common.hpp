@@ -1,0 +1,126 @@
+// Device-side building blocks shared by the gfx950 kernels of the QLoRA linear path:
+// the NF4 table (Appendix E of arXiv 2305.14314), nearest-value thresholds, the
+// 8-bit-float (OCP E4M3) encode/decode used by Double Quantization (Section 3),
+// bf16 helpers and wave-level reductions.  gfx950 only: wave64, MFMA, 160 KB LDS.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qlora {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;   // plain 16-byte vector (usable in LDS)
+
+constexpr int kBlock = 64;      // first-level blocksize (Section 3, after Eq. 6)
+constexpr int kDqBlock = 256;   // second-level blocksize
+constexpr float kF8Max = 448.0f;  // largest finite E4M3 magnitude
+
+// The 16 values of the NF4 data type, index 0..15 (Appendix E).
+#define QLORA_NF4_VALUES                                                                         \
+  -1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,                      \
+  -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,                     \
+  0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f, 0.33791524171829224f,        \
+  0.44070982933044434f, 0.5626170039176941f, 0.7229568362236023f, 1.0f
+
+__host__ __device__ constexpr float nf4_value(int i) {
+  constexpr float t[16] = {QLORA_NF4_VALUES};
+  return t[i];
+}
+
+// Decision threshold between index j and j+1: the midpoint of the two values
+// rounded toward -infinity to fp32, so that for fp32 x  (x > threshold) holds
+// exactly when x lies strictly above the real midpoint (ties go to the lower index).
+__host__ __device__ constexpr float nf4_threshold(int j) {
+  const double mid = ((double)nf4_value(j) + (double)nf4_value(j + 1)) * 0.5;   // exact
+  float t = (float)mid;
+  if ((double)t > mid) {
+    uint32_t u = __builtin_bit_cast(uint32_t, t);
+    u = (t > 0.0f) ? u - 1 : u + 1;          // next fp32 toward -infinity (t is never 0 here)
+    t = __builtin_bit_cast(float, u);
+  }
+  return t;
+}
+
+// Nearest NF4 index of a normalised value: 4-level binary search over the 15 thresholds.
+__device__ __forceinline__ uint32_t nf4_index(float x) {
+  constexpr float t0 = nf4_threshold(0), t1 = nf4_threshold(1), t2 = nf4_threshold(2), t3 = nf4_threshold(3),
+                  t4 = nf4_threshold(4), t5 = nf4_threshold(5), t6 = nf4_threshold(6), t7 = nf4_threshold(7),
+                  t8 = nf4_threshold(8), t9 = nf4_threshold(9), t10 = nf4_threshold(10),
+                  t11 = nf4_threshold(11), t12 = nf4_threshold(12), t13 = nf4_threshold(13),
+                  t14 = nf4_threshold(14);
+  const bool b3 = x > t7;
+  const float ta = b3 ? t11 : t3;
+  const bool b2 = x > ta;
+  const float tb = b3 ? (b2 ? t13 : t9) : (b2 ? t5 : t1);
+  const bool b1 = x > tb;
+  const float tc = b3 ? (b2 ? (b1 ? t14 : t12) : (b1 ? t10 : t8)) : (b2 ? (b1 ? t6 : t4) : (b1 ? t2 : t0));
+  const bool b0 = x > tc;
+  return ((uint32_t)b3 << 3) | ((uint32_t)b2 << 2) | ((uint32_t)b1 << 1) | (uint32_t)b0;
+}
+
+// ---- bf16 ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {   // RNE, lo in bits 15:0
+  bf16x2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint16_t bf16_bits(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ float bf16_lo_to_f32(uint32_t pair) { return __builtin_bit_cast(float, pair << 16); }
+__device__ __forceinline__ float bf16_hi_to_f32(uint32_t pair) { return __builtin_bit_cast(float, pair & 0xffff0000u); }
+
+// ---- 8-bit float (OCP E4M3: 1-4-3, bias 7, no infinities, max 448) ---------------------------
+// Exact value of a code (codes 0x7f / 0xff are NaN and never produced by the encoder).
+__device__ __forceinline__ float e4m3_value(uint32_t code) {
+  const uint32_t e = (code >> 3) & 15u, m = code & 7u;
+  float mag = e ? __builtin_bit_cast(float, ((e + 120u) << 23) | (m << 20)) : (float)m * 0x1p-9f;
+  return (code & 0x80u) ? -mag : mag;
+}
+// Decode-table entry used by doubleDequant: value / 448 as one correctly rounded fp32 division.
+__device__ __forceinline__ float e4m3_unit(uint32_t code) { return __fdiv_rn(e4m3_value(code), kF8Max); }
+
+// Round-to-nearest-even onto the E4M3 grid, saturating at +-448; a zero result is always 0x00.
+__device__ __forceinline__ uint32_t e4m3_encode(float z) {
+  const float a = __builtin_fabsf(z);
+  uint32_t code;
+  if (a >= kF8Max) {
+    code = 0x7eu;
+  } else if (a < 0x1p-6f) {
+    code = (uint32_t)__builtin_rintf(a * 512.0f);          // subnormal grid 2^-9; 8 -> 0x08 = 2^-6
+  } else {
+    const uint32_t u = __builtin_bit_cast(uint32_t, a);
+    const uint32_t r = u + 0x7ffffu + ((u >> 20) & 1u);      // RNE at mantissa bit 20, carry into exponent
+    code = (r >> 20) - (120u << 3);
+  }
+  return (code != 0u && z < 0.0f) ? (code | 0x80u) : code;
+}
+
+// ---- wave-level helpers ----------------------------------------------------------------------
+// max over aligned groups of 16 lanes (a DPP row); every lane of the row gets the result.
+__device__ __forceinline__ float row16_max(float v) {
+  int x = __builtin_bit_cast(int, v);
+  // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror
+  v = __builtin_fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true)));
+  x = __builtin_bit_cast(int, v);
+  v = __builtin_fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true)));
+  x = __builtin_bit_cast(int, v);
+  v = __builtin_fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0x141, 0xF, 0xF, true)));
+  x = __builtin_bit_cast(int, v);
+  v = __builtin_fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(x, 0x140, 0xF, 0xF, true)));
+  return v;
+}
+// max over the whole wave64; every lane gets the result.
+__device__ __forceinline__ float wave_max(float v) {
+  v = row16_max(v);
+  v = __builtin_fmaxf(v, __shfl_xor(v, 16));
+  v = __builtin_fmaxf(v, __shfl_xor(v, 32));
+  return v;
+}
+
+}  // namespace qlora

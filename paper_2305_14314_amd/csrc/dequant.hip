@@ -1,0 +1,107 @@
+// Standalone doubleDequant (arXiv 2305.14314, Eq. 6 and Eq. 2): packed NF4 indices and
+// double-quantised constants -> bf16 weights.  HBM-bound: 0.516 B read + 2 B written per element.
+// One lane decodes one packed dword (8 weights of one 64-block) and stores 16 bytes.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace qlora {
+
+constexpr int kDeqThreads = 256;
+
+__global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
+    const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
+    const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords) {
+  __shared__ float lut[16];
+  __shared__ float unit[256];
+  if (threadIdx.x < 16) {
+    constexpr float t[16] = {QLORA_NF4_VALUES};
+    lut[threadIdx.x] = t[threadIdx.x];
+  }
+  unit[threadIdx.x] = e4m3_unit(threadIdx.x);               // 256 threads, 256 codes
+  __syncthreads();
+  const float mean = *mean_ptr;
+
+  const int64_t stride = (int64_t)gridDim.x * kDeqThreads;
+  for (int64_t d = (int64_t)blockIdx.x * kDeqThreads + threadIdx.x; d < n_dwords; d += stride) {
+    const uint32_t p = packed[d];
+    const int64_t blk = d >> 3;                             // 8 dwords per 64-block
+    // dequant(c1, c2): two separately rounded fp32 steps
+    const float c2 = __fadd_rn(__fmul_rn(unit[code[blk]], c1[blk >> 8]), mean);
+    uint4 o;
+    o.x = pack_bf16x2(__fmul_rn(lut[p & 15u], c2), __fmul_rn(lut[(p >> 4) & 15u], c2));
+    o.y = pack_bf16x2(__fmul_rn(lut[(p >> 8) & 15u], c2), __fmul_rn(lut[(p >> 12) & 15u], c2));
+    o.z = pack_bf16x2(__fmul_rn(lut[(p >> 16) & 15u], c2), __fmul_rn(lut[(p >> 20) & 15u], c2));
+    o.w = pack_bf16x2(__fmul_rn(lut[(p >> 24) & 15u], c2), __fmul_rn(lut[p >> 28], c2));
+    out[d] = o;
+  }
+}
+
+// Transposed variant for the forward GEMM: out[n][k] = dequant(W)[k][n], row stride ld_out >= h.
+// A workgroup owns 64 input rows (k) x 256 columns (n); each wave a 64 x 64 sub-tile, i.e. one
+// 64-block per row.  A lane loads one packed dword (8 n) from each of 8 consecutive rows and
+// writes, for each of its 8 columns, the 8 k-consecutive bf16 as one 16-byte store, so stores
+// form 128-byte runs along k.  No LDS staging of data.
+__global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
+    const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
+    const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out) {
+  __shared__ float lut[16];
+  __shared__ float unit[256];
+  if (threadIdx.x < 16) {
+    constexpr float t[16] = {QLORA_NF4_VALUES};
+    lut[threadIdx.x] = t[threadIdx.x];
+  }
+  unit[threadIdx.x] = e4m3_unit(threadIdx.x);
+  __syncthreads();
+  const float mean = *mean_ptr;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int kg = lane >> 3, ng = lane & 7;
+  const int n_blk = blockIdx.x * 4 + wave;                  // 64-column block index within a row
+  if (n_blk * 64 >= o) return;
+  const int k_base = blockIdx.y * 64 + kg * 8;
+  const int blocks_per_row = o >> 6;
+
+  uint32_t p[8];
+  float c2[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int k = k_base + j;
+    const bool ok = k < h;
+    const int64_t blk = (int64_t)(ok ? k : 0) * blocks_per_row + n_blk;
+    p[j] = ok ? packed[blk * 8 + ng] : 0x77777777u;         // index 7 is the exact zero
+    c2[j] = ok ? __fadd_rn(__fmul_rn(unit[code[blk]], c1[blk >> 8]), mean) : 0.0f;
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = __fmul_rn(lut[(p[j] >> (4 * e)) & 15u], c2[j]);
+    uint4 q;
+    q.x = pack_bf16x2(v[0], v[1]);
+    q.y = pack_bf16x2(v[2], v[3]);
+    q.z = pack_bf16x2(v[4], v[5]);
+    q.w = pack_bf16x2(v[6], v[7]);
+    const int n = n_blk * 64 + ng * 8 + e;
+    if (k_base < h) *(uint4*)(out + (int64_t)n * ld_out + k_base) = q;   // h % 8 == 0: all 8 or none
+  }
+}
+
+hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st) {
+  const int h = (int)w.rows, o = (int)w.cols;
+  dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64));
+  hipLaunchKernelGGL(dequant_nf4_t_kernel, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
+                     w.c1, w.mean, out, h, o, ld_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
+  const int64_t n_dwords = w.rows * w.cols / 8;
+  int64_t blocks = (n_dwords + kDeqThreads - 1) / kDeqThreads;
+  const int64_t cap = 256 * 32;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(dequant_nf4_kernel, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
+                     (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords);
+  return hipGetLastError();
+}
+
+}  // namespace qlora

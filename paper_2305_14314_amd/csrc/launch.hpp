@@ -1,0 +1,47 @@
+// Internal launchers behind the C ABI.  Each enqueues kernels on `st` and returns hipGetLastError().
+// Shapes have been validated by the caller (api.cpp); nothing here synchronises or allocates.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace qlora {
+
+struct NF4Dev {            // device views of one quantised h x o weight
+  const uint8_t* packed;
+  const uint8_t* code;
+  const float* c1;
+  const float* mean;
+  int64_t rows, cols;      // h, o
+};
+
+// quantize.hip
+constexpr size_t kQuantBinsBytes = 256 * sizeof(unsigned long long);
+hipError_t launch_quantize(const float* W, int64_t elems, uint8_t* packed, uint8_t* code, float* c1,
+                           float* mean, void* scratch, hipStream_t st);
+
+// dequant.hip
+hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);
+// out[n][k] = dequant(W)[k][n] with row stride ld_out (elements); requires h % 8 == 0.
+hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st);
+
+// gemm.hip: C[M x N] = A0 B0^T + A1 B1^T, all operands K-contiguous bf16, K0 and K1 multiples of 64.
+hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
+                          const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
+                          uint16_t* C, int64_t ldc, int M, int N, hipStream_t st);
+
+// small.hip: skinny GEMMs of the LoRA branch with split-K fp32 partials, and layout helpers.
+//   part[split][I x J] = A(i,k) B(k,j);  ta: A stored [k][i] instead of [i][k];  tb: B stored [k][j] instead of [j][k].
+int small_gemm_splits(int I, int J, int K);
+hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb,
+                             int I, int J, int K, float* part, int splits, hipStream_t st);
+//   out0 = bf16(scale0 * sum of splits), w0 columns written (zeros beyond J); out1 likewise; either may be NULL.
+hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
+                                 float scale0, uint16_t* out1, int64_t ld1, int w1, float scale1, hipStream_t st);
+//   dst[c][r] = src[r][c], rows r >= R zero-filled up to Rp.
+hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
+                                hipStream_t st);
+hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st);
+
+}  // namespace qlora

@@ -1,0 +1,154 @@
+// Blockwise NF4 quantisation with Double Quantization (arXiv 2305.14314, Eq. 1 and Section 3).
+//
+// Four launches on the caller's stream, no host synchronisation:
+//   zero_bins      clears the 256 exponent bins used for the exact mean
+//   quantize_nf4   per 64-block: absmax (DPP row reduce), reciprocal, nearest NF4 index, nibble pack;
+//                  writes the fp32 constant c2 to scratch and adds it to the exponent bins
+//   dq_mean        exact sum of all c2 from the bins, divided by n, rounded once to fp32
+//   dq_encode      per run of 256 constants: c2 - mean, absmax -> c1, E4M3 codes
+//
+// The mean is exact and independent of summation order: every fp32 constant is
+// mantissa * 2^(exponent), the mantissas are summed per exponent in 64-bit integers
+// (integer atomics commute), and the bins are combined in multi-word integer arithmetic.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace qlora {
+
+constexpr int kQThreads = 256;
+
+__global__ void zero_bins_kernel(unsigned long long* bins) { bins[threadIdx.x] = 0ull; }
+
+// One float4 per lane per step; 16 consecutive lanes hold one 64-block.
+__global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
+    const float4* __restrict__ W, int64_t n_vec4,          // n_vec4 = elements / 4
+    uint16_t* __restrict__ packed16,                       // one 16-bit store per lane: 4 nibbles
+    float* __restrict__ c2_out, unsigned long long* __restrict__ bins) {
+  __shared__ unsigned long long lbins[256];
+  lbins[threadIdx.x] = 0ull;
+  __syncthreads();
+
+  const int64_t stride = (int64_t)gridDim.x * kQThreads;
+  for (int64_t v = (int64_t)blockIdx.x * kQThreads + threadIdx.x; v < n_vec4; v += stride) {
+    const float4 w = W[v];
+    float amax = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(w.x), __builtin_fabsf(w.y)),
+                                 __builtin_fmaxf(__builtin_fabsf(w.z), __builtin_fabsf(w.w)));
+    amax = row16_max(amax);                                 // c2 of this lane's block
+    // Eq. 1: the constant is range/absmax (range 1); elements are multiplied by it.
+    const float rc = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(1.0f, amax);
+    const uint32_t i0 = nf4_index(__fmul_rn(w.x, rc));
+    const uint32_t i1 = nf4_index(__fmul_rn(w.y, rc));
+    const uint32_t i2 = nf4_index(__fmul_rn(w.z, rc));
+    const uint32_t i3 = nf4_index(__fmul_rn(w.w, rc));
+    packed16[v] = (uint16_t)(i0 | (i1 << 4) | (i2 << 8) | (i3 << 12));
+    if ((threadIdx.x & 15) == 0) {
+      c2_out[v >> 4] = amax;
+      const uint32_t u = __builtin_bit_cast(uint32_t, amax);
+      uint32_t e = u >> 23, m = u & 0x7fffffu;
+      if (e == 0) e = 1; else m |= 0x800000u;               // value = m * 2^(e - 150)
+      atomicAdd(&lbins[e], (unsigned long long)m);
+    }
+  }
+  __syncthreads();
+  const unsigned long long mine = lbins[threadIdx.x];
+  if (mine) atomicAdd(&bins[threadIdx.x], mine);
+}
+
+// Single wave.  sum = SUM_e bins[e] * 2^(e-1) in units of 2^-149, as 12 x 32-bit limbs;
+// mean = round_to_nearest_even_fp32(sum / n).
+__global__ __launch_bounds__(64) void dq_mean_kernel(const unsigned long long* __restrict__ bins,
+                                                     uint32_t n, float* __restrict__ mean_out) {
+  __shared__ unsigned long long lb[256];
+  for (int i = threadIdx.x; i < 256; i += 64) lb[i] = bins[i];
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+
+  constexpr int L = 12;
+  uint32_t acc[L];
+  for (int k = 0; k < L; ++k) acc[k] = 0;
+  for (int e = 1; e < 255; ++e) {
+    const unsigned long long b = lb[e];
+    if (b == 0ull) continue;
+    const int sh = e - 1, limb = sh >> 5, off = sh & 31;
+    // b < 2^56; b << off spans at most three limbs
+    const uint32_t p0 = (uint32_t)(b << off);
+    const unsigned long long hi = off ? (b >> (32 - off)) : (b >> 32);
+    const uint32_t p1 = (uint32_t)hi, p2 = (uint32_t)(hi >> 32);
+    const uint32_t parts[3] = {p0, p1, p2};
+    unsigned long long carry = 0;
+    for (int k = 0; k < L - limb; ++k) {
+      const unsigned long long t = (unsigned long long)acc[limb + k] + (k < 3 ? parts[k] : 0u) + carry;
+      acc[limb + k] = (uint32_t)t;
+      carry = t >> 32;
+      if (k >= 2 && carry == 0) break;
+    }
+  }
+  uint32_t q[L];
+  unsigned long long rem = 0;
+  for (int k = L - 1; k >= 0; --k) {
+    const unsigned long long cur = (rem << 32) | acc[k];
+    q[k] = (uint32_t)(cur / n);
+    rem = cur % n;
+  }
+  int top = -1;
+  for (int k = L - 1; k >= 0; --k)
+    if (q[k]) { top = k * 32 + 31 - __builtin_clz(q[k]); break; }
+  if (top < 0 && rem == 0) { *mean_out = 0.0f; return; }
+  // keep the 24 leading bits of q (all of q if it is shorter), round on the rest and on rem/n
+  const int drop = top >= 24 ? top - 23 : 0;
+  auto bit = [&](int i) -> uint32_t { return (q[i >> 5] >> (i & 31)) & 1u; };
+  uint32_t kept = 0;
+  for (int i = top; i >= drop; --i) kept = (kept << 1) | bit(i);
+  bool half, sticky;
+  if (drop == 0) {
+    half = 2 * rem >= n;
+    sticky = 2 * rem > n;
+  } else {
+    half = bit(drop - 1) != 0;
+    sticky = rem != 0;
+    for (int i = drop - 2; i >= 0 && !sticky; --i) sticky = bit(i) != 0;
+  }
+  if (half && (sticky || (kept & 1u))) ++kept;              // kept <= 2^24, exact in fp32
+  // result = kept * 2^(drop - 149) with kept <= 2^24: with drop = 0 the integer is the bit pattern itself
+  // (subnormals and the first binades); each further dropped bit raises the exponent field by one.
+  *mean_out = __builtin_bit_cast(float, kept + ((uint32_t)drop << 23));
+}
+
+// One workgroup per run of 256 first-level constants.
+__global__ __launch_bounds__(kDqBlock) void dq_encode_kernel(const float* __restrict__ c2, int64_t n,
+                                                             const float* __restrict__ mean_ptr,
+                                                             uint8_t* __restrict__ code,
+                                                             float* __restrict__ c1) {
+  __shared__ float wmax[kDqBlock / 64];
+  const int64_t b = (int64_t)blockIdx.x * kDqBlock + threadIdx.x;
+  const float mean = *mean_ptr;
+  const float d = (b < n) ? __fsub_rn(c2[b], mean) : 0.0f;  // centred constant
+  const float m = wave_max(__builtin_fabsf(d));
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+  __syncthreads();
+  const float amax = __builtin_fmaxf(__builtin_fmaxf(wmax[0], wmax[1]), __builtin_fmaxf(wmax[2], wmax[3]));
+  float rc1 = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(kF8Max, amax);
+  if (__builtin_isinf(rc1)) rc1 = 0.0f;
+  if (b < n) code[b] = (uint8_t)e4m3_encode(__fmul_rn(d, rc1));
+  if (threadIdx.x == 0) c1[blockIdx.x] = amax;
+}
+
+hipError_t launch_quantize(const float* W, int64_t elems, uint8_t* packed, uint8_t* code, float* c1,
+                           float* mean, void* scratch, hipStream_t st) {
+  const int64_t n = elems / kBlock;
+  unsigned long long* bins = (unsigned long long*)scratch;           // 256 x u64
+  float* c2 = (float*)((char*)scratch + 256 * sizeof(unsigned long long));
+  const int64_t n_vec4 = elems / 4;
+  int64_t blocks = (n_vec4 + kQThreads - 1) / kQThreads;
+  const int64_t cap = 256 * 16;                                      // 16 workgroups per CU
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(zero_bins_kernel, dim3(1), dim3(256), 0, st, bins);
+  hipLaunchKernelGGL(quantize_nf4_kernel, dim3((unsigned)blocks), dim3(kQThreads), 0, st,
+                     (const float4*)W, n_vec4, (uint16_t*)packed, c2, bins);
+  hipLaunchKernelGGL(dq_mean_kernel, dim3(1), dim3(64), 0, st, bins, (uint32_t)n, mean);
+  const int64_t n1 = (n + kDqBlock - 1) / kDqBlock;
+  hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)n1), dim3(kDqBlock), 0, st, c2, n, mean, code, c1);
+  return hipGetLastError();
+}
+
+}  // namespace qlora

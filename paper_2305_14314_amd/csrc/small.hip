@@ -1,0 +1,219 @@
+// Skinny bf16 MFMA GEMMs of the LoRA branch (arXiv 2305.14314, Eq. 3 / Eq. 5 and the adapter
+// gradients): T = X L1, U = dY L2^T, dL1 = s X^T U, dL2 = s T^T dY.  One dimension is the adapter
+// rank (<= 256), so these are bound by streaming X or dY from HBM, not by MFMA.
+//
+//   part[split][I x J] (fp32) = sum over this split's K range of A(i,k) * B(k,j)
+//   finalize: out = bf16(scale * sum over splits), optionally a second output with another scale
+//
+// Operand layouts are template flags: TA = false means A is stored [i][k] (K-contiguous),
+// TA = true means A is stored [k][i] (the contraction index is the row index, as for X^T);
+// likewise TB for B ([j][k] or [k][j]).  K-contiguous tiles are kept in LDS XOR-swizzled in 16-byte
+// chunks and read with ds_read_b128; row-index-contracted tiles are kept as loaded and their
+// MFMA fragments are gathered with 16-bit LDS reads.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace qlora {
+
+constexpr int ST = 64;                       // tile edge in I, J and K
+constexpr int kSmallThreads = 256;
+
+struct SmallArgs {
+  const uint16_t* A; int64_t lda;
+  const uint16_t* B; int64_t ldb;
+  float* part;
+  int I, J, K, k_per_split;
+};
+
+typedef __attribute__((address_space(3))) char lds_char;
+
+// fetch one 16-byte chunk of an operand tile (zero outside the matrix)
+template <bool T>
+__device__ __forceinline__ u32x4 fetch_chunk(const uint16_t* __restrict__ src, int64_t ld, int r0, int R, int k0,
+                                             int k_end, int c) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  if constexpr (!T) {                         // src[row][k]: chunk = (row, 8 consecutive k)
+    const int row = r0 + (c >> 3), k = k0 + (c & 7) * 8;
+    if (row < R && k < k_end) return *(const u32x4*)(src + (int64_t)row * ld + k);
+    return z;
+  } else {                                    // src[k][row]: chunk = (k, 8 consecutive rows)
+    const int k = k0 + (c >> 3), row = r0 + (c & 7) * 8;
+    if (k < k_end && row < R) return *(const u32x4*)(src + (int64_t)k * ld + row);
+    return z;
+  }
+}
+
+template <bool T>
+__device__ __forceinline__ void stash_chunk(lds_char* tile, int c, u32x4 v) {
+  if constexpr (!T) {
+    const int row = c >> 3, kc = c & 7;
+    *(u32x4 __attribute__((address_space(3)))*)(tile + row * 128 + ((kc ^ (row & 7)) * 16)) = v;
+  } else {
+    *(u32x4 __attribute__((address_space(3)))*)(tile + c * 16) = v;      // [k][64 rows], as loaded
+  }
+}
+
+// MFMA 32x32x16 fragment: lane holds row (lane % 32) of the 32-row sub-tile, 8 consecutive k
+template <bool T>
+__device__ __forceinline__ bf16x8 small_frag(const lds_char* tile, int row, int kk, int half) {
+  if constexpr (!T) {
+    const int chunk = (2 * kk + half) ^ (row & 7);
+    return *(const bf16x8 __attribute__((address_space(3)))*)(tile + row * 128 + chunk * 16);
+  } else {
+    bf16x8 f;
+    const int kb = kk * 16 + half * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      f[e] = *(const __bf16 __attribute__((address_space(3)))*)(tile + ((kb + e) * 64 + row) * 2);
+    return f;
+  }
+}
+
+template <bool TA, bool TB>
+__global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallArgs p) {
+  __shared__ __attribute__((aligned(16))) char sA_[ST * ST * 2];
+  __shared__ __attribute__((aligned(16))) char sB_[ST * ST * 2];
+  lds_char* sA = (lds_char*)sA_;
+  lds_char* sB = (lds_char*)sB_;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int i0 = blockIdx.x * ST, j0 = blockIdx.y * ST;
+  const int k_begin = blockIdx.z * p.k_per_split;
+  const int k_end = (k_begin + p.k_per_split < p.K) ? k_begin + p.k_per_split : p.K;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int a_row = wi * 32 + (lane & 31), b_row = wj * 32 + (lane & 31), half = lane >> 5;
+
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+  u32x4 ra[2], rb[2];
+  ra[0] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k_begin, k_end, tid);
+  ra[1] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k_begin, k_end, tid + 256);
+  rb[0] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k_begin, k_end, tid);
+  rb[1] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k_begin, k_end, tid + 256);
+
+  for (int k0 = k_begin; k0 < k_end; k0 += ST) {
+    __syncthreads();                                        // previous step's fragment reads are done
+    stash_chunk<TA>(sA, tid, ra[0]);
+    stash_chunk<TA>(sA, tid + 256, ra[1]);
+    stash_chunk<TB>(sB, tid, rb[0]);
+    stash_chunk<TB>(sB, tid + 256, rb[1]);
+    __syncthreads();
+    if (k0 + ST < k_end) {                                  // prefetch the next step into registers
+      ra[0] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0 + ST, k_end, tid);
+      ra[1] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0 + ST, k_end, tid + 256);
+      rb[0] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k0 + ST, k_end, tid);
+      rb[1] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k0 + ST, k_end, tid + 256);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 a = small_frag<TA>(sA, a_row, kk, half);
+      const bf16x8 b = small_frag<TB>(sB, b_row, kk, half);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+    }
+  }
+
+  float* out = p.part + (int64_t)blockIdx.z * p.I * p.J;
+  const int j = j0 + wj * 32 + (lane & 31);
+  if (j < p.J) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = i0 + wi * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+      if (i < p.I) out[(int64_t)i * p.J + j] = acc[v];
+    }
+  }
+}
+
+// out0[i][j] = bf16(scale0 * sum_s part[s][i][j]) for j < J, 0 for J <= j < ld-padded width;
+// out1 likewise with scale1 (either may be NULL).  Fixed summation order: deterministic.
+__global__ void small_finalize_kernel(const float* __restrict__ part, int splits, int I, int J,
+                                      uint16_t* __restrict__ out0, int64_t ld0, int w0, float scale0,
+                                      uint16_t* __restrict__ out1, int64_t ld1, int w1, float scale1) {
+  const int wmax = (w0 > w1) ? w0 : w1;
+  const int64_t total = (int64_t)I * wmax;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int i = (int)(e / wmax), j = (int)(e % wmax);
+    float s = 0.0f;
+    if (j < J)
+      for (int sp = 0; sp < splits; ++sp) s += part[((int64_t)sp * I + i) * J + j];
+    if (out0 && j < w0) out0[(int64_t)i * ld0 + j] = bf16_bits(s * scale0);
+    if (out1 && j < w1) out1[(int64_t)i * ld1 + j] = bf16_bits(s * scale1);
+  }
+}
+
+// dst[c][r] = src[r][c] for r < R, zero for R <= r < Rp.  src is R x C (ld = lds_), dst is C x Rp.
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int64_t ld_src, int R,
+                                                            int C, uint16_t* __restrict__ dst, int Rp) {
+  __shared__ uint16_t tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+    const int r = r0 + e / 64, c = c0 + e % 64;
+    tile[e / 64][e % 64] = (r < R && c < C) ? src[(int64_t)r * ld_src + c] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+    const int c = c0 + e / 64, r = r0 + e % 64;
+    if (c < C && r < Rp) dst[(int64_t)c * Rp + r] = tile[e % 64][e / 64];
+  }
+}
+
+// dst[row][0..Cp) = src[row][0..C) followed by zeros
+__global__ void copy_pad_kernel(const uint16_t* __restrict__ src, int R, int C, uint16_t* __restrict__ dst, int Cp) {
+  const int64_t total = (int64_t)R * Cp;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int row = (int)(e / Cp), c = (int)(e % Cp);
+    dst[e] = (c < C) ? src[(int64_t)row * C + c] : (uint16_t)0;
+  }
+}
+
+int small_gemm_splits(int I, int J, int K) {
+  const int tiles = ((I + ST - 1) / ST) * ((J + ST - 1) / ST);
+  const int ksteps = (K + ST - 1) / ST;
+  int splits = (1024 + tiles - 1) / tiles;                  // aim for ~4 workgroups per CU
+  if (splits > ksteps) splits = ksteps;
+  if (splits > 64) splits = 64;
+  if (splits < 1) splits = 1;
+  return splits;
+}
+
+hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb,
+                             int I, int J, int K, float* part, int splits, hipStream_t st) {
+  SmallArgs a;
+  a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.part = part; a.I = I; a.J = J; a.K = K;
+  const int ksteps = (K + ST - 1) / ST;
+  a.k_per_split = ((ksteps + splits - 1) / splits) * ST;
+  dim3 grid((unsigned)((I + ST - 1) / ST), (unsigned)((J + ST - 1) / ST), (unsigned)splits);
+  dim3 block(kSmallThreads);
+  if (!ta && !tb) hipLaunchKernelGGL((small_gemm_kernel<false, false>), grid, block, 0, st, a);
+  else if (!ta && tb) hipLaunchKernelGGL((small_gemm_kernel<false, true>), grid, block, 0, st, a);
+  else if (ta && !tb) hipLaunchKernelGGL((small_gemm_kernel<true, false>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((small_gemm_kernel<true, true>), grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
+                                 float scale0, uint16_t* out1, int64_t ld1, int w1, float scale1, hipStream_t st) {
+  const int wmax = (w0 > w1) ? w0 : w1;
+  int64_t blocks = ((int64_t)I * wmax + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, out0, ld0,
+                     w0, scale0, out1, ld1, w1, scale1);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
+                                hipStream_t st) {
+  dim3 grid((unsigned)((C + 63) / 64), (unsigned)((Rp + 63) / 64));
+  hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, st, src, ld_src, R, C, dst, Rp);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st) {
+  int64_t blocks = ((int64_t)R * Cp + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(copy_pad_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, R, C, dst, Cp);
+  return hipGetLastError();
+}
+
+}  // namespace qlora
