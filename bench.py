@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""Benchmark of the QLoRA linear hot path on one MI355X.
+
+A step is one forward + backward pass (Y, then dX, dL1, dL2) through the seven linears of one
+LLaMA-65B-shaped decoder block (q/k/v/o 8192x8192, gate/up 8192x22016, down 22016x8192) at 4096
+tokens with LoRA r = 64, alpha = 16 on every linear; the weights are NF4 + Double Quantization,
+quantised by this library before the timed region and resident in HBM.  Successive steps cycle
+through a pool of differently-seeded blocks so weights are not served from cache.
+
+Prints ONE JSON line: the metric is fwd+bwd TFLOP/s (algorithmic FLOPs 4*M*h*o + 6*M*r*(h+o) per
+linear); `roofline` is the main MFMA GEMM kernel against the bf16 dense peak, timed with HIP events
+around every launch inside the timed region; `cpu_baseline` is the fp64 CPU oracle on a bounded
+sample of the same workload.  The other rows of the path (quantise, standalone dequant, few-token
+GEMV) are measured after the timed region and reported in `extra`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
+PEAK_HBM_GBS = 8000.0
+
+
+def _ensure_built():
+    from paper_2305_14314_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(verbose=False)
+
+
+def _time_ms(torch, fn, iters, warmup=2):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def _read_traffic():
+    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "gemm_nt_llama65b_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(seconds_target=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload:
+    forward and input-gradient rows of the 8192 x 8192 linear (fp64, OpenMP)."""
+    import oracle
+    from paper_2305_14314_amd import synth
+    h = o = 8192
+    r, s = 64, 0.25
+    W = synth.normal_f32((h, o), synth.SIGMA_W, synth.tensor_seed(3, 0, "W"))
+    q = oracle.nf4_quantize(W)
+    What = oracle.nf4_dequant(q)
+    rows = 256
+    X = synth.normal_bf16((rows, h), 1.0, synth.tensor_seed(3, 0, "X"))
+    dY = synth.normal_bf16((rows, o), 1.0, synth.tensor_seed(3, 0, "dY"))
+    L1 = synth.normal_bf16((h, r), 0.01, synth.tensor_seed(3, 0, "L1"))
+    L2 = synth.normal_bf16((r, o), 0.01, synth.tensor_seed(3, 0, "L2"))
+    flops, secs, reps = 0.0, 0.0, 0
+    while secs < seconds_target and reps < 16:
+        t0 = time.perf_counter()
+        oracle.linear_fwd(X, What, L1, L2, s)
+        oracle.linear_bwd_dx(dY, What, L1, L2, s)
+        secs += time.perf_counter() - t0
+        flops += 2 * (2.0 * rows * h * o + 2.0 * rows * r * (h + o))
+        reps += 1
+    return {"value": flops / secs * 1e-12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{reps} x (Y and dX for {rows} token rows of the 8192x8192 linear, r=64), fp64 loops, "
+                      f"{secs:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--pool-blocks", type=int, default=80, help="differently-seeded weight blocks resident in HBM")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build is single-GPU; --gpus must be 1 (see DESIGN.md for how the path "
+                         "would shard)\n")
+        sys.exit(2)
+
+    _ensure_built()
+    import torch
+    import paper_2305_14314_amd as ql
+    from paper_2305_14314_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = synth.CONFIGS[3]
+    M, r = cfg["M"], cfg["r"]
+    s = cfg["alpha"] / r
+    linears = cfg["linears"]
+    d, ffn = 8192, 22016
+
+    # ---- resident pool: quantise `pool_blocks` blocks of 7 tensors with this library -------------
+    pool = []
+    t_quant_ms, quant_elems = 0.0, 0
+    scratch = torch.empty(max(ql.qlora_nf4_sizes(h, o)[3] for h, o in linears), dtype=torch.uint8, device=dev)
+    for b in range(args.pool_blocks):
+        block = []
+        for li, (h, o) in enumerate(linears):
+            W = synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(3, li, "W") + b, dev)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            Wq = ql.qlora_nf4_quantize(W, scratch=scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            if b > 0:                                   # the first block warms up
+                t_quant_ms += e0.elapsed_time(e1)
+                quant_elems += h * o
+            block.append(Wq)
+            del W
+        pool.append(block)
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED)
+    rnd = lambda *shape, sd=1.0: (torch.randn(*shape, device=dev, dtype=torch.float32, generator=gen) * sd).to(
+        torch.bfloat16)
+    X = {d: rnd(M, d), ffn: rnd(M, ffn)}
+    dY = {d: rnd(M, d), ffn: rnd(M, ffn)}
+    L1 = [rnd(h, r, sd=cfg["sigma_l"]) for h, o in linears]
+    L2 = [rnd(r, o, sd=cfg["sigma_l"]) for h, o in linears]
+    Y = {d: torch.empty(M, d, device=dev, dtype=torch.bfloat16), ffn: torch.empty(M, ffn, device=dev, dtype=torch.bfloat16)}
+    dX = {d: torch.empty(M, d, device=dev, dtype=torch.bfloat16), ffn: torch.empty(M, ffn, device=dev, dtype=torch.bfloat16)}
+    T = [torch.empty(M, r, device=dev, dtype=torch.bfloat16) for _ in linears]
+    dL1 = [torch.empty_like(a) for a in L1]
+    dL2 = [torch.empty_like(a) for a in L2]
+    ws_bytes = max(max(ql.qlora_linear_fwd_sizes(M, h, o, r), ql.qlora_linear_bwd_sizes(M, h, o, r)) for h, o in linears)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step(k):
+        block = pool[k % len(pool)]
+        for li, (h, o) in enumerate(linears):
+            ql.qlora_linear_fwd(X[h], block[li], L1[li], L2[li], s, Y=Y[o], T_save=T[li], workspace=ws)
+        for li in reversed(range(len(linears))):
+            h, o = linears[li]
+            ql.qlora_linear_bwd(dY[o], X[h], block[li], L1[li], L2[li], s, T_saved=T[li], dX=dX[h], dL1=dL1[li],
+                                dL2=dL2[li], workspace=ws)
+
+    flops_step = sum(4.0 * M * h * o + 6.0 * M * r * (h + o) for h, o in linears)
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    ql.qlora_profile_gemm(True)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ql.qlora_profile_gemm(False)
+    gemm_ms, gemm_launches, gemm_flops = ql.qlora_profile_gemm_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tflops = flops_step / (ms_per_step * 1e-3) * 1e-12
+
+    achieved = gemm_flops / (gemm_ms * 1e-3) * 1e-12 if gemm_ms > 0 else 0.0
+    out = {
+        "metric": "QLoRA linear fwd+bwd TFLOP/s (% bf16 MFMA peak); 4-bit GEMV HBM GB/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[3]: LLaMA-65B-shaped block, 7 linears (4x 8192x8192, 2x 8192x22016, "
+                               "1x 22016x8192), NF4+DQ weights, LoRA r=64 alpha=16, 4096 tokens bf16, fwd+bwd",
+                   "tokens": M, "r": r, "pool_blocks": len(pool), "flops_per_step": flops_step,
+                   "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2)},
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": _read_traffic(), "launches": gemm_launches,
+                     "avg_launch_ms": round(gemm_ms / max(1, gemm_launches), 5),
+                     "flops_per_launch": gemm_flops / max(1, gemm_launches)},
+    }
+
+    extra = {}
+    if not args.no_extra:
+        if quant_elems:
+            extra["quantize"] = {"GBps": round(quant_elems * 4.5159 / (t_quant_ms * 1e-3) * 1e-9, 1),
+                                 "frac_hbm": round(quant_elems * 4.5159 / (t_quant_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                                 "elements": quant_elems, "ms": round(t_quant_ms, 3),
+                                 "bytes_per_element": 4.5159}
+        # standalone doubleDequant over the pool (cold weights): 0.5159 B read + 2 B written per element
+        outb = torch.empty(ffn * d, dtype=torch.bfloat16, device=dev)
+        k = [0]
+
+        def deq():
+            blk = pool[k[0] % len(pool)]
+            k[0] += 1
+            for Wq in blk:
+                ql.qlora_nf4_dequant(Wq, out=outb[:Wq.rows * Wq.cols].view(Wq.rows, Wq.cols))
+        t = _time_ms(torch, deq, max(4, len(pool)))
+        el = sum(h * o for h, o in linears)
+        extra["dequant"] = {"GBps": round(el * 2.5159 / (t * 1e-3) * 1e-9, 1),
+                            "frac_hbm": round(el * 2.5159 / (t * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                            "bytes_per_element": 2.5159}
+        del outb
+        # few-token regime (workload configs[4]): forward and input gradient at 1, 4, 16 tokens
+        gemv = {}
+        for m in cfg_few_tokens():
+            Xs = {d: rnd(m, d), ffn: rnd(m, ffn)}
+            Ys = {d: torch.empty(m, d, device=dev, dtype=torch.bfloat16),
+                  ffn: torch.empty(m, ffn, device=dev, dtype=torch.bfloat16)}
+            wsz = max(max(ql.qlora_linear_fwd_sizes(m, h, o, r), ql.qlora_linear_bwd_sizes(m, h, o, r))
+                      for h, o in linears)
+            wss = ws[:wsz]
+            kk = [0]
+
+            def few_fwd():
+                blk = pool[kk[0] % len(pool)]
+                kk[0] += 1
+                for li, (h, o) in enumerate(linears):
+                    ql.qlora_linear_fwd(Xs[h], blk[li], L1[li], L2[li], s, Y=Ys[o], workspace=wss)
+
+            def few_bwd():
+                blk = pool[kk[0] % len(pool)]
+                kk[0] += 1
+                for li, (h, o) in enumerate(linears):
+                    ql.qlora_linear_bwd(Xs[o], None, blk[li], L1[li], L2[li], s, dX=Ys[h], need_dL=False,
+                                        workspace=wss)
+            bytes_block = sum(h * o * 0.51587 for h, o in linears)
+            tf = _time_ms(torch, few_fwd, 2 * len(pool))
+            tb = _time_ms(torch, few_bwd, 2 * len(pool))
+            gemv[f"tokens_{m}"] = {"fwd_GBps": round(bytes_block / (tf * 1e-3) * 1e-9, 1),
+                                   "bwd_dx_GBps": round(bytes_block / (tb * 1e-3) * 1e-9, 1),
+                                   "fwd_frac_hbm": round(bytes_block / (tf * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                                   "bwd_dx_frac_hbm": round(bytes_block / (tb * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                                   "fwd_us_per_linear": round(tf * 1e3 / 7, 2), "bwd_us_per_linear": round(tb * 1e3 / 7, 2)}
+        extra["gemv"] = {"bytes_per_weight": 0.51587, "note": "packed + 8-bit constants + c1 traffic only; weights "
+                         "cycle through the resident pool", **gemv}
+    out["extra"] = extra
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+def cfg_few_tokens():
+    from paper_2305_14314_amd import synth
+    return synth.CONFIGS[4]["M"]
+
+
+if __name__ == "__main__":
+    main()

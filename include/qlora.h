@@ -135,6 +135,15 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
                               uint16_t* dX, uint16_t* dL1, uint16_t* dL2,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid for the benchmark (not part of the method): while enabled, every launch of the
+ * main MFMA GEMM kernel made by qlora_linear_fwd / qlora_linear_bwd is bracketed by a pair of HIP
+ * events recorded on the call's stream.  qlora_profile_gemm_read waits for those events, returns
+ * the summed kernel time in milliseconds, the number of launches and the summed algorithmic FLOPs
+ * (2*M*N*K per launch, adapter segment included), and clears the record.  Not thread-safe; the
+ * events are the only objects the library ever creates. */
+void qlora_profile_gemm(int enable);
+qlora_status qlora_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -3,7 +3,8 @@
 The public functions mirror the C ABI of include/qlora.h one to one.
 """
 from .binding import (NF4Weight, QloraError, lib, qlora_linear_bwd, qlora_linear_bwd_sizes, qlora_linear_fwd,
-                      qlora_linear_fwd_sizes, qlora_nf4_dequant, qlora_nf4_quantize, qlora_nf4_sizes)
+                      qlora_linear_fwd_sizes, qlora_nf4_dequant, qlora_nf4_quantize, qlora_nf4_sizes,
+                      qlora_profile_gemm, qlora_profile_gemm_read)
 
 # the paper-level names used in prose
 nf4_quantize = qlora_nf4_quantize
@@ -11,4 +12,4 @@ nf4_dequant = qlora_nf4_dequant
 
 __all__ = ["NF4Weight", "QloraError", "lib", "qlora_nf4_sizes", "qlora_nf4_quantize", "qlora_nf4_dequant",
            "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd", "qlora_linear_bwd",
-           "nf4_quantize", "nf4_dequant"]
+           "nf4_quantize", "nf4_dequant", "qlora_profile_gemm", "qlora_profile_gemm_read"]

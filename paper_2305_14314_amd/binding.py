@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libqlora_hip.so")
 EXPORTS = [
     "qlora_status_string", "qlora_last_hip_error", "qlora_nf4_sizes", "qlora_nf4_quantize",
     "qlora_nf4_dequant", "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd",
-    "qlora_linear_bwd",
+    "qlora_linear_bwd", "qlora_profile_gemm", "qlora_profile_gemm_read",
 ]
 
 
@@ -58,8 +58,11 @@ def lib():
                                    vp, c_size_t, vp]
     L.qlora_linear_bwd.argtypes = [vp, vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp,
                                    vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_profile_gemm.argtypes = [ctypes.c_int]
+    L.qlora_profile_gemm.restype = None
+    L.qlora_profile_gemm_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64), POINTER(ctypes.c_double)]
     for name in EXPORTS:
-        if name not in ("qlora_status_string", "qlora_last_hip_error"):
+        if name not in ("qlora_status_string", "qlora_last_hip_error", "qlora_profile_gemm"):
             getattr(L, name).restype = c_int32
     _lib = L
     return L
@@ -177,3 +180,15 @@ def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1
                                   _ptr(dX), _ptr(dL1), _ptr(dL2), _ptr(workspace), workspace.numel(),
                                   _stream(stream)))
     return dX, dL1, dL2
+
+
+def qlora_profile_gemm(enable: bool):
+    """Bracket every main-GEMM launch with HIP events on its stream (benchmark aid)."""
+    lib().qlora_profile_gemm(1 if enable else 0)
+
+
+def qlora_profile_gemm_read():
+    """(total kernel ms, launches, total algorithmic FLOPs) since the last read."""
+    ms, n, fl = ctypes.c_double(0), c_int64(0), ctypes.c_double(0)
+    _check(lib().qlora_profile_gemm_read(byref(ms), byref(n), byref(fl)))
+    return ms.value, int(n.value), fl.value

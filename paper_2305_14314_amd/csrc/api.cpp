@@ -5,9 +5,34 @@
 
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "launch.hpp"
 
 namespace {
+
+// ---- optional event bracket around the main GEMM launches (benchmark aid) ----
+struct GemmProfile {
+  bool enabled = false;
+  struct Rec { hipEvent_t start, stop; double flops; };
+  std::vector<Rec> recs;
+} g_prof;
+
+hipError_t gemm_nt_timed(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
+                         const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
+                         uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
+  if (!g_prof.enabled)
+    return qlora::launch_gemm_nt(A0, B0, lda0, ldb0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
+  GemmProfile::Rec r{};
+  if (hipError_t e = hipEventCreate(&r.start)) return e;
+  if (hipError_t e = hipEventCreate(&r.stop)) return e;
+  r.flops = 2.0 * (double)M * (double)N * (double)(K0 + K1);
+  (void)hipEventRecord(r.start, st);
+  const hipError_t e = qlora::launch_gemm_nt(A0, B0, lda0, ldb0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
+  (void)hipEventRecord(r.stop, st);
+  g_prof.recs.push_back(r);
+  return e;
+}
 
 thread_local int g_last_hip_error = 0;
 
@@ -140,6 +165,26 @@ const char* qlora_status_string(qlora_status st) {
 
 int qlora_last_hip_error(void) { return g_last_hip_error; }
 
+void qlora_profile_gemm(int enable) { g_prof.enabled = enable != 0; }
+
+qlora_status qlora_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops) {
+  if (!total_ms || !launches || !total_flops) return QLORA_ERR_NULL;
+  double ms = 0.0, fl = 0.0;
+  hipError_t bad = hipSuccess;
+  for (auto& r : g_prof.recs) {
+    float t = 0.0f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+    if (e != hipSuccess) bad = e;
+    ms += t; fl += r.flops;
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  *total_ms = ms; *launches = (int64_t)g_prof.recs.size(); *total_flops = fl;
+  g_prof.recs.clear();
+  return hip_status(bad);
+}
+
 qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
                              size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
                              size_t* scratch_bytes) {
@@ -216,7 +261,7 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
     QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
   }
   // Y = X What + Ts L2 (Eq. 5): the adapter term is the second K segment of the same accumulators
-  QL_TRY(qlora::launch_gemm_nt(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
+  QL_TRY(gemm_nt_timed(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
                                st));
   return QLORA_OK;
 }
@@ -250,7 +295,7 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
     if (r > 0 && p.L1p) { QL_TRY(qlora::launch_copy_pad(L1, (int)h, r, p.L1p, p.rp, st)); B1 = p.L1p; }
     QL_TRY(qlora::launch_dequant(W, p.Wd, st));
     // dX = dY What^T + Us L1^T
-    QL_TRY(qlora::launch_gemm_nt(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, r > 0 ? p.rp : 0, dX, h, (int)M, (int)h,
+    QL_TRY(gemm_nt_timed(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, r > 0 ? p.rp : 0, dX, h, (int)M, (int)h,
                                  st));
   }
   if (dL1) {
