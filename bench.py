@@ -151,7 +151,7 @@ def main():
     L2 = [rnd(r, o, sd=cfg["sigma_l"]) for h, o in linears]
     Y = {d: torch.empty(M, d, device=dev, dtype=torch.bfloat16), ffn: torch.empty(M, ffn, device=dev, dtype=torch.bfloat16)}
     dX = {d: torch.empty(M, d, device=dev, dtype=torch.bfloat16), ffn: torch.empty(M, ffn, device=dev, dtype=torch.bfloat16)}
-    T = [torch.empty(M, r, device=dev, dtype=torch.bfloat16) for _ in linears]
+    T = [torch.empty(M, 2 * r, device=dev, dtype=torch.bfloat16) for _ in linears]
     dL1 = [torch.empty_like(a) for a in L1]
     dL2 = [torch.empty_like(a) for a in L2]
     ws_bytes = max(max(ql.qlora_linear_fwd_sizes(M, h, o, r), ql.qlora_linear_bwd_sizes(M, h, o, r)) for h, o in linears)

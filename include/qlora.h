@@ -109,8 +109,9 @@ qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, 
  *   Y = X * doubleDequant(Wq) + s * (X * L1) * L2          (bf16 in, fp32 accumulate, bf16 out)
  * X: M x h, L1: h x r, L2: r x o, Y: M x o, with h = Wq->rows and o = Wq->cols.
  * r may be 0 (then L1, L2 may be NULL and the adapter term is skipped); otherwise
- * r must be a multiple of 16 and at most 256.  T_save (M x r bf16, may be NULL)
- * receives T = X * L1 for the backward pass.  Any M >= 1 is accepted: a few
+ * r must be a multiple of 16 and at most 256.  T_save (M x 2r bf16, may be NULL)
+ * receives T = X * L1 for the backward pass as a pair of bf16 matrices side by
+ * side: columns [0, r) hold bf16(T), columns [r, 2r) hold bf16(T - bf16(T)).  Any M >= 1 is accepted: a few
  * tokens (M <= 16) take a bandwidth-bound streaming path, larger M the MFMA
  * GEMM path. */
 qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq,

@@ -145,7 +145,8 @@ def qlora_linear_bwd_sizes(M, h, o, r) -> int:
 
 
 def qlora_linear_fwd(X, Wq: NF4Weight, L1, L2, s, Y=None, T_save=None, workspace=None, stream=None):
-    """Y = X dequant(Wq) + s (X L1) L2.  X (M, h), L1 (h, r), L2 (r, o) bf16 device tensors."""
+    """Y = X dequant(Wq) + s (X L1) L2.  X (M, h), L1 (h, r), L2 (r, o) bf16 device tensors;
+    T_save, if given, is an (M, 2r) bf16 tensor that receives X L1 as a [hi | lo] pair."""
     M, h = X.shape
     o = Wq.cols
     r = 0 if L1 is None else L1.shape[1]

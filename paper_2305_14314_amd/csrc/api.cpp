@@ -93,17 +93,25 @@ struct FwdPlan {
   uint16_t* L2t;     // o x rp    L2^T, rank zero-padded to a multiple of 64
   uint16_t* Ts;      // M x rp    bf16(s * X L1)
   float* part;       // split-K partials of X L1
-  int rp, splits;
+  float* fpart;      // few-token path: split partials of X What
+  int rp, splits, fsplits;
+  bool few;
   size_t bytes;
 };
 FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   FwdPlan p{};
   Carver c(ws);
   p.rp = (r + 63) / 64 * 64;
-  p.Wt = c.take<uint16_t>((size_t)h * o);
+  p.few = M <= qlora::kFewTokens;
+  if (p.few) {
+    p.fsplits = qlora::fewtok_fwd_splits((int)h, (int)o);
+    p.fpart = c.take<float>((size_t)p.fsplits * M * o);
+  } else {
+    p.Wt = c.take<uint16_t>((size_t)h * o);
+  }
   if (r > 0) {
     p.splits = qlora::small_gemm_splits((int)M, r, (int)h);
-    p.L2t = c.take<uint16_t>((size_t)o * p.rp);
+    if (!p.few) p.L2t = c.take<uint16_t>((size_t)o * p.rp);
     p.Ts = c.take<uint16_t>((size_t)M * p.rp);
     p.part = c.take<float>((size_t)p.splits * M * r);
   }
@@ -115,30 +123,38 @@ struct BwdPlan {
   uint16_t* Wd;      // h x o     dequantised weight (K-contiguous for the backward)
   uint16_t* L1p;     // h x rp    L1 with the rank zero-padded (only when r % 64 != 0)
   uint16_t* Us;      // M x rp    bf16(s * dY L2^T)
-  uint16_t* U16;     // M x r     bf16(dY L2^T)
-  uint16_t* T16;     // M x r     bf16(X L1), recomputed when the caller saved none
+  uint16_t* Uhl;     // M x 2r    dY L2^T as a [hi | lo] bf16 pair
+  uint16_t* Thl;     // M x 2r    X L1 as a [hi | lo] pair, recomputed when the caller saved none
   float* part;       // split-K partials, reused by the four skinny products
-  int rp, sU, sT, sL1, sL2;
+  float* fpart;      // few-token path: split partials of dY What^T
+  int rp, sU, sT, sL1, sL2, fsplits;
+  bool few;
   size_t bytes;
 };
 BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   BwdPlan p{};
   Carver c(ws);
   p.rp = (r + 63) / 64 * 64;
-  p.Wd = c.take<uint16_t>((size_t)h * o);
+  p.few = M <= qlora::kFewTokens;
+  if (p.few) {
+    p.fsplits = qlora::fewtok_bwd_splits((int)h, (int)o);
+    p.fpart = c.take<float>((size_t)p.fsplits * M * h);
+  } else {
+    p.Wd = c.take<uint16_t>((size_t)h * o);
+  }
   if (r > 0) {
     p.sU = qlora::small_gemm_splits((int)M, r, (int)o);
     p.sT = qlora::small_gemm_splits((int)M, r, (int)h);
-    p.sL1 = qlora::small_gemm_splits((int)h, r, (int)M);
-    p.sL2 = qlora::small_gemm_splits(r, (int)o, (int)M);
+    p.sL1 = qlora::small_gemm_splits((int)h, 2 * r, (int)M);
+    p.sL2 = qlora::small_gemm_splits(2 * r, (int)o, (int)M);
     size_t pe = (size_t)p.sU * M * r;
     if ((size_t)p.sT * M * r > pe) pe = (size_t)p.sT * M * r;
-    if ((size_t)p.sL1 * h * r > pe) pe = (size_t)p.sL1 * h * r;
-    if ((size_t)p.sL2 * r * o > pe) pe = (size_t)p.sL2 * r * o;
-    p.L1p = (r % 64) ? c.take<uint16_t>((size_t)h * p.rp) : nullptr;
+    if ((size_t)p.sL1 * h * 2 * r > pe) pe = (size_t)p.sL1 * h * 2 * r;
+    if ((size_t)p.sL2 * 2 * r * o > pe) pe = (size_t)p.sL2 * 2 * r * o;
+    p.L1p = (r % 64 && !p.few) ? c.take<uint16_t>((size_t)h * p.rp) : nullptr;
     p.Us = c.take<uint16_t>((size_t)M * p.rp);
-    p.U16 = c.take<uint16_t>((size_t)M * r);
-    p.T16 = c.take<uint16_t>((size_t)M * r);
+    p.Uhl = c.take<uint16_t>((size_t)M * 2 * r);
+    p.Thl = c.take<uint16_t>((size_t)M * 2 * r);
     p.part = c.take<float>(pe);
   }
   p.bytes = c.off;
@@ -253,13 +269,19 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   hipStream_t st = (hipStream_t)hip_stream;
   const qlora::NF4Dev W = to_dev(Wq);
 
-  QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
   if (r > 0) {
-    // T = X L1 (Eq. 3): split-K partials, then T_save = bf16(T) and Ts = bf16(s T), rank zero-padded
+    // T = X L1 (Eq. 3): split-K partials, then Ts = bf16(s T) (rank zero-padded) and T_save = [hi | lo] of T
     QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.splits, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, r, r, 1.0f, st));
-    QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, 0, p.Ts, p.rp, p.rp, s, T_save, st));
   }
+  if (p.few) {
+    // few tokens: stream the packed weight once, dequantise in registers, add the adapter term in the finalize
+    QL_TRY(qlora::launch_fewtok_fwd(X, (int)M, W, p.fpart, p.fsplits, st));
+    QL_TRY(qlora::launch_fewtok_finalize(p.fpart, p.fsplits, (int)M, (int)o, p.Ts, p.rp, r, L2, o, 1, Y, st));
+    return QLORA_OK;
+  }
+  QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
+  if (r > 0) QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
   // Y = X What + Ts L2 (Eq. 5): the adapter term is the second K segment of the same accumulators
   QL_TRY(gemm_nt_timed(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
                                st));
@@ -286,11 +308,14 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
   const qlora::NF4Dev W = to_dev(Wq);
 
   if (r > 0 && (dX || dL1)) {
-    // U = dY L2^T: U16 = bf16(U) feeds dL1, Us = bf16(s U) feeds the adapter segment of dX
+    // U = dY L2^T: Us = bf16(s U) feeds the adapter segment of dX, the [hi | lo] pair of U feeds dL1
     QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, (int)M, r, (int)o, p.part, p.sU, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, p.Us, p.rp, p.rp, s, p.U16, r, r, 1.0f, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, 0, p.Us, p.rp, p.rp, s, p.Uhl, st));
   }
-  if (dX) {
+  if (dX && p.few) {
+    QL_TRY(qlora::launch_fewtok_bwd(dY, (int)M, W, p.fpart, p.fsplits, st));
+    QL_TRY(qlora::launch_fewtok_finalize(p.fpart, p.fsplits, (int)M, (int)h, p.Us, p.rp, r, L1, 1, r, dX, st));
+  } else if (dX) {
     const uint16_t* B1 = L1;
     if (r > 0 && p.L1p) { QL_TRY(qlora::launch_copy_pad(L1, (int)h, r, p.L1p, p.rp, st)); B1 = p.L1p; }
     QL_TRY(qlora::launch_dequant(W, p.Wd, st));
@@ -299,20 +324,20 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
                                  st));
   }
   if (dL1) {
-    // dL1 = s X^T U: contraction over the tokens, both operands stored token-major
-    QL_TRY(qlora::launch_small_gemm(X, h, true, p.U16, r, true, (int)h, r, (int)M, p.part, p.sL1, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, r, dL1, r, r, s, nullptr, 0, 0, 0.0f, st));
+    // dL1 = s X^T U: contraction over the tokens, both operands stored token-major; U enters as hi + lo
+    QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * r, true, (int)h, 2 * r, (int)M, p.part, p.sL1, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, 2 * r, 1, dL1, r, r, s, nullptr, st));
   }
   if (dL2) {
     const uint16_t* T = T_saved;
     if (!T) {                                               // gradient checkpointing: recompute T = X L1
       QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.sT, st));
-      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, p.T16, r, r, 1.0f, nullptr, 0, 0, 0.0f, st));
-      T = p.T16;
+      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, 0, nullptr, 0, 0, 0.0f, p.Thl, st));
+      T = p.Thl;
     }
-    // dL2 = s T^T dY
-    QL_TRY(qlora::launch_small_gemm(T, r, true, dY, o, true, r, (int)o, (int)M, p.part, p.sL2, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, r, (int)o, dL2, o, (int)o, s, nullptr, 0, 0, 0.0f, st));
+    // dL2 = s T^T dY with T as hi + lo rows
+    QL_TRY(qlora::launch_small_gemm(T, 2 * r, true, dY, o, true, 2 * r, (int)o, (int)M, p.part, p.sL2, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, 2 * r, (int)o, 2, dL2, o, (int)o, s, nullptr, st));
   }
   return QLORA_OK;
 }

@@ -8,80 +8,78 @@
 // or L1): the adapter rides as extra K-steps of the same accumulators, so the output is rounded
 // to bf16 exactly once.
 //
-// Tiling for gfx950: 256 x 256 output tile per workgroup of 4 waves (2 x 2), each wave 128 x 128
-// as 4 x 4 MFMA 32x32x16 tiles (256 fp32 accumulators per lane), K-step 64.  Tiles are fetched
-// with global_load_lds_dwordx4 (no VGPR staging) into two LDS stages of 2 x 32 KB; the 16-byte
-// chunks of each 128-byte row are XOR-swizzled with the row index so ds_read_b128 of MFMA
-// fragments is bank-conflict free.  Workgroup ids are remapped so that the 32 tiles resident on
-// one XCD form a compact patch and share operand tiles in that XCD's L2.
+// Design for gfx950 (256 CUs in 8 XCDs, 160 KB LDS, MFMA 32x32x16 bf16 = 32 cycles per SIMD):
+//  * 256 x 256 output tile per workgroup of 4 waves (2 x 2), each wave 128 x 128 as 4 x 4 MFMA
+//    tiles: 256 fp32 accumulators per lane (AGPRs), half an LDS fragment read per MFMA.
+//  * K-step 32, four LDS stages of (A tile 16 KB, B tile 16 KB).  Tiles arrive by
+//    global_load_lds_dwordx4 (no VGPR staging).  One barrier per K-step, placed in the MIDDLE of
+//    the step: it publishes stage k+1 (requested two steps earlier) and frees the stage of step
+//    k-1 for the DMA of step k+3, so fragment reads of the next step never wait at a barrier and
+//    the MFMA stream continues across step boundaries.
+//  * The 8 DMA instructions of a step are spread one per row of 4 MFMAs (waves issue in order: a
+//    burst of DMAs would stall the MFMA stream behind the texture-address FIFO).
+//  * Fragment reads are software-pipelined one 16-wide sub-step ahead (the compiler is left free
+//    to place them among the MFMAs of the sub-step: pinning two reads per row of 4 MFMAs with
+//    scheduling barriers measured 15 % slower).  They are issued through inline asm with hand-placed s_waitcnt: the compiler's
+//    automatic wait insertion cannot tell a DMA into one stage from a read of another across the
+//    loop back-edge and would drain all DMAs every iteration.
+//  * LDS rows are 64 bytes (32 k); the four 16-byte chunks of row r sit at chunk ^ ((r >> 2) & 3).
+//    LDS has 64 banks: a ds_read_b128 is served 16 lanes (256 bytes) per cycle, and 16 consecutive
+//    rows then cover all 16 sixteen-byte bank groups (measured 225 B/clk/CU against 114 for the
+//    8-lane pattern that would suit a 32-bank LDS).
+//  * Workgroup ids are remapped so each XCD (which receives every 8th id) works on a contiguous
+//    range of the tile order, and tiles are ordered in groups of GM tile-rows, so the 32 tiles
+//    resident on an XCD share A and B tiles in that XCD's L2.
+//  * Rows beyond M / N are clamped for loads and masked at the store; steps beyond the last
+//    re-fetch the last tile into a free stage, which keeps the loop body free of branches.
 #include "common.hpp"
 #include "launch.hpp"
 
 namespace qlora {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kGemmThreads = 256;
-constexpr int kTileBytes = BM * BK * 2;                     // 32 KB per operand per stage
+namespace {
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
+constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
+constexpr int kGemmThreads = 256;
+constexpr int kOpBytes = BM * BK * 2;                       // 16 KB per operand per stage
+constexpr int GM = 4;                                       // tile-rows per raster group
+
+typedef __attribute__((address_space(3))) char lchar;
 
 struct GemmArgs {
-  const uint16_t* A0; const uint16_t* B0; int64_t lda0, ldb0; int K0;
-  const uint16_t* A1; const uint16_t* B1; int64_t lda1, ldb1; int K1;
+  const uint16_t* A0; const uint16_t* B0; int64_t lda0, ldb0; int KT0;   // KT = K / BK
+  const uint16_t* A1; const uint16_t* B1; int64_t lda1, ldb1; int KT1;
   uint16_t* C; int64_t ldc;
-  int M, N;
-  int tiles_m, tiles_n;
+  int M, N, tiles_m, tiles_n;
 };
 
-// One operand tile (256 rows x 64 k) -> LDS.  Wave w, instruction j fills LDS rows (4j + w) * 8 .. + 7;
-// lane l lands at row l / 8, physical chunk l % 8, and therefore fetches logical chunk (l % 8) ^ (l / 8).
-__device__ __forceinline__ void load_tile(const uint16_t* __restrict__ base, const int64_t* row_off, int k0,
-                                          char __attribute__((address_space(3)))* lds, int wave, int lane) {
-  const int chunk = (lane & 7) ^ (lane >> 3);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint16_t* g = base + row_off[j] + k0 + chunk * 8;
-    __builtin_amdgcn_global_load_lds(g, (lds_ptr_t)(lds + (4 * j + wave) * 1024), 16, 0, 0);
-  }
+struct Frags { bf16x8 a[4], b[4]; };
+
+// DMA instruction j of an operand tile: wave w fills LDS rows (4j + w) * 16 .. + 15 of the stage;
+// lane l lands at row l / 4, physical chunk l % 4 (the caller's pointer already selects the
+// logical chunk (l % 4) ^ ((l >> 4) & 3) of that row).
+__device__ __forceinline__ void dma16(const uint16_t* g, lchar* stage_tile, int j, int wave) {
+  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)(stage_tile + (4 * j + wave) * 1024),
+                                   16, 0, 0);
 }
 
-__device__ __forceinline__ bf16x8 read_frag(const char __attribute__((address_space(3)))* lds, int row, int chunk) {
-  const int phys = chunk ^ (row & 7);
-  return *(const bf16x8 __attribute__((address_space(3)))*)(lds + row * 128 + phys * 16);
-}
-
-__device__ __forceinline__ void compute_stage(const char __attribute__((address_space(3)))* sA,
-                                              const char __attribute__((address_space(3)))* sB,
-                                              int a_row, int b_row, int half, f32x16 (&acc)[4][4]) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    bf16x8 a[4], b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] = read_frag(sA, a_row + 32 * i, 2 * kk + half);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) b[i] = read_frag(sB, b_row + 32 * i, 2 * kk + half);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < 4; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-  }
-}
+#define QL_LDS_READ(dst, addr) asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr))
+#define QL_WAIT_FRAGS(f)                                                                                    \
+  asm volatile("s_waitcnt lgkmcnt(0)"                                                                       \
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]),       \
+                 "+v"(f.b[2]), "+v"(f.b[3]))
+#define QL_MMA_ROW(f, i)                                                                                    \
+  _Pragma("unroll") for (int ni_ = 0; ni_ < 4; ++ni_)                                                       \
+      acc[i][ni_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[ni_], acc[i][ni_], 0, 0, 0);
 
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p) {
-  // separate objects per stage so the compiler can tell a DMA into one stage from reads of the other
-  __shared__ __attribute__((aligned(1024))) char sA0[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char sA1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char sB0[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char sB1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char smem[NST * 2 * kOpBytes];       // 128 KB
+  lchar* const lds = (lchar*)smem;
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
 
-  // ---- workgroup id -> output tile, XCD-aware -------------------------------------------------
-  // Hardware deals consecutive workgroup ids round-robin to the 8 XCDs.  Give each XCD a
-  // contiguous range of the tile order, and order tiles in groups of 4 tile-rows so that the
-  // tiles resident together share A and B tiles.
+  // ---- workgroup id -> output tile -------------------------------------------------------------
   const int n_tiles = p.tiles_m * p.tiles_n;
   int pid = blockIdx.x;
   {
@@ -89,29 +87,56 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
     const int q = n_tiles >> 3, rem = n_tiles & 7;
     pid = (xcd < rem) ? xcd * (q + 1) + local : rem * (q + 1) + (xcd - rem) * q + local;
   }
-  constexpr int GM = 4;
   const int per_group = GM * p.tiles_n;
   const int group = pid / per_group;
   const int first_m = group * GM;
   const int gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
   const int in_group = pid - group * per_group;
-  const int tile_m = first_m + in_group % gsz;
-  const int tile_n = in_group / gsz;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
 
-  // ---- per-lane global row offsets for the 8 load instructions per operand ---------------------
-  int a_rows[8], b_rows[8];
+  // ---- per-lane global pointers of the 4 + 4 DMA instructions of a step ------------------------
+  const int KT = p.KT0 + p.KT1;
+  const int dma_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+  int a_rows[4], b_rows[4];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int r = (4 * j + wave) * 8 + (lane >> 3);
-    int ra = m0 + r; if (ra > p.M - 1) ra = p.M - 1;        // clamp: padded rows are never stored
-    int rb = n0 + r; if (rb > p.N - 1) rb = p.N - 1;
-    a_rows[j] = ra; b_rows[j] = rb;
+  for (int j = 0; j < 4; ++j) {
+    const int r = (4 * j + wave) * 16 + (lane >> 2);
+    a_rows[j] = (m0 + r < p.M) ? m0 + r : p.M - 1;          // clamp: padded rows are never stored
+    b_rows[j] = (n0 + r < p.N) ? n0 + r : p.N - 1;
   }
-  int64_t a_off[8], b_off[8];
+  const uint16_t* pa[4];
+  const uint16_t* pb[4];
+  auto seek = [&](const uint16_t* (&ptr)[4], const int (&rows)[4], int k, bool is_a) {
+    // pointers of step k (clamped to the last step); K segment 0 first, then segment 1
+    const int kc = k < KT ? k : KT - 1;
+    const bool s0 = kc < p.KT0;
+    const uint16_t* base = is_a ? (s0 ? p.A0 : p.A1) : (s0 ? p.B0 : p.B1);
+    const int64_t ld = is_a ? (s0 ? p.lda0 : p.lda1) : (s0 ? p.ldb0 : p.ldb1);
+    const int kofs = (s0 ? kc : kc - p.KT0) * BK + dma_chunk;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ptr[j] = base + (int64_t)rows[j] * ld + kofs;
+  };
+  // after issuing step k: move to step k + 1 (one add per pointer except at the segment switch)
+  auto advance = [&](const uint16_t* (&ptr)[4], const int (&rows)[4], int k, bool is_a) {
+    if (k + 1 >= KT) return;                                // stay: the tail re-fetches the last tile
+    if (k + 1 == p.KT0) { seek(ptr, rows, k + 1, is_a); return; }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ptr[j] += BK;
+  };
 
+  // ---- per-lane LDS addresses of the fragments of the two 16-wide sub-steps ---------------------
   const int wm = wave >> 1, wn = wave & 1;
   const int a_row = wm * 128 + (lane & 31), b_row = wn * 128 + (lane & 31), half = lane >> 5;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+  uint32_t offA[2][4], offB[2][4];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ra = a_row + 32 * i, rb = b_row + 32 * i;
+      offA[kk][i] = lds0 + ra * 64 + (((2 * kk + half) ^ ((ra >> 2) & 3)) * 16);
+      offB[kk][i] = lds0 + kOpBytes + rb * 64 + (((2 * kk + half) ^ ((rb >> 2) & 3)) * 16);
+    }
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -121,44 +146,68 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  auto sA0p = (char __attribute__((address_space(3)))*)sA0;
-  auto sA1p = (char __attribute__((address_space(3)))*)sA1;
-  auto sB0p = (char __attribute__((address_space(3)))*)sB0;
-  auto sB1p = (char __attribute__((address_space(3)))*)sB1;
-
-#pragma unroll 1
-  for (int seg = 0; seg < 2; ++seg) {
-    const uint16_t* A = seg ? p.A1 : p.A0;
-    const uint16_t* B = seg ? p.B1 : p.B0;
-    const int64_t lda = seg ? p.lda1 : p.lda0, ldb = seg ? p.ldb1 : p.ldb0;
-    const int KT = (seg ? p.K1 : p.K0) / BK;
-    if (KT == 0) continue;
+  // ---- prologue: stages 0 and 1 complete, the A half of stage 2 ---------------------------------
+  // Steady state: the B tile of step k+2 goes out during the first half of step k, the A tile of
+  // step k+3 during the second half, each DMA instruction behind one row of MFMAs.
+  seek(pa, a_rows, 0, true);
+  seek(pb, b_rows, 0, false);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { a_off[j] = a_rows[j] * lda; b_off[j] = b_rows[j] * ldb; }
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma16(pa[j], lds + s * 2 * kOpBytes, j, wave);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma16(pb[j], lds + s * 2 * kOpBytes + kOpBytes, j, wave);
+    advance(pa, a_rows, s, true);
+    advance(pb, b_rows, s, false);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dma16(pa[j], lds + 2 * 2 * kOpBytes, j, wave);
+  advance(pa, a_rows, 2, true);
+  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 landed; stage 1 and half of stage 2 in flight
+  asm volatile("s_barrier" ::: "memory");
 
-    __syncthreads();                                        // previous segment's reads are done
-    load_tile(A, a_off, 0, sA0p, wave, lane);
-    load_tile(B, b_off, 0, sB0p, wave, lane);
-#pragma unroll 1
-    for (int kt = 0; kt < KT; kt += 2) {
-      __syncthreads();                                      // stage 0 has landed; stage 1 is free
-      if (kt + 1 < KT) {
-        load_tile(A, a_off, (kt + 1) * BK, sA1p, wave, lane);
-        load_tile(B, b_off, (kt + 1) * BK, sB1p, wave, lane);
-      }
-      compute_stage(sA0p, sB0p, a_row, b_row, half, acc);
-      if (kt + 1 < KT) {
-        __syncthreads();                                    // stage 1 has landed; stage 0 is free
-        if (kt + 2 < KT) {
-          load_tile(A, a_off, (kt + 2) * BK, sA0p, wave, lane);
-          load_tile(B, b_off, (kt + 2) * BK, sB0p, wave, lane);
-        }
-        compute_stage(sA1p, sB1p, a_row, b_row, half, acc);
-      }
-    }
+  Frags f0, f1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { QL_LDS_READ(f0.a[i], offA[0][i]); QL_LDS_READ(f0.b[i], offB[0][i]); }
+
+  // One 16-wide sub-step: multiply fragments `cur` while fetching fragments `nxt` (stage `st`,
+  // sub-step kk) and issuing the 4 DMA instructions `ptr` into tile `dst`.
+#define QL_SUBSTEP(cur, nxt, st, kk, ptr, dst)                                                              \
+  {                                                                                                         \
+    const uint32_t sb_ = (st) * 2 * kOpBytes;                                                               \
+    QL_WAIT_FRAGS(cur);                                                                                     \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
+      QL_LDS_READ(nxt.a[i_], offA[kk][i_] + sb_);                                                           \
+      QL_LDS_READ(nxt.b[i_], offB[kk][i_] + sb_);                                                           \
+      QL_MMA_ROW(cur, i_)                                                                                   \
+      dma16(ptr[i_], dst, i_, wave);                                                                        \
+    }                                                                                                       \
+  }
+  // One K-step; ST is the (static) stage of step k.
+#define QL_STEP(ST)                                                                                         \
+  {                                                                                                         \
+    QL_SUBSTEP(f0, f1, ST, 1, pb, lds + ((ST + 2) & 3) * 2 * kOpBytes + kOpBytes)   /* B of step k+2 */     \
+    advance(pb, b_rows, k + 2, false);                                                                      \
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");          /* stage k+1 has landed (this wave's part) */ \
+    asm volatile("s_barrier" ::: "memory");                   /* ... and everyone's; stage k-1 is free */   \
+    QL_SUBSTEP(f1, f0, (ST + 1) & 3, 0, pa, lds + ((ST + 3) & 3) * 2 * kOpBytes)    /* A of step k+3 */     \
+    advance(pa, a_rows, k + 3, true);                                                                       \
+    ++k;                                                                                                    \
   }
 
-  // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ---------
+  int k = 0;
+#pragma unroll 1
+  while (k + 4 <= KT) {
+    QL_STEP(0) QL_STEP(1) QL_STEP(2) QL_STEP(3)
+  }
+  if (k < KT) QL_STEP(0)
+  if (k < KT) QL_STEP(1)
+  if (k < KT) QL_STEP(2)
+#undef QL_STEP
+#undef QL_SUBSTEP
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // drain the tail's redundant loads and reads
+
+  // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
 #pragma unroll
   for (int ni = 0; ni < 4; ++ni) {
     const int n = n0 + wn * 128 + ni * 32 + (lane & 31);
@@ -174,12 +223,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
   }
 }
 
+}  // namespace
+
 hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
                           const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                           uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
   GemmArgs a;
-  a.A0 = A0; a.B0 = B0; a.lda0 = lda0; a.ldb0 = ldb0; a.K0 = K0;
-  a.A1 = A1; a.B1 = B1; a.lda1 = lda1; a.ldb1 = ldb1; a.K1 = K1;
+  a.A0 = A0; a.B0 = B0; a.lda0 = lda0; a.ldb0 = ldb0; a.KT0 = K0 / BK;
+  a.A1 = A1; a.B1 = B1; a.lda1 = lda1; a.ldb1 = ldb1; a.KT1 = K1 / BK;
   a.C = C; a.ldc = ldc; a.M = M; a.N = N;
   a.tiles_m = (M + BM - 1) / BM;
   a.tiles_n = (N + BN - 1) / BN;

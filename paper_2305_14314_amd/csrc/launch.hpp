@@ -36,12 +36,25 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
 int small_gemm_splits(int I, int J, int K);
 hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb,
                              int I, int J, int K, float* part, int splits, hipStream_t st);
-//   out0 = bf16(scale0 * sum of splits), w0 columns written (zeros beyond J); out1 likewise; either may be NULL.
-hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
-                                 float scale0, uint16_t* out1, int64_t ld1, int w1, float scale1, hipStream_t st);
+//   Sums the splits (fold = 1 adds column j + J/2 to j, fold = 2 adds row i + I/2 to i), then writes
+//   out0 = bf16(scale0 * sum) (w0 columns, zeros beyond) and/or hl = [bf16(sum) | bf16(sum - bf16(sum))].
+hipError_t launch_small_finalize(const float* part, int splits, int I, int J, int fold, uint16_t* out0, int64_t ld0,
+                                 int w0, float scale0, uint16_t* hl, hipStream_t st);
 //   dst[c][r] = src[r][c], rows r >= R zero-filled up to Rp.
 hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
                                 hipStream_t st);
 hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st);
+
+// fewtok.hip: few-token (M <= 16) streaming path; fp32 split partials, then one finalize per output.
+constexpr int kFewTokens = 16;
+int fewtok_fwd_splits(int h, int o);
+int fewtok_bwd_splits(int h, int o);
+//   part[split][M][o] = X (M x h) * dequant(W) over the split's rows
+hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* part, int splits, hipStream_t st);
+//   part[split][M][h] = dY (M x o) * dequant(W)^T over the split's columns
+hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, hipStream_t st);
+//   out[m][n] = bf16(sum of splits + sum_j A[m][j] * Bmat[j * ldb_j + n * ldb_n]); A is M x rp bf16, j < r
+hipError_t launch_fewtok_finalize(const float* part, int splits, int M, int N, const uint16_t* A, int rp, int r,
+                                  const uint16_t* Bmat, int64_t ldb_j, int64_t ldb_n, uint16_t* out, hipStream_t st);
 
 }  // namespace qlora

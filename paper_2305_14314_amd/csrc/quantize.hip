@@ -55,45 +55,58 @@ __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
 }
 
 // Single wave.  sum = SUM_e bins[e] * 2^(e-1) in units of 2^-149, as 12 x 32-bit limbs;
-// mean = round_to_nearest_even_fp32(sum / n).
+// mean = round_to_nearest_even_fp32(sum / n).  Only the non-empty bins (found with wave ballots)
+// and the non-zero limbs are visited, so the serial part is a few dozen operations.
 __global__ __launch_bounds__(64) void dq_mean_kernel(const unsigned long long* __restrict__ bins,
                                                      uint32_t n, float* __restrict__ mean_out) {
   __shared__ unsigned long long lb[256];
-  for (int i = threadIdx.x; i < 256; i += 64) lb[i] = bins[i];
+  unsigned long long present[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const unsigned long long v = bins[q * 64 + threadIdx.x];
+    lb[q * 64 + threadIdx.x] = v;
+    present[q] = __ballot(v != 0ull);
+  }
   __syncthreads();
   if (threadIdx.x != 0) return;
 
   constexpr int L = 12;
   uint32_t acc[L];
   for (int k = 0; k < L; ++k) acc[k] = 0;
-  for (int e = 1; e < 255; ++e) {
-    const unsigned long long b = lb[e];
-    if (b == 0ull) continue;
-    const int sh = e - 1, limb = sh >> 5, off = sh & 31;
-    // b < 2^56; b << off spans at most three limbs
-    const uint32_t p0 = (uint32_t)(b << off);
-    const unsigned long long hi = off ? (b >> (32 - off)) : (b >> 32);
-    const uint32_t p1 = (uint32_t)hi, p2 = (uint32_t)(hi >> 32);
-    const uint32_t parts[3] = {p0, p1, p2};
-    unsigned long long carry = 0;
-    for (int k = 0; k < L - limb; ++k) {
-      const unsigned long long t = (unsigned long long)acc[limb + k] + (k < 3 ? parts[k] : 0u) + carry;
-      acc[limb + k] = (uint32_t)t;
-      carry = t >> 32;
-      if (k >= 2 && carry == 0) break;
+  int top_limb = -1;
+  for (int q = 0; q < 4; ++q) {
+    unsigned long long mask = present[q];
+    while (mask) {
+      const int e = q * 64 + __builtin_ctzll(mask);
+      mask &= mask - 1;
+      if (e < 1 || e > 254) continue;                       // exponent 255 (inf/nan) never occurs: inputs are finite
+      const unsigned long long b = lb[e];
+      const int sh = e - 1, limb = sh >> 5, off = sh & 31;
+      // b < 2^56; b << off spans at most three limbs
+      const uint32_t p0 = (uint32_t)(b << off);
+      const unsigned long long hi = off ? (b >> (32 - off)) : (b >> 32);
+      const uint32_t parts[3] = {p0, (uint32_t)hi, (uint32_t)(hi >> 32)};
+      unsigned long long carry = 0;
+      for (int k = 0; k < L - limb; ++k) {
+        const unsigned long long t = (unsigned long long)acc[limb + k] + (k < 3 ? parts[k] : 0u) + carry;
+        acc[limb + k] = (uint32_t)t;
+        carry = t >> 32;
+        if (t && limb + k > top_limb) top_limb = limb + k;
+        if (k >= 2 && carry == 0) break;
+      }
     }
   }
   uint32_t q[L];
+  for (int k = 0; k < L; ++k) q[k] = 0;
   unsigned long long rem = 0;
-  for (int k = L - 1; k >= 0; --k) {
+  for (int k = top_limb; k >= 0; --k) {                      // long division by n < 2^32
     const unsigned long long cur = (rem << 32) | acc[k];
     q[k] = (uint32_t)(cur / n);
     rem = cur % n;
   }
   int top = -1;
-  for (int k = L - 1; k >= 0; --k)
+  for (int k = top_limb; k >= 0; --k)
     if (q[k]) { top = k * 32 + 31 - __builtin_clz(q[k]); break; }
-  if (top < 0 && rem == 0) { *mean_out = 0.0f; return; }
   // keep the 24 leading bits of q (all of q if it is shorter), round on the rest and on rem/n
   const int drop = top >= 24 ? top - 23 : 0;
   auto bit = [&](int i) -> uint32_t { return (q[i >> 5] >> (i & 31)) & 1u; };
@@ -108,7 +121,7 @@ __global__ __launch_bounds__(64) void dq_mean_kernel(const unsigned long long* _
     sticky = rem != 0;
     for (int i = drop - 2; i >= 0 && !sticky; --i) sticky = bit(i) != 0;
   }
-  if (half && (sticky || (kept & 1u))) ++kept;              // kept <= 2^24, exact in fp32
+  if (half && (sticky || (kept & 1u))) ++kept;              // kept <= 2^24
   // result = kept * 2^(drop - 149) with kept <= 2^24: with drop = 0 the integer is the bit pattern itself
   // (subnormals and the first binades); each further dropped bit raises the exponent field by one.
   *mean_out = __builtin_bit_cast(float, kept + ((uint32_t)drop << 23));

@@ -125,20 +125,38 @@ __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallAr
   }
 }
 
-// out0[i][j] = bf16(scale0 * sum_s part[s][i][j]) for j < J, 0 for J <= j < ld-padded width;
-// out1 likewise with scale1 (either may be NULL).  Fixed summation order: deterministic.
-__global__ void small_finalize_kernel(const float* __restrict__ part, int splits, int I, int J,
+// Reduces the split partials in a fixed order (deterministic) and writes up to two bf16 outputs.
+//   sum(i, j) = sum over splits of part[s][i][j], folded first if asked:
+//     fold = 1: columns j and j + J/2 are added (the B operand was a [hi | lo] pair), J_eff = J / 2
+//     fold = 2: rows i and i + I/2 are added    (the A operand was a [hi | lo] pair), I_eff = I / 2
+//   out0[i][j] = bf16(scale0 * sum) for j < J_eff, zero for J_eff <= j < w0            (row stride ld0)
+//   hl[i][j]   = bf16(sum),  hl[i][J_eff + j] = bf16(sum - hl[i][j])                   (row stride 2 * J_eff)
+// The hi/lo pair carries 16 significant bits of an intermediate (T = X L1 or U = dY L2^T) into the
+// bf16 MFMA products that form the adapter gradients.
+__global__ void small_finalize_kernel(const float* __restrict__ part, int splits, int I, int J, int fold,
                                       uint16_t* __restrict__ out0, int64_t ld0, int w0, float scale0,
-                                      uint16_t* __restrict__ out1, int64_t ld1, int w1, float scale1) {
-  const int wmax = (w0 > w1) ? w0 : w1;
-  const int64_t total = (int64_t)I * wmax;
+                                      uint16_t* __restrict__ hl) {
+  const int Ie = (fold == 2) ? I / 2 : I, Je = (fold == 1) ? J / 2 : J;
+  const int wmax = (out0 && w0 > Je) ? w0 : Je;
+  const int64_t total = (int64_t)Ie * wmax;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
     const int i = (int)(e / wmax), j = (int)(e % wmax);
     float s = 0.0f;
-    if (j < J)
-      for (int sp = 0; sp < splits; ++sp) s += part[((int64_t)sp * I + i) * J + j];
+    if (j < Je) {
+#pragma unroll 8
+      for (int sp = 0; sp < splits; ++sp) {
+        const float* ps = part + (int64_t)sp * I * J;
+        s += ps[(int64_t)i * J + j];
+        if (fold == 1) s += ps[(int64_t)i * J + j + Je];
+        if (fold == 2) s += ps[(int64_t)(i + Ie) * J + j];
+      }
+    }
     if (out0 && j < w0) out0[(int64_t)i * ld0 + j] = bf16_bits(s * scale0);
-    if (out1 && j < w1) out1[(int64_t)i * ld1 + j] = bf16_bits(s * scale1);
+    if (hl && j < Je) {
+      const uint16_t hi = bf16_bits(s);
+      hl[(int64_t)i * 2 * Je + j] = hi;
+      hl[(int64_t)i * 2 * Je + Je + j] = bf16_bits(s - bf16_lo_to_f32(hi));
+    }
   }
 }
 
@@ -192,13 +210,14 @@ hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint
   return hipGetLastError();
 }
 
-hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
-                                 float scale0, uint16_t* out1, int64_t ld1, int w1, float scale1, hipStream_t st) {
-  const int wmax = (w0 > w1) ? w0 : w1;
-  int64_t blocks = ((int64_t)I * wmax + 255) / 256;
+hipError_t launch_small_finalize(const float* part, int splits, int I, int J, int fold, uint16_t* out0, int64_t ld0,
+                                 int w0, float scale0, uint16_t* hl, hipStream_t st) {
+  const int Ie = (fold == 2) ? I / 2 : I, Je = (fold == 1) ? J / 2 : J;
+  const int wmax = (out0 && w0 > Je) ? w0 : Je;
+  int64_t blocks = ((int64_t)Ie * wmax + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, out0, ld0,
-                     w0, scale0, out1, ld1, w1, scale1);
+  hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, fold, out0,
+                     ld0, w0, scale0, hl);
   return hipGetLastError();
 }
 

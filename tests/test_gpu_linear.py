@@ -11,12 +11,20 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
-def _check(got_bits, ref, tag):
+def _check(got_bits, ref, tag, few_terms=False):
+    """max|err| <= 2e-2 * rms(ref).  few_terms: the output is a sum of only a handful of products
+    (adapter gradients at a few tokens), its distribution is heavy-tailed and the largest entries'
+    own bf16 rounding (2^-9 relative) can exceed 2e-2 * rms; such entries must then be within one
+    bf16 rounding step of the reference instead."""
     got = bits_f64(got_bits).reshape(ref.shape)
     rms = np.sqrt((ref ** 2).mean())
-    err = np.abs(got - ref).max()
-    print(f"  {tag}: max|err|/rms = {err / rms:.4f}", flush=True)
+    aerr = np.abs(got - ref)
+    err = aerr.max()
+    print(f"  {tag}: max|err|/rms = {err / rms if rms > 0 else 0.0:.4f}", flush=True)
     assert np.isfinite(got).all(), tag
+    if few_terms:
+        assert np.all(aerr <= np.maximum(TOL * rms, 2.0 ** -8 * np.abs(ref))), tag
+        return
     assert err <= TOL * rms, f"{tag}: max|err| {err:.4g} > {TOL} * rms {rms:.4g}"
 
 
@@ -33,7 +41,7 @@ def _run_case(oracle, ql, L, tag, with_lora=True, rows=None):
     hL1 = L["L1"] if with_lora else None
     hL2 = L["L2"] if with_lora else None
     print(f"case {tag}: M={M} h={h} o={o} r={r if with_lora else 0}", flush=True)
-    T = torch.empty((M, r), dtype=torch.bfloat16, device="cuda") if with_lora else None
+    T = torch.empty((M, 2 * r), dtype=torch.bfloat16, device="cuda") if with_lora else None
     Y = ql.qlora_linear_fwd(X, Wq, L1, L2, s, T_save=T)
     dX, dL1, dL2 = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s, T_saved=T)
     torch.cuda.synchronize()
@@ -43,12 +51,12 @@ def _run_case(oracle, ql, L, tag, with_lora=True, rows=None):
            oracle.linear_bwd_dx(L["dY"], What, hL1, hL2, s, rows=rows), f"{tag} dX")
     if with_lora:
         r1, r2 = oracle.linear_bwd_dl(L["dY"], L["X"], hL1, hL2, s)
-        _check(host_bits(dL1), r1, f"{tag} dL1")
-        _check(host_bits(dL2), r2, f"{tag} dL2")
+        _check(host_bits(dL1), r1, f"{tag} dL1", few_terms=M < 64)
+        _check(host_bits(dL2), r2, f"{tag} dL2", few_terms=M < 64)
         # gradient checkpointing: no saved T, recompute X L1 in the backward
         dXb, dL1b, dL2b = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s, T_saved=None)
         torch.cuda.synchronize()
-        _check(host_bits(dL2b), r2, f"{tag} dL2 (recomputed T)")
+        _check(host_bits(dL2b), r2, f"{tag} dL2 (recomputed T)", few_terms=M < 64)
         assert torch.equal(dXb, dX) and torch.equal(dL1b, dL1)
     return Y, dX
 
@@ -131,7 +139,7 @@ def test_full_size_sampled(oracle, synth, config, layer):
     hL1 = synth.normal_bf16((h, r), cfg["sigma_l"], synth.tensor_seed(config, layer, "L1"))
     hL2 = synth.normal_bf16((r, o), cfg["sigma_l"], synth.tensor_seed(config, layer, "L2"))
     X, dY, L1, L2 = dev_bf16(hX), dev_bf16(hdY), dev_bf16(hL1), dev_bf16(hL2)
-    T = torch.empty((M, r), dtype=torch.bfloat16, device="cuda")
+    T = torch.empty((M, 2 * r), dtype=torch.bfloat16, device="cuda")
     Y = ql.qlora_linear_fwd(X, Wq, L1, L2, s, T_save=T)
     dX, dL1, dL2 = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s, T_saved=T)
     torch.cuda.synchronize()
