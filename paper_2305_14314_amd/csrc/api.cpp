@@ -94,7 +94,8 @@ struct FwdPlan {
   uint16_t* Ts;      // M x rp    bf16(s * X L1)
   float* part;       // split-K partials of X L1
   float* fpart;      // few-token path: split partials of X What
-  int rp, splits, fsplits;
+  float* lpart;      // few-token path: partials of X L1
+  int rp, splits, fsplits, n_lparts;
   bool few;
   size_t bytes;
 };
@@ -106,12 +107,15 @@ FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   if (p.few) {
     p.fsplits = qlora::fewtok_fwd_splits((int)h, (int)o);
     p.fpart = c.take<float>((size_t)p.fsplits * M * o);
-  } else {
-    p.Wt = c.take<uint16_t>((size_t)h * o);
+    p.n_lparts = qlora::fewtok_fwd_lparts((int)h, r);
+    p.lpart = c.take<float>((size_t)p.n_lparts * M * r + 4);
+    p.bytes = c.off;
+    return p;
   }
+  p.Wt = c.take<uint16_t>((size_t)h * o);
   if (r > 0) {
     p.splits = qlora::small_gemm_splits((int)M, r, (int)h);
-    if (!p.few) p.L2t = c.take<uint16_t>((size_t)o * p.rp);
+    p.L2t = c.take<uint16_t>((size_t)o * p.rp);
     p.Ts = c.take<uint16_t>((size_t)M * p.rp);
     p.part = c.take<float>((size_t)p.splits * M * r);
   }
@@ -127,7 +131,8 @@ struct BwdPlan {
   uint16_t* Thl;     // M x 2r    X L1 as a [hi | lo] pair, recomputed when the caller saved none
   float* part;       // split-K partials, reused by the four skinny products
   float* fpart;      // few-token path: split partials of dY What^T
-  int rp, sU, sT, sL1, sL2, fsplits;
+  float* lpart;      // few-token path: partials of dY L2^T
+  int rp, sU, sT, sL1, sL2, fsplits, n_lparts;
   bool few;
   size_t bytes;
 };
@@ -139,6 +144,8 @@ BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   if (p.few) {
     p.fsplits = qlora::fewtok_bwd_splits((int)h, (int)o);
     p.fpart = c.take<float>((size_t)p.fsplits * M * h);
+    p.n_lparts = qlora::fewtok_bwd_lparts((int)o, r);
+    p.lpart = c.take<float>((size_t)p.n_lparts * M * r + 4);
   } else {
     p.Wd = c.take<uint16_t>((size_t)h * o);
   }
@@ -269,16 +276,18 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   hipStream_t st = (hipStream_t)hip_stream;
   const qlora::NF4Dev W = to_dev(Wq);
 
+  if (p.few) {
+    // few tokens: stream the packed weight once, dequantise in registers; the adapter's T = X L1 comes from a
+    // few extra workgroups of the same launch and is applied (and saved) by the finalize
+    QL_TRY(qlora::launch_fewtok_fwd(X, (int)M, W, p.fpart, p.fsplits, L1, r, p.lpart, st));
+    QL_TRY(qlora::launch_fewtok_finalize(false, p.fpart, p.fsplits, (int)M, (int)o, p.lpart, p.n_lparts, r, s, L2, Y,
+                                         r > 0 ? T_save : nullptr, st));
+    return QLORA_OK;
+  }
   if (r > 0) {
     // T = X L1 (Eq. 3): split-K partials, then Ts = bf16(s T) (rank zero-padded) and T_save = [hi | lo] of T
     QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.splits, st));
     QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, 0, p.Ts, p.rp, p.rp, s, T_save, st));
-  }
-  if (p.few) {
-    // few tokens: stream the packed weight once, dequantise in registers, add the adapter term in the finalize
-    QL_TRY(qlora::launch_fewtok_fwd(X, (int)M, W, p.fpart, p.fsplits, st));
-    QL_TRY(qlora::launch_fewtok_finalize(p.fpart, p.fsplits, (int)M, (int)o, p.Ts, p.rp, r, L2, o, 1, Y, st));
-    return QLORA_OK;
   }
   QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
   if (r > 0) QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
@@ -307,15 +316,18 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
   hipStream_t st = (hipStream_t)hip_stream;
   const qlora::NF4Dev W = to_dev(Wq);
 
-  if (r > 0 && (dX || dL1)) {
+  if (p.few && dX) {
+    // few tokens: stream the packed weight once; U = dY L2^T comes from extra workgroups of the same launch, is
+    // applied by the finalize and left as a [hi | lo] pair for dL1
+    QL_TRY(qlora::launch_fewtok_bwd(dY, (int)M, W, p.fpart, p.fsplits, L2, r, p.lpart, st));
+    QL_TRY(qlora::launch_fewtok_finalize(true, p.fpart, p.fsplits, (int)M, (int)h, p.lpart, p.n_lparts, r, s, L1, dX,
+                                         (r > 0 && dL1) ? p.Uhl : nullptr, st));
+  } else if (r > 0 && (dX || dL1)) {
     // U = dY L2^T: Us = bf16(s U) feeds the adapter segment of dX, the [hi | lo] pair of U feeds dL1
     QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, (int)M, r, (int)o, p.part, p.sU, st));
     QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, 0, p.Us, p.rp, p.rp, s, p.Uhl, st));
   }
-  if (dX && p.few) {
-    QL_TRY(qlora::launch_fewtok_bwd(dY, (int)M, W, p.fpart, p.fsplits, st));
-    QL_TRY(qlora::launch_fewtok_finalize(p.fpart, p.fsplits, (int)M, (int)h, p.Us, p.rp, r, L1, 1, r, dX, st));
-  } else if (dX) {
+  if (!p.few && dX) {
     const uint16_t* B1 = L1;
     if (r > 0 && p.L1p) { QL_TRY(qlora::launch_copy_pad(L1, (int)h, r, p.L1p, p.rp, st)); B1 = p.L1p; }
     QL_TRY(qlora::launch_dequant(W, p.Wd, st));

@@ -45,16 +45,23 @@ hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int 
                                 hipStream_t st);
 hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st);
 
-// fewtok.hip: few-token (M <= 16) streaming path; fp32 split partials, then one finalize per output.
+// fewtok.hip: few-token (M <= 16) streaming path: one main launch (fp32 split partials of the frozen
+// product plus partials of the adapter's inner product), one finalize launch per output.
 constexpr int kFewTokens = 16;
 int fewtok_fwd_splits(int h, int o);
 int fewtok_bwd_splits(int h, int o);
-//   part[split][M][o] = X (M x h) * dequant(W) over the split's rows
-hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* part, int splits, hipStream_t st);
-//   part[split][M][h] = dY (M x o) * dequant(W)^T over the split's columns
-hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, hipStream_t st);
-//   out[m][n] = bf16(sum of splits + sum_j A[m][j] * Bmat[j * ldb_j + n * ldb_n]); A is M x rp bf16, j < r
-hipError_t launch_fewtok_finalize(const float* part, int splits, int M, int N, const uint16_t* A, int rp, int r,
-                                  const uint16_t* Bmat, int64_t ldb_j, int64_t ldb_n, uint16_t* out, hipStream_t st);
+int fewtok_fwd_lparts(int h, int r);          // number of [M][r] partial slots of T = X L1
+int fewtok_bwd_lparts(int o, int r);          // ... of U = dY L2^T
+//   part[split][M][o] = X (M x h) * dequant(W) over the split's rows;  lpart[p][M][r] = partials of X L1
+hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L1,
+                             int r, float* lpart, hipStream_t st);
+//   part[split][M][h] = dY (M x o) * dequant(W)^T over the split's columns;  lpart = partials of dY L2^T
+hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L2,
+                             int r, float* lpart, hipStream_t st);
+//   out[m][n] = bf16(sum of splits + scale * sum_j T[m][j] * B(j, n)), T = sum of lpart;
+//   forward: Bmat = L2 (r x N); backward: Bmat = L1 (N x r).  hl (M x 2r, may be NULL) receives T as [hi | lo].
+hipError_t launch_fewtok_finalize(bool bwd, const float* part, int splits, int M, int N, const float* lpart,
+                                  int n_lparts, int r, float scale, const uint16_t* Bmat, uint16_t* out, uint16_t* hl,
+                                  hipStream_t st);
 
 }  // namespace qlora

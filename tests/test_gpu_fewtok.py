@@ -11,7 +11,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("M,h,o,r", [(1, 64, 64, 0), (3, 192, 320, 16), (7, 448, 192, 32), (16, 1024, 1024, 16),
-                                      (5, 2048, 64, 64), (16, 64, 2048, 64), (2, 4160, 4224, 16)])
+                                      (5, 2048, 64, 64), (16, 64, 2048, 64), (2, 4160, 4224, 16), (9, 320, 448, 256),
+                                      (16, 2112, 8256, 144)])
 def test_fewtok_small_shapes(oracle, synth, M, h, o, r):
     import paper_2305_14314_amd as ql
     L = synth.make_layer(0, 0, M=M, h=h, o=o, r=max(r, 16))
