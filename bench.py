@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--pool-blocks", type=int, default=80, help="differently-seeded weight blocks resident in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 512 MiB device copy, the known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build is single-GPU; --gpus must be 1 (see DESIGN.md for how the path "
@@ -121,25 +124,26 @@ def main():
     d, ffn = 8192, 22016
 
     # ---- resident pool: quantise `pool_blocks` blocks of 7 tensors with this library -------------
-    pool = []
+    # Weights are drawn on the device, one tensor at a time (a block is 3.2 GB of fp32), quantised into
+    # preallocated buffers and discarded.  The quantise row is timed here: HIP events around each call of a
+    # block, calls of one block back to back on the stream (the fp32 sources of a block are resident first).
+    pool = [[ql.nf4_alloc(h, o, dev) for h, o in linears] for _ in range(args.pool_blocks)]
     t_quant_ms, quant_elems = 0.0, 0
     scratch = torch.empty(max(ql.qlora_nf4_sizes(h, o)[3] for h, o in linears), dtype=torch.uint8, device=dev)
     for b in range(args.pool_blocks):
-        block = []
-        for li, (h, o) in enumerate(linears):
-            W = synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(3, li, "W") + b, dev)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            Wq = ql.qlora_nf4_quantize(W, scratch=scratch)
-            e1.record()
-            torch.cuda.synchronize()
-            if b > 0:                                   # the first block warms up
-                t_quant_ms += e0.elapsed_time(e1)
-                quant_elems += h * o
-            block.append(Wq)
-            del W
-        pool.append(block)
+        Ws = [synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(3, li, "W") + b, dev)
+              for li, (h, o) in enumerate(linears)]
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for li in range(len(linears)):
+            ql.qlora_nf4_quantize(Ws[li], scratch=scratch, out=pool[b][li])
+        e1.record()
+        torch.cuda.synchronize()
+        if b > 0:                                       # the first block warms up
+            t_quant_ms += e0.elapsed_time(e1)
+            quant_elems += sum(h * o for h, o in linears)
+        del Ws
 
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.BASE_SEED)
@@ -167,6 +171,13 @@ def main():
                                 dL2=dL2[li], workspace=ws)
 
     flops_step = sum(4.0 * M * h * o + 6.0 * M * r * (h + o) for h, o in linears)
+
+    if args.pmc_calibration:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                  # reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for k in range(args.warmup):
         step(k)

@@ -106,21 +106,30 @@ def qlora_nf4_sizes(rows, cols, blocksize=64, dq_blocksize=256):
     return tuple(int(x.value) for x in out)
 
 
-def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None) -> NF4Weight:
-    """W: fp32 device tensor (h, o).  Returns the quantised weight (new device buffers)."""
+def nf4_alloc(rows, cols, device, blocksize=64, dq_blocksize=256) -> NF4Weight:
+    """Uninitialised device buffers for a quantised rows x cols weight."""
+    pb, cb, c1b, _ = qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize)
+    return NF4Weight(rows, cols, torch.empty(pb, dtype=torch.uint8, device=device),
+                     torch.empty(cb, dtype=torch.uint8, device=device),
+                     torch.empty(c1b // 4, dtype=torch.float32, device=device),
+                     torch.empty(1, dtype=torch.float32, device=device), blocksize, dq_blocksize)
+
+
+def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None, out=None) -> NF4Weight:
+    """W: fp32 device tensor (h, o).  Returns the quantised weight (in `out` if given, else new buffers)."""
     assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
     rows, cols = W.shape
-    pb, cb, c1b, sb = qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize)
+    sb = qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize)[3]
     dev = W.device
-    packed = torch.empty(pb, dtype=torch.uint8, device=dev)
-    code = torch.empty(cb, dtype=torch.uint8, device=dev)
-    c1 = torch.empty(c1b // 4, dtype=torch.float32, device=dev)
-    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    if out is None:
+        out = nf4_alloc(rows, cols, dev, blocksize, dq_blocksize)
+    assert (out.rows, out.cols, out.blocksize, out.dq_blocksize) == (rows, cols, blocksize, dq_blocksize)
+    packed, code, c1, mean = out.packed, out.code, out.c1, out.mean
     if scratch is None:
         scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
     _check(lib().qlora_nf4_quantize(_ptr(W), rows, cols, blocksize, dq_blocksize, _ptr(packed), _ptr(code),
                                     _ptr(c1), _ptr(mean), _ptr(scratch), scratch.numel(), _stream(stream)))
-    return NF4Weight(rows, cols, packed, code, c1, mean, blocksize, dq_blocksize)
+    return out
 
 
 def qlora_nf4_dequant(Wq: NF4Weight, out=None, stream=None):

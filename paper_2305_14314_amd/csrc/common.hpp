@@ -48,7 +48,7 @@ __host__ __device__ constexpr float nf4_threshold(int j) {
 }
 
 // Nearest NF4 index of a normalised value: 4-level binary search over the 15 thresholds.
-__device__ __forceinline__ uint32_t nf4_index(float x) {
+__host__ __device__ __forceinline__ uint32_t nf4_index_search(float x) {
   constexpr float t0 = nf4_threshold(0), t1 = nf4_threshold(1), t2 = nf4_threshold(2), t3 = nf4_threshold(3),
                   t4 = nf4_threshold(4), t5 = nf4_threshold(5), t6 = nf4_threshold(6), t7 = nf4_threshold(7),
                   t8 = nf4_threshold(8), t9 = nf4_threshold(9), t10 = nf4_threshold(10),
@@ -62,6 +62,51 @@ __device__ __forceinline__ uint32_t nf4_index(float x) {
   const float tc = b3 ? (b2 ? (b1 ? t14 : t12) : (b1 ? t10 : t8)) : (b2 ? (b1 ? t6 : t4) : (b1 ? t2 : t0));
   const bool b0 = x > tc;
   return ((uint32_t)b3 << 3) | ((uint32_t)b2 << 2) | ((uint32_t)b1 << 1) | (uint32_t)b0;
+}
+
+// The same index in ~7 operations: the range is cut into 32 buckets of width 1/16,
+// bucket(x) = clamp(floor(16 x) + 16, 0, 31) (16 x is exact, so the bucket edges are exact).  Neighbouring
+// thresholds are at least 0.0805 > 1/16 apart, so a bucket holds at most one threshold: the index is the
+// number of thresholds below the bucket plus one comparison against the bucket's own threshold.
+struct Nf4Bucket { float thr; uint32_t base; };
+__host__ __device__ constexpr Nf4Bucket nf4_bucket(int b) {
+  const float lo = (float)(b - 16) / 16.0f, hi = (float)(b - 15) / 16.0f;     // exact
+  uint32_t base = 0;
+  float thr = __builtin_huge_valf();                        // no threshold inside: the comparison is always false
+  int inside = 0;
+  for (int j = 0; j < 15; ++j) {
+    const float t = nf4_threshold(j);
+    if (b > 0 && t < lo) ++base;                              // below the whole bucket (bucket 0 extends to -inf)
+    else if (b == 31 || t < hi) { thr = t; ++inside; }        // bucket 31 extends to +inf
+  }
+  // more than one threshold in a bucket would break the scheme; base = 99 makes any test fail loudly
+  return inside > 1 ? Nf4Bucket{thr, 99u} : Nf4Bucket{thr, base};
+}
+__host__ __device__ constexpr bool nf4_buckets_ok() {
+  for (int b = 0; b < 32; ++b) if (nf4_bucket(b).base > 15u) return false;
+  return true;
+}
+static_assert(nf4_buckets_ok(), "an NF4 bucket holds more than one decision threshold");
+
+// Bucket number of a normalised value (shared by the device lookup and the host-side check).
+__host__ __device__ __forceinline__ int nf4_bucket_of(float x) {
+  int k = (int)__builtin_floorf(x * 16.0f) + 16;
+  k = k < 0 ? 0 : k;
+  return k > 31 ? 31 : k;
+}
+// Host/device reference of the bucket scheme with the table recomputed on the fly (slow; for checks).
+__host__ __device__ inline uint32_t nf4_index_bucket_ref(float x) {
+  const Nf4Bucket e = nf4_bucket(nf4_bucket_of(x));
+  return e.base + (x > e.thr ? 1u : 0u);
+}
+// Device lookup: `table` is the 32-entry (threshold, base) table in LDS, 256 bytes = one pass over the
+// 64 LDS banks, so lanes reading different entries never collide and equal entries broadcast.
+__device__ __forceinline__ void nf4_bucket_table_init(Nf4Bucket* table /* LDS, 256-byte aligned */, int tid) {
+  if (tid < 32) table[tid] = nf4_bucket(tid);
+}
+__device__ __forceinline__ uint32_t nf4_index(float x, const Nf4Bucket* table) {
+  const Nf4Bucket e = table[nf4_bucket_of(x)];
+  return e.base + (x > e.thr ? 1u : 0u);
 }
 
 // ---- bf16 ------------------------------------------------------------------------------------

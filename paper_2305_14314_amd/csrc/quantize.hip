@@ -2,7 +2,8 @@
 //
 // Four launches on the caller's stream, no host synchronisation:
 //   zero_bins      clears the 256 exponent bins used for the exact mean
-//   quantize_nf4   per 64-block: absmax (DPP row reduce), reciprocal, nearest NF4 index, nibble pack;
+//   quantize_nf4   per 64-block: absmax (DPP row reduce), reciprocal, nearest NF4 index (32-bucket table
+//                  in LDS plus one comparison), nibble pack;
 //                  writes the fp32 constant c2 to scratch and adds it to the exponent bins
 //   dq_mean        exact sum of all c2 from the bins, divided by n, rounded once to fp32
 //   dq_encode      per run of 256 constants: c2 - mean, absmax -> c1, E4M3 codes
@@ -16,6 +17,7 @@
 namespace qlora {
 
 constexpr int kQThreads = 256;
+constexpr int kQUnroll = 4;
 
 __global__ void zero_bins_kernel(unsigned long long* bins) { bins[threadIdx.x] = 0ull; }
 
@@ -25,28 +27,43 @@ __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
     uint16_t* __restrict__ packed16,                       // one 16-bit store per lane: 4 nibbles
     float* __restrict__ c2_out, unsigned long long* __restrict__ bins) {
   __shared__ unsigned long long lbins[256];
+  __shared__ __attribute__((aligned(256))) Nf4Bucket buckets[32];
   lbins[threadIdx.x] = 0ull;
+  nf4_bucket_table_init(buckets, threadIdx.x);
   __syncthreads();
 
+  // kQUnroll independent float4 loads are issued before any is used: a wave keeps 4 KB in flight, which
+  // the HBM latency-bandwidth product needs at 8 waves per SIMD.
   const int64_t stride = (int64_t)gridDim.x * kQThreads;
-  for (int64_t v = (int64_t)blockIdx.x * kQThreads + threadIdx.x; v < n_vec4; v += stride) {
-    const float4 w = W[v];
-    float amax = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(w.x), __builtin_fabsf(w.y)),
-                                 __builtin_fmaxf(__builtin_fabsf(w.z), __builtin_fabsf(w.w)));
-    amax = row16_max(amax);                                 // c2 of this lane's block
-    // Eq. 1: the constant is range/absmax (range 1); elements are multiplied by it.
-    const float rc = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(1.0f, amax);
-    const uint32_t i0 = nf4_index(__fmul_rn(w.x, rc));
-    const uint32_t i1 = nf4_index(__fmul_rn(w.y, rc));
-    const uint32_t i2 = nf4_index(__fmul_rn(w.z, rc));
-    const uint32_t i3 = nf4_index(__fmul_rn(w.w, rc));
-    packed16[v] = (uint16_t)(i0 | (i1 << 4) | (i2 << 8) | (i3 << 12));
-    if ((threadIdx.x & 15) == 0) {
-      c2_out[v >> 4] = amax;
-      const uint32_t u = __builtin_bit_cast(uint32_t, amax);
-      uint32_t e = u >> 23, m = u & 0x7fffffu;
-      if (e == 0) e = 1; else m |= 0x800000u;               // value = m * 2^(e - 150)
-      atomicAdd(&lbins[e], (unsigned long long)m);
+  for (int64_t v0 = (int64_t)blockIdx.x * kQThreads + threadIdx.x; v0 < n_vec4; v0 += kQUnroll * stride) {
+    float4 wv[kQUnroll];
+#pragma unroll
+    for (int u = 0; u < kQUnroll; ++u) {
+      const int64_t v = v0 + u * stride;
+      wv[u] = W[v < n_vec4 ? v : v0];                        // clamped: no branch around the load
+    }
+#pragma unroll
+    for (int u = 0; u < kQUnroll; ++u) {
+      const int64_t v = v0 + u * stride;
+      if (v >= n_vec4) break;                                 // whole 16-lane rows drop out together
+      const float4 w = wv[u];
+      float amax = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(w.x), __builtin_fabsf(w.y)),
+                                   __builtin_fmaxf(__builtin_fabsf(w.z), __builtin_fabsf(w.w)));
+      amax = row16_max(amax);                                 // c2 of this lane's block
+      // Eq. 1: the constant is range/absmax (range 1); elements are multiplied by it.
+      const float rc = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(1.0f, amax);
+      const uint32_t i0 = nf4_index(__fmul_rn(w.x, rc), buckets);
+      const uint32_t i1 = nf4_index(__fmul_rn(w.y, rc), buckets);
+      const uint32_t i2 = nf4_index(__fmul_rn(w.z, rc), buckets);
+      const uint32_t i3 = nf4_index(__fmul_rn(w.w, rc), buckets);
+      packed16[v] = (uint16_t)(i0 | (i1 << 4) | (i2 << 8) | (i3 << 12));
+      if ((threadIdx.x & 15) == 0) {
+        c2_out[v >> 4] = amax;
+        const uint32_t u32 = __builtin_bit_cast(uint32_t, amax);
+        uint32_t e = u32 >> 23, m = u32 & 0x7fffffu;
+        if (e == 0) e = 1; else m |= 0x800000u;               // value = m * 2^(e - 150)
+        atomicAdd(&lbins[e], (unsigned long long)m);
+      }
     }
   }
   __syncthreads();

@@ -1,0 +1,23 @@
+"""Host-side checks of device logic that can run without a GPU: the product's own NF4 index
+schemes (bucket table, binary search) against a plain threshold count, compiled for the host."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2305_14314_amd", "csrc")
+
+
+def test_nf4_index_schemes_agree(tmp_path):
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    exe = str(tmp_path / "nf4_index_check")
+    src = os.path.join(CSRC, "host_checks", "nf4_index_check.cpp")
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-ffp-contract=off", "-x", "hip", "-I", CSRC,
+                    src, "-o", exe], check=True, capture_output=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout
+    assert out.startswith("OK "), out
+    assert int(out.split()[1]) > 30_000_000
