@@ -49,6 +49,30 @@ def _time_ms(torch, fn, iters, warmup=2):
     return e0.elapsed_time(e1) / iters
 
 
+def _time_graph_ms(torch, fn, calls, replays=3):
+    """ms per fn() with `calls` invocations captured into one HIP graph, so that the timed region holds GPU
+    work only (eager launches of ~20 us kernels from Python are bound by the host)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(calls):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * calls)
+
+
 def _read_traffic():
     """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", "gemm_nt_llama65b_pmc.txt")
@@ -159,7 +183,7 @@ def main():
     dL1 = [torch.empty_like(a) for a in L1]
     dL2 = [torch.empty_like(a) for a in L2]
     ws_bytes = max(max(ql.qlora_linear_fwd_sizes(M, h, o, r), ql.qlora_linear_bwd_sizes(M, h, o, r)) for h, o in linears)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ws = ql.workspace_alloc(ws_bytes, dev)
 
     def step(k):
         block = pool[k % len(pool)]
@@ -256,15 +280,22 @@ def main():
                     ql.qlora_linear_bwd(Xs[o], None, blk[li], L1[li], L2[li], s, dX=Ys[h], need_dL=False,
                                         workspace=wss)
             bytes_block = sum(h * o * 0.51587 for h, o in linears)
-            tf = _time_ms(torch, few_fwd, 2 * len(pool))
-            tb = _time_ms(torch, few_bwd, 2 * len(pool))
+            tfe = _time_ms(torch, few_fwd, 2 * len(pool))
+            tbe = _time_ms(torch, few_bwd, 2 * len(pool))
+            kk[0] = 0
+            tf = _time_graph_ms(torch, few_fwd, len(pool))
+            kk[0] = 0
+            tb = _time_graph_ms(torch, few_bwd, len(pool))
             gemv[f"tokens_{m}"] = {"fwd_GBps": round(bytes_block / (tf * 1e-3) * 1e-9, 1),
                                    "bwd_dx_GBps": round(bytes_block / (tb * 1e-3) * 1e-9, 1),
                                    "fwd_frac_hbm": round(bytes_block / (tf * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                                    "bwd_dx_frac_hbm": round(bytes_block / (tb * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
-                                   "fwd_us_per_linear": round(tf * 1e3 / 7, 2), "bwd_us_per_linear": round(tb * 1e3 / 7, 2)}
+                                   "fwd_us_per_linear": round(tf * 1e3 / 7, 2), "bwd_us_per_linear": round(tb * 1e3 / 7, 2),
+                                   "fwd_eager_GBps": round(bytes_block / (tfe * 1e-3) * 1e-9, 1),
+                                   "bwd_dx_eager_GBps": round(bytes_block / (tbe * 1e-3) * 1e-9, 1)}
         extra["gemv"] = {"bytes_per_weight": 0.51587, "note": "packed + 8-bit constants + c1 traffic only; weights "
-                         "cycle through the resident pool", **gemv}
+                         "cycle through the resident pool; one pass over the pool captured in a HIP graph "
+                         "(the eager figures include Python launch cost)", **gemv}
     out["extra"] = extra
 
     if not args.no_cpu_baseline:

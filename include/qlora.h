@@ -21,8 +21,13 @@
  *     on the host before any HIP call is made; on an argument error nothing is
  *     launched and no output is touched.  No exception or abort crosses the ABI.
  *   - Outputs are overwritten, never accumulated into.  Inputs must be finite.
- *   - Workspace / scratch contents are undefined on entry and on exit.  Two
- *     calls that share a workspace must be ordered on one stream.
+ *   - Workspace / scratch contents are undefined on entry and on exit, with one
+ *     exception: the first QLORA_WORKSPACE_HEADER_BYTES of a qlora_linear_*
+ *     workspace hold arrival counters of the few-token kernels.  They must be
+ *     zero before the first call that uses the buffer (qlora_workspace_init, or
+ *     any zero fill), every call leaves them zero again, and the caller must not
+ *     write them in between.  Two calls that share a workspace must be ordered
+ *     on one stream.
  */
 #ifndef QLORA_H
 #define QLORA_H
@@ -60,8 +65,17 @@ int qlora_last_hip_error(void);
  *             2i+1 in bits 7:4, each a 4-bit index into the NF4 table (Appendix E).
  *   c2_code : n = rows*cols/blocksize bytes, the 8-bit-float codes of the
  *             mean-subtracted first-level constants (OCP E4M3 bit patterns),
- *             quantised in runs of `dq_blocksize` = 256 (Double Quantization).
- *   c1      : ceil(n / dq_blocksize) fp32 second-level constants.
+ *             quantised in runs of `dq_blocksize` = 256 consecutive blocks of the
+ *             flattened matrix (Double Quantization).  The codes are STORED
+ *             column-group-major: the bpr = cols/blocksize blocks of a row are taken
+ *             in groups of 4 (256 columns), and group G holds, row after row, the
+ *             codes of its w blocks (w = 4, or bpr - 4G for the last group):
+ *               position(row, blk) = 4*rows*(blk/4) + row*w + blk%4.
+ *             Both products of the linear layer then find the constants of the
+ *             weights they stream in contiguous runs, whichever dimension they
+ *             contract over.  Which constants share a c1 is not affected.
+ *   c1      : ceil(n / dq_blocksize) fp32 second-level constants; block
+ *             b = row*bpr + blk uses c1[b / dq_blocksize].
  *   c2_mean : one fp32, the mean that was subtracted from c2 (per tensor).
  * cols must be a multiple of blocksize, so a block never straddles two rows.
  */
@@ -101,7 +115,18 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
  *   bf16_rne( NF4[index] * fl32( fl32(E4M3(code)/448 * c1) + mean ) ). */
 qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void* hip_stream);
 
-/* Workspace (bytes) qlora_linear_fwd / qlora_linear_bwd need for this shape. */
+/* Size of the counter header at the start of every qlora_linear_* workspace. */
+#define QLORA_WORKSPACE_HEADER_BYTES 16384
+
+/* Zeroes the counter header of a freshly allocated workspace (one small fill
+ * kernel on the stream; safe to capture in a HIP graph).  Needed once per
+ * buffer, before its first use by qlora_linear_fwd / qlora_linear_bwd; a buffer
+ * that was allocated zero-filled needs no call.  Call it again only after a
+ * call on that buffer was abandoned half-way (device reset, failed launch). */
+qlora_status qlora_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Workspace (bytes) qlora_linear_fwd / qlora_linear_bwd need for this shape
+ * (header included). */
 qlora_status qlora_linear_fwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes);
 qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes);
 

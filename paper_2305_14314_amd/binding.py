@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libqlora_hip.so")
 EXPORTS = [
     "qlora_status_string", "qlora_last_hip_error", "qlora_nf4_sizes", "qlora_nf4_quantize",
     "qlora_nf4_dequant", "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd",
-    "qlora_linear_bwd", "qlora_profile_gemm", "qlora_profile_gemm_read",
+    "qlora_linear_bwd", "qlora_workspace_init", "qlora_profile_gemm", "qlora_profile_gemm_read",
 ]
 
 
@@ -98,6 +98,19 @@ class NF4Weight:
     def nbytes(self) -> int:
         return self.packed.numel() + self.code.numel() + 4 * self.c1.numel() + 4
 
+    def code_flat(self):
+        """The 8-bit codes in flattened block order (block row * cols/64 + blk), as a new device tensor.
+
+        The library stores them column-group-major (include/qlora.h): position(row, blk) =
+        4 * rows * (blk // 4) + row * w + blk % 4, with w = 4 or, for the last group, cols/64 - 4 * (blk // 4)."""
+        bpr = self.cols // self.blocksize
+        dev = self.code.device
+        row = torch.arange(self.rows, device=dev, dtype=torch.int64).repeat_interleave(bpr)
+        blk = torch.arange(bpr, device=dev, dtype=torch.int64).repeat(self.rows)
+        grp = blk // 4
+        width = torch.clamp(bpr - 4 * grp, max=4)
+        return self.code[4 * self.rows * grp + row * width + blk % 4]
+
 
 def qlora_nf4_sizes(rows, cols, blocksize=64, dq_blocksize=256):
     """(packed_bytes, code_bytes, c1_bytes, scratch_bytes)"""
@@ -153,6 +166,21 @@ def qlora_linear_bwd_sizes(M, h, o, r) -> int:
     return int(out.value)
 
 
+WORKSPACE_HEADER_BYTES = 16384
+
+
+def qlora_workspace_init(workspace, stream=None):
+    """Zeroes the counter header of a workspace buffer: once per buffer, before its first use."""
+    _check(lib().qlora_workspace_init(_ptr(workspace), workspace.numel(), _stream(stream)))
+    return workspace
+
+
+def workspace_alloc(nbytes, device="cuda", stream=None):
+    """A uint8 workspace of at least `nbytes` whose counter header is zeroed."""
+    ws = torch.empty(max(int(nbytes), WORKSPACE_HEADER_BYTES), dtype=torch.uint8, device=device)
+    return qlora_workspace_init(ws, stream)
+
+
 def qlora_linear_fwd(X, Wq: NF4Weight, L1, L2, s, Y=None, T_save=None, workspace=None, stream=None):
     """Y = X dequant(Wq) + s (X L1) L2.  X (M, h), L1 (h, r), L2 (r, o) bf16 device tensors;
     T_save, if given, is an (M, 2r) bf16 tensor that receives X L1 as a [hi | lo] pair."""
@@ -162,7 +190,7 @@ def qlora_linear_fwd(X, Wq: NF4Weight, L1, L2, s, Y=None, T_save=None, workspace
     if Y is None:
         Y = torch.empty((M, o), dtype=torch.bfloat16, device=X.device)
     if workspace is None:
-        workspace = torch.empty(max(16, qlora_linear_fwd_sizes(M, h, o, r)), dtype=torch.uint8, device=X.device)
+        workspace = workspace_alloc(qlora_linear_fwd_sizes(M, h, o, r), X.device, stream)
     v = Wq.view()
     _check(lib().qlora_linear_fwd(_ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(Y), _ptr(T_save),
                                   _ptr(workspace), workspace.numel(), _stream(stream)))
@@ -184,7 +212,7 @@ def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1
         if dL2 is None:
             dL2 = torch.empty((r, o), dtype=torch.bfloat16, device=dev)
     if workspace is None:
-        workspace = torch.empty(max(16, qlora_linear_bwd_sizes(M, h, o, r)), dtype=torch.uint8, device=dev)
+        workspace = workspace_alloc(qlora_linear_bwd_sizes(M, h, o, r), dev, stream)
     v = Wq.view()
     _check(lib().qlora_linear_bwd(_ptr(dY), _ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(T_saved),
                                   _ptr(dX), _ptr(dL1), _ptr(dL2), _ptr(workspace), workspace.numel(),

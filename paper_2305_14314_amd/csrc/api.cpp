@@ -77,9 +77,10 @@ qlora_status check_linear(int64_t M, int64_t h, int64_t o, int32_t r) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Bump allocator over the caller's workspace; the same walk computes the size query.
+// Bump allocator over the caller's workspace; the same walk computes the size query.  Every plan starts
+// behind the counter header, which only the few-token kernels touch (and leave zero).
 struct Carver {
-  char* base; size_t off = 0;
+  char* base; size_t off = qlora::kWorkspaceHeaderBytes;
   explicit Carver(void* b) : base((char*)b) {}
   template <class T> T* take(size_t count) {
     T* p = base ? (T*)(base + off) : nullptr;
@@ -103,7 +104,7 @@ FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   FwdPlan p{};
   Carver c(ws);
   p.rp = (r + 63) / 64 * 64;
-  p.few = M <= qlora::kFewTokens;
+  p.few = M <= qlora::kFewTokens && qlora::fewtok_fwd_slabs((int)o) <= qlora::kFewMaxSlabs;
   if (p.few) {
     p.fsplits = qlora::fewtok_fwd_splits((int)h, (int)o);
     p.fpart = c.take<float>((size_t)p.fsplits * M * o);
@@ -140,7 +141,7 @@ BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   BwdPlan p{};
   Carver c(ws);
   p.rp = (r + 63) / 64 * 64;
-  p.few = M <= qlora::kFewTokens;
+  p.few = M <= qlora::kFewTokens && qlora::fewtok_bwd_slabs((int)h) <= qlora::kFewMaxSlabs;
   if (p.few) {
     p.fsplits = qlora::fewtok_bwd_splits((int)h, (int)o);
     p.fpart = c.take<float>((size_t)p.fsplits * M * h);
@@ -232,7 +233,7 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
   if (!aligned16(W) || !aligned16(packed) || !aligned16(c2_code) || !aligned16(c1) || !aligned16(scratch) ||
       ((uintptr_t)c2_mean & 3u))
     return QLORA_ERR_ALIGN;
-  return hip_status(qlora::launch_quantize(W, rows * cols, packed, c2_code, c1, c2_mean, scratch,
+  return hip_status(qlora::launch_quantize(W, rows, cols, packed, c2_code, c1, c2_mean, scratch,
                                            (hipStream_t)hip_stream));
 }
 
@@ -258,6 +259,13 @@ qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, 
   return QLORA_OK;
 }
 
+qlora_status qlora_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace) return QLORA_ERR_NULL;
+  if (workspace_bytes < qlora::kWorkspaceHeaderBytes) return QLORA_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_workspace_init(workspace, (hipStream_t)hip_stream));
+}
+
 #define QL_TRY(expr) do { if (hipError_t e_ = (expr)) return hip_status(e_); } while (0)
 
 qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1, const uint16_t* L2,
@@ -277,11 +285,10 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   const qlora::NF4Dev W = to_dev(Wq);
 
   if (p.few) {
-    // few tokens: stream the packed weight once, dequantise in registers; the adapter's T = X L1 comes from a
-    // few extra workgroups of the same launch and is applied (and saved) by the finalize
-    QL_TRY(qlora::launch_fewtok_fwd(X, (int)M, W, p.fpart, p.fsplits, L1, r, p.lpart, st));
-    QL_TRY(qlora::launch_fewtok_finalize(false, p.fpart, p.fsplits, (int)M, (int)o, p.lpart, p.n_lparts, r, s, L2, Y,
-                                         r > 0 ? T_save : nullptr, st));
+    // few tokens: one launch streams the packed weight once and dequantises in registers; the adapter's
+    // T = X L1 comes from a few extra workgroups and is applied (and saved) by each slab's last arriver
+    QL_TRY(qlora::launch_fewtok_fwd(X, (int)M, W, p.fpart, p.fsplits, L1, L2, r, s, p.lpart, (unsigned*)workspace, Y,
+                                    T_save, st));
     return QLORA_OK;
   }
   if (r > 0) {
@@ -317,11 +324,10 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
   const qlora::NF4Dev W = to_dev(Wq);
 
   if (p.few && dX) {
-    // few tokens: stream the packed weight once; U = dY L2^T comes from extra workgroups of the same launch, is
-    // applied by the finalize and left as a [hi | lo] pair for dL1
-    QL_TRY(qlora::launch_fewtok_bwd(dY, (int)M, W, p.fpart, p.fsplits, L2, r, p.lpart, st));
-    QL_TRY(qlora::launch_fewtok_finalize(true, p.fpart, p.fsplits, (int)M, (int)h, p.lpart, p.n_lparts, r, s, L1, dX,
-                                         (r > 0 && dL1) ? p.Uhl : nullptr, st));
+    // few tokens: one launch streams the packed weight once; U = dY L2^T comes from extra workgroups, is applied
+    // by each slab's last arriver and left as a [hi | lo] pair for dL1
+    QL_TRY(qlora::launch_fewtok_bwd(dY, (int)M, W, p.fpart, p.fsplits, L1, L2, r, s, p.lpart, (unsigned*)workspace, dX,
+                                    (r > 0 && dL1) ? p.Uhl : nullptr, st));
   } else if (r > 0 && (dX || dL1)) {
     // U = dY L2^T: Us = bf16(s U) feeds the adapter segment of dX, the [hi | lo] pair of U feeds dL1
     QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, (int)M, r, (int)o, p.part, p.sU, st));

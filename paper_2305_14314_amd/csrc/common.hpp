@@ -130,6 +130,15 @@ __device__ __forceinline__ float e4m3_value(uint32_t code) {
 // Decode-table entry used by doubleDequant: value / 448 as one correctly rounded fp32 division.
 __device__ __forceinline__ float e4m3_unit(uint32_t code) { return __fdiv_rn(e4m3_value(code), kF8Max); }
 
+// Storage position of the 8-bit constant of block `blk` (0 .. bpr-1) of row `row`: column-group-major, groups of
+// 4 blocks (256 columns), the last group possibly narrower.  The double-quantisation runs are NOT permuted:
+// block row * bpr + blk still belongs to c1[(row * bpr + blk) / 256].
+__device__ __forceinline__ int64_t code_pos(int64_t rows, int bpr, int64_t row, int blk) {
+  const int G = blk >> 2;
+  const int w = (4 * G + 4 <= bpr) ? 4 : bpr - 4 * G;
+  return (int64_t)4 * rows * G + row * w + (blk & 3);
+}
+
 // Round-to-nearest-even onto the E4M3 grid, saturating at +-448; a zero result is always 0x00.
 __device__ __forceinline__ uint32_t e4m3_encode(float z) {
   const float a = __builtin_fabsf(z);

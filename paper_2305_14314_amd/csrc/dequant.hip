@@ -10,7 +10,7 @@ constexpr int kDeqThreads = 256;
 
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
-    const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords) {
+    const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr) {
   __shared__ float lut[16];
   __shared__ float unit[256];
   if (threadIdx.x < 16) {
@@ -24,9 +24,11 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
   const int64_t stride = (int64_t)gridDim.x * kDeqThreads;
   for (int64_t d = (int64_t)blockIdx.x * kDeqThreads + threadIdx.x; d < n_dwords; d += stride) {
     const uint32_t p = packed[d];
-    const int64_t blk = d >> 3;                             // 8 dwords per 64-block
+    const uint32_t blk = (uint32_t)(d >> 3);                // 8 dwords per 64-block
+    const uint32_t row = blk / bpr;
+    const uint8_t cd = code[code_pos(rows, (int)bpr, row, (int)(blk - row * bpr))];
     // dequant(c1, c2): two separately rounded fp32 steps
-    const float c2 = __fadd_rn(__fmul_rn(unit[code[blk]], c1[blk >> 8]), mean);
+    const float c2 = __fadd_rn(__fmul_rn(unit[cd], c1[blk >> 8]), mean);
     uint4 o;
     o.x = pack_bf16x2(__fmul_rn(lut[p & 15u], c2), __fmul_rn(lut[(p >> 4) & 15u], c2));
     o.y = pack_bf16x2(__fmul_rn(lut[(p >> 8) & 15u], c2), __fmul_rn(lut[(p >> 12) & 15u], c2));
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const bool ok = k < h;
     const int64_t blk = (int64_t)(ok ? k : 0) * blocks_per_row + n_blk;
     p[j] = ok ? packed[blk * 8 + ng] : 0x77777777u;         // index 7 is the exact zero
-    c2[j] = ok ? __fadd_rn(__fmul_rn(unit[code[blk]], c1[blk >> 8]), mean) : 0.0f;
+    c2[j] = ok ? __fadd_rn(__fmul_rn(unit[code[code_pos(h, blocks_per_row, k, n_blk)]], c1[blk >> 8]), mean) : 0.0f;
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -100,7 +102,8 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
   const int64_t cap = 256 * 32;
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(dequant_nf4_kernel, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
-                     (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords);
+                     (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
+                     (uint32_t)(w.cols / 64));
   return hipGetLastError();
 }
 

@@ -2,15 +2,24 @@
 // Eq. 5 / Eq. 6 at generation-time batch sizes): bandwidth-bound streaming kernels that read the
 // packed NF4 weight and its double-quantised constants exactly once (0.516 B per weight),
 // dequantise in registers to the same bf16 values as the standalone doubleDequant, and feed
-// MFMA 16x16x32 with the tokens as the 16-wide dimension.  Two launches per call:
+// MFMA 16x16x32 with the tokens as the 16-wide dimension.  One launch per call:
 //
-//   main    : part[split][m][n]  = partial sums of X * What   (forward)  or  dY * What^T (backward)
-//             lpart[p][m][j]     = partial sums of the adapter's inner product T = X L1 or U = dY L2^T,
-//                                  computed by a few extra workgroups of the same launch
-//   finalize: out = bf16( sum of splits + s * (sum of lpart) * L2 )   resp.  ... * L1^T   -- one rounding
+//   main workgroups    : part[split][m][n] = partial sums of X * What (forward) or dY * What^T (backward)
+//                        over the split's share of the contraction, for a slab of 256 outputs
+//   adapter workgroups : lpart[p][m][j] = partial sums of the adapter's inner product T = X L1 or U = dY L2^T
+//   last arriver       : every workgroup counts itself in at its slab's arrival counter (device-scope atomic
+//                        after a fence); the adapter, once all its workgroups are in, counts itself in at every
+//                        slab.  Whoever completes a slab's count computes
+//                        out = bf16( sum of splits + s * (sum of lpart) * L2 )  resp.  ... * L1^T  -- one rounding.
+//                        Nobody waits for anybody, so the scheme cannot hang; the sums are taken in a fixed
+//                        order, so results do not depend on who arrives last.
+// The counters live in the zeroed header of the caller's workspace and are reset by the last arriver.  A kernel
+// boundary costs ~3 us of idle GPU plus ~4 us of fixed launch cost here, which a separate reduction kernel
+// would pay on top of a 20-40 us stream.
 //
-// The main loop keeps kDepth steps of global loads in flight per wave (a wave only runs 4-16 steps,
-// so without explicit prefetch every step would expose the full HBM latency).
+// A step of a wave costs address-unit, LDS-lookup, VALU and MFMA time one after the other (a wave issues
+// in order), so workgroups are 16 waves (4 per SIMD, 128 VGPRs each) and every wave keeps 2-3 steps of
+// global loads in flight.
 // NF4 decode uses a byte -> (value[lo nibble], value[hi nibble]) table in LDS, one 64-bit LDS read per
 // two weights.  The table is replicated 32 times with the copies interleaved at 8-byte granularity
 // (entry e of copy c at byte 256 e + 8 c), so lane l always reads the two banks of copy l % 32 whatever
@@ -23,11 +32,22 @@ namespace qlora {
 
 namespace {
 
-constexpr int kFewThreads = 512;             // 8 waves share one replicated decode table
+constexpr int kFewThreads = 1024;            // 16 waves share one replicated decode table
+constexpr int kWaves = kFewThreads / 64;
 constexpr int kLutCopies = 32;
-constexpr int kDepth = 4;                    // steps of loads in flight per wave
+constexpr int kBwdDepth = 2;
+constexpr int kLoraDepth = 2;
 constexpr int kLoraK = 2048;                 // forward: rows of L1 per adapter workgroup
 constexpr int kLoraN = 4096;                 // backward: columns of L2 per adapter workgroup
+
+// LDS map of a main workgroup.  The decode table is dead once the main loop is over, so the cross-wave
+// sums reuse the space from offset 0.
+constexpr int kLutBytes = 256 * kLutCopies * 8;              // 64 KB
+constexpr int kRedBytes = kWaves * 16 * 128 * 4;             // 128 KB: one 16 x 128 fp32 tile per wave
+constexpr int kUnitOff = kRedBytes;                          // float[256]
+constexpr int kStripOff = kUnitOff + 1024;                   // float[kWaves][2][32]
+constexpr int kSmemBytes = kStripOff + kWaves * 256;
+static_assert(kLutBytes <= kRedBytes && kSmemBytes <= 160 * 1024, "LDS map");
 
 __device__ __forceinline__ void init_pair_lut(f32x2* lut2 /* [256][32] */, float* unit /* [256] */) {
   constexpr float t[16] = {QLORA_NF4_VALUES};
@@ -52,26 +72,201 @@ struct FewArgs {
   float* part;                               // [splits][M][N]
   int per_split;                             // contraction elements per split
   int n_slabs, splits;
-  // adapter inner product, handled by workgroups with blockIdx.x >= n_slabs * splits
+  // adapter inner product, handled by the first n_lparts workgroups in work_index() order
   const uint16_t* L; int r;                  // forward: L1 (h x r); backward: L2 (r x o)
-  float* lpart;                              // [n_lora_wgs][M][r]
+  float* lpart;                              // [n_lparts][M][r]
+  int n_lparts;
+  // output stage, run by the last workgroup to arrive at a slab
+  unsigned* ctr;                             // arrival counters: one per slab, kCtrLora for the adapter; zero on entry and exit
+  const uint16_t* Bmat;                      // forward: L2 (r x o); backward: L1 (h x r)
+  float scale;
+  uint16_t* out;                             // M x N bf16
+  uint16_t* hl;                              // M x 2r: T (resp. U) as a [hi | lo] bf16 pair, or NULL
 };
+
+constexpr int kCtrLora = 4095;               // counter index of the adapter workgroups; slabs use [0, 4095)
+
+// Workgroup b runs on die (XCD) b % 8, and each die has its own L2.  The work list -- adapter partials first,
+// then (split, slab) pairs in split-major order -- is cut into 8 contiguous pieces, one per die, so that the
+// workgroups of one split sit together: they read the same rows of the token operand and, in the forward, the
+// same 128-byte lines of the 8-bit constants (a line holds one row's constants of 32 slabs).  With the plain
+// b -> (b % n_slabs, b / n_slabs) map every die pulled every constant line: 1.5x the algorithmic HBM bytes.
+__device__ __forceinline__ int work_index() {
+  const int grid = gridDim.x, b = blockIdx.x;
+  const int x = b & 7, q = b >> 3;
+  return x * (grid >> 3) + (x < (grid & 7) ? x : (grid & 7)) + q;
+}
+
+// Counts this workgroup in at *c; true for the workgroup that completes `total` arrivals.  Everything the
+// workgroup stored before the call is visible to the last arriver.  Only thread 0 pays for the device-scope
+// fences (a release is an L2 write-back, an acquire an L2 invalidate on this multi-die part): the barriers
+// order the other threads' stores before its release and their later loads after its acquire.  The partials
+// themselves are stored write-through (relaxed device-scope atomic stores), which leaves the write-back
+// nothing to do: plain stores followed by full fences in every wave measured 8x slower kernels.
+__device__ __forceinline__ bool arrive_last(unsigned* c, unsigned total, volatile int* flag) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    const unsigned old = atomicAdd(c, 1u);
+    const int last = old + 1 == total;
+    if (last) {
+      atomicExch(c, 0u);                                     // nobody else touches this counter any more
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    *flag = last;
+  }
+  __syncthreads();
+  return *flag != 0;
+}
+
+// ---- output stage ---------------------------------------------------------------------------------
+// out[m][n] = bf16( sum_s part[s][m][n] + scale * sum_j T[m][j] * B(j, n) ),  T = sum_p lpart[p], for the 256
+// outputs n of one slab; forward: B(j, n) = L2[j][n]; backward: B(j, n) = L1[n][j].  Run by all 1024 threads of
+// one workgroup: a thread owns one column and four tokens.  Slab 0 also stores T as a [hi | lo] bf16 pair.
+template <bool BWD>
+__device__ void finalize_slab(const FewArgs& p, int slab, char* smem) {
+  constexpr int RC = 64;                                     // rank columns staged at a time
+  constexpr int kPitch = RC + 8;                             // backward tile row pitch keeps 16-byte alignment
+  float* Ts = (float*)smem;                                  // T[j][m], unscaled: 16 KB
+  uint16_t* Bs = (uint16_t*)(smem + 16384);                  // forward [RC][256], backward [256][kPitch]
+  const int N = BWD ? p.h : p.o;
+  const int n0 = slab * 256;
+  const int c = threadIdx.x & 255, m0 = 4 * (threadIdx.x >> 8);   // column within the slab, first of four tokens
+  const int n = n0 + c;
+  const bool n_ok = n < N;
+  const bool active = m0 < p.M;                              // uniform per wave
+
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (active) {
+    const int64_t nn = n_ok ? n : 0;
+#pragma unroll 4
+    for (int sp = 0; sp < p.splits; ++sp) {
+      const float* ps = p.part + (int64_t)sp * p.M * N + nn;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int m = m0 + u;
+        const float v = ps[(int64_t)(m < p.M ? m : 0) * N];
+        acc[u] += m < p.M ? v : 0.0f;
+      }
+    }
+  }
+  float lora[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (p.r > 0) {
+    for (int e = threadIdx.x; e < p.M * p.r; e += kFewThreads) {
+      float t = 0.0f;
+      for (int q0 = 0; q0 < p.n_lparts; q0 += 8) {           // 8 loads in flight, then a fixed-order sum
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const bool ok = q0 + q < p.n_lparts;
+          const float x = p.lpart[(int64_t)(ok ? q0 + q : 0) * p.M * p.r + e];
+          v[q] = ok ? x : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) t += v[q];
+      }
+      const int m = e / p.r, j = e - m * p.r;
+      Ts[j * 16 + m] = t;
+      if (p.hl && slab == 0) {
+        const uint16_t hi = bf16_bits(t);
+        p.hl[(int64_t)m * 2 * p.r + j] = hi;
+        p.hl[(int64_t)m * 2 * p.r + p.r + j] = bf16_bits(t - bf16_lo_to_f32(hi));
+      }
+    }
+    for (int j0 = 0; j0 < p.r; j0 += RC) {
+      const int rc = (p.r - j0 < RC) ? p.r - j0 : RC;
+      const int cpr = rc >> 3;                               // backward: 16-byte chunks per row
+      u32x4 stage[2];
+      int dst[2];
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const int e = it * kFewThreads + threadIdx.x;
+        bool ok;
+        int64_t off;
+        if (!BWD) {                                          // row j0 + e / 32 of L2, columns n0 + 8 (e % 32) .. +7
+          const int j = e >> 5, ch = e & 31;
+          ok = j < rc && n0 + 8 * ch < N;
+          off = (int64_t)(j0 + j) * N + n0 + 8 * ch;
+          dst[it] = j * 256 + 8 * ch;
+        } else {                                             // row n0 + cc of L1, rank columns j0 + 8 ch .. +7
+          const int cc = e / cpr, ch = e - cc * cpr;
+          ok = cc < 256 && n0 + cc < N;
+          off = (int64_t)(n0 + cc) * p.r + j0 + 8 * ch;
+          dst[it] = cc * kPitch + 8 * ch;
+        }
+        const u32x4 v = *(const u32x4*)(p.Bmat + (ok ? off : 0));
+        stage[it] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+        if (!ok && (BWD ? (e / cpr >= 256) : ((e >> 5) >= rc))) dst[it] = -1;   // outside the tile: nothing to store
+      }
+      if (j0 > 0) __syncthreads();                           // previous tile consumed
+#pragma unroll
+      for (int it = 0; it < 2; ++it)
+        if (dst[it] >= 0) *(u32x4*)(Bs + dst[it]) = stage[it];
+      __syncthreads();                                       // tile and Ts visible
+      if (active) {
+#pragma unroll 8
+        for (int j = 0; j < rc; ++j) {
+          const float b = bf16_lo_to_f32(BWD ? Bs[c * kPitch + j] : Bs[j * 256 + c]);
+          const f32x4 t = *(const f32x4*)&Ts[(j0 + j) * 16 + m0];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) lora[u] = __builtin_fmaf(t[u], b, lora[u]);
+        }
+      }
+    }
+  }
+  if (!n_ok || !active) return;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (m0 + u < p.M) p.out[(int64_t)(m0 + u) * N + n] = bf16_bits(acc[u] + p.scale * lora[u]);
+}
+
+// Called by every adapter workgroup after its partial is stored.  The last of them counts the adapter in at
+// every slab; a slab whose splits were all in already (rare: the adapter reads far less than a split) is
+// finished right here.
+template <bool BWD>
+__device__ void adapter_arrive(const FewArgs& p, char* smem, volatile int* flag) {
+  if (!arrive_last(p.ctr + kCtrLora, (unsigned)p.n_lparts, flag)) return;
+  int* npend = (int*)(smem + 65536);                         // beyond what finalize_slab uses
+  int* pend = npend + 1;
+  if (threadIdx.x == 0) *npend = 0;
+  __syncthreads();
+  const unsigned total = (unsigned)p.splits + 1u;
+  for (int t = threadIdx.x; t < p.n_slabs; t += kFewThreads) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");       // every adapter partial, seen through the count above
+    const unsigned old = atomicAdd(p.ctr + t, 1u);
+    if (old + 1 == total) {
+      atomicExch(p.ctr + t, 0u);
+      pend[atomicAdd(npend, 1)] = t;
+    }
+  }
+  __syncthreads();
+  const int n = *npend;
+  if (n > 0) {
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the splits counted before us
+    __syncthreads();
+  }
+  for (int q = 0; q < n; ++q) {
+    finalize_slab<BWD>(p, pend[q], smem);
+    __syncthreads();
+  }
+}
+
 
 // ---- adapter partials -----------------------------------------------------------------------------
 // Both run on MFMA 16x16x32 with the tokens as one 16-wide dimension and 16 rank columns as the other,
-// kDepth steps of loads in flight, and a cross-wave sum through LDS; one partial slot per workgroup.
+// kLoraDepth steps of loads in flight, and a cross-wave sum through LDS; one partial slot per workgroup.
 //
 // forward: lpart[wg][m][j] = sum over k in [kLoraK * wg, +kLoraK) of X[m][k] * L1[k][j]
 // L1 is [h][r] (rank contiguous), so a fragment of 8 consecutive k for one rank column is gathered from
 // 8 rows: lane (i, g) loads columns 4i .. 4i+3 of rows kb + 8g + j and splits them with byte permutes.
 struct LFwdStep { uint32_t l[8][2]; u32x4 x; };
 
-__device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [8][16][64] */) {
+__device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [kWaves][16][64] */) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave index is uniform
   const int i = lane & 15, g = lane >> 4;
   const int k_begin = wg * kLoraK;
   const int k_end = (k_begin + kLoraK < p.h) ? k_begin + kLoraK : p.h;
-  const int stride = 8 * 32, kb0 = k_begin + wave * 32;      // 8 waves interleave 32-row steps
+  const int stride = kWaves * 32, kb0 = k_begin + wave * 32; // the waves interleave 32-row steps
   float* out = p.lpart + (int64_t)wg * p.M * p.r;
   for (int j0 = 0; j0 < p.r; j0 += 64) {
     const bool col_ok = j0 + 4 * i < p.r;                    // r % 16 == 0: the 4 columns are in or out together
@@ -94,12 +289,12 @@ __device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [8][16]
     f32x4 acc[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    LFwdStep buf[kDepth];
+    LFwdStep buf[kLoraDepth];
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) load_step(buf[d], kb0 + d * stride);
-    for (int kb = kb0; kb < k_end; kb += kDepth * stride) {
+    for (int d = 0; d < kLoraDepth; ++d) load_step(buf[d], kb0 + d * stride);
+    for (int kb = kb0; kb < k_end; kb += kLoraDepth * stride) {
 #pragma unroll
-      for (int d = 0; d < kDepth; ++d) {
+      for (int d = 0; d < kLoraDepth; ++d) {
         if (kb + d * stride < k_end) {
           const bf16x8 xa = __builtin_bit_cast(bf16x8, buf[d].x);
 #pragma unroll
@@ -111,7 +306,7 @@ __device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [8][16]
               w[jp] = __builtin_amdgcn_perm(buf[d].l[2 * jp + 1][e >> 1], buf[d].l[2 * jp][e >> 1], sel);
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, __builtin_bit_cast(bf16x8, w), acc[e], 0, 0, 0);
           }
-          load_step(buf[d], kb + (d + kDepth) * stride);
+          load_step(buf[d], kb + (d + kLoraDepth) * stride);
         }
       }
     }
@@ -127,8 +322,8 @@ __device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [8][16]
       if (j0 + c < p.r) {
         float t = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) t += red[w * 16 * 64 + idx];
-        out[(int64_t)m * p.r + j0 + c] = t;
+        for (int w = 0; w < kWaves; ++w) t += red[w * 16 * 64 + idx];
+        __hip_atomic_store(out + (int64_t)m * p.r + j0 + c, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
@@ -138,12 +333,12 @@ __device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [8][16]
 // Both operands are contiguous along n: fragments are plain 16-byte loads.
 struct LBwdStep { u32x4 l[4]; u32x4 y; };
 
-__device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [8][16][64] */) {
+__device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [kWaves][16][64] */) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave index is uniform
   const int i = lane & 15, g = lane >> 4;
   const int n_begin = wg * kLoraN;
   const int n_end = (n_begin + kLoraN < p.o) ? n_begin + kLoraN : p.o;
-  const int stride = 8 * 32, nb0 = n_begin + wave * 32;      // 8 waves interleave 32-column steps
+  const int stride = kWaves * 32, nb0 = n_begin + wave * 32; // the waves interleave 32-column steps
   float* out = p.lpart + (int64_t)wg * p.M * p.r;
   for (int j0 = 0; j0 < p.r; j0 += 64) {
     auto load_step = [&](LBwdStep& s, int nb) {
@@ -162,18 +357,18 @@ __device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [8][16]
     f32x4 acc[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    LBwdStep buf[kDepth];
+    LBwdStep buf[kLoraDepth];
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) load_step(buf[d], nb0 + d * stride);
-    for (int nb = nb0; nb < n_end; nb += kDepth * stride) {
+    for (int d = 0; d < kLoraDepth; ++d) load_step(buf[d], nb0 + d * stride);
+    for (int nb = nb0; nb < n_end; nb += kLoraDepth * stride) {
 #pragma unroll
-      for (int d = 0; d < kDepth; ++d) {
+      for (int d = 0; d < kLoraDepth; ++d) {
         if (nb + d * stride < n_end) {
           const bf16x8 ya = __builtin_bit_cast(bf16x8, buf[d].y);
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ya, __builtin_bit_cast(bf16x8, buf[d].l[e]), acc[e], 0, 0, 0);
-          load_step(buf[d], nb + (d + kDepth) * stride);
+          load_step(buf[d], nb + (d + kLoraDepth) * stride);
         }
       }
     }
@@ -189,107 +384,144 @@ __device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [8][16]
       if (j0 + c < p.r) {
         float t = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) t += red[w * 16 * 64 + idx];
-        out[(int64_t)m * p.r + j0 + c] = t;
+        for (int w = 0; w < kWaves; ++w) t += red[w * 16 * 64 + idx];
+        __hip_atomic_store(out + (int64_t)m * p.r + j0 + c, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
 }
 
 // ---- forward main ---------------------------------------------------------------------------------
-// W is [h][o], o contiguous.  A workgroup owns 128 output columns and a range of k rows; its 4 waves
-// take interleaved 32-row steps and are summed through LDS at the end.  Lane (i = lane % 16,
-// g = lane / 16) loads, for rows kb + 8g + j (j = 0..7), the packed dword of columns n0 + 8i .. +7;
-// MFMA e (0..7) multiplies the 16 tokens with columns {n0 + 8i + e}.  The 64 constants of a step
-// (32 rows x 2 blocks) are decoded one per lane and exchanged through a wave-private LDS strip.
+// W is [h][o], o contiguous.  A workgroup owns a slab of 256 output columns (128 packed bytes per row: one
+// full L2 line) and a range of k rows; its 16 waves take interleaved 16-row steps and are summed through
+// LDS at the end.  Lane (c = lane % 32, rh = lane / 32) loads, for rows kb + 8 rh + j (j = 0..7), packed
+// dword c of the slab, so every load instruction reads two whole 128-byte lines (a wave that reads half
+// lines, the other half going to a sibling wave, measured 25% less HBM bandwidth, and reading the constants
+// as one byte per row-major line halved it again: they are stored column-group-major for this reason).
+//
+// MFMA 16x16x32 wants lane (s = lane % 16, g = lane / 16) to hold 8 k-values of B column slot s.  Here
+// g = 2 rh + c / 16: the groups g in {0, 2} hold columns 8 (c % 16) + e of the first 128 columns (rows
+// kb .. +7 and kb + 8 .. +15), the groups {1, 3} the same rows of the second 128 columns.  The token operand
+// selects: its k-slots of the groups that do not belong are zero.
+//   MT = 8  (M <= 8): A rows 0-7 = tokens with the first-half groups, rows 8-15 = the same tokens with the
+//           second-half groups; one MFMA per column phase e, D rows 0-7 / 8-15 = first / second 128 columns.
+//   MT = 16 (M <= 16): two MFMAs per phase, A1 (groups 0, 2) and A2 (groups 1, 3), two accumulator sets.
+// Each MFMA thus contracts 16 rows; the matrix pipe has the room (it is ~15% busy).
+// The 64 constants of a step (16 rows x 4 blocks, 64 contiguous bytes) are decoded one per lane and exchanged
+// through a wave-private LDS strip.
 struct FwdStep { uint32_t pk[8]; u32x4 x; uint32_t code; float c1; };   // raw loads only: nothing here is consumed before compute()
 
+template <int MT>
 __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p) {
-  __shared__ f32x2 lut2[256 * kLutCopies];                           // 64 KB
-  __shared__ float unit[256];
-  __shared__ __attribute__((aligned(16))) float red[4 * 16 * 128];   // per-wave output tiles of one column half
-  __shared__ __attribute__((aligned(16))) float strip[8][2][32];     // per-wave constants: [block half][row]
-  const int n_main = p.n_slabs * p.splits;
-  if ((int)blockIdx.x >= n_main) { lora_fwd_partial(p, blockIdx.x - n_main, red); return; }   // uses 16 KB of red
-  init_pair_lut(lut2, unit);
-  __syncthreads();
+  constexpr int NA = MT / 8;                                 // accumulator sets (and MFMAs per column phase)
+  constexpr int kDepth = MT == 8 ? 3 : 2;
+  __shared__ __attribute__((aligned(256))) char smem[kSmemBytes];
+  f32x2* lut2 = (f32x2*)smem;
+  float* red = (float*)smem;
+  float* unit = (float*)(smem + kUnitOff);
+  __shared__ int flag;
+  const int work = work_index();
+  if (work < p.n_lparts) {
+    lora_fwd_partial(p, work, red);
+    adapter_arrive<false>(p, smem, &flag);
+    return;
+  }
 
-  const int wave8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // uniform
-  const int wave = wave8 & 3, chalf = wave8 >> 2;            // k interleave index, 128-column half of the slab
-  const int i = lane & 15, g = lane >> 4;
-  const int slab = blockIdx.x % p.n_slabs, split = blockIdx.x / p.n_slabs;
-  const int n0 = slab * 256 + chalf * 128;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // uniform
+  const int c = lane & 31, rh = lane >> 5;
+  const int sl = lane & 15, g = lane >> 4;                   // MFMA slot and k group
+  float* strip = (float*)(smem + kStripOff) + wave * 64;     // [block 4][row 16]
+  const int slab = (work - p.n_lparts) % p.n_slabs, split = (work - p.n_lparts) / p.n_slabs;
   const int k_begin = split * p.per_split;
   const int k_end = (k_begin + p.per_split < p.h) ? k_begin + p.per_split : p.h;
   const float mean = *p.mean;
   const int bpr = p.o >> 6, o_dw = p.o >> 3;
-  const bool col_ok = n0 + 8 * i < p.o;                      // o % 64 == 0: a dword is in or out as a whole
+  const bool col_ok = slab * 256 + 8 * c < p.o;              // o % 64 == 0: a dword is in or out as a whole
   const uint32_t* packed = (const uint32_t*)p.packed;
-  // the constant this lane decodes for a step: row kb + lane / 2, block half lane % 2
-  const int c_blk = (n0 >> 6) + (lane & 1);
-  const bool c_col_ok = c_blk < bpr;
 
-  // Per-lane offsets are fixed for the whole kernel; a step only moves a wave-uniform base, so a load is
-  // one instruction with no address arithmetic.  k ranges are multiples of 32 rows, so every row of a
-  // step inside the range is valid; steps past the range (prefetch overrun) are redirected to the last
-  // valid step and never consumed.  Lanes outside the tensor (columns >= o, tokens >= M) read a valid
-  // dummy address and are masked once, at compute time.
-  const int k_last = k_end - 32;
+  // Per-lane offsets are fixed for the whole kernel; a step only moves a wave-uniform base.  k ranges are
+  // multiples of 16 rows, so every row of a step inside the range is valid; steps past the range (prefetch
+  // overrun, empty splits) are redirected to the last valid step and never consumed.  Lanes outside the
+  // tensor (columns >= o, tokens >= M) read a valid dummy address and are masked at compute time, or
+  // produce output columns that are never stored.
+  const int k_last = k_end - 16;
   uint32_t w_off[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) w_off[j] = (uint32_t)((8 * g + j) * o_dw + (col_ok ? (n0 >> 3) + i : 0));
-  const bool x_row_ok = i < p.M;
-  const uint32_t x_off = (uint32_t)((x_row_ok ? i : 0) * p.h + 8 * g);
-  const uint32_t c_off = (uint32_t)((lane >> 1) * bpr + (c_col_ok ? c_blk : 0));
+  for (int j = 0; j < 8; ++j) w_off[j] = (uint32_t)((8 * rh + j) * o_dw + (col_ok ? slab * 32 + c : 0));
+  // token operand: lane (sl, g) feeds k-slots of rows kb + 8 (g / 2) .. +7
+  const int tok = MT == 8 ? (sl & 7) : sl;
+  const bool x_ok = tok < p.M && (MT == 16 || (g & 1) == (sl >> 3));
+  const uint32_t x_off = (uint32_t)((tok < p.M ? tok : 0) * p.h + 8 * (g >> 1));
+  // the constant this lane decodes for a step: row kb + lane / 4, block 4 slab + lane % 4 (64 contiguous bytes)
+  const int c_blk = 4 * slab + (lane & 3);
+  const int cw = (4 * slab + 4 <= bpr) ? 4 : bpr - 4 * slab; // blocks in this column group
+  const bool c_ok = (lane & 3) < cw;
+  const uint8_t* code_g = p.code + (int64_t)4 * p.h * slab + (c_ok ? (lane & 3) : 0);
+  const uint32_t c_row = (uint32_t)(lane >> 2);
   auto load_step = [&](FwdStep& s, int kb) {
     const int kc = kb < k_end ? kb : k_last;                 // uniform
     const uint32_t* wbase = packed + (int64_t)kc * o_dw;
 #pragma unroll
     for (int j = 0; j < 8; ++j) s.pk[j] = wbase[w_off[j]];
     s.x = *(const u32x4*)(p.X + kc + x_off);
-    const int64_t cbase = (int64_t)kc * bpr;
-    s.code = p.code[cbase + c_off];
-    s.c1 = p.c1[(cbase + c_off) >> 8];
+    const uint32_t crow = (uint32_t)kc + c_row;
+    s.code = code_g[(int64_t)crow * cw];
+    s.c1 = p.c1[(crow * (uint32_t)bpr + (uint32_t)(c_ok ? c_blk : 4 * slab)) >> 8];
   };
 
-  f32x4 acc[8];
+  // the first loads are in flight while the decode table is built
+  const int stride = kWaves * 16;
+  const int kb0 = k_begin + wave * 16;
+  FwdStep buf[kDepth];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int d = 0; d < kDepth; ++d) load_step(buf[d], kb0 + d * stride);
+  init_pair_lut(lut2, unit);
+  __syncthreads();
+
+  f32x4 acc[NA][8];
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[a][e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   auto compute = [&](const FwdStep& s) {
     // dequant(c1, c2): two separately rounded fp32 steps; wave-private strip: no barrier needed
-    strip[wave8][lane & 1][lane >> 1] = __fadd_rn(__fmul_rn(unit[s.code], s.c1), mean);
-    const f32x4* sp = (const f32x4*)&strip[wave8][i >> 3][8 * g];
+    strip[(lane & 3) * 16 + (lane >> 2)] = __fadd_rn(__fmul_rn(unit[s.code], s.c1), mean);
+    const f32x4* sp = (const f32x4*)&strip[(c >> 3) * 16 + 8 * rh];
     const f32x4 ca = sp[0], cb = sp[1];
     const float c2[8] = {ca[0], ca[1], ca[2], ca[3], cb[0], cb[1], cb[2], cb[3]};
-    float v[8][8];                                           // [row j][column e]
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const f32x2 q = pair_lookup(lut2, (s.pk[j] >> (8 * b)) & 0xffu, lane);
-        v[j][2 * b] = __fmul_rn(q[0], c2[j]);
-        v[j][2 * b + 1] = __fmul_rn(q[1], c2[j]);
-      }
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    bf16x8 xa[NA];
+    if (MT == 8) {
+      xa[0] = __builtin_bit_cast(bf16x8, x_ok ? s.x : zero);
+    } else {
+      xa[0] = __builtin_bit_cast(bf16x8, (x_ok && !(g & 1)) ? s.x : zero);
+      xa[NA - 1] = __builtin_bit_cast(bf16x8, (x_ok && (g & 1)) ? s.x : zero);
     }
-    const bf16x8 xa = __builtin_bit_cast(bf16x8, x_row_ok ? s.x : u32x4{0u, 0u, 0u, 0u});
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int b = 0; b < 4; ++b) {                            // byte b of every row: columns 2b, 2b + 1 of the dword
+      float lo[8], hi[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const f32x2 q = pair_lookup(lut2, (s.pk[j] >> (8 * b)) & 0xffu, lane);
+        lo[j] = __fmul_rn(q[0], c2[j]);
+        hi[j] = __fmul_rn(q[1], c2[j]);
+      }
       u32x4 w;
-      w[0] = pack_bf16x2(v[0][e], v[1][e]);
-      w[1] = pack_bf16x2(v[2][e], v[3][e]);
-      w[2] = pack_bf16x2(v[4][e], v[5][e]);
-      w[3] = pack_bf16x2(v[6][e], v[7][e]);
-      acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, __builtin_bit_cast(bf16x8, w), acc[e], 0, 0, 0);
+#pragma unroll
+      for (int jp = 0; jp < 4; ++jp) w[jp] = pack_bf16x2(lo[2 * jp], lo[2 * jp + 1]);
+#pragma unroll
+      for (int a = 0; a < NA; ++a)
+        acc[a][2 * b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[a], __builtin_bit_cast(bf16x8, w), acc[a][2 * b], 0, 0, 0);
+#pragma unroll
+      for (int jp = 0; jp < 4; ++jp) w[jp] = pack_bf16x2(hi[2 * jp], hi[2 * jp + 1]);
+#pragma unroll
+      for (int a = 0; a < NA; ++a)
+        acc[a][2 * b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[a], __builtin_bit_cast(bf16x8, w), acc[a][2 * b + 1], 0, 0, 0);
     }
   };
 
-  // software pipeline over this wave's steps kb = k_begin + 32 * (wave + 4 t)
-  const int stride = 4 * 32;
-  const int kb0 = k_begin + wave * 32;
-  FwdStep buf[kDepth];
-#pragma unroll
-  for (int d = 0; d < kDepth; ++d) load_step(buf[d], kb0 + d * stride);   // loads past k_end are masked off
+  // software pipeline over this wave's steps kb = k_begin + 16 * (wave + 16 t)
   for (int kb = kb0; kb < k_end; kb += kDepth * stride) {
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
@@ -300,49 +532,81 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p
     }
   }
 
-  // D layout: column slot = lane % 16 (= i), token rows 4 * (lane / 16) + v.  The four waves of a column
-  // half are summed through LDS, one half after the other.
+  // D layout: column slot = lane % 16, rows 4 * (lane / 16) + v.  Row R of accumulator set a is token R % MT of
+  // column half (MT == 8 ? R / 8 : a); column within the half = 8 slot + e.  The waves store [MT][256] tiles over
+  // the decode table (dead now) and the tiles are summed; with MT = 16 they do not all fit, so the upper eight
+  // waves hand theirs to the lower eight first.
   float* out = p.part + (int64_t)split * p.M * p.o;
-  const int nbase = slab * 256;
-  for (int hsel = 0; hsel < 2; ++hsel) {
-    __syncthreads();
-    if (chalf == hsel) {
-      float* my = red + wave * (16 * 128);
+  auto store_tile = [&](float* my) {
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
       for (int e = 0; e < 8; ++e)
 #pragma unroll
-        for (int vv = 0; vv < 4; ++vv) my[(4 * g + vv) * 128 + 8 * i + e] = acc[e][vv];
+        for (int vv = 0; vv < 4; ++vv) {
+          const int R = 4 * g + vv;
+          const int m = MT == 8 ? (R & 7) : R, half = MT == 8 ? (R >> 3) : a;
+          my[m * 256 + half * 128 + 8 * sl + e] = acc[a][e][vv];
+        }
+  };
+  constexpr int kTile = MT * 256;
+  int n_tiles = kWaves;
+  __syncthreads();                                           // every wave is done with the decode table
+  if (MT == 16) {
+    if (wave >= 8) store_tile(red + (wave - 8) * kTile);
+    __syncthreads();
+    if (wave < 8) {
+      const float* other = red + wave * kTile;
+#pragma unroll
+      for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+          for (int vv = 0; vv < 4; ++vv) acc[a][e][vv] += other[(4 * g + vv) * 256 + a * 128 + 8 * sl + e];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < p.M * 128; idx += kFewThreads) {
-      const int m = idx >> 7, c = idx & 127;
-      const int n = nbase + hsel * 128 + c;
-      if (n < p.o)
-        out[(int64_t)m * p.o + n] = red[idx] + red[16 * 128 + idx] + red[2 * 16 * 128 + idx] + red[3 * 16 * 128 + idx];
-    }
+    if (wave < 8) store_tile(red + wave * kTile);
+    n_tiles = 8;
+  } else {
+    store_tile(red + wave * kTile);
   }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < p.M * 256; idx += kFewThreads) {
+    const int n = slab * 256 + (idx & 255);
+    float t = 0.0f;
+    for (int w = 0; w < n_tiles; ++w) t += red[w * kTile + idx];
+    if (n < p.o) __hip_atomic_store(out + (int64_t)(idx >> 8) * p.o + n, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (arrive_last(p.ctr + slab, (unsigned)p.splits + (p.r > 0 ? 1u : 0u), &flag)) finalize_slab<false>(p, slab, smem);
 }
 
 // ---- backward main --------------------------------------------------------------------------------
 // Contraction runs along o, the contiguous dimension of W, so a lane's 16-byte load is 32 consecutive
-// weights of one row and one quantisation constant.  A workgroup owns 128 weight rows (4 waves x 32)
-// and a range of columns; per step of 128 columns a lane (i = lane % 16, g = lane / 16) loads rows
-// r0 + i and r0 + 16 + i at columns kb + 32g .. +31; MFMA t (0..3) uses dword t of each load.
-struct BwdStep { u32x4 w[2]; u32x4 y[4]; uint32_t code[2]; float c1[2]; };   // raw loads only
+// weights of one row and one quantisation constant.  A workgroup owns 256 weight rows and a range of
+// columns: wave (rg = wave % 4, cw = wave / 4) owns rows 64 rg .. +63 and takes the 128-column steps
+// cw, cw + 4, ...; the 4 waves of a row group are summed through LDS at the end.  Per step a lane
+// (i = lane % 16, g = lane / 16) loads rows r0 + 16u + i (u = 0..3) at columns kb + 32g .. +31; MFMA t
+// (0..3) uses dword t of each load, so one token fragment serves four weight rows.
+struct BwdStep { u32x4 w[4]; u32x4 y[4]; uint32_t code[4]; float c1[4]; };   // raw loads only
 
 __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p) {
-  __shared__ f32x2 lut2[256 * kLutCopies];                           // 64 KB
-  __shared__ float unit[256];
-  __shared__ __attribute__((aligned(16))) float red[8 * 16 * 64];    // cross-wave sum of the adapter workgroups
-  const int n_main = p.n_slabs * p.splits;
-  if ((int)blockIdx.x >= n_main) { lora_bwd_partial(p, blockIdx.x - n_main, red); return; }
-  init_pair_lut(lut2, unit);
-  __syncthreads();
+  __shared__ __attribute__((aligned(256))) char smem[kSmemBytes];
+  f32x2* lut2 = (f32x2*)smem;
+  float* red = (float*)smem;
+  float* unit = (float*)(smem + kUnitOff);
+  __shared__ int flag;
+  const int work = work_index();
+  if (work < p.n_lparts) {
+    lora_bwd_partial(p, work, red);
+    adapter_arrive<true>(p, smem, &flag);
+    return;
+  }
 
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave index is uniform
+  const int wave16 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // uniform
+  const int rg = wave16 & 3, cw = wave16 >> 2;
   const int i = lane & 15, g = lane >> 4;
-  const int slab = blockIdx.x % p.n_slabs, split = blockIdx.x / p.n_slabs;
-  const int r0 = slab * 256 + wave * 32;
+  const int slab = (work - p.n_lparts) % p.n_slabs, split = (work - p.n_lparts) / p.n_slabs;
+  const int r0 = slab * 256 + rg * 64;
   const int c_begin = split * p.per_split;
   const int c_end = (c_begin + p.per_split < p.o) ? c_begin + p.per_split : p.o;
   const float mean = *p.mean;
@@ -353,47 +617,58 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
   // split is a multiple of 64, a step is 128 wide: the last step may be half empty, which is masked on
   // the token operand (zeros) at compute time, with the weight loads redirected to valid addresses.
   const int c_last = c_end - 64;                             // start of the last valid 64-column block
-  bool row_ok[2];
-  uint32_t w_off[2], cd_off[2];
+  uint32_t w_off[4], cd_off[4], row_c[4];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
+  for (int u = 0; u < 4; ++u) {
     const int row = r0 + 16 * u + i;
-    row_ok[u] = row < p.h;
-    w_off[u] = (uint32_t)((row_ok[u] ? row : 0) * o_q);
-    cd_off[u] = (uint32_t)((row_ok[u] ? row : 0) * bpr);
+    const bool row_ok = row < p.h;
+    row_c[u] = (uint32_t)(row_ok ? row : 0);
+    w_off[u] = row_c[u] * (uint32_t)o_q;
+    cd_off[u] = row_c[u] * (uint32_t)bpr;
   }
   const bool y_row_ok = i < p.M;
   const uint32_t y_off = (uint32_t)((y_row_ok ? i : 0) * p.o);
   auto load_step = [&](BwdStep& s, int kb) {
     int col = kb + 32 * g;                                   // per lane
-    if (col > c_last + 32) col = c_last + 32 * (g & 1);      // overrun: any valid column (masked at compute)
+    if (col >= c_end) col = c_last + 32 * (g & 1);           // overrun: any valid column (masked at compute)
     const u32x4* wbase = packed + (col >> 5);
-    const uint8_t* cbase = p.code + (col >> 6);
+    // constants are stored column-group-major: the 16 rows x 2 blocks of one load sit within 64 bytes
+    const int blk = col >> 6, G = blk >> 2;
+    const uint32_t cw = (4 * G + 4 <= bpr) ? 4u : (uint32_t)(bpr - 4 * G);
+    const uint8_t* cbase = p.code + (int64_t)4 * p.h * G + (blk & 3);
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
       s.w[u] = wbase[w_off[u]];
-      s.code[u] = cbase[cd_off[u]];
-      s.c1[u] = p.c1[(cd_off[u] + (uint32_t)(col >> 6)) >> 8];
+      s.code[u] = cbase[row_c[u] * cw];
+      s.c1[u] = p.c1[(cd_off[u] + (uint32_t)blk) >> 8];
     }
     const uint16_t* ysrc = p.X + y_off + col;
 #pragma unroll
     for (int t = 0; t < 4; ++t) s.y[t] = *(const u32x4*)(ysrc + 8 * t);
   };
 
-  f32x4 acc[2];
-  acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
-  acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int stride = 4 * 128;
+  const int kb0 = c_begin + cw * 128;
+  BwdStep buf[kBwdDepth];
+#pragma unroll
+  for (int d = 0; d < kBwdDepth; ++d) load_step(buf[d], kb0 + d * stride);   // in flight while the table is built
+  init_pair_lut(lut2, unit);
+  __syncthreads();
+
+  f32x4 acc[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   auto compute = [&](const BwdStep& s, int kb) {
     const bool y_ok = y_row_ok && kb + 32 * g < c_end;       // tokens >= M and columns past the split contribute zero
-    float c2v[2];
+    float c2v[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) c2v[u] = __fadd_rn(__fmul_rn(unit[s.code[u]], s.c1[u]), mean);
+    for (int u = 0; u < 4; ++u) c2v[u] = __fadd_rn(__fmul_rn(unit[s.code[u]], s.c1[u]), mean);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const bf16x8 ya = __builtin_bit_cast(bf16x8, y_ok ? s.y[t] : u32x4{0u, 0u, 0u, 0u});
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < 4; ++u) {
         const uint32_t d = s.w[u][t];
         u32x4 w;
 #pragma unroll
@@ -406,131 +681,40 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
     }
   };
 
-  BwdStep buf[kDepth];
+  for (int kb = kb0; kb < c_end; kb += kBwdDepth * stride) {
 #pragma unroll
-  for (int d = 0; d < kDepth; ++d) load_step(buf[d], c_begin + d * 128);
-  for (int kb = c_begin; kb < c_end; kb += kDepth * 128) {
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
-      if (kb + d * 128 < c_end) {
-        compute(buf[d], kb + d * 128);
-        load_step(buf[d], kb + (d + kDepth) * 128);
+    for (int d = 0; d < kBwdDepth; ++d) {
+      if (kb + d * stride < c_end) {
+        compute(buf[d], kb + d * stride);
+        load_step(buf[d], kb + (d + kBwdDepth) * stride);
       }
     }
   }
 
+  // D layout: column slot = lane % 16 = weight row within the 16-row group, token rows 4 * (lane / 16) + v.
+  // Every wave stores its 16 x 64 tile over the dead decode table; the 4 tiles of a row group are summed.
+  __syncthreads();
+  float* my = red + wave16 * (16 * 64);
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int vv = 0; vv < 4; ++vv) my[(4 * g + vv) * 64 + 16 * u + i] = acc[u][vv];
+  __syncthreads();
   float* out = p.part + (int64_t)split * p.M * p.h;
+  for (int idx = threadIdx.x; idx < p.M * 256; idx += kFewThreads) {
+    const int m = idx >> 8, rr = idx & 255;
+    const int row = slab * 256 + rr;
+    const float* src = red + (rr >> 6) * (16 * 64) + m * 64 + (rr & 63);
+    float t = 0.0f;
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int row = r0 + 16 * u + i;                         // D column slot = lane % 16 = weight row
-    if (row < p.h) {
-#pragma unroll
-      for (int vv = 0; vv < 4; ++vv) {
-        const int m = 4 * g + vv;
-        if (m < p.M) out[(int64_t)m * p.h + row] = acc[u][vv];
-      }
-    }
+    for (int c = 0; c < 4; ++c) t += src[c * 4 * 16 * 64];
+    if (row < p.h) __hip_atomic_store(out + (int64_t)m * p.h + row, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  if (arrive_last(p.ctr + slab, (unsigned)p.splits + (p.r > 0 ? 1u : 0u), &flag)) finalize_slab<true>(p, slab, smem);
 }
 
-// ---- finalize -------------------------------------------------------------------------------------
-// out[m][n] = bf16( sum_s part[s][m][n] + scale * sum_j T[m][j] * B(j, n) ),  T = sum_p lpart[p]
-// forward: B(j, n) = L2[j][n] (Bmat is r x N); backward: B(j, n) = L1[n][j] (Bmat is N x r).
-// Workgroup 0 also stores T as a [hi | lo] bf16 pair (M x 2r) when hl is given.
-struct FinArgs {
-  const float* part; int splits; int M, N;
-  const float* lpart; int n_lparts; int r; float scale;
-  const uint16_t* Bmat;
-  uint16_t* out; uint16_t* hl;
-};
-
-constexpr int kFinThreads = 256;
-
-template <bool BWD>
-__global__ __launch_bounds__(kFinThreads) void fewtok_finalize_kernel(const FinArgs p) {
-  constexpr int RC = 128;                                    // rank columns staged at a time
-  __shared__ float Ts[16 * 256];                             // T[m][j], unscaled
-  constexpr int kBsPitch = RC + 8;                           // backward tile row pitch: keeps 16-byte alignment
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[128 * kBsPitch];   // adapter tile: forward [RC][128], backward [128][pitch]
-  const int n0 = blockIdx.x * 128;
-  for (int e = threadIdx.x; e < p.M * p.r; e += kFinThreads) {
-    float s = 0.0f;
-#pragma unroll 4
-    for (int q = 0; q < p.n_lparts; ++q) s += p.lpart[(int64_t)q * p.M * p.r + e];
-    Ts[e] = s;
-    if (p.hl && blockIdx.x == 0) {
-      const int m = e / p.r, j = e - m * p.r;
-      const uint16_t hi = bf16_bits(s);
-      p.hl[(int64_t)m * 2 * p.r + j] = hi;
-      p.hl[(int64_t)m * 2 * p.r + p.r + j] = bf16_bits(s - bf16_lo_to_f32(hi));
-    }
-  }
-  const int c = threadIdx.x & 127, mh = threadIdx.x >> 7;    // column within the slab, token half
-  const int n = n0 + c;
-  float acc[8], lora[8];
-#pragma unroll
-  for (int u = 0; u < 8; ++u) { acc[u] = 0.0f; lora[u] = 0.0f; }
-  if (n < p.N) {
-#pragma unroll 4
-    for (int sp = 0; sp < p.splits; ++sp) {
-      const float* ps = p.part + (int64_t)sp * p.M * p.N + n;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int m = mh * 8 + u;
-        if (m < p.M) acc[u] += ps[(int64_t)m * p.N];
-      }
-    }
-  }
-  for (int j0 = 0; j0 < p.r; j0 += RC) {
-    const int rc = (p.r - j0 < RC) ? p.r - j0 : RC;
-    __syncthreads();                                         // Ts written / previous tile consumed
-    // all loads of the tile are issued at once (coalesced); the products below run out of LDS
-    u32x4 stage[RC / 16];
-    if (!BWD) {                                              // rows j of L2, 128 columns = 16 chunks of 16 bytes
-#pragma unroll
-      for (int it = 0; it < RC / 16; ++it) {
-        const int j = it * 16 + (threadIdx.x >> 4), cc = (threadIdx.x & 15) * 8;
-        stage[it] = u32x4{0u, 0u, 0u, 0u};
-        if (j < rc && n0 + cc < p.N) stage[it] = *(const u32x4*)(p.Bmat + (int64_t)(j0 + j) * p.N + n0 + cc);
-      }
-#pragma unroll
-      for (int it = 0; it < RC / 16; ++it) {
-        const int j = it * 16 + (threadIdx.x >> 4), cc = (threadIdx.x & 15) * 8;
-        if (j < rc) *(u32x4*)(Bs + j * 128 + cc) = stage[it];
-      }
-    } else {                                                 // rows n0 + c of L1, rc rank columns = rc / 8 chunks
-      const int cpr = rc >> 3;                               // chunks per row
-#pragma unroll
-      for (int it = 0; it < RC / 16; ++it) {
-        const int e = it * kFinThreads + threadIdx.x;
-        const int cc = e / cpr, ch = e - cc * cpr;
-        stage[it] = u32x4{0u, 0u, 0u, 0u};
-        if (cc < 128 && n0 + cc < p.N) stage[it] = *(const u32x4*)(p.Bmat + (int64_t)(n0 + cc) * p.r + j0 + ch * 8);
-      }
-#pragma unroll
-      for (int it = 0; it < RC / 16; ++it) {
-        const int e = it * kFinThreads + threadIdx.x;
-        const int cc = e / cpr, ch = e - cc * cpr;
-        if (cc < 128) *(u32x4*)(Bs + cc * kBsPitch + ch * 8) = stage[it];
-      }
-    }
-    __syncthreads();
-    for (int j = 0; j < rc; ++j) {
-      const float b = bf16_lo_to_f32(BWD ? Bs[c * kBsPitch + j] : Bs[j * 128 + c]);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) lora[u] = __builtin_fmaf(Ts[(mh * 8 + u) * p.r + j0 + j], b, lora[u]);
-    }
-  }
-  if (n >= p.N) return;
-#pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const int m = mh * 8 + u;
-    if (m < p.M) p.out[(int64_t)m * p.N + n] = bf16_bits(acc[u] + p.scale * lora[u]);
-  }
-}
-
-// One 8-wave workgroup occupies a CU (its decode table alone is 64 KB of LDS), so the launch is sized to
-// fit the 256 CUs in a single round: slabs * splits + adapter workgroups <= 256 whenever possible.
+// One 16-wave workgroup occupies a CU (its LDS map is 133 KB), so the launch is sized to fit the 256 CUs
+// in a single round: slabs * splits + adapter workgroups <= 256 whenever possible.
 int pick_splits(int slabs, int steps_total, int min_steps, int reserved) {
   int splits = (256 - reserved) / slabs;
   int cap = steps_total / min_steps;
@@ -546,46 +730,56 @@ int pick_splits(int slabs, int steps_total, int min_steps, int reserved) {
 int fewtok_fwd_lparts(int h, int r) { return r > 0 ? (h + kLoraK - 1) / kLoraK : 0; }
 int fewtok_bwd_lparts(int o, int r) { return r > 0 ? (o + kLoraN - 1) / kLoraN : 0; }
 // the split count leaves room for the adapter workgroups of the largest rank (same workspace for every r)
-int fewtok_fwd_splits(int h, int o) { return pick_splits((o + 255) / 256, (h + 31) / 32, 16, fewtok_fwd_lparts(h, 16)); }
-int fewtok_bwd_splits(int h, int o) { return pick_splits((h + 255) / 256, (o + 127) / 128, 4, fewtok_bwd_lparts(o, 16)); }
+int fewtok_fwd_splits(int h, int o) { return pick_splits((o + 255) / 256, (h + 15) / 16, 32, fewtok_fwd_lparts(h, 16)); }
+int fewtok_bwd_splits(int h, int o) { return pick_splits((h + 255) / 256, (o + 127) / 128, 8, fewtok_bwd_lparts(o, 16)); }
+
+int fewtok_fwd_slabs(int o) { return (o + 255) / 256; }
+int fewtok_bwd_slabs(int h) { return (h + 255) / 256; }
 
 hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L1,
-                             int r, float* lpart, hipStream_t st) {
+                             const uint16_t* L2, int r, float scale, float* lpart, unsigned* ctr, uint16_t* Y,
+                             uint16_t* T_hl, hipStream_t st) {
   FewArgs a;
   a.X = X; a.M = M; a.packed = w.packed; a.code = w.code; a.c1 = w.c1; a.mean = w.mean;
   a.h = (int)w.rows; a.o = (int)w.cols; a.part = part;
-  const int steps = (a.h + 31) / 32;
-  a.per_split = ((steps + splits - 1) / splits) * 32;
-  a.n_slabs = (a.o + 255) / 256; a.splits = splits;
-  a.L = L1; a.r = r; a.lpart = lpart;
-  const int lora_wgs = fewtok_fwd_lparts(a.h, r);
-  hipLaunchKernelGGL(fewtok_fwd_kernel, dim3((unsigned)(a.n_slabs * splits + lora_wgs)), dim3(kFewThreads), 0, st, a);
+  const int steps = (a.h + 15) / 16;
+  a.per_split = ((steps + splits - 1) / splits) * 16;
+  a.n_slabs = fewtok_fwd_slabs(a.o); a.splits = splits;
+  a.L = L1; a.r = r; a.lpart = lpart; a.n_lparts = fewtok_fwd_lparts(a.h, r);
+  a.ctr = ctr; a.Bmat = L2; a.scale = scale; a.out = Y; a.hl = r > 0 ? T_hl : nullptr;
+  if (a.n_slabs > kCtrLora) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(a.n_slabs * splits + a.n_lparts));
+  if (M <= 8) hipLaunchKernelGGL(fewtok_fwd_kernel<8>, grid, dim3(kFewThreads), 0, st, a);
+  else hipLaunchKernelGGL(fewtok_fwd_kernel<16>, grid, dim3(kFewThreads), 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L2,
-                             int r, float* lpart, hipStream_t st) {
+hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L1,
+                             const uint16_t* L2, int r, float scale, float* lpart, unsigned* ctr, uint16_t* dX,
+                             uint16_t* U_hl, hipStream_t st) {
   FewArgs a;
   a.X = dY; a.M = M; a.packed = w.packed; a.code = w.code; a.c1 = w.c1; a.mean = w.mean;
   a.h = (int)w.rows; a.o = (int)w.cols; a.part = part;
   const int steps = (a.o + 127) / 128;
   a.per_split = ((steps + splits - 1) / splits) * 128;
-  a.n_slabs = (a.h + 255) / 256; a.splits = splits;
-  a.L = L2; a.r = r; a.lpart = lpart;
-  const int lora_wgs = fewtok_bwd_lparts(a.o, r);
-  hipLaunchKernelGGL(fewtok_bwd_kernel, dim3((unsigned)(a.n_slabs * splits + lora_wgs)), dim3(kFewThreads), 0, st, a);
+  a.n_slabs = fewtok_bwd_slabs(a.h); a.splits = splits;
+  a.L = L2; a.r = r; a.lpart = lpart; a.n_lparts = fewtok_bwd_lparts(a.o, r);
+  a.ctr = ctr; a.Bmat = L1; a.scale = scale; a.out = dX; a.hl = r > 0 ? U_hl : nullptr;
+  if (a.n_slabs > kCtrLora) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fewtok_bwd_kernel, dim3((unsigned)(a.n_slabs * splits + a.n_lparts)), dim3(kFewThreads), 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_fewtok_finalize(bool bwd, const float* part, int splits, int M, int N, const float* lpart,
-                                  int n_lparts, int r, float scale, const uint16_t* Bmat, uint16_t* out, uint16_t* hl,
-                                  hipStream_t st) {
-  FinArgs a;
-  a.part = part; a.splits = splits; a.M = M; a.N = N; a.lpart = lpart; a.n_lparts = n_lparts; a.r = r;
-  a.scale = scale; a.Bmat = Bmat; a.out = out; a.hl = hl;
-  dim3 grid((unsigned)((N + 127) / 128));
-  if (bwd) hipLaunchKernelGGL(fewtok_finalize_kernel<true>, grid, dim3(kFinThreads), 0, st, a);
-  else hipLaunchKernelGGL(fewtok_finalize_kernel<false>, grid, dim3(kFinThreads), 0, st, a);
+// Zeroes the counter header of a workspace (a fill kernel, not a memset node, so it can be captured in a graph).
+namespace {
+__global__ void zero_header_kernel(unsigned* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+}  // namespace
+hipError_t launch_workspace_init(void* workspace, hipStream_t st) {
+  const int n = (int)(kWorkspaceHeaderBytes / sizeof(unsigned));
+  hipLaunchKernelGGL(zero_header_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (unsigned*)workspace, n);
   return hipGetLastError();
 }
 

@@ -18,7 +18,7 @@ struct NF4Dev {            // device views of one quantised h x o weight
 
 // quantize.hip
 constexpr size_t kQuantBinsBytes = 256 * sizeof(unsigned long long);
-hipError_t launch_quantize(const float* W, int64_t elems, uint8_t* packed, uint8_t* code, float* c1,
+hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
                            float* mean, void* scratch, hipStream_t st);
 
 // dequant.hip
@@ -45,23 +45,28 @@ hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int 
                                 hipStream_t st);
 hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st);
 
-// fewtok.hip: few-token (M <= 16) streaming path: one main launch (fp32 split partials of the frozen
-// product plus partials of the adapter's inner product), one finalize launch per output.
+// fewtok.hip: few-token (M <= 16) streaming path, one launch per call: fp32 split partials of the frozen product,
+// partials of the adapter's inner product, and the output written by the last workgroup to arrive at each slab
+// of 256 outputs.  `ctr` points at the workspace header (kWorkspaceHeaderBytes, zero on entry, zero again on exit).
 constexpr int kFewTokens = 16;
+constexpr size_t kWorkspaceHeaderBytes = 16384;
+constexpr int kFewMaxSlabs = 4095;
 int fewtok_fwd_splits(int h, int o);
 int fewtok_bwd_splits(int h, int o);
+int fewtok_fwd_slabs(int o);
+int fewtok_bwd_slabs(int h);
 int fewtok_fwd_lparts(int h, int r);          // number of [M][r] partial slots of T = X L1
 int fewtok_bwd_lparts(int o, int r);          // ... of U = dY L2^T
-//   part[split][M][o] = X (M x h) * dequant(W) over the split's rows;  lpart[p][M][r] = partials of X L1
+//   Y = bf16(X dequant(W) + scale (X L1) L2); part: [splits][M][o] floats, lpart: [lparts][M][r] floats;
+//   T_hl (M x 2r, may be NULL) receives X L1 as [hi | lo].
 hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L1,
-                             int r, float* lpart, hipStream_t st);
-//   part[split][M][h] = dY (M x o) * dequant(W)^T over the split's columns;  lpart = partials of dY L2^T
-hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L2,
-                             int r, float* lpart, hipStream_t st);
-//   out[m][n] = bf16(sum of splits + scale * sum_j T[m][j] * B(j, n)), T = sum of lpart;
-//   forward: Bmat = L2 (r x N); backward: Bmat = L1 (N x r).  hl (M x 2r, may be NULL) receives T as [hi | lo].
-hipError_t launch_fewtok_finalize(bool bwd, const float* part, int splits, int M, int N, const float* lpart,
-                                  int n_lparts, int r, float scale, const uint16_t* Bmat, uint16_t* out, uint16_t* hl,
-                                  hipStream_t st);
+                             const uint16_t* L2, int r, float scale, float* lpart, unsigned* ctr, uint16_t* Y,
+                             uint16_t* T_hl, hipStream_t st);
+//   dX = bf16(dY dequant(W)^T + scale (dY L2^T) L1^T); part: [splits][M][h], lpart: [lparts][M][r];
+//   U_hl (M x 2r, may be NULL) receives dY L2^T as [hi | lo].
+hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L1,
+                             const uint16_t* L2, int r, float scale, float* lpart, unsigned* ctr, uint16_t* dX,
+                             uint16_t* U_hl, hipStream_t st);
+hipError_t launch_workspace_init(void* workspace, hipStream_t st);
 
 }  // namespace qlora

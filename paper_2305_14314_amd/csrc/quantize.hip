@@ -148,7 +148,7 @@ __global__ __launch_bounds__(64) void dq_mean_kernel(const unsigned long long* _
 __global__ __launch_bounds__(kDqBlock) void dq_encode_kernel(const float* __restrict__ c2, int64_t n,
                                                              const float* __restrict__ mean_ptr,
                                                              uint8_t* __restrict__ code,
-                                                             float* __restrict__ c1) {
+                                                             float* __restrict__ c1, uint32_t rows, uint32_t bpr) {
   __shared__ float wmax[kDqBlock / 64];
   const int64_t b = (int64_t)blockIdx.x * kDqBlock + threadIdx.x;
   const float mean = *mean_ptr;
@@ -159,12 +159,16 @@ __global__ __launch_bounds__(kDqBlock) void dq_encode_kernel(const float* __rest
   const float amax = __builtin_fmaxf(__builtin_fmaxf(wmax[0], wmax[1]), __builtin_fmaxf(wmax[2], wmax[3]));
   float rc1 = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(kF8Max, amax);
   if (__builtin_isinf(rc1)) rc1 = 0.0f;
-  if (b < n) code[b] = (uint8_t)e4m3_encode(__fmul_rn(d, rc1));
+  if (b < n) {                                               // runs follow the flattened order, storage is column-group-major
+    const uint32_t row = (uint32_t)b / bpr, blk = (uint32_t)b - row * bpr;
+    code[code_pos(rows, (int)bpr, row, (int)blk)] = (uint8_t)e4m3_encode(__fmul_rn(d, rc1));
+  }
   if (threadIdx.x == 0) c1[blockIdx.x] = amax;
 }
 
-hipError_t launch_quantize(const float* W, int64_t elems, uint8_t* packed, uint8_t* code, float* c1,
+hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
                            float* mean, void* scratch, hipStream_t st) {
+  const int64_t elems = rows * cols;
   const int64_t n = elems / kBlock;
   unsigned long long* bins = (unsigned long long*)scratch;           // 256 x u64
   float* c2 = (float*)((char*)scratch + 256 * sizeof(unsigned long long));
@@ -177,7 +181,8 @@ hipError_t launch_quantize(const float* W, int64_t elems, uint8_t* packed, uint8
                      (const float4*)W, n_vec4, (uint16_t*)packed, c2, bins);
   hipLaunchKernelGGL(dq_mean_kernel, dim3(1), dim3(64), 0, st, bins, (uint32_t)n, mean);
   const int64_t n1 = (n + kDqBlock - 1) / kDqBlock;
-  hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)n1), dim3(kDqBlock), 0, st, c2, n, mean, code, c1);
+  hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)n1), dim3(kDqBlock), 0, st, c2, n, mean, code, c1,
+                     (uint32_t)rows, (uint32_t)(cols / kBlock));
   return hipGetLastError();
 }
 

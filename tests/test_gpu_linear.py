@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import bits_f64, dev_bf16, dev_f32, host_bits, upload_quant
+from gpu_util import bits_f64, dev_bf16, dev_f32, download_quant, host_bits, upload_quant
 
 pytestmark = pytest.mark.gpu
 
@@ -131,8 +131,7 @@ def test_full_size_sampled(oracle, synth, config, layer):
     Wd = synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(config, layer, "W"))
     Wq = ql.qlora_nf4_quantize(Wd)
     del Wd
-    q = dict(packed=Wq.packed.cpu().numpy(), code=Wq.code.cpu().numpy(), c1=Wq.c1.cpu().numpy(),
-             mean=np.float32(Wq.mean.cpu().numpy()[0]), rows=h, cols=o, blocksize=64, dq_blocksize=256)
+    q = download_quant(Wq)
     What = oracle.nf4_dequant(q)
     hX = synth.normal_bf16((M, h), 1.0, synth.tensor_seed(config, layer, "X"))
     hdY = synth.normal_bf16((M, o), 1.0, synth.tensor_seed(config, layer, "dY"))

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_util import dev_f32, host_bits, host_u8, host_u32, upload_quant
+from gpu_util import code_to_flat, dev_f32, host_bits, host_u8, host_u32, upload_quant
 
 pytestmark = pytest.mark.gpu
 
@@ -14,7 +14,7 @@ def _compare_quant(oracle, W_host, Wq, tag):
     np.testing.assert_array_equal(host_u8(Wq.packed), q["packed"], err_msg=f"{tag}: packed nibbles")
     assert host_u32(Wq.mean)[0] == np.float32(q["mean"]).view(np.uint32), f"{tag}: mean"
     np.testing.assert_array_equal(host_u32(Wq.c1), q["c1"].view(np.uint32), err_msg=f"{tag}: c1")
-    np.testing.assert_array_equal(host_u8(Wq.code), q["code"], err_msg=f"{tag}: c2 codes")
+    np.testing.assert_array_equal(code_to_flat(host_u8(Wq.code), Wq.rows, Wq.cols), q["code"], err_msg=f"{tag}: c2 codes")
     return q
 
 
