@@ -8,11 +8,13 @@
 //                        over the split's share of the contraction, for a slab of 256 outputs
 //   adapter workgroups : lpart[p][m][j] = partial sums of the adapter's inner product T = X L1 or U = dY L2^T
 //   last arriver       : every workgroup counts itself in at its slab's arrival counter (device-scope atomic
-//                        after a fence); the adapter, once all its workgroups are in, counts itself in at every
-//                        slab.  Whoever completes a slab's count computes
+//                        after a fence); the workgroup that brings in a slab's last split then meets the adapter
+//                        workgroups, each of which counts itself in at every slab's handshake word.  Whoever
+//                        completes that count computes
 //                        out = bf16( sum of splits + s * (sum of lpart) * L2 )  resp.  ... * L1^T  -- one rounding.
-//                        Nobody waits for anybody, so the scheme cannot hang; the sums are taken in a fixed
-//                        order, so results do not depend on who arrives last.
+//                        The only wait is a bounded poll of the last split for the adapter, so every wave exits
+//                        whatever the scheduling; the sums are taken in a fixed order, so results do not depend
+//                        on who arrives last.
 // The counters live in the zeroed header of the caller's workspace and are reset by the last arriver.  A kernel
 // boundary costs ~3 us of idle GPU plus ~4 us of fixed launch cost here, which a separate reduction kernel
 // would pay on top of a 20-40 us stream.
@@ -32,13 +34,13 @@ namespace qlora {
 
 namespace {
 
-constexpr int kFewThreads = 1024;            // 16 waves share one replicated decode table
+constexpr int kFewThreads = 1024;            // 16 waves share one replicated decode table (8 where 256 VGPRs are needed)
 constexpr int kWaves = kFewThreads / 64;
 constexpr int kLutCopies = 32;
 constexpr int kBwdDepth = 2;
 constexpr int kLoraDepth = 2;
-constexpr int kLoraK = 2048;                 // forward: rows of L1 per adapter workgroup
-constexpr int kLoraN = 4096;                 // backward: columns of L2 per adapter workgroup
+constexpr int kLoraK = 1024;                 // forward: rows of L1 per adapter workgroup (short: they must not arrive last)
+constexpr int kLoraN = 1024;                 // backward: columns of L2 per adapter workgroup
 
 // LDS map of a main workgroup.  The decode table is dead once the main loop is over, so the cross-wave
 // sums reuse the space from offset 0.
@@ -49,9 +51,10 @@ constexpr int kStripOff = kUnitOff + 1024;                   // float[kWaves][2]
 constexpr int kSmemBytes = kStripOff + kWaves * 256;
 static_assert(kLutBytes <= kRedBytes && kSmemBytes <= 160 * 1024, "LDS map");
 
+template <int NT>
 __device__ __forceinline__ void init_pair_lut(f32x2* lut2 /* [256][32] */, float* unit /* [256] */) {
   constexpr float t[16] = {QLORA_NF4_VALUES};
-  for (int e = threadIdx.x; e < 256 * kLutCopies; e += kFewThreads) {
+  for (int e = threadIdx.x; e < 256 * kLutCopies; e += NT) {
     const int b = e / kLutCopies;
     f32x2 v;
     v[0] = t[b & 15];
@@ -77,14 +80,17 @@ struct FewArgs {
   float* lpart;                              // [n_lparts][M][r]
   int n_lparts;
   // output stage, run by the last workgroup to arrive at a slab
-  unsigned* ctr;                             // arrival counters: one per slab, kCtrLora for the adapter; zero on entry and exit
+  unsigned* ctr;                             // arrival counters (split arrivals, adapter handshakes, adapter count); zero on entry and exit
   const uint16_t* Bmat;                      // forward: L2 (r x o); backward: L1 (h x r)
   float scale;
   uint16_t* out;                             // M x N bf16
   uint16_t* hl;                              // M x 2r: T (resp. U) as a [hi | lo] bf16 pair, or NULL
 };
 
-constexpr int kCtrLora = 4095;               // counter index of the adapter workgroups; slabs use [0, 4095)
+// Counter map of the workspace header (4096 words): [slab] counts the splits of a slab; [kCtrShake + slab] is the
+// handshake of the slab's last split with the adapter workgroups.
+constexpr int kCtrShake = 2048;
+constexpr int kSpinLimit = 64;               // bounded wait (polls) of a slab's last split for the adapter
 
 // Workgroup b runs on die (XCD) b % 8, and each die has its own L2.  The work list -- adapter partials first,
 // then (split, slab) pairs in split-major order -- is cut into 8 contiguous pieces, one per die, so that the
@@ -119,40 +125,103 @@ __device__ __forceinline__ bool arrive_last(unsigned* c, unsigned total, volatil
   return *flag != 0;
 }
 
+// The workgroup that brought in a slab's last split meets the adapter here: the slab's handshake word counts the
+// adapter workgroups (each counts itself in at every slab) plus this one.  The adapter's workgroups read a few
+// hundred KB and are normally long done; when they are a little late (the smallest layers, cold adapter matrices)
+// the split waits for them -- a BOUNDED number of polls, so every wave exits whatever happens -- and only then
+// counts itself in.  Whoever completes the count owns the output stage: true = this workgroup.
+__device__ __forceinline__ bool meet_adapter(unsigned* shake, unsigned n_adapter, volatile int* flag) {
+  __syncthreads();                                           // everybody has read the previous flag
+  if (threadIdx.x == 0) {
+    for (int it = 0; it < kSpinLimit; ++it) {
+      if (__hip_atomic_load(shake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_adapter) break;
+      __builtin_amdgcn_s_sleep(16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");       // hands the splits' partials on if an adapter workgroup is last
+    const unsigned old = atomicAdd(shake, 1u);
+    const int mine = old == n_adapter;
+    if (mine) {
+      atomicExch(shake, 0u);
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // the adapter's partials
+    }
+    *flag = mine;
+  }
+  __syncthreads();
+  return *flag != 0;
+}
+
 // ---- output stage ---------------------------------------------------------------------------------
 // out[m][n] = bf16( sum_s part[s][m][n] + scale * sum_j T[m][j] * B(j, n) ),  T = sum_p lpart[p], for the 256
-// outputs n of one slab; forward: B(j, n) = L2[j][n]; backward: B(j, n) = L1[n][j].  Run by all 1024 threads of
-// one workgroup: a thread owns one column and four tokens.  Slab 0 also stores T as a [hi | lo] bf16 pair.
-template <bool BWD>
-__device__ void finalize_slab(const FewArgs& p, int slab, char* smem) {
+// outputs n of one slab; forward: B(j, n) = L2[j][n]; backward: B(j, n) = L1[n][j].  Run by all NT threads of one
+// workgroup: a thread owns one column and four tokens per pass.  Slab 0 also stores T as a [hi | lo] bf16 pair.
+template <bool BWD, int NT>
+__device__ void finalize_slab(const FewArgs& p, int slab, char* smem, unsigned* shake, volatile int* flag) {
   constexpr int RC = 64;                                     // rank columns staged at a time
   constexpr int kPitch = RC + 8;                             // backward tile row pitch keeps 16-byte alignment
+  constexpr int P = 1024 / NT;                               // passes over the tokens (4 per 256 threads and pass)
+  constexpr int IT = 2048 / NT;                              // an adapter tile is at most 2048 chunks of 16 bytes
   float* Ts = (float*)smem;                                  // T[j][m], unscaled: 16 KB
   uint16_t* Bs = (uint16_t*)(smem + 16384);                  // forward [RC][256], backward [256][kPitch]
   const int N = BWD ? p.h : p.o;
   const int n0 = slab * 256;
-  const int c = threadIdx.x & 255, m0 = 4 * (threadIdx.x >> 8);   // column within the slab, first of four tokens
+  const int c = threadIdx.x & 255, tq = threadIdx.x >> 8;    // column within the slab, token quad of a pass
   const int n = n0 + c;
   const bool n_ok = n < N;
-  const bool active = m0 < p.M;                              // uniform per wave
 
-  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-  if (active) {
-    const int64_t nn = n_ok ? n : 0;
-#pragma unroll 4
-    for (int sp = 0; sp < p.splits; ++sp) {
-      const float* ps = p.part + (int64_t)sp * p.M * N + nn;
+  // Everything that does not depend on the adapter's partials is loaded first: the split partials of this
+  // thread's outputs and the first tile of the adapter's outer matrix.
+  u32x4 stage[IT];
+  int dst[IT];
+  auto stage_load = [&](int j0, int rc) {
+    const int cpr = rc >> 3;                                 // backward: 16-byte chunks per row
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int m = m0 + u;
-        const float v = ps[(int64_t)(m < p.M ? m : 0) * N];
-        acc[u] += m < p.M ? v : 0.0f;
+    for (int it = 0; it < IT; ++it) {
+      const int e = it * NT + threadIdx.x;
+      bool ok, inside;
+      int64_t off;
+      if (!BWD) {                                            // row j0 + e / 32 of L2, columns n0 + 8 (e % 32) .. +7
+        const int j = e >> 5, ch = e & 31;
+        inside = j < rc;
+        ok = inside && n0 + 8 * ch < N;
+        off = (int64_t)(j0 + j) * N + n0 + 8 * ch;
+        dst[it] = j * 256 + 8 * ch;
+      } else {                                               // row n0 + cc of L1, rank columns j0 + 8 ch .. +7
+        const int cc = e / cpr, ch = e - cc * cpr;
+        inside = cc < 256;
+        ok = inside && n0 + cc < N;
+        off = (int64_t)(n0 + cc) * p.r + j0 + 8 * ch;
+        dst[it] = cc * kPitch + 8 * ch;
+      }
+      const u32x4 v = *(const u32x4*)(p.Bmat + (ok ? off : 0));
+      stage[it] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+      if (!inside) dst[it] = -1;                             // outside the tile: nothing to store
+    }
+  };
+  if (p.r > 0) stage_load(0, p.r < RC ? p.r : RC);           // without an adapter Bmat may be NULL: no load at all
+
+  float acc[P][4], lora[P][4];
+#pragma unroll
+  for (int q = 0; q < P; ++q) {
+    const int m0 = 4 * tq + q * (NT / 64);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { acc[q][u] = 0.0f; lora[q][u] = 0.0f; }
+    if (m0 < p.M) {                                          // uniform per wave
+      const int64_t nn = n_ok ? n : 0;
+#pragma unroll 4
+      for (int sp = 0; sp < p.splits; ++sp) {
+        const float* ps = p.part + (int64_t)sp * p.M * N + nn;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int m = m0 + u;
+          const float v = ps[(int64_t)(m < p.M ? m : 0) * N];
+          acc[q][u] += m < p.M ? v : 0.0f;
+        }
       }
     }
   }
-  float lora[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (p.r > 0) {
-    for (int e = threadIdx.x; e < p.M * p.r; e += kFewThreads) {
+    if (shake && !meet_adapter(shake, (unsigned)p.n_lparts, flag)) return;         // the adapter came after the bounded wait: the slab is its
+    for (int e = threadIdx.x; e < p.M * p.r; e += NT) {
       float t = 0.0f;
       for (int q0 = 0; q0 < p.n_lparts; q0 += 8) {           // 8 loads in flight, then a fixed-order sum
         float v[8];
@@ -175,78 +244,63 @@ __device__ void finalize_slab(const FewArgs& p, int slab, char* smem) {
     }
     for (int j0 = 0; j0 < p.r; j0 += RC) {
       const int rc = (p.r - j0 < RC) ? p.r - j0 : RC;
-      const int cpr = rc >> 3;                               // backward: 16-byte chunks per row
-      u32x4 stage[2];
-      int dst[2];
-#pragma unroll
-      for (int it = 0; it < 2; ++it) {
-        const int e = it * kFewThreads + threadIdx.x;
-        bool ok;
-        int64_t off;
-        if (!BWD) {                                          // row j0 + e / 32 of L2, columns n0 + 8 (e % 32) .. +7
-          const int j = e >> 5, ch = e & 31;
-          ok = j < rc && n0 + 8 * ch < N;
-          off = (int64_t)(j0 + j) * N + n0 + 8 * ch;
-          dst[it] = j * 256 + 8 * ch;
-        } else {                                             // row n0 + cc of L1, rank columns j0 + 8 ch .. +7
-          const int cc = e / cpr, ch = e - cc * cpr;
-          ok = cc < 256 && n0 + cc < N;
-          off = (int64_t)(n0 + cc) * p.r + j0 + 8 * ch;
-          dst[it] = cc * kPitch + 8 * ch;
-        }
-        const u32x4 v = *(const u32x4*)(p.Bmat + (ok ? off : 0));
-        stage[it] = ok ? v : u32x4{0u, 0u, 0u, 0u};
-        if (!ok && (BWD ? (e / cpr >= 256) : ((e >> 5) >= rc))) dst[it] = -1;   // outside the tile: nothing to store
+      if (j0 > 0) {
+        __syncthreads();                                     // previous tile consumed
+        stage_load(j0, rc);
       }
-      if (j0 > 0) __syncthreads();                           // previous tile consumed
 #pragma unroll
-      for (int it = 0; it < 2; ++it)
+      for (int it = 0; it < IT; ++it)
         if (dst[it] >= 0) *(u32x4*)(Bs + dst[it]) = stage[it];
       __syncthreads();                                       // tile and Ts visible
-      if (active) {
-#pragma unroll 8
-        for (int j = 0; j < rc; ++j) {
-          const float b = bf16_lo_to_f32(BWD ? Bs[c * kPitch + j] : Bs[j * 256 + c]);
-          const f32x4 t = *(const f32x4*)&Ts[(j0 + j) * 16 + m0];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) lora[u] = __builtin_fmaf(t[u], b, lora[u]);
+      for (int q = 0; q < P; ++q) {
+        const int m0 = 4 * tq + q * (NT / 64);
+        if (m0 < p.M) {
+#pragma unroll 8
+          for (int j = 0; j < rc; ++j) {
+            const float b = bf16_lo_to_f32(BWD ? Bs[c * kPitch + j] : Bs[j * 256 + c]);
+            const f32x4 t = *(const f32x4*)&Ts[(j0 + j) * 16 + m0];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) lora[q][u] = __builtin_fmaf(t[u], b, lora[q][u]);
+          }
         }
       }
     }
   }
-  if (!n_ok || !active) return;
+  if (!n_ok) return;
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (m0 + u < p.M) p.out[(int64_t)(m0 + u) * N + n] = bf16_bits(acc[u] + p.scale * lora[u]);
+  for (int q = 0; q < P; ++q) {
+    const int m0 = 4 * tq + q * (NT / 64);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (m0 + u < p.M) p.out[(int64_t)(m0 + u) * N + n] = bf16_bits(acc[q][u] + p.scale * lora[q][u]);
+  }
 }
 
-// Called by every adapter workgroup after its partial is stored.  The last of them counts the adapter in at
-// every slab; a slab whose splits were all in already (rare: the adapter reads far less than a split) is
-// finished right here.
-template <bool BWD>
+// Called by every adapter workgroup after its partial is stored: it counts itself in at every slab's handshake.
+// A slab whose count it completes (the slab's splits gave up waiting: rare) is finished right here.
+template <bool BWD, int NT>
 __device__ void adapter_arrive(const FewArgs& p, char* smem, volatile int* flag) {
-  if (!arrive_last(p.ctr + kCtrLora, (unsigned)p.n_lparts, flag)) return;
   int* npend = (int*)(smem + 65536);                         // beyond what finalize_slab uses
   int* pend = npend + 1;
   if (threadIdx.x == 0) *npend = 0;
-  __syncthreads();
-  const unsigned total = (unsigned)p.splits + 1u;
-  for (int t = threadIdx.x; t < p.n_slabs; t += kFewThreads) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");       // every adapter partial, seen through the count above
-    const unsigned old = atomicAdd(p.ctr + t, 1u);
-    if (old + 1 == total) {
-      atomicExch(p.ctr + t, 0u);
+  __syncthreads();                                           // the partial of this workgroup is stored
+  for (int t = threadIdx.x; t < p.n_slabs; t += NT) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    const unsigned old = atomicAdd(p.ctr + kCtrShake + t, 1u);
+    if (old == (unsigned)p.n_lparts) {                       // every other adapter workgroup and the slab's splits are in
+      atomicExch(p.ctr + kCtrShake + t, 0u);
       pend[atomicAdd(npend, 1)] = t;
     }
   }
   __syncthreads();
   const int n = *npend;
   if (n > 0) {
-    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the splits counted before us
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // everybody counted before us
     __syncthreads();
   }
   for (int q = 0; q < n; ++q) {
-    finalize_slab<BWD>(p, pend[q], smem);
+    finalize_slab<BWD, NT>(p, pend[q], smem, nullptr, flag);
     __syncthreads();
   }
 }
@@ -261,12 +315,13 @@ __device__ void adapter_arrive(const FewArgs& p, char* smem, volatile int* flag)
 // 8 rows: lane (i, g) loads columns 4i .. 4i+3 of rows kb + 8g + j and splits them with byte permutes.
 struct LFwdStep { uint32_t l[8][2]; u32x4 x; };
 
-__device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [kWaves][16][64] */) {
+template <int NT>
+__device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [NT / 64][16][64] */) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave index is uniform
   const int i = lane & 15, g = lane >> 4;
   const int k_begin = wg * kLoraK;
   const int k_end = (k_begin + kLoraK < p.h) ? k_begin + kLoraK : p.h;
-  const int stride = kWaves * 32, kb0 = k_begin + wave * 32; // the waves interleave 32-row steps
+  const int stride = (NT / 64) * 32, kb0 = k_begin + wave * 32; // the waves interleave 32-row steps
   float* out = p.lpart + (int64_t)wg * p.M * p.r;
   for (int j0 = 0; j0 < p.r; j0 += 64) {
     const bool col_ok = j0 + 4 * i < p.r;                    // r % 16 == 0: the 4 columns are in or out together
@@ -317,12 +372,12 @@ __device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [kWaves
 #pragma unroll
       for (int vv = 0; vv < 4; ++vv) my[(4 * g + vv) * 64 + 4 * i + e] = acc[e][vv];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < p.M * 64; idx += kFewThreads) {
+    for (int idx = threadIdx.x; idx < p.M * 64; idx += NT) {
       const int m = idx >> 6, c = idx & 63;
       if (j0 + c < p.r) {
         float t = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) t += red[w * 16 * 64 + idx];
+        for (int w = 0; w < NT / 64; ++w) t += red[w * 16 * 64 + idx];
         __hip_atomic_store(out + (int64_t)m * p.r + j0 + c, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
@@ -333,12 +388,13 @@ __device__ void lora_fwd_partial(const FewArgs& p, int wg, float* red /* [kWaves
 // Both operands are contiguous along n: fragments are plain 16-byte loads.
 struct LBwdStep { u32x4 l[4]; u32x4 y; };
 
-__device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [kWaves][16][64] */) {
+template <int NT>
+__device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [NT / 64][16][64] */) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave index is uniform
   const int i = lane & 15, g = lane >> 4;
   const int n_begin = wg * kLoraN;
   const int n_end = (n_begin + kLoraN < p.o) ? n_begin + kLoraN : p.o;
-  const int stride = kWaves * 32, nb0 = n_begin + wave * 32; // the waves interleave 32-column steps
+  const int stride = (NT / 64) * 32, nb0 = n_begin + wave * 32; // the waves interleave 32-column steps
   float* out = p.lpart + (int64_t)wg * p.M * p.r;
   for (int j0 = 0; j0 < p.r; j0 += 64) {
     auto load_step = [&](LBwdStep& s, int nb) {
@@ -379,12 +435,12 @@ __device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [kWaves
 #pragma unroll
       for (int vv = 0; vv < 4; ++vv) my[(4 * g + vv) * 64 + 16 * e + i] = acc[e][vv];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < p.M * 64; idx += kFewThreads) {
+    for (int idx = threadIdx.x; idx < p.M * 64; idx += NT) {
       const int m = idx >> 6, c = idx & 63;
       if (j0 + c < p.r) {
         float t = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) t += red[w * 16 * 64 + idx];
+        for (int w = 0; w < NT / 64; ++w) t += red[w * 16 * 64 + idx];
         __hip_atomic_store(out + (int64_t)m * p.r + j0 + c, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
@@ -411,10 +467,12 @@ __device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [kWaves
 // through a wave-private LDS strip.
 struct FwdStep { uint32_t pk[8]; u32x4 x; uint32_t code; float c1; };   // raw loads only: nothing here is consumed before compute()
 
-template <int MT>
-__global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p) {
+template <int MT, int NT>
+__global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
   constexpr int NA = MT / 8;                                 // accumulator sets (and MFMAs per column phase)
-  constexpr int kDepth = MT == 8 ? 3 : 2;
+  constexpr int kDepth = 3;
+  constexpr int NW = NT / 64;                                // waves: 16 with 128 VGPRs each, or 8 with 256 (MT = 16)
+  static_assert(NW * MT * 1024 <= kRedBytes, "one [MT][256] fp32 tile per wave");
   __shared__ __attribute__((aligned(256))) char smem[kSmemBytes];
   f32x2* lut2 = (f32x2*)smem;
   float* red = (float*)smem;
@@ -422,8 +480,8 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p
   __shared__ int flag;
   const int work = work_index();
   if (work < p.n_lparts) {
-    lora_fwd_partial(p, work, red);
-    adapter_arrive<false>(p, smem, &flag);
+    lora_fwd_partial<NT>(p, work, red);
+    adapter_arrive<false, NT>(p, smem, &flag);
     return;
   }
 
@@ -470,12 +528,12 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p
   };
 
   // the first loads are in flight while the decode table is built
-  const int stride = kWaves * 16;
+  const int stride = NW * 16;
   const int kb0 = k_begin + wave * 16;
   FwdStep buf[kDepth];
 #pragma unroll
   for (int d = 0; d < kDepth; ++d) load_step(buf[d], kb0 + d * stride);
-  init_pair_lut(lut2, unit);
+  init_pair_lut<NT>(lut2, unit);
   __syncthreads();
 
   f32x4 acc[NA][8];
@@ -534,8 +592,7 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p
 
   // D layout: column slot = lane % 16, rows 4 * (lane / 16) + v.  Row R of accumulator set a is token R % MT of
   // column half (MT == 8 ? R / 8 : a); column within the half = 8 slot + e.  The waves store [MT][256] tiles over
-  // the decode table (dead now) and the tiles are summed; with MT = 16 they do not all fit, so the upper eight
-  // waves hand theirs to the lower eight first.
+  // the decode table (dead now) and the tiles are summed.
   float* out = p.part + (int64_t)split * p.M * p.o;
   auto store_tile = [&](float* my) {
 #pragma unroll
@@ -550,34 +607,18 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p
         }
   };
   constexpr int kTile = MT * 256;
-  int n_tiles = kWaves;
   __syncthreads();                                           // every wave is done with the decode table
-  if (MT == 16) {
-    if (wave >= 8) store_tile(red + (wave - 8) * kTile);
-    __syncthreads();
-    if (wave < 8) {
-      const float* other = red + wave * kTile;
-#pragma unroll
-      for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-#pragma unroll
-          for (int vv = 0; vv < 4; ++vv) acc[a][e][vv] += other[(4 * g + vv) * 256 + a * 128 + 8 * sl + e];
-    }
-    __syncthreads();
-    if (wave < 8) store_tile(red + wave * kTile);
-    n_tiles = 8;
-  } else {
-    store_tile(red + wave * kTile);
-  }
+  store_tile(red + wave * kTile);
   __syncthreads();
-  for (int idx = threadIdx.x; idx < p.M * 256; idx += kFewThreads) {
+  for (int idx = threadIdx.x; idx < p.M * 256; idx += NT) {
     const int n = slab * 256 + (idx & 255);
     float t = 0.0f;
-    for (int w = 0; w < n_tiles; ++w) t += red[w * kTile + idx];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += red[w * kTile + idx];
     if (n < p.o) __hip_atomic_store(out + (int64_t)(idx >> 8) * p.o + n, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  if (arrive_last(p.ctr + slab, (unsigned)p.splits + (p.r > 0 ? 1u : 0u), &flag)) finalize_slab<false>(p, slab, smem);
+  if (!arrive_last(p.ctr + slab, (unsigned)p.splits, &flag)) return;
+  finalize_slab<false, NT>(p, slab, smem, p.ctr + kCtrShake + slab, &flag);
 }
 
 // ---- backward main --------------------------------------------------------------------------------
@@ -590,6 +631,7 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_fwd_kernel(const FewArgs p
 struct BwdStep { u32x4 w[4]; u32x4 y[4]; uint32_t code[4]; float c1[4]; };   // raw loads only
 
 __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p) {
+  constexpr int NT = kFewThreads;
   __shared__ __attribute__((aligned(256))) char smem[kSmemBytes];
   f32x2* lut2 = (f32x2*)smem;
   float* red = (float*)smem;
@@ -597,8 +639,8 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
   __shared__ int flag;
   const int work = work_index();
   if (work < p.n_lparts) {
-    lora_bwd_partial(p, work, red);
-    adapter_arrive<true>(p, smem, &flag);
+    lora_bwd_partial<NT>(p, work, red);
+    adapter_arrive<true, NT>(p, smem, &flag);
     return;
   }
 
@@ -652,7 +694,7 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
   BwdStep buf[kBwdDepth];
 #pragma unroll
   for (int d = 0; d < kBwdDepth; ++d) load_step(buf[d], kb0 + d * stride);   // in flight while the table is built
-  init_pair_lut(lut2, unit);
+  init_pair_lut<NT>(lut2, unit);
   __syncthreads();
 
   f32x4 acc[4];
@@ -710,7 +752,8 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
     for (int c = 0; c < 4; ++c) t += src[c * 4 * 16 * 64];
     if (row < p.h) __hip_atomic_store(out + (int64_t)m * p.h + row, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  if (arrive_last(p.ctr + slab, (unsigned)p.splits + (p.r > 0 ? 1u : 0u), &flag)) finalize_slab<true>(p, slab, smem);
+  if (!arrive_last(p.ctr + slab, (unsigned)p.splits, &flag)) return;
+  finalize_slab<true, NT>(p, slab, smem, p.ctr + kCtrShake + slab, &flag);
 }
 
 // One 16-wave workgroup occupies a CU (its LDS map is 133 KB), so the launch is sized to fit the 256 CUs
@@ -747,10 +790,10 @@ hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* p
   a.n_slabs = fewtok_fwd_slabs(a.o); a.splits = splits;
   a.L = L1; a.r = r; a.lpart = lpart; a.n_lparts = fewtok_fwd_lparts(a.h, r);
   a.ctr = ctr; a.Bmat = L2; a.scale = scale; a.out = Y; a.hl = r > 0 ? T_hl : nullptr;
-  if (a.n_slabs > kCtrLora) return hipErrorInvalidValue;
+  if (a.n_slabs > kFewMaxSlabs) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(a.n_slabs * splits + a.n_lparts));
-  if (M <= 8) hipLaunchKernelGGL(fewtok_fwd_kernel<8>, grid, dim3(kFewThreads), 0, st, a);
-  else hipLaunchKernelGGL(fewtok_fwd_kernel<16>, grid, dim3(kFewThreads), 0, st, a);
+  if (M <= 8) hipLaunchKernelGGL((fewtok_fwd_kernel<8, 1024>), grid, dim3(1024), 0, st, a);
+  else hipLaunchKernelGGL((fewtok_fwd_kernel<16, 512>), grid, dim3(512), 0, st, a);
   return hipGetLastError();
 }
 
@@ -765,7 +808,7 @@ hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* 
   a.n_slabs = fewtok_bwd_slabs(a.h); a.splits = splits;
   a.L = L2; a.r = r; a.lpart = lpart; a.n_lparts = fewtok_bwd_lparts(a.o, r);
   a.ctr = ctr; a.Bmat = L1; a.scale = scale; a.out = dX; a.hl = r > 0 ? U_hl : nullptr;
-  if (a.n_slabs > kCtrLora) return hipErrorInvalidValue;
+  if (a.n_slabs > kFewMaxSlabs) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fewtok_bwd_kernel, dim3((unsigned)(a.n_slabs * splits + a.n_lparts)), dim3(kFewThreads), 0, st, a);
   return hipGetLastError();
 }

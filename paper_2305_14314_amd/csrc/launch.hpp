@@ -50,7 +50,7 @@ hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int
 // of 256 outputs.  `ctr` points at the workspace header (kWorkspaceHeaderBytes, zero on entry, zero again on exit).
 constexpr int kFewTokens = 16;
 constexpr size_t kWorkspaceHeaderBytes = 16384;
-constexpr int kFewMaxSlabs = 4095;
+constexpr int kFewMaxSlabs = 2047;
 int fewtok_fwd_splits(int h, int o);
 int fewtok_bwd_splits(int h, int o);
 int fewtok_fwd_slabs(int o);
