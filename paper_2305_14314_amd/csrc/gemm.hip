@@ -11,11 +11,11 @@
 // Design for gfx950 (256 CUs in 8 XCDs, 160 KB LDS, MFMA 32x32x16 bf16 = 32 cycles per SIMD):
 //  * 256 x 256 output tile per workgroup of 4 waves (2 x 2), each wave 128 x 128 as 4 x 4 MFMA
 //    tiles: 256 fp32 accumulators per lane (AGPRs), half an LDS fragment read per MFMA.
-//  * K-step 32, four LDS stages of (A tile 16 KB, B tile 16 KB).  Tiles arrive by
-//    global_load_lds_dwordx4 (no VGPR staging).  One barrier per K-step, placed in the MIDDLE of
-//    the step: it publishes stage k+1 (requested two steps earlier) and frees the stage of step
-//    k-1 for the DMA of step k+3, so fragment reads of the next step never wait at a barrier and
-//    the MFMA stream continues across step boundaries.
+//  * K-step 32, five LDS stages of (A tile 16 KB, B tile 16 KB): all 160 KB of the CU.  Tiles arrive
+//    by global_load_lds_dwordx4 (no VGPR staging).  One barrier per K-step, placed in the MIDDLE of
+//    the step: it publishes stage k+1 (requested about three steps earlier) and frees the stage of
+//    step k-1 for the DMA of step k+4, so fragment reads of the next step never wait at a barrier
+//    and the MFMA stream continues across step boundaries.
 //  * The 8 DMA instructions of a step are spread one per row of 4 MFMAs (waves issue in order: a
 //    burst of DMAs would stall the MFMA stream behind the texture-address FIFO).
 //  * Fragment reads are software-pipelined one 16-wide sub-step ahead (the compiler is left free
@@ -39,9 +39,9 @@ namespace qlora {
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
+constexpr int BM = 256, BK = 32, NST = 5;                    // BN is 256, or 128 for the tail launch (template parameter)
 constexpr int kGemmThreads = 256;
-constexpr int kOpBytes = BM * BK * 2;                       // 16 KB per operand per stage
+constexpr int kOpBytes = BM * BK * 2;                       // 16 KB per 256-row operand tile per stage
 constexpr int GM = 4;                                       // tile-rows per raster group
 
 typedef __attribute__((address_space(3))) char lchar;
@@ -51,9 +51,10 @@ struct GemmArgs {
   const uint16_t* A1; const uint16_t* B1; int64_t lda1, ldb1; int KT1;
   uint16_t* C; int64_t ldc;
   int M, N, tiles_m, tiles_n;
+  int n_begin;                                               // first output column of this launch
 };
 
-struct Frags { bf16x8 a[4], b[4]; };
+template <int NI> struct Frags { bf16x8 a[4], b[NI]; };
 
 // DMA instruction j of an operand tile: wave w fills LDS rows (4j + w) * 16 .. + 15 of the stage;
 // lane l lands at row l / 4, physical chunk l % 4 (the caller's pointer already selects the
@@ -64,16 +65,32 @@ __device__ __forceinline__ void dma16(const uint16_t* g, lchar* stage_tile, int 
 }
 
 #define QL_LDS_READ(dst, addr) asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr))
-#define QL_WAIT_FRAGS(f)                                                                                    \
-  asm volatile("s_waitcnt lgkmcnt(0)"                                                                       \
-               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]),       \
-                 "+v"(f.b[2]), "+v"(f.b[3]))
+__device__ __forceinline__ void wait_frags(Frags<4>& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]),
+                 "+v"(f.b[2]), "+v"(f.b[3]));
+}
+__device__ __forceinline__ void wait_frags(Frags<2>& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]));
+}
+#define QL_WAIT_FRAGS(f) wait_frags(f)
+// The MFMAs are volatile asm like the LDS reads and waits, so the instruction order below IS the program order:
+// left to the scheduler, the reads of the next sub-step sank behind the rows that free their registers, the last
+// ones three MFMAs before the wait that needs them, and every sub-step began with an exposed LDS latency (the
+// MFMA pipes measured 62 % busy).
+#define QL_MFMA(c, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b))
 #define QL_MMA_ROW(f, i)                                                                                    \
-  _Pragma("unroll") for (int ni_ = 0; ni_ < 4; ++ni_)                                                       \
-      acc[i][ni_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[ni_], acc[i][ni_], 0, 0, 0);
+  _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) QL_MFMA(acc[i][ni_], f.a[i], f.b[ni_]);
 
+// BN = 256 is the main configuration.  BN = 128 (wave tiles 128 x 64, two B DMA instructions per step) serves
+// the columns left over when the 256-wide tiles do not fill a whole number of rounds of the 256 CUs: half-width
+// tiles finish that last, partly filled round in half the time.
+template <int BN>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p) {
-  __shared__ __attribute__((aligned(1024))) char smem[NST * 2 * kOpBytes];       // 128 KB
+  constexpr int NI = BN / 64;                                // MFMA columns per wave = B DMA instructions per step
+  constexpr int kStage = kOpBytes + BN * BK * 2;             // A tile + B tile
+  __shared__ __attribute__((aligned(1024))) char smem[NST * kStage];             // 160 KB (120 KB for BN = 128)
   lchar* const lds = (lchar*)smem;
 
   const int tid = threadIdx.x;
@@ -92,7 +109,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
   const int first_m = group * GM;
   const int gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
   const int in_group = pid - group * per_group;
-  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = p.n_begin + (in_group / gsz) * BN;
 
   // ---- per-lane global pointers of the 4 + 4 DMA instructions of a step ------------------------
   const int KT = p.KT0 + p.KT1;
@@ -102,7 +119,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
   for (int j = 0; j < 4; ++j) {
     const int r = (4 * j + wave) * 16 + (lane >> 2);
     a_rows[j] = (m0 + r < p.M) ? m0 + r : p.M - 1;          // clamp: padded rows are never stored
-    b_rows[j] = (n0 + r < p.N) ? n0 + r : p.N - 1;
+    b_rows[j] = (n0 + r < p.N) ? n0 + r : p.N - 1;          // (entries j >= NI are not used)
   }
   const uint16_t* pa[4];
   const uint16_t* pb[4];
@@ -126,91 +143,107 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
 
   // ---- per-lane LDS addresses of the fragments of the two 16-wide sub-steps ---------------------
   const int wm = wave >> 1, wn = wave & 1;
-  const int a_row = wm * 128 + (lane & 31), b_row = wn * 128 + (lane & 31), half = lane >> 5;
+  const int a_row = wm * 128 + (lane & 31), b_row = wn * (BN / 2) + (lane & 31), half = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-  uint32_t offA[2][4], offB[2][4];
+  uint32_t offA[2][4], offB[2][NI];
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int ra = a_row + 32 * i, rb = b_row + 32 * i;
       offA[kk][i] = lds0 + ra * 64 + (((2 * kk + half) ^ ((ra >> 2) & 3)) * 16);
-      offB[kk][i] = lds0 + kOpBytes + rb * 64 + (((2 * kk + half) ^ ((rb >> 2) & 3)) * 16);
+      if (i < NI) offB[kk][i] = lds0 + kOpBytes + rb * 64 + (((2 * kk + half) ^ ((rb >> 2) & 3)) * 16);
     }
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][NI];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  // ---- prologue: stages 0 and 1 complete, the A half of stage 2 ---------------------------------
-  // Steady state: the B tile of step k+2 goes out during the first half of step k, the A tile of
-  // step k+3 during the second half, each DMA instruction behind one row of MFMAs.
+  // ---- prologue: stages 0, 1 and 2 complete, the A half of stage 3 ----------------------------------
+  // Steady state: the B tile of step k+3 goes out during the first half of step k, the A tile of
+  // step k+4 during the second half, each DMA instruction behind one row of MFMAs.  A tile is thus
+  // requested 2.5 - 3 steps (about 1.5 us) before the barrier that publishes it: with one step less
+  // (four stages) every step waited ~0.3 us for tiles that miss the XCD's L2, and the MFMA pipes were
+  // busy 62 % of the time.
   seek(pa, a_rows, 0, true);
   seek(pb, b_rows, 0, false);
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
+  for (int s = 0; s < 3; ++s) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dma16(pa[j], lds + s * 2 * kOpBytes, j, wave);
+    for (int j = 0; j < 4; ++j) dma16(pa[j], lds + s * kStage, j, wave);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dma16(pb[j], lds + s * 2 * kOpBytes + kOpBytes, j, wave);
+    for (int j = 0; j < NI; ++j) dma16(pb[j], lds + s * kStage + kOpBytes, j, wave);
     advance(pa, a_rows, s, true);
     advance(pb, b_rows, s, false);
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) dma16(pa[j], lds + 2 * 2 * kOpBytes, j, wave);
-  advance(pa, a_rows, 2, true);
-  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 landed; stage 1 and half of stage 2 in flight
+  for (int j = 0; j < 4; ++j) dma16(pa[j], lds + 3 * kStage, j, wave);
+  advance(pa, a_rows, 3, true);
+  // stage 0 landed; stages 1, 2 and the A half of stage 3 (2 (4 + NI) + 4 instructions) in flight
+  if (NI == 4) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
   asm volatile("s_barrier" ::: "memory");
 
-  Frags f0, f1;
+  Frags<NI> f0, f1;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { QL_LDS_READ(f0.a[i], offA[0][i]); QL_LDS_READ(f0.b[i], offB[0][i]); }
+  for (int i = 0; i < 4; ++i) {
+    QL_LDS_READ(f0.a[i], offA[0][i]);
+    if (i < NI) QL_LDS_READ(f0.b[i], offB[0][i]);
+  }
 
   // One 16-wide sub-step: multiply fragments `cur` while fetching fragments `nxt` (stage `st`,
   // sub-step kk) and issuing the 4 DMA instructions `ptr` into tile `dst`.
-#define QL_SUBSTEP(cur, nxt, st, kk, ptr, dst)                                                              \
+#define QL_SUBSTEP(cur, nxt, st, kk, ptr, dst, ndma)                                                        \
   {                                                                                                         \
-    const uint32_t sb_ = (st) * 2 * kOpBytes;                                                               \
+    const uint32_t sb_ = (st) * kStage;                                                                     \
     QL_WAIT_FRAGS(cur);                                                                                     \
+    /* One fragment read of the next sub-step behind each of the first 4 + NI MFMAs (issued in the MFMA's */ \
+    /* shadow, and landed long before the next wait); one DMA instruction behind each row.               */ \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
-      QL_LDS_READ(nxt.a[i_], offA[kk][i_] + sb_);                                                           \
-      QL_LDS_READ(nxt.b[i_], offB[kk][i_] + sb_);                                                           \
-      QL_MMA_ROW(cur, i_)                                                                                   \
-      dma16(ptr[i_], dst, i_, wave);                                                                        \
+      _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) {                                                \
+        QL_MFMA(acc[i_][ni_], cur.a[i_], cur.b[ni_]);                                                       \
+        const int r_ = i_ * NI + ni_;                        /* MFMA number; reads 0 .. 3 + NI: a[], then b[] */ \
+        if (r_ < 4) QL_LDS_READ(nxt.a[r_ & 3], offA[kk][r_ & 3] + sb_);                                     \
+        else if (r_ < 4 + NI) QL_LDS_READ(nxt.b[(r_ - 4) % NI], offB[kk][(r_ - 4) % NI] + sb_);             \
+      }                                                                                                     \
+      if (i_ < (ndma)) dma16(ptr[i_], dst, i_, wave);                                                       \
     }                                                                                                       \
   }
   // One K-step; ST is the (static) stage of step k.
 #define QL_STEP(ST)                                                                                         \
   {                                                                                                         \
-    QL_SUBSTEP(f0, f1, ST, 1, pb, lds + ((ST + 2) & 3) * 2 * kOpBytes + kOpBytes)   /* B of step k+2 */     \
-    advance(pb, b_rows, k + 2, false);                                                                      \
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");          /* stage k+1 has landed (this wave's part) */ \
+    QL_SUBSTEP(f0, f1, ST, 1, pb, lds + ((ST + 3) % NST) * kStage + kOpBytes, NI)   /* B of step k+3 */     \
+    advance(pb, b_rows, k + 3, false);                                                                      \
+    /* stage k+1 has landed (this wave's part): only A, B of k+2 and k+3 may still be in flight */          \
+    if (NI == 4) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");                                          \
+    else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");                                                  \
     asm volatile("s_barrier" ::: "memory");                   /* ... and everyone's; stage k-1 is free */   \
-    QL_SUBSTEP(f1, f0, (ST + 1) & 3, 0, pa, lds + ((ST + 3) & 3) * 2 * kOpBytes)    /* A of step k+3 */     \
-    advance(pa, a_rows, k + 3, true);                                                                       \
+    QL_SUBSTEP(f1, f0, (ST + 1) % NST, 0, pa, lds + ((ST + 4) % NST) * kStage, 4)   /* A of step k+4 */     \
+    advance(pa, a_rows, k + 4, true);                                                                       \
     ++k;                                                                                                    \
   }
 
   int k = 0;
 #pragma unroll 1
-  while (k + 4 <= KT) {
-    QL_STEP(0) QL_STEP(1) QL_STEP(2) QL_STEP(3)
+  while (k + 5 <= KT) {
+    QL_STEP(0) QL_STEP(1) QL_STEP(2) QL_STEP(3) QL_STEP(4)
   }
   if (k < KT) QL_STEP(0)
   if (k < KT) QL_STEP(1)
   if (k < KT) QL_STEP(2)
+  if (k < KT) QL_STEP(3)
 #undef QL_STEP
 #undef QL_SUBSTEP
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // drain the tail's redundant loads and reads
 
   // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
 #pragma unroll
-  for (int ni = 0; ni < 4; ++ni) {
-    const int n = n0 + wn * 128 + ni * 32 + (lane & 31);
+  for (int ni = 0; ni < NI; ++ni) {
+    const int n = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
     if (n >= p.N) continue;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
@@ -233,8 +266,23 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
   a.A1 = A1; a.B1 = B1; a.lda1 = lda1; a.ldb1 = ldb1; a.KT1 = K1 / BK;
   a.C = C; a.ldc = ldc; a.M = M; a.N = N;
   a.tiles_m = (M + BM - 1) / BM;
-  a.tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(gemm_nt_kernel, dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(kGemmThreads), 0, st, a);
+  const int tiles_n = (N + 255) / 256;
+  // One workgroup per CU: tiles run in rounds of 256.  When the last round would be at most half full and is made
+  // of whole tile columns, those columns go to a second launch with half-width tiles (twice as many workgroups,
+  // half the time each) instead of occupying a full round.
+  constexpr int kCUs = 256;
+  const int total = a.tiles_m * tiles_n;
+  const int rem = total % kCUs;
+  int tail_cols = 0;
+  if (total > kCUs && rem > 0 && 2 * rem <= kCUs && rem % a.tiles_m == 0) tail_cols = rem / a.tiles_m;
+  a.n_begin = 0;
+  a.tiles_n = tiles_n - tail_cols;
+  hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(kGemmThreads), 0, st, a);
+  if (tail_cols > 0) {
+    a.n_begin = a.tiles_n * 256;
+    a.tiles_n = (N - a.n_begin + 127) / 128;
+    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(kGemmThreads), 0, st, a);
+  }
   return hipGetLastError();
 }
 
