@@ -8,8 +8,11 @@
 // Operand layouts are template flags: TA = false means A is stored [i][k] (K-contiguous),
 // TA = true means A is stored [k][i] (the contraction index is the row index, as for X^T);
 // likewise TB for B ([j][k] or [k][j]).  K-contiguous tiles are kept in LDS XOR-swizzled in 16-byte
-// chunks and read with ds_read_b128; row-index-contracted tiles are kept as loaded and their
-// MFMA fragments are gathered with 16-bit LDS reads.
+// chunks and read with ds_read_b128; row-index-contracted tiles are kept as loaded ([k][64 rows], pitch 72)
+// and their MFMA fragments come from the transposing LDS read of gfx950 (ds_read_b64_tr_b16): within a group
+// of 16 lanes, lane c supplies the address of an 8-byte chunk and lane i receives element i % 4 of the chunks
+// i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12 -- so with lane c pointing at (k0 + c / 4, rows R0 + 4 (c % 4) .. +3),
+// lane i ends up with row R0 + i at k0 .. k0 + 3, which is half an MFMA fragment (8 gathers of 16 bits before).
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -17,6 +20,8 @@ namespace qlora {
 
 constexpr int ST = 64;                       // tile edge in I, J and K
 constexpr int kSmallThreads = 256;
+constexpr int kTPitch = 72;                  // elements per k-row of a row-index-contracted tile: 4 consecutive k-rows hit distinct banks
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 
 struct SmallArgs {
   const uint16_t* A; int64_t lda;
@@ -49,7 +54,7 @@ __device__ __forceinline__ void stash_chunk(lds_char* tile, int c, u32x4 v) {
     const int row = c >> 3, kc = c & 7;
     *(u32x4 __attribute__((address_space(3)))*)(tile + row * 128 + ((kc ^ (row & 7)) * 16)) = v;
   } else {
-    *(u32x4 __attribute__((address_space(3)))*)(tile + c * 16) = v;      // [k][64 rows], as loaded
+    *(u32x4 __attribute__((address_space(3)))*)(tile + (c >> 3) * (kTPitch * 2) + (c & 7) * 16) = v;   // [k][64 rows], as loaded
   }
 }
 
@@ -60,19 +65,24 @@ __device__ __forceinline__ bf16x8 small_frag(const lds_char* tile, int row, int 
     const int chunk = (2 * kk + half) ^ (row & 7);
     return *(const bf16x8 __attribute__((address_space(3)))*)(tile + row * 128 + chunk * 16);
   } else {
-    bf16x8 f;
-    const int kb = kk * 16 + half * 8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      f[e] = *(const __bf16 __attribute__((address_space(3)))*)(tile + ((kb + e) * 64 + row) * 2);
-    return f;
+    // lane l = 32 half + row32: 16-lane group g = l / 16 covers rows R0 = 16 (g % 2) .. +15 of the sub-tile
+    const int lane = threadIdx.x & 63, c = lane & 15;
+    const int r0 = (row & ~31) + (lane & 16);               // first row of this group's 16 rows
+    const int k0 = kk * 16 + half * 8;
+    const lds_char* src = tile + ((k0 + (c >> 2)) * kTPitch + r0 + 4 * (c & 3)) * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)src);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(src + 4 * kTPitch * 2));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    const s16x8 f = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, f);
   }
 }
 
 template <bool TA, bool TB>
 __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallArgs p) {
-  __shared__ __attribute__((aligned(16))) char sA_[ST * ST * 2];
-  __shared__ __attribute__((aligned(16))) char sB_[ST * ST * 2];
+  __shared__ __attribute__((aligned(16))) char sA_[ST * kTPitch * 2];
+  __shared__ __attribute__((aligned(16))) char sB_[ST * kTPitch * 2];
   lds_char* sA = (lds_char*)sA_;
   lds_char* sB = (lds_char*)sB_;
 
