@@ -63,9 +63,23 @@ __device__ __forceinline__ void init_pair_lut(f32x2* lut2 /* [256][32] */, float
   }
   if (threadIdx.x < 256) unit[threadIdx.x] = e4m3_unit(threadIdx.x);
 }
-// (value[lo nibble], value[hi nibble]) of byte `b` from this lane's copy of the table
-__device__ __forceinline__ f32x2 pair_lookup(const f32x2* lut2, uint32_t b, int lane) {
-  return lut2[b * kLutCopies + (lane & (kLutCopies - 1))];
+// (value[lo nibble], value[hi nibble]) of byte B (0..3) of packed dword `pk`, from this lane's copy of the table.
+// Entry e of copy c sits at byte offset 256 e + 8 c: the offset is assembled by one byte permute
+// (byte 1 = the weight byte, byte 0 = 8 * copy), instead of shift, mask and add.
+template <int B>
+__device__ __forceinline__ f32x2 pair_lookup(const f32x2* lut2, uint32_t pk, uint32_t lane_off /* 8 * (lane % 32) */) {
+  const uint32_t off = __builtin_amdgcn_perm(pk, lane_off, 0x0c0c0400u + ((uint32_t)B << 8));
+  return *(const f32x2*)((const char*)lut2 + off);
+}
+
+// the same with the byte number as a (constant-folded) argument
+__device__ __forceinline__ f32x2 pair_lookup_b(const f32x2* lut2, uint32_t pk, uint32_t lane_off, int b) {
+  switch (b) {
+    case 0: return pair_lookup<0>(lut2, pk, lane_off);
+    case 1: return pair_lookup<1>(lut2, pk, lane_off);
+    case 2: return pair_lookup<2>(lut2, pk, lane_off);
+    default: return pair_lookup<3>(lut2, pk, lane_off);
+  }
 }
 
 struct FewArgs {
@@ -488,6 +502,7 @@ __global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // uniform
   const int c = lane & 31, rh = lane >> 5;
   const int sl = lane & 15, g = lane >> 4;                   // MFMA slot and k group
+  const uint32_t lane_off = 8u * (uint32_t)(lane & (kLutCopies - 1));
   float* strip = (float*)(smem + kStripOff) + wave * 64;     // [block 4][row 16]
   const int slab = (work - p.n_lparts) % p.n_slabs, split = (work - p.n_lparts) / p.n_slabs;
   const int k_begin = split * p.per_split;
@@ -561,7 +576,7 @@ __global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
       float lo[8], hi[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const f32x2 q = pair_lookup(lut2, (s.pk[j] >> (8 * b)) & 0xffu, lane);
+        const f32x2 q = pair_lookup_b(lut2, s.pk[j], lane_off, b);
         lo[j] = __fmul_rn(q[0], c2[j]);
         hi[j] = __fmul_rn(q[1], c2[j]);
       }
@@ -647,6 +662,7 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
   const int wave16 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // uniform
   const int rg = wave16 & 3, cw = wave16 >> 2;
   const int i = lane & 15, g = lane >> 4;
+  const uint32_t lane_off = 8u * (uint32_t)(lane & (kLutCopies - 1));
   const int slab = (work - p.n_lparts) % p.n_slabs, split = (work - p.n_lparts) / p.n_slabs;
   const int r0 = slab * 256 + rg * 64;
   const int c_begin = split * p.per_split;
@@ -715,7 +731,7 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
         u32x4 w;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          const f32x2 q = pair_lookup(lut2, (d >> (8 * b)) & 0xffu, lane);
+          const f32x2 q = pair_lookup_b(lut2, d, lane_off, b);
           w[b] = pack_bf16x2(__fmul_rn(q[0], c2v[u]), __fmul_rn(q[1], c2v[u]));
         }
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ya, __builtin_bit_cast(bf16x8, w), acc[u], 0, 0, 0);

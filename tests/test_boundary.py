@@ -58,3 +58,61 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert L.qlora_nf4_dequant(ctypes.byref(v), fake, None) == -2
     v = qlora_nf4_view(0x1000, 0, 0x1000, 0x1000, 4, 128, 64, 256)
     assert L.qlora_nf4_dequant(ctypes.byref(v), fake, None) == -1
+
+
+def test_linear_arguments_are_rejected_on_the_host(L):
+    from paper_2305_14314_amd import QloraError, qlora_linear_bwd_sizes, qlora_linear_fwd_sizes
+    from paper_2305_14314_amd.binding import WORKSPACE_HEADER_BYTES, qlora_nf4_view
+    # shapes: in/out features multiples of 64, rank a multiple of 16 up to 256, at least one token
+    for fn in (qlora_linear_fwd_sizes, qlora_linear_bwd_sizes):
+        for args, st in [((0, 64, 64, 0), -2), ((4, 96, 64, 0), -3), ((4, 64, 96, 0), -3), ((4, 64, 64, 8), -3),
+                         ((4, 64, 64, 272), -3), ((4, 64, 64, -16), -2)]:
+            with pytest.raises(QloraError) as e:
+                fn(*args)
+            assert e.value.status == st
+        # every workspace starts with the counter header, whichever path the token count selects
+        assert fn(1, 64, 64, 0) > WORKSPACE_HEADER_BYTES and fn(4096, 64, 64, 16) > WORKSPACE_HEADER_BYTES
+    fake = ctypes.c_void_p(0x1000)                # never dereferenced: validation fails first
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256)
+    big = 1 << 30
+    f = L.qlora_linear_fwd
+    assert f(None, ctypes.byref(v), None, None, 1.0, 4, 0, fake, None, fake, big, None) == -1          # X
+    assert f(fake, ctypes.byref(v), None, None, 1.0, 4, 0, None, None, fake, big, None) == -1          # Y
+    assert f(fake, ctypes.byref(v), None, None, 1.0, 4, 0, fake, None, None, big, None) == -1          # workspace
+    assert f(fake, ctypes.byref(v), None, fake, 1.0, 4, 16, fake, None, fake, big, None) == -1         # L1 with r > 0
+    assert f(fake, ctypes.byref(v), None, None, 1.0, 4, 0, fake, None, fake, 64, None) == -4           # too small
+    assert f(ctypes.c_void_p(0x1008), ctypes.byref(v), None, None, 1.0, 4, 0, fake, None, fake, big, None) == -5
+    b = L.qlora_linear_bwd
+    assert b(None, None, ctypes.byref(v), None, None, 1.0, 4, 0, None, fake, None, None, fake, big, None) == -1   # dY
+    assert b(fake, None, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, fake, fake, None, fake, big, None) == -1  # dL1 needs X
+    assert b(fake, None, ctypes.byref(v), None, None, 1.0, 4, 0, None, fake, None, None, fake, 64, None) == -4
+    w = L.qlora_workspace_init
+    assert w(None, big, None) == -1
+    assert w(fake, WORKSPACE_HEADER_BYTES - 1, None) == -4
+    assert w(ctypes.c_void_p(0x1004), big, None) == -5
+
+
+def test_constant_storage_order_is_a_permutation_that_keeps_groups_together():
+    """The 8-bit constants are stored column-group-major (include/qlora.h).  The index map used by the parity
+    tests and the one the binding offers agree, are permutations, and put the <= 4 constants of one row and one
+    256-column group side by side -- for widths that are and are not multiples of 256 columns."""
+    import numpy as np
+    import torch
+    from gpu_util import code_from_flat, code_positions, code_to_flat
+    from paper_2305_14314_amd import NF4Weight
+    for rows, cols in [(1, 64), (3, 256), (5, 320), (7, 704), (64, 22016 // 43)]:
+        bpr = cols // 64
+        pos = code_positions(rows, cols)
+        assert sorted(pos.tolist()) == list(range(rows * bpr))
+        flat = np.arange(rows * bpr, dtype=np.int64)
+        lib_order = code_from_flat(flat, rows, cols)
+        assert np.array_equal(code_to_flat(lib_order, rows, cols), flat)
+        for r in range(rows):
+            for g in range((bpr + 3) // 4):
+                w = min(4, bpr - 4 * g)
+                p0 = pos[r * bpr + 4 * g]
+                assert p0 == 4 * rows * g + r * w                       # the formula of the header
+                assert np.array_equal(pos[r * bpr + 4 * g:r * bpr + 4 * g + w], p0 + np.arange(w))
+        codes = torch.from_numpy((lib_order % 251).astype(np.uint8))
+        Wq = NF4Weight(rows, cols, None, codes, None, None)
+        assert np.array_equal(Wq.code_flat().numpy(), (flat % 251).astype(np.uint8))
