@@ -147,16 +147,24 @@ __device__ __forceinline__ bool arrive_last(unsigned* c, unsigned total, volatil
 __device__ __forceinline__ bool meet_adapter(unsigned* shake, unsigned n_adapter, volatile int* flag) {
   __syncthreads();                                           // everybody has read the previous flag
   if (threadIdx.x == 0) {
+    int mine = 0;
     for (int it = 0; it < kSpinLimit; ++it) {
-      if (__hip_atomic_load(shake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_adapter) break;
+      if (__hip_atomic_load(shake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_adapter) { mine = 1; break; }
       __builtin_amdgcn_s_sleep(16);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");       // hands the splits' partials on if an adapter workgroup is last
-    const unsigned old = atomicAdd(shake, 1u);
-    const int mine = old == n_adapter;
     if (mine) {
-      atomicExch(shake, 0u);
+      // every adapter workgroup is in, so this arrival is the last: the word only has to go back to zero
+      // (nobody reads it any more), and there is no round trip to wait for
+      __hip_atomic_store(shake, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");     // the adapter's partials
+    } else {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");     // hands the splits' partials on to the adapter workgroup that will be last
+      const unsigned old = atomicAdd(shake, 1u);
+      mine = old == n_adapter;                               // it came in after the last poll after all
+      if (mine) {
+        atomicExch(shake, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
     }
     *flag = mine;
   }
