@@ -40,9 +40,12 @@ namespace qlora {
 namespace {
 
 constexpr int BM = 256, BK = 32, NST = 5;                    // BN is 256, or 128 for the tail launch (template parameter)
-constexpr int kGemmThreads = 256;
 constexpr int kOpBytes = BM * BK * 2;                       // 16 KB per 256-row operand tile per stage
 constexpr int GM = 4;                                       // tile-rows per raster group
+#ifndef QL_GEMM_WAVES
+#define QL_GEMM_WAVES 8
+#endif
+constexpr int kMainWaves = QL_GEMM_WAVES;                    // waves per workgroup of the main (BN = 256) kernel
 
 typedef __attribute__((address_space(3))) char lchar;
 
@@ -56,19 +59,24 @@ struct GemmArgs {
 
 template <int NI> struct Frags { bf16x8 a[4], b[NI]; };
 
-// DMA instruction j of an operand tile: wave w fills LDS rows (4j + w) * 16 .. + 15 of the stage;
+// DMA instruction j of an operand tile: wave w of NW fills LDS rows (NW j + w) * 16 .. + 15 of the stage;
 // lane l lands at row l / 4, physical chunk l % 4 (the caller's pointer already selects the
 // logical chunk (l % 4) ^ ((l >> 4) & 3) of that row).
+template <int NW>
 __device__ __forceinline__ void dma16(const uint16_t* g, lchar* stage_tile, int j, int wave) {
-  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)(stage_tile + (4 * j + wave) * 1024),
+  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)(stage_tile + (NW * j + wave) * 1024),
                                    16, 0, 0);
 }
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 #define QL_LDS_READ(dst, addr) asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr))
 __device__ __forceinline__ void wait_frags(Frags<4>& f) {
   asm volatile("s_waitcnt lgkmcnt(0)"
                : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]),
                  "+v"(f.b[2]), "+v"(f.b[3]));
+}
+__device__ __forceinline__ void wait_frags(Frags<1>& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]));
 }
 __device__ __forceinline__ void wait_frags(Frags<2>& f) {
   asm volatile("s_waitcnt lgkmcnt(0)"
@@ -83,12 +91,16 @@ __device__ __forceinline__ void wait_frags(Frags<2>& f) {
 #define QL_MMA_ROW(f, i)                                                                                    \
   _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) QL_MFMA(acc[i][ni_], f.a[i], f.b[ni_]);
 
-// BN = 256 is the main configuration.  BN = 128 (wave tiles 128 x 64, two B DMA instructions per step) serves
-// the columns left over when the 256-wide tiles do not fill a whole number of rounds of the 256 CUs: half-width
-// tiles finish that last, partly filled round in half the time.
-template <int BN>
-__global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p) {
-  constexpr int NI = BN / 64;                                // MFMA columns per wave = B DMA instructions per step
+// BN = 256 is the main configuration.  BN = 128 serves the columns left over when the 256-wide tiles do not fill
+// a whole number of rounds of the 256 CUs: half-width tiles finish that last, partly filled round in half the time.
+// NW = waves per workgroup, laid out 2 x NW/2: wave tiles are 128 x (BN / (NW / 2)).  With NW = 8 every SIMD
+// holds two waves, so one can issue MFMAs while the other sits at the barrier or waits for its fragments.
+template <int BN, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
+  constexpr int WN = BN / (NW / 2);                          // wave tile width
+  constexpr int NI = WN / 32;                                // MFMA columns per wave
+  constexpr int NA = 16 / NW, NB = (BN / 16) / NW;           // DMA instructions per wave, step and operand
+  static_assert(NI >= 2 && NA >= 1 && NB >= 1, "tile / wave split (the read schedule needs 4 NI >= 4 + NI)");
   constexpr int kStage = kOpBytes + BN * BK * 2;             // A tile + B tile
   __shared__ __attribute__((aligned(1024))) char smem[NST * kStage];             // 160 KB (120 KB for BN = 128)
   lchar* const lds = (lchar*)smem;
@@ -114,16 +126,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
   // ---- per-lane global pointers of the 4 + 4 DMA instructions of a step ------------------------
   const int KT = p.KT0 + p.KT1;
   const int dma_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
-  int a_rows[4], b_rows[4];
+  int a_rows[NA], b_rows[NB];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int r = (4 * j + wave) * 16 + (lane >> 2);
+  for (int j = 0; j < NA; ++j) {
+    const int r = (NW * j + wave) * 16 + (lane >> 2);
     a_rows[j] = (m0 + r < p.M) ? m0 + r : p.M - 1;          // clamp: padded rows are never stored
-    b_rows[j] = (n0 + r < p.N) ? n0 + r : p.N - 1;          // (entries j >= NI are not used)
   }
-  const uint16_t* pa[4];
-  const uint16_t* pb[4];
-  auto seek = [&](const uint16_t* (&ptr)[4], const int (&rows)[4], int k, bool is_a) {
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int r = (NW * j + wave) * 16 + (lane >> 2);
+    b_rows[j] = (n0 + r < p.N) ? n0 + r : p.N - 1;
+  }
+  const uint16_t* pa[NA];
+  const uint16_t* pb[NB];
+  auto seek = [&](auto& ptr, const auto& rows, int cnt, int k, bool is_a) {
     // pointers of step k (clamped to the last step); K segment 0 first, then segment 1
     const int kc = k < KT ? k : KT - 1;
     const bool s0 = kc < p.KT0;
@@ -131,19 +147,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
     const int64_t ld = is_a ? (s0 ? p.lda0 : p.lda1) : (s0 ? p.ldb0 : p.ldb1);
     const int kofs = (s0 ? kc : kc - p.KT0) * BK + dma_chunk;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ptr[j] = base + (int64_t)rows[j] * ld + kofs;
+    for (int j = 0; j < cnt; ++j) ptr[j] = base + (int64_t)rows[j] * ld + kofs;
   };
   // after issuing step k: move to step k + 1 (one add per pointer except at the segment switch)
-  auto advance = [&](const uint16_t* (&ptr)[4], const int (&rows)[4], int k, bool is_a) {
+  auto advance = [&](auto& ptr, const auto& rows, int cnt, int k, bool is_a) {
     if (k + 1 >= KT) return;                                // stay: the tail re-fetches the last tile
-    if (k + 1 == p.KT0) { seek(ptr, rows, k + 1, is_a); return; }
+    if (k + 1 == p.KT0) { seek(ptr, rows, cnt, k + 1, is_a); return; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ptr[j] += BK;
+    for (int j = 0; j < cnt; ++j) ptr[j] += BK;
   };
 
   // ---- per-lane LDS addresses of the fragments of the two 16-wide sub-steps ---------------------
-  const int wm = wave >> 1, wn = wave & 1;
-  const int a_row = wm * 128 + (lane & 31), b_row = wn * (BN / 2) + (lane & 31), half = lane >> 5;
+  const int wm = wave / (NW / 2), wn = wave % (NW / 2);
+  const int a_row = wm * 128 + (lane & 31), b_row = wn * WN + (lane & 31), half = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
   uint32_t offA[2][4], offB[2][NI];
 #pragma unroll
@@ -169,23 +185,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
   // requested 2.5 - 3 steps (about 1.5 us) before the barrier that publishes it: with one step less
   // (four stages) every step waited ~0.3 us for tiles that miss the XCD's L2, and the MFMA pipes were
   // busy 62 % of the time.
-  seek(pa, a_rows, 0, true);
-  seek(pb, b_rows, 0, false);
+  seek(pa, a_rows, NA, 0, true);
+  seek(pb, b_rows, NB, 0, false);
 #pragma unroll
   for (int s = 0; s < 3; ++s) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dma16(pa[j], lds + s * kStage, j, wave);
+    for (int j = 0; j < NA; ++j) dma16<NW>(pa[j], lds + s * kStage, j, wave);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) dma16(pb[j], lds + s * kStage + kOpBytes, j, wave);
-    advance(pa, a_rows, s, true);
-    advance(pb, b_rows, s, false);
+    for (int j = 0; j < NB; ++j) dma16<NW>(pb[j], lds + s * kStage + kOpBytes, j, wave);
+    advance(pa, a_rows, NA, s, true);
+    advance(pb, b_rows, NB, s, false);
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) dma16(pa[j], lds + 3 * kStage, j, wave);
-  advance(pa, a_rows, 3, true);
-  // stage 0 landed; stages 1, 2 and the A half of stage 3 (2 (4 + NI) + 4 instructions) in flight
-  if (NI == 4) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  for (int j = 0; j < NA; ++j) dma16<NW>(pa[j], lds + 3 * kStage, j, wave);
+  advance(pa, a_rows, NA, 3, true);
+  // stage 0 landed; stages 1, 2 and the A half of stage 3 (2 (NA + NB) + NA instructions) in flight
+  wait_vmcnt<2 * (NA + NB) + NA>();
   asm volatile("s_barrier" ::: "memory");
 
   Frags<NI> f0, f1;
@@ -210,20 +225,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
         if (r_ < 4) QL_LDS_READ(nxt.a[r_ & 3], offA[kk][r_ & 3] + sb_);                                     \
         else if (r_ < 4 + NI) QL_LDS_READ(nxt.b[(r_ - 4) % NI], offB[kk][(r_ - 4) % NI] + sb_);             \
       }                                                                                                     \
-      if (i_ < (ndma)) dma16(ptr[i_], dst, i_, wave);                                                       \
+      if (i_ < (ndma)) dma16<NW>(ptr[i_], dst, i_, wave);                                                       \
     }                                                                                                       \
   }
   // One K-step; ST is the (static) stage of step k.
 #define QL_STEP(ST)                                                                                         \
   {                                                                                                         \
-    QL_SUBSTEP(f0, f1, ST, 1, pb, lds + ((ST + 3) % NST) * kStage + kOpBytes, NI)   /* B of step k+3 */     \
-    advance(pb, b_rows, k + 3, false);                                                                      \
+    QL_SUBSTEP(f0, f1, ST, 1, pb, lds + ((ST + 3) % NST) * kStage + kOpBytes, NB)   /* B of step k+3 */     \
+    advance(pb, b_rows, NB, k + 3, false);                                                                  \
     /* stage k+1 has landed (this wave's part): only A, B of k+2 and k+3 may still be in flight */          \
-    if (NI == 4) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");                                          \
-    else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");                                                  \
+    wait_vmcnt<2 * (NA + NB)>();                                                                            \
     asm volatile("s_barrier" ::: "memory");                   /* ... and everyone's; stage k-1 is free */   \
-    QL_SUBSTEP(f1, f0, (ST + 1) % NST, 0, pa, lds + ((ST + 4) % NST) * kStage, 4)   /* A of step k+4 */     \
-    advance(pa, a_rows, k + 4, true);                                                                       \
+    QL_SUBSTEP(f1, f0, (ST + 1) % NST, 0, pa, lds + ((ST + 4) % NST) * kStage, NA)  /* A of step k+4 */     \
+    advance(pa, a_rows, NA, k + 4, true);                                                                   \
     ++k;                                                                                                    \
   }
 
@@ -243,7 +257,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs p)
   // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
-    const int n = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
+    const int n = n0 + wn * WN + ni * 32 + (lane & 31);
     if (n >= p.N) continue;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
@@ -277,11 +291,12 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
   if (total > kCUs && rem > 0 && 2 * rem <= kCUs && rem % a.tiles_m == 0) tail_cols = rem / a.tiles_m;
   a.n_begin = 0;
   a.tiles_n = tiles_n - tail_cols;
-  hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(kGemmThreads), 0, st, a);
+  hipLaunchKernelGGL((gemm_nt_kernel<256, kMainWaves>), dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(kMainWaves * 64), 0, st,
+                     a);
   if (tail_cols > 0) {
     a.n_begin = a.tiles_n * 256;
     a.tiles_n = (N - a.n_begin + 127) / 128;
-    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(kGemmThreads), 0, st, a);
+    hipLaunchKernelGGL((gemm_nt_kernel<128, 4>), dim3((unsigned)(a.tiles_m * a.tiles_n)), dim3(256), 0, st, a);
   }
   return hipGetLastError();
 }
