@@ -126,8 +126,8 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.stderr.write("bench.py: this build is single-GPU; --gpus must be 1 (see DESIGN.md for how the path "
-                         "would shard)\n")
+        sys.stderr.write("bench.py: this build is single-GPU; --gpus must be 1 (tokens would shard across GPUs with one "
+                         "sum of the adapter gradients per step; that path is not built)\n")
         sys.exit(2)
 
     _ensure_built()
