@@ -153,12 +153,12 @@ BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   if (r > 0) {
     p.sU = qlora::small_gemm_splits((int)M, r, (int)o);
     p.sT = qlora::small_gemm_splits((int)M, r, (int)h);
-    p.sL1 = qlora::small_gemm_splits((int)h, 2 * r, (int)M);
-    p.sL2 = qlora::small_gemm_splits(2 * r, (int)o, (int)M);
+    p.sL1 = qlora::small_gemm_splits((int)h, r, (int)M);
+    p.sL2 = qlora::small_gemm_splits(r, (int)o, (int)M);
     size_t pe = (size_t)p.sU * M * r;
     if ((size_t)p.sT * M * r > pe) pe = (size_t)p.sT * M * r;
-    if ((size_t)p.sL1 * h * 2 * r > pe) pe = (size_t)p.sL1 * h * 2 * r;
-    if ((size_t)p.sL2 * 2 * r * o > pe) pe = (size_t)p.sL2 * 2 * r * o;
+    if ((size_t)p.sL1 * h * r > pe) pe = (size_t)p.sL1 * h * r;
+    if ((size_t)p.sL2 * r * o > pe) pe = (size_t)p.sL2 * r * o;
     p.L1p = (r % 64 && !p.few) ? c.take<uint16_t>((size_t)h * p.rp) : nullptr;
     p.Us = c.take<uint16_t>((size_t)M * p.rp);
     p.Uhl = c.take<uint16_t>((size_t)M * 2 * r);
@@ -293,8 +293,8 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   }
   if (r > 0) {
     // T = X L1 (Eq. 3): split-K partials, then Ts = bf16(s T) (rank zero-padded) and T_save = [hi | lo] of T
-    QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.splits, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, 0, p.Ts, p.rp, p.rp, s, T_save, st));
+    QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.splits, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, st));
   }
   QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
   if (r > 0) QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
@@ -330,8 +330,8 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
                                     (r > 0 && dL1) ? p.Uhl : nullptr, st));
   } else if (r > 0 && (dX || dL1)) {
     // U = dY L2^T: Us = bf16(s U) feeds the adapter segment of dX, the [hi | lo] pair of U feeds dL1
-    QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, (int)M, r, (int)o, p.part, p.sU, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, 0, p.Us, p.rp, p.rp, s, p.Uhl, st));
+    QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, 0, 0, (int)M, r, (int)o, p.part, p.sU, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, p.Us, p.rp, p.rp, s, p.Uhl, st));
   }
   if (!p.few && dX) {
     const uint16_t* B1 = L1;
@@ -343,19 +343,19 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
   }
   if (dL1) {
     // dL1 = s X^T U: contraction over the tokens, both operands stored token-major; U enters as hi + lo
-    QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * r, true, (int)h, 2 * r, (int)M, p.part, p.sL1, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, 2 * r, 1, dL1, r, r, s, nullptr, st));
+    QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * r, true, 2, r, (int)h, r, (int)M, p.part, p.sL1, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, r, dL1, r, r, s, nullptr, st));
   }
   if (dL2) {
     const uint16_t* T = T_saved;
     if (!T) {                                               // gradient checkpointing: recompute T = X L1
-      QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, (int)M, r, (int)h, p.part, p.sT, st));
-      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, 0, nullptr, 0, 0, 0.0f, p.Thl, st));
+      QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.sT, st));
+      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, nullptr, 0, 0, 0.0f, p.Thl, st));
       T = p.Thl;
     }
     // dL2 = s T^T dY with T as hi + lo rows
-    QL_TRY(qlora::launch_small_gemm(T, 2 * r, true, dY, o, true, 2 * r, (int)o, (int)M, p.part, p.sL2, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, 2 * r, (int)o, 2, dL2, o, (int)o, s, nullptr, st));
+    QL_TRY(qlora::launch_small_gemm(T, 2 * r, true, dY, o, true, 1, r, r, (int)o, (int)M, p.part, p.sL2, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, r, (int)o, dL2, o, (int)o, s, nullptr, st));
   }
   return QLORA_OK;
 }

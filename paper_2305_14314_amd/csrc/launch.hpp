@@ -33,13 +33,15 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
 
 // small.hip: skinny GEMMs of the LoRA branch with split-K fp32 partials, and layout helpers.
 //   part[split][I x J] = A(i,k) B(k,j);  ta: A stored [k][i] instead of [i][k];  tb: B stored [k][j] instead of [j][k].
+//   hl = 1 / 2: A / B is a [hi | lo] pair (the lo half hl_off elements behind the hi half) and enters as hi + lo;
+//   supported: (ta, tb, hl) = (0,1,0), (0,0,0), (1,1,1), (1,1,2).
 int small_gemm_splits(int I, int J, int K);
-hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb,
-                             int I, int J, int K, float* part, int splits, hipStream_t st);
-//   Sums the splits (fold = 1 adds column j + J/2 to j, fold = 2 adds row i + I/2 to i), then writes
-//   out0 = bf16(scale0 * sum) (w0 columns, zeros beyond) and/or hl = [bf16(sum) | bf16(sum - bf16(sum))].
-hipError_t launch_small_finalize(const float* part, int splits, int I, int J, int fold, uint16_t* out0, int64_t ld0,
-                                 int w0, float scale0, uint16_t* hl, hipStream_t st);
+hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb, int hl,
+                             int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st);
+//   Sums the splits, then writes out0 = bf16(scale0 * sum) (w0 columns, zeros beyond J) and/or
+//   hl = [bf16(sum) | bf16(sum - bf16(sum))] (row stride 2 J).
+hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
+                                 float scale0, uint16_t* hl, hipStream_t st);
 //   dst[c][r] = src[r][c], rows r >= R zero-filled up to Rp.
 hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
                                 hipStream_t st);

@@ -3,7 +3,11 @@
 // rank (<= 256), so these are bound by streaming X or dY from HBM, not by MFMA.
 //
 //   part[split][I x J] (fp32) = sum over this split's K range of A(i,k) * B(k,j)
-//   finalize: out = bf16(scale * sum over splits), optionally a second output with another scale
+//   finalize: out = bf16(scale * sum over splits) and/or the sum as a [hi | lo] pair of bf16 matrices
+//
+// Such a pair carries 16 significant bits of an intermediate (T or U) into the adapter gradients.  Where it is
+// an operand (HL = 1: A, HL = 2: B) the kernel loads both halves' tiles and issues two MFMAs per fragment of
+// the other operand into the same accumulators, so X (resp. dY) is streamed once.
 //
 // Operand layouts are template flags: TA = false means A is stored [i][k] (K-contiguous),
 // TA = true means A is stored [k][i] (the contraction index is the row index, as for X^T);
@@ -26,6 +30,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 struct SmallArgs {
   const uint16_t* A; int64_t lda;
   const uint16_t* B; int64_t ldb;
+  int64_t hl_off;            // HL != 0: element offset of the pair's lo half from its hi half (same row)
   float* part;
   int I, J, K, k_per_split;
 };
@@ -79,12 +84,15 @@ __device__ __forceinline__ bf16x8 small_frag(const lds_char* tile, int row, int 
   }
 }
 
-template <bool TA, bool TB>
+template <bool TA, bool TB, int HL>
 __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallArgs p) {
+  static_assert(HL == 0 || (HL == 1 && TA) || (HL == 2 && TB), "a [hi | lo] operand is stored token-major");
   __shared__ __attribute__((aligned(16))) char sA_[ST * kTPitch * 2];
   __shared__ __attribute__((aligned(16))) char sB_[ST * kTPitch * 2];
+  __shared__ __attribute__((aligned(16))) char sC_[HL ? ST * kTPitch * 2 : 16];
   lds_char* sA = (lds_char*)sA_;
   lds_char* sB = (lds_char*)sB_;
+  lds_char* sC = (lds_char*)sC_;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int i0 = blockIdx.x * ST, j0 = blockIdx.y * ST;
@@ -92,36 +100,56 @@ __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallAr
   const int k_end = (k_begin + p.k_per_split < p.K) ? k_begin + p.k_per_split : p.K;
   const int wi = wave >> 1, wj = wave & 1;
   const int a_row = wi * 32 + (lane & 31), b_row = wj * 32 + (lane & 31), half = lane >> 5;
+  const uint16_t* lo_src = (HL == 1) ? p.A + p.hl_off : p.B + p.hl_off;
+  const int64_t lo_ld = (HL == 1) ? p.lda : p.ldb;
+  const int lo_r0 = (HL == 1) ? i0 : j0, lo_R = (HL == 1) ? p.I : p.J;
 
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-  u32x4 ra[2], rb[2];
-  ra[0] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k_begin, k_end, tid);
-  ra[1] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k_begin, k_end, tid + 256);
-  rb[0] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k_begin, k_end, tid);
-  rb[1] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k_begin, k_end, tid + 256);
-
-  for (int k0 = k_begin; k0 < k_end; k0 += ST) {
-    __syncthreads();                                        // previous step's fragment reads are done
-    stash_chunk<TA>(sA, tid, ra[0]);
-    stash_chunk<TA>(sA, tid + 256, ra[1]);
-    stash_chunk<TB>(sB, tid, rb[0]);
-    stash_chunk<TB>(sB, tid + 256, rb[1]);
-    __syncthreads();
-    if (k0 + ST < k_end) {                                  // prefetch the next step into registers
-      ra[0] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0 + ST, k_end, tid);
-      ra[1] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0 + ST, k_end, tid + 256);
-      rb[0] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k0 + ST, k_end, tid);
-      rb[1] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k0 + ST, k_end, tid + 256);
+  // Two steps of operand tiles are kept in flight in registers (sets 0 and 1 alternate): with two or three
+  // workgroups per CU one step ahead is too little to cover the HBM latency.
+  struct Regs { u32x4 a[2], b[2], c[2]; };
+  auto fetch = [&](Regs& R, int k0) {                       // k0 >= k_end loads nothing and yields zeros
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      R.a[u] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0, k_end, tid + 256 * u);
+      R.b[u] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k0, k_end, tid + 256 * u);
+      if constexpr (HL != 0) R.c[u] = fetch_chunk<true>(lo_src, lo_ld, lo_r0, lo_R, k0, k_end, tid + 256 * u);
     }
+  };
+  auto step = [&](Regs& R, int k_next) {
+    __syncthreads();                                        // previous step's fragment reads are done
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      stash_chunk<TA>(sA, tid + 256 * u, R.a[u]);
+      stash_chunk<TB>(sB, tid + 256 * u, R.b[u]);
+      if constexpr (HL != 0) stash_chunk<true>(sC, tid + 256 * u, R.c[u]);
+    }
+    __syncthreads();
+    fetch(R, k_next);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       const bf16x8 a = small_frag<TA>(sA, a_row, kk, half);
       const bf16x8 b = small_frag<TB>(sB, b_row, kk, half);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+      if constexpr (HL == 1) {
+        const bf16x8 a2 = small_frag<true>(sC, a_row, kk, half);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b, acc, 0, 0, 0);
+      }
+      if constexpr (HL == 2) {
+        const bf16x8 b2 = small_frag<true>(sC, b_row, kk, half);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b2, acc, 0, 0, 0);
+      }
     }
+  };
+  Regs R0, R1;
+  fetch(R0, k_begin);
+  fetch(R1, k_begin + ST);
+  for (int k0 = k_begin; k0 < k_end; k0 += 2 * ST) {
+    step(R0, k0 + 2 * ST);
+    if (k0 + ST < k_end) step(R1, k0 + 3 * ST);
   }
 
   float* out = p.part + (int64_t)blockIdx.z * p.I * p.J;
@@ -136,36 +164,26 @@ __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallAr
 }
 
 // Reduces the split partials in a fixed order (deterministic) and writes up to two bf16 outputs.
-//   sum(i, j) = sum over splits of part[s][i][j], folded first if asked:
-//     fold = 1: columns j and j + J/2 are added (the B operand was a [hi | lo] pair), J_eff = J / 2
-//     fold = 2: rows i and i + I/2 are added    (the A operand was a [hi | lo] pair), I_eff = I / 2
-//   out0[i][j] = bf16(scale0 * sum) for j < J_eff, zero for J_eff <= j < w0            (row stride ld0)
-//   hl[i][j]   = bf16(sum),  hl[i][J_eff + j] = bf16(sum - hl[i][j])                   (row stride 2 * J_eff)
-// The hi/lo pair carries 16 significant bits of an intermediate (T = X L1 or U = dY L2^T) into the
-// bf16 MFMA products that form the adapter gradients.
-__global__ void small_finalize_kernel(const float* __restrict__ part, int splits, int I, int J, int fold,
+//   sum(i, j)  = sum over splits of part[s][i][j]
+//   out0[i][j] = bf16(scale0 * sum) for j < J, zero for J <= j < w0                    (row stride ld0)
+//   hl[i][j]   = bf16(sum),  hl[i][J + j] = bf16(sum - hl[i][j])                       (row stride 2 J)
+__global__ void small_finalize_kernel(const float* __restrict__ part, int splits, int I, int J,
                                       uint16_t* __restrict__ out0, int64_t ld0, int w0, float scale0,
                                       uint16_t* __restrict__ hl) {
-  const int Ie = (fold == 2) ? I / 2 : I, Je = (fold == 1) ? J / 2 : J;
-  const int wmax = (out0 && w0 > Je) ? w0 : Je;
-  const int64_t total = (int64_t)Ie * wmax;
+  const int wmax = (out0 && w0 > J) ? w0 : J;
+  const int64_t total = (int64_t)I * wmax;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
     const int i = (int)(e / wmax), j = (int)(e % wmax);
     float s = 0.0f;
-    if (j < Je) {
+    if (j < J) {
 #pragma unroll 8
-      for (int sp = 0; sp < splits; ++sp) {
-        const float* ps = part + (int64_t)sp * I * J;
-        s += ps[(int64_t)i * J + j];
-        if (fold == 1) s += ps[(int64_t)i * J + j + Je];
-        if (fold == 2) s += ps[(int64_t)(i + Ie) * J + j];
-      }
+      for (int sp = 0; sp < splits; ++sp) s += part[(int64_t)sp * I * J + (int64_t)i * J + j];
     }
     if (out0 && j < w0) out0[(int64_t)i * ld0 + j] = bf16_bits(s * scale0);
-    if (hl && j < Je) {
+    if (hl && j < J) {
       const uint16_t hi = bf16_bits(s);
-      hl[(int64_t)i * 2 * Je + j] = hi;
-      hl[(int64_t)i * 2 * Je + Je + j] = bf16_bits(s - bf16_lo_to_f32(hi));
+      hl[(int64_t)i * 2 * J + j] = hi;
+      hl[(int64_t)i * 2 * J + J + j] = bf16_bits(s - bf16_lo_to_f32(hi));
     }
   }
 }
@@ -198,36 +216,38 @@ __global__ void copy_pad_kernel(const uint16_t* __restrict__ src, int R, int C, 
 int small_gemm_splits(int I, int J, int K) {
   const int tiles = ((I + ST - 1) / ST) * ((J + ST - 1) / ST);
   const int ksteps = (K + ST - 1) / ST;
-  int splits = (1024 + tiles - 1) / tiles;                  // aim for ~4 workgroups per CU
+  // ~2 workgroups per CU: every further split adds an fp32 partial tile to write and read back, and past this
+  // point that traffic costs more than the extra loads in flight gain (measured: 256 -> +30 %, 1024 -> +8 % time)
+  int splits = (512 + tiles - 1) / tiles;
   if (splits > ksteps) splits = ksteps;
   if (splits > 64) splits = 64;
   if (splits < 1) splits = 1;
   return splits;
 }
 
-hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb,
-                             int I, int J, int K, float* part, int splits, hipStream_t st) {
+hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb, int hl,
+                             int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st) {
   SmallArgs a;
-  a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.part = part; a.I = I; a.J = J; a.K = K;
+  a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.hl_off = hl_off; a.part = part; a.I = I; a.J = J; a.K = K;
   const int ksteps = (K + ST - 1) / ST;
   a.k_per_split = ((ksteps + splits - 1) / splits) * ST;
   dim3 grid((unsigned)((I + ST - 1) / ST), (unsigned)((J + ST - 1) / ST), (unsigned)splits);
   dim3 block(kSmallThreads);
-  if (!ta && !tb) hipLaunchKernelGGL((small_gemm_kernel<false, false>), grid, block, 0, st, a);
-  else if (!ta && tb) hipLaunchKernelGGL((small_gemm_kernel<false, true>), grid, block, 0, st, a);
-  else if (ta && !tb) hipLaunchKernelGGL((small_gemm_kernel<true, false>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((small_gemm_kernel<true, true>), grid, block, 0, st, a);
+  if (!ta && tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, true, 0>), grid, block, 0, st, a);
+  else if (!ta && !tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, false, 0>), grid, block, 0, st, a);
+  else if (ta && tb && hl == 1) hipLaunchKernelGGL((small_gemm_kernel<true, true, 1>), grid, block, 0, st, a);
+  else if (ta && tb && hl == 2) hipLaunchKernelGGL((small_gemm_kernel<true, true, 2>), grid, block, 0, st, a);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-hipError_t launch_small_finalize(const float* part, int splits, int I, int J, int fold, uint16_t* out0, int64_t ld0,
-                                 int w0, float scale0, uint16_t* hl, hipStream_t st) {
-  const int Ie = (fold == 2) ? I / 2 : I, Je = (fold == 1) ? J / 2 : J;
-  const int wmax = (out0 && w0 > Je) ? w0 : Je;
-  int64_t blocks = ((int64_t)Ie * wmax + 255) / 256;
+hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
+                                 float scale0, uint16_t* hl, hipStream_t st) {
+  const int wmax = (out0 && w0 > J) ? w0 : J;
+  int64_t blocks = ((int64_t)I * wmax + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, fold, out0,
-                     ld0, w0, scale0, hl);
+  hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, out0, ld0, w0,
+                     scale0, hl);
   return hipGetLastError();
 }
 
