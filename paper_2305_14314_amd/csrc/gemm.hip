@@ -9,29 +9,38 @@
 // to bf16 exactly once.
 //
 // Design for gfx950 (256 CUs in 8 XCDs, 160 KB LDS, MFMA 32x32x16 bf16 = 32 cycles per SIMD):
-//  * 256 x 256 output tile per workgroup of 4 waves (2 x 2), each wave 128 x 128 as 4 x 4 MFMA
-//    tiles: 256 fp32 accumulators per lane (AGPRs), half an LDS fragment read per MFMA.
-//  * K-step 32, five LDS stages of (A tile 16 KB, B tile 16 KB): all 160 KB of the CU.  Tiles arrive
-//    by global_load_lds_dwordx4 (no VGPR staging).  One barrier per K-step, placed in the MIDDLE of
-//    the step: it publishes stage k+1 (requested about three steps earlier) and frees the stage of
-//    step k-1 for the DMA of step k+4, so fragment reads of the next step never wait at a barrier
-//    and the MFMA stream continues across step boundaries.
-//  * The 8 DMA instructions of a step are spread one per row of 4 MFMAs (waves issue in order: a
-//    burst of DMAs would stall the MFMA stream behind the texture-address FIFO).
-//  * Fragment reads are software-pipelined one 16-wide sub-step ahead (the compiler is left free
-//    to place them among the MFMAs of the sub-step: pinning two reads per row of 4 MFMAs with
-//    scheduling barriers measured 15 % slower).  They are issued through inline asm with hand-placed s_waitcnt: the compiler's
-//    automatic wait insertion cannot tell a DMA into one stage from a read of another across the
-//    loop back-edge and would drain all DMAs every iteration.
-//  * LDS rows are 64 bytes (32 k); the four 16-byte chunks of row r sit at chunk ^ ((r >> 2) & 3).
-//    LDS has 64 banks: a ds_read_b128 is served 16 lanes (256 bytes) per cycle, and 16 consecutive
-//    rows then cover all 16 sixteen-byte bank groups (measured 225 B/clk/CU against 114 for the
-//    8-lane pattern that would suit a 32-bank LDS).
+//  * 256 x 256 output tile per workgroup of 8 waves (2 x 4), each wave 128 x 64 as 4 x 2 MFMA tiles: 128 fp32
+//    accumulators per lane (AGPRs).  Two waves per SIMD: one can issue MFMAs while the other waits.
+//  * K-step 64: a tile row is one whole 128-byte line.  With 32-wide steps every DMA instruction fetched 16 half
+//    lines, each line was pulled from L2 twice (the L1 does not keep it for a step) and the MFMA pipes measured
+//    67 % busy; the same kernel fetching whole lines (and nothing else changed) ran 5 - 17 % faster.
+//  * Operand tiles (256 rows x 128 B = 32 KB) arrive by buffer_load_dwordx4 ... lds (no VGPR staging) into a ring
+//    of five 32 KB slots -- all 160 KB of the CU -- in the order A(0) B(0) A(1) B(1) A(2) ...: tile n sits in slot
+//    n % 5.  While step k is computed, A(k+1), B(k+1) and A(k+2) are resident or landing.
+//  * One barrier per K-step, before its LAST 16-wide sub-step (by then a wave holds the step's last fragments in
+//    registers): it publishes the tiles of step k+1 -- so the first fragments of step k+1 are read during that
+//    last sub-step and the MFMA stream continues across the step boundary -- and frees the two slots of step k,
+//    into which B(k+2) and A(k+3) are requested over the following four sub-steps, one DMA instruction behind a
+//    row of MFMAs (waves issue in order: a burst of DMAs would stall the MFMA stream).  B thus has one step
+//    (about 1 us) and A two steps to arrive.
+//  * Addresses cost no vector ALU instruction in the loop (VALU instructions share the MFMA's issue port): a DMA
+//    instruction takes a buffer resource based at the tile's first row, a per-lane byte offset that never
+//    changes and a scalar offset that advances by 128 per step; a fragment read takes one of a few base
+//    registers plus a 16-bit immediate (slot, MFMA tile).
+//  * Fragment reads are software-pipelined one 16-wide sub-step ahead, one read behind each of the first MFMAs of
+//    a sub-step; reads, MFMAs and waits are volatile asm so that this order is the program order, with
+//    hand-placed s_waitcnt (the compiler's automatic waits cannot tell a DMA into one slot from a read of another
+//    across the loop back-edge and would drain all DMAs every iteration).
+//  * LDS rows are 128 bytes (64 k); the eight 16-byte chunks of row r sit at chunk ^ ((r >> 1) & 7).  LDS has 64
+//    banks: a ds_read_b128 is served 16 lanes (256 bytes) per cycle; 16 consecutive rows alternate between the
+//    two halves of the bank space and the swizzle spreads the 8 rows of each half over its 8 sixteen-byte groups.
 //  * Workgroup ids are remapped so each XCD (which receives every 8th id) works on a contiguous
 //    range of the tile order, and tiles are ordered in groups of GM tile-rows, so the 32 tiles
 //    resident on an XCD share A and B tiles in that XCD's L2.
 //  * Rows beyond M / N are clamped for loads and masked at the store; steps beyond the last
-//    re-fetch the last tile into a free stage, which keeps the loop body free of branches.
+//    re-fetch the last tile into a free slot, which keeps the loop body free of branches.
+#include <algorithm>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -39,8 +48,8 @@ namespace qlora {
 
 namespace {
 
-constexpr int BM = 256, BK = 32, NST = 5;                    // BN is 256, or 128 for the tail launch (template parameter)
-constexpr int kOpBytes = BM * BK * 2;                       // 16 KB per 256-row operand tile per stage
+constexpr int BM = 256, BK = 64, NSLOT = 5;                  // BN is 256, or 128 for the tail launch (template parameter)
+constexpr int kSlot = BM * BK * 2;                           // 32 KB: one 256-row operand tile
 constexpr int GM = 4;                                       // tile-rows per raster group
 #ifndef QL_GEMM_WAVES
 #define QL_GEMM_WAVES 8
@@ -59,50 +68,50 @@ struct GemmArgs {
 
 template <int NI> struct Frags { bf16x8 a[4], b[NI]; };
 
-// DMA instruction j of an operand tile: wave w of NW fills LDS rows (NW j + w) * 16 .. + 15 of the stage;
-// lane l lands at row l / 4, physical chunk l % 4 (the caller's pointer already selects the
-// logical chunk (l % 4) ^ ((l >> 4) & 3) of that row).
-template <int NW>
-__device__ __forceinline__ void dma16(const uint16_t* g, lchar* stage_tile, int j, int wave) {
-  __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)(stage_tile + (NW * j + wave) * 1024),
-                                   16, 0, 0);
+// One operand's DMA state.  The tile's rows are addressed through a buffer resource based at the tile's first
+// row: a per-lane byte offset that never changes (row * ld + chunk) plus a scalar byte offset that advances by one
+// K-step.
+template <int CNT> struct Dma {
+  __amdgpu_buffer_rsrc_t rsrc;
+  int soff;                                                  // scalar byte offset of the current step
+  int voff[CNT];                                             // per-lane byte offset of DMA instruction j
+};
+constexpr int kRsrcFlags = 0x00020000;                       // raw buffer, 32-bit data format
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint16_t* base) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7FFFFFFF, kRsrcFlags);
+}
+// DMA instruction j of an operand tile: wave w of NW fills LDS rows (NW j + w) * 8 .. + 7 of the slot (1 KB);
+// lane l lands at row l / 8, physical chunk l % 8 (its offset selects the logical chunk
+// (l % 8) ^ ((row >> 1) & 7) of that row).
+template <int NW, int CNT>
+__device__ __forceinline__ void dma16(const Dma<CNT>& d, lchar* slot, int j, int wave) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(d.rsrc,
+                                           (__attribute__((address_space(3))) void*)(slot + (NW * j + wave) * 1024),
+                                           16, d.voff[j], d.soff, 0, 0);
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-#define QL_LDS_READ(dst, addr) asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr))
-__device__ __forceinline__ void wait_frags(Frags<4>& f) {
-  asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]),
-                 "+v"(f.b[2]), "+v"(f.b[3]));
-}
-__device__ __forceinline__ void wait_frags(Frags<1>& f) {
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]));
-}
+#define QL_LDS_READ(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm))
 __device__ __forceinline__ void wait_frags(Frags<2>& f) {
   asm volatile("s_waitcnt lgkmcnt(0)"
                : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]));
 }
-#define QL_WAIT_FRAGS(f) wait_frags(f)
 // The MFMAs are volatile asm like the LDS reads and waits, so the instruction order below IS the program order:
 // left to the scheduler, the reads of the next sub-step sank behind the rows that free their registers, the last
-// ones three MFMAs before the wait that needs them, and every sub-step began with an exposed LDS latency (the
-// MFMA pipes measured 62 % busy).
+// ones three MFMAs before the wait that needs them, and every sub-step began with an exposed LDS latency.
 #define QL_MFMA(c, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b))
-#define QL_MMA_ROW(f, i)                                                                                    \
-  _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) QL_MFMA(acc[i][ni_], f.a[i], f.b[ni_]);
 
 // BN = 256 is the main configuration.  BN = 128 serves the columns left over when the 256-wide tiles do not fill
 // a whole number of rounds of the 256 CUs: half-width tiles finish that last, partly filled round in half the time.
-// NW = waves per workgroup, laid out 2 x NW/2: wave tiles are 128 x (BN / (NW / 2)).  With NW = 8 every SIMD
-// holds two waves, so one can issue MFMAs while the other sits at the barrier or waits for its fragments.
+// NW = waves per workgroup, laid out 2 x NW/2; every wave tile is 128 x 64 (BN = 32 NW).
 template <int BN, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
-  constexpr int WN = BN / (NW / 2);                          // wave tile width
-  constexpr int NI = WN / 32;                                // MFMA columns per wave
-  constexpr int NA = 16 / NW, NB = (BN / 16) / NW;           // DMA instructions per wave, step and operand
-  static_assert(NI >= 2 && NA >= 1 && NB >= 1, "tile / wave split (the read schedule needs 4 NI >= 4 + NI)");
-  constexpr int kStage = kOpBytes + BN * BK * 2;             // A tile + B tile
-  __shared__ __attribute__((aligned(1024))) char smem[NST * kStage];             // 160 KB (120 KB for BN = 128)
+  constexpr int NI = 2;                                      // MFMA columns per wave (wave tile 128 x 64)
+  static_assert(BN == 32 * NW, "2 x NW/2 waves of 128 x 64");
+  constexpr int NA = 32 / NW, NB = (BN / 8) / NW;            // DMA instructions per wave, step and operand
+  constexpr int PER = (NA + NB) / 4;                         // DMA instructions per wave and sub-step
+  static_assert((NA + NB) % 4 == 0 && PER <= 4, "DMA instructions are spread evenly over the four sub-steps");
+  __shared__ __attribute__((aligned(1024))) char smem[NSLOT * kSlot];             // 160 KB
   lchar* const lds = (lchar*)smem;
 
   const int tid = threadIdx.x;
@@ -123,53 +132,58 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   const int in_group = pid - group * per_group;
   const int m0 = (first_m + in_group % gsz) * BM, n0 = p.n_begin + (in_group / gsz) * BN;
 
-  // ---- per-lane global pointers of the 4 + 4 DMA instructions of a step ------------------------
+  // ---- DMA state of the two operands ------------------------------------------------------------
   const int KT = p.KT0 + p.KT1;
-  const int dma_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
-  int a_rows[NA], b_rows[NB];
+  int a_rows[NA], b_rows[NB], a_chunk[NA], b_chunk[NB];      // row within the tile (clamped to the matrix), logical chunk
 #pragma unroll
   for (int j = 0; j < NA; ++j) {
-    const int r = (NW * j + wave) * 16 + (lane >> 2);
-    a_rows[j] = (m0 + r < p.M) ? m0 + r : p.M - 1;          // clamp: padded rows are never stored
+    const int r = (NW * j + wave) * 8 + (lane >> 3);
+    a_rows[j] = (m0 + r < p.M) ? r : p.M - 1 - m0;          // clamp: padded rows are never stored
+    a_chunk[j] = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
   }
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
-    const int r = (NW * j + wave) * 16 + (lane >> 2);
-    b_rows[j] = (n0 + r < p.N) ? n0 + r : p.N - 1;
+    const int r = (NW * j + wave) * 8 + (lane >> 3);
+    b_rows[j] = (n0 + r < p.N) ? r : p.N - 1 - n0;
+    b_chunk[j] = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
   }
-  const uint16_t* pa[NA];
-  const uint16_t* pb[NB];
-  auto seek = [&](auto& ptr, const auto& rows, int cnt, int k, bool is_a) {
-    // pointers of step k (clamped to the last step); K segment 0 first, then segment 1
+  Dma<NA> da;
+  Dma<NB> db;
+  // state for step k (clamped to the last step); K segment 0 first, then segment 1
+  auto seek = [&](auto& d, const auto& rows, const auto& chunk, int cnt, int row0, int k, bool is_a) {
     const int kc = k < KT ? k : KT - 1;
     const bool s0 = kc < p.KT0;
     const uint16_t* base = is_a ? (s0 ? p.A0 : p.A1) : (s0 ? p.B0 : p.B1);
     const int64_t ld = is_a ? (s0 ? p.lda0 : p.lda1) : (s0 ? p.ldb0 : p.ldb1);
-    const int kofs = (s0 ? kc : kc - p.KT0) * BK + dma_chunk;
+    d.rsrc = tile_rsrc(base + (int64_t)row0 * ld);
+    d.soff = (s0 ? kc : kc - p.KT0) * (BK * 2);
 #pragma unroll
-    for (int j = 0; j < cnt; ++j) ptr[j] = base + (int64_t)rows[j] * ld + kofs;
+    for (int j = 0; j < cnt; ++j) d.voff[j] = (rows[j] * (int)ld + chunk[j]) * 2;
   };
-  // after issuing step k: move to step k + 1 (one add per pointer except at the segment switch)
-  auto advance = [&](auto& ptr, const auto& rows, int cnt, int k, bool is_a) {
+  // after issuing step k: move to step k + 1 (one scalar add except at the segment switch)
+  auto advance = [&](auto& d, const auto& rows, const auto& chunk, int cnt, int row0, int k, bool is_a) {
     if (k + 1 >= KT) return;                                // stay: the tail re-fetches the last tile
-    if (k + 1 == p.KT0) { seek(ptr, rows, cnt, k + 1, is_a); return; }
-#pragma unroll
-    for (int j = 0; j < cnt; ++j) ptr[j] += BK;
+    if (k + 1 == p.KT0) { seek(d, rows, chunk, cnt, row0, k + 1, is_a); return; }
+    d.soff += BK * 2;
   };
 
-  // ---- per-lane LDS addresses of the fragments of the two 16-wide sub-steps ---------------------
+  // ---- per-lane LDS addresses of the fragments --------------------------------------------------
+  // Sub-step kk (16 k) of a tile: logical chunk 2 kk + half of row r, at physical chunk (2 kk + half) ^ ((r >> 1) & 7).
+  // ds_read takes a 16-bit immediate: one base register per sub-step, operand and 64 KB window of the ring; the
+  // slot within the window and the 32-row MFMA tile (4 KB apart, same swizzle) are immediates.
   const int wm = wave / (NW / 2), wn = wave % (NW / 2);
-  const int a_row = wm * 128 + (lane & 31), b_row = wn * WN + (lane & 31), half = lane >> 5;
+  const int a_row = wm * 128 + (lane & 31), b_row = wn * 64 + (lane & 31), half = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-  uint32_t offA[2][4], offB[2][NI];
+  uint32_t baseA[4][3], baseB[4][3];
 #pragma unroll
-  for (int kk = 0; kk < 2; ++kk)
+  for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ra = a_row + 32 * i, rb = b_row + 32 * i;
-      offA[kk][i] = lds0 + ra * 64 + (((2 * kk + half) ^ ((ra >> 2) & 3)) * 16);
-      if (i < NI) offB[kk][i] = lds0 + kOpBytes + rb * 64 + (((2 * kk + half) ^ ((rb >> 2) & 3)) * 16);
+    for (int w = 0; w < 3; ++w) {
+      baseA[kk][w] = lds0 + w * 65536 + a_row * 128 + (((2 * kk + half) ^ ((a_row >> 1) & 7)) * 16);
+      baseB[kk][w] = lds0 + w * 65536 + b_row * 128 + (((2 * kk + half) ^ ((b_row >> 1) & 7)) * 16);
     }
+#define QL_READ_A(dst, slot, kk, i) QL_LDS_READ(dst, baseA[kk][(slot) >> 1], ((slot) & 1) * kSlot + (i) * 4096)
+#define QL_READ_B(dst, slot, kk, i) QL_LDS_READ(dst, baseB[kk][(slot) >> 1], ((slot) & 1) * kSlot + (i) * 4096)
 
   f32x16 acc[4][NI];
 #pragma unroll
@@ -178,86 +192,116 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  // The MFMAs below are inline asm, invisible to the compiler's hazard recogniser: a vector-ALU write of an
+  // accumulator register needs 2 wait states before an MFMA reads it as its addend.  Pin every initialisation
+  // in front of a few idle cycles (without this the compiler sank the zeroing of one accumulator right in front
+  // of its first MFMA, which then read the register's old contents).
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j) asm volatile("s_nop 3" : "+a"(acc[i][j]));
 
-  // ---- prologue: stages 0, 1 and 2 complete, the A half of stage 3 ----------------------------------
-  // Steady state: the B tile of step k+3 goes out during the first half of step k, the A tile of
-  // step k+4 during the second half, each DMA instruction behind one row of MFMAs.  A tile is thus
-  // requested 2.5 - 3 steps (about 1.5 us) before the barrier that publishes it: with one step less
-  // (four stages) every step waited ~0.3 us for tiles that miss the XCD's L2, and the MFMA pipes were
-  // busy 62 % of the time.
-  seek(pa, a_rows, NA, 0, true);
-  seek(pb, b_rows, NB, 0, false);
+  // ---- prologue: A(0) B(0) A(1) B(1) A(2) into slots 0 .. 4 ---------------------------------------
+  seek(da, a_rows, a_chunk, NA, m0, 0, true);
+  seek(db, b_rows, b_chunk, NB, n0, 0, false);
 #pragma unroll
-  for (int s = 0; s < 3; ++s) {
+  for (int s = 0; s < 2; ++s) {
 #pragma unroll
-    for (int j = 0; j < NA; ++j) dma16<NW>(pa[j], lds + s * kStage, j, wave);
+    for (int j = 0; j < NA; ++j) dma16<NW>(da, lds + (2 * s) * kSlot, j, wave);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) dma16<NW>(pb[j], lds + s * kStage + kOpBytes, j, wave);
-    advance(pa, a_rows, NA, s, true);
-    advance(pb, b_rows, NB, s, false);
+    for (int j = 0; j < NB; ++j) dma16<NW>(db, lds + (2 * s + 1) * kSlot, j, wave);
+    advance(da, a_rows, a_chunk, NA, m0, s, true);
+    advance(db, b_rows, b_chunk, NB, n0, s, false);
   }
 #pragma unroll
-  for (int j = 0; j < NA; ++j) dma16<NW>(pa[j], lds + 3 * kStage, j, wave);
-  advance(pa, a_rows, NA, 3, true);
-  // stage 0 landed; stages 1, 2 and the A half of stage 3 (2 (NA + NB) + NA instructions) in flight
-  wait_vmcnt<2 * (NA + NB) + NA>();
+  for (int j = 0; j < NA; ++j) dma16<NW>(da, lds + 4 * kSlot, j, wave);
+  advance(da, a_rows, a_chunk, NA, m0, 2, true);
+  // A(0), B(0) landed; A(1), B(1), A(2) (2 NA + NB instructions) in flight
+  wait_vmcnt<2 * NA + NB>();
   asm volatile("s_barrier" ::: "memory");
 
   Frags<NI> f0, f1;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    QL_LDS_READ(f0.a[i], offA[0][i]);
-    if (i < NI) QL_LDS_READ(f0.b[i], offB[0][i]);
+    QL_READ_A(f0.a[i], 0, 0, i);
+    if (i < NI) QL_READ_B(f0.b[i], 1, 0, i);
   }
 
-  // One 16-wide sub-step: multiply fragments `cur` while fetching fragments `nxt` (stage `st`,
-  // sub-step kk) and issuing the 4 DMA instructions `ptr` into tile `dst`.
-#define QL_SUBSTEP(cur, nxt, st, kk, ptr, dst, ndma)                                                        \
+  // One 16-wide sub-step: multiply fragments `cur` while fetching fragments `nxt` (sub-step kk of the tiles in
+  // slots sa, sb) and issuing this sub-step's share q0 .. q0 + PER - 1 of the step's DMA instructions: first the
+  // NB of B(k+2) into slot db_, then the NA of A(k+3) into slot da_.  One fragment read behind each of the first
+  // 4 + NI MFMAs (issued in the MFMA's shadow, and landed long before the next wait); one DMA behind each row.
+#define QL_DMA_Q(q, da_, db_)                                                                               \
+  if ((q) < NB) dma16<NW>(db, lds + (db_) * kSlot, (q) < NB ? (q) : 0, wave);                               \
+  else dma16<NW>(da, lds + (da_) * kSlot, (q) >= NB ? (q) - NB : 0, wave);
+#define QL_SUBSTEP(cur, nxt, sa, sb, kk, q0, da_, db_, with_dma)                                            \
   {                                                                                                         \
-    const uint32_t sb_ = (st) * kStage;                                                                     \
-    QL_WAIT_FRAGS(cur);                                                                                     \
-    /* One fragment read of the next sub-step behind each of the first 4 + NI MFMAs (issued in the MFMA's */ \
-    /* shadow, and landed long before the next wait); one DMA instruction behind each row.               */ \
+    wait_frags(cur);                                                                                        \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
       _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) {                                                \
         QL_MFMA(acc[i_][ni_], cur.a[i_], cur.b[ni_]);                                                       \
         const int r_ = i_ * NI + ni_;                        /* MFMA number; reads 0 .. 3 + NI: a[], then b[] */ \
-        if (r_ < 4) QL_LDS_READ(nxt.a[r_ & 3], offA[kk][r_ & 3] + sb_);                                     \
-        else if (r_ < 4 + NI) QL_LDS_READ(nxt.b[(r_ - 4) % NI], offB[kk][(r_ - 4) % NI] + sb_);             \
+        if (r_ < 4) QL_READ_A(nxt.a[r_ & 3], sa, kk, r_ & 3);                                               \
+        else if (r_ < 4 + NI) QL_READ_B(nxt.b[(r_ - 4) % NI], sb, kk, (r_ - 4) % NI);                       \
       }                                                                                                     \
-      if (i_ < (ndma)) dma16<NW>(ptr[i_], dst, i_, wave);                                                       \
+      if ((with_dma) && i_ < PER) { QL_DMA_Q((q0) + i_, da_, db_) }                                         \
     }                                                                                                       \
   }
-  // One K-step; ST is the (static) stage of step k.
-#define QL_STEP(ST)                                                                                         \
+  // Sub-steps 0 .. 2 of a step whose tiles sit in slots SA, SB (fragments of sub-step 0 are in f0).
+#define QL_HEAD(SA, SB)                                                                                     \
+  QL_SUBSTEP(f0, f1, SA, SB, 1, 0, 0, 0, false)                                                             \
+  QL_SUBSTEP(f1, f0, SA, SB, 2, 0, 0, 0, false)                                                             \
+  QL_SUBSTEP(f0, f1, SA, SB, 3, 0, 0, 0, false)
+  // One iteration: the last sub-step of step k (tiles in slots S0 = 2k % 5 and S0 + 1) and the first three of
+  // step k+1 (slots S0 + 2, S0 + 3), requesting B(k+2) into slot S0 and A(k+3) into slot S0 + 1.
+#define QL_ITER(S0)                                                                                         \
   {                                                                                                         \
-    QL_SUBSTEP(f0, f1, ST, 1, pb, lds + ((ST + 3) % NST) * kStage + kOpBytes, NB)   /* B of step k+3 */     \
-    advance(pb, b_rows, NB, k + 3, false);                                                                  \
-    /* stage k+1 has landed (this wave's part): only A, B of k+2 and k+3 may still be in flight */          \
-    wait_vmcnt<2 * (NA + NB)>();                                                                            \
-    asm volatile("s_barrier" ::: "memory");                   /* ... and everyone's; stage k-1 is free */   \
-    QL_SUBSTEP(f1, f0, (ST + 1) % NST, 0, pa, lds + ((ST + 4) % NST) * kStage, NA)  /* A of step k+4 */     \
-    advance(pa, a_rows, NA, k + 4, true);                                                                   \
+    constexpr int sa_ = ((S0) + 2) % NSLOT, sb_ = ((S0) + 3) % NSLOT, fa_ = (S0) % NSLOT, fb_ = ((S0) + 1) % NSLOT; \
+    wait_frags(f1);                                           /* this wave has read all it needs of step k */ \
+    wait_vmcnt<NA>();                                         /* its part of A(k+1), B(k+1) has landed      */ \
+    asm volatile("s_barrier" ::: "memory");                   /* ... and everyone's; slots of step k are free */ \
+    QL_SUBSTEP(f1, f0, sa_, sb_, 0, 0 * PER, fb_, fa_, true)                                                \
+    QL_SUBSTEP(f0, f1, sa_, sb_, 1, 1 * PER, fb_, fa_, true)                                                \
+    QL_SUBSTEP(f1, f0, sa_, sb_, 2, 2 * PER, fb_, fa_, true)                                                \
+    QL_SUBSTEP(f0, f1, sa_, sb_, 3, 3 * PER, fb_, fa_, true)                                                \
+    advance(db, b_rows, b_chunk, NB, n0, k + 2, false);                                                     \
+    advance(da, a_rows, a_chunk, NA, m0, k + 3, true);                                                      \
     ++k;                                                                                                    \
   }
 
-  int k = 0;
+  QL_HEAD(0, 1)                                               // step 0, sub-steps 0 .. 2 (no DMA: the ring is full)
+  int k = 0;                                                 // f1 holds the fragments of sub-step 3 of step k
 #pragma unroll 1
-  while (k + 5 <= KT) {
-    QL_STEP(0) QL_STEP(1) QL_STEP(2) QL_STEP(3) QL_STEP(4)
+  while (k + 5 < KT) {
+    QL_ITER(0) QL_ITER(2) QL_ITER(4) QL_ITER(1) QL_ITER(3)
   }
-  if (k < KT) QL_STEP(0)
-  if (k < KT) QL_STEP(1)
-  if (k < KT) QL_STEP(2)
-  if (k < KT) QL_STEP(3)
-#undef QL_STEP
+  if (k + 1 < KT) QL_ITER(0)
+  if (k + 1 < KT) QL_ITER(2)
+  if (k + 1 < KT) QL_ITER(4)
+  if (k + 1 < KT) QL_ITER(1)
+  // the last sub-step of the last step; its fragments are in f1
+  wait_frags(f1);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) QL_MFMA(acc[i][ni], f1.a[i], f1.b[ni]);
+#undef QL_ITER
+#undef QL_HEAD
 #undef QL_SUBSTEP
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // drain the tail's redundant loads and reads
+#undef QL_DMA_Q
+#undef QL_READ_A
+#undef QL_READ_B
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // drain the tail's redundant loads
+  // likewise the other way: an MFMA's result may be read by the vector ALU only 18 wait states after its issue
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+a"(acc[i][j]));
 
   // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
-    const int n = n0 + wn * WN + ni * 32 + (lane & 31);
+    const int n = n0 + wn * 64 + ni * 32 + (lane & 31);
     if (n >= p.N) continue;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
@@ -275,6 +319,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
 hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
                           const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                           uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
+  if (K0 <= 0 || K0 % BK != 0 || K1 < 0 || K1 % BK != 0) return hipErrorInvalidValue;
+  // a tile's rows are addressed with 32-bit byte offsets from its first row
+  const int64_t ld_max = std::max(std::max(lda0, ldb0), std::max(K1 ? lda1 : 0, K1 ? ldb1 : 0));
+  if (256 * ld_max * 2 + (int64_t)(K0 > K1 ? K0 : K1) * 2 >= (1ll << 31)) return hipErrorInvalidValue;
   GemmArgs a;
   a.A0 = A0; a.B0 = B0; a.lda0 = lda0; a.ldb0 = ldb0; a.KT0 = K0 / BK;
   a.A1 = A1; a.B1 = B1; a.lda1 = lda1; a.ldb1 = ldb1; a.KT1 = K1 / BK;
