@@ -80,14 +80,9 @@ constexpr int kRsrcFlags = 0x00020000;                       // raw buffer, 32-b
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint16_t* base) {
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7FFFFFFF, kRsrcFlags);
 }
-// DMA instruction j of an operand tile: wave w of NW fills LDS rows (NW j + w) * 8 .. + 7 of the slot (1 KB);
-// lane l lands at row l / 8, physical chunk l % 8 (its offset selects the logical chunk
-// (l % 8) ^ ((row >> 1) & 7) of that row).
-template <int NW, int CNT>
-__device__ __forceinline__ void dma16(const Dma<CNT>& d, lchar* slot, int j, int wave) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(d.rsrc,
-                                           (__attribute__((address_space(3))) void*)(slot + (NW * j + wave) * 1024),
-                                           16, d.voff[j], d.soff, 0, 0);
+// one DMA instruction: 64 lanes x 16 bytes from rsrc + voff (per lane) + soff (scalar) to 1 KB of LDS at dst
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, lchar* dst, int voff, int soff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)dst, 16, voff, soff, 0, 0);
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
@@ -95,6 +90,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_
 __device__ __forceinline__ void wait_frags(Frags<2>& f) {
   asm volatile("s_waitcnt lgkmcnt(0)"
                : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]));
+}
+__device__ __forceinline__ void wait_frags(Frags<4>& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]),
+                 "+v"(f.b[3]));
 }
 // The MFMAs are volatile asm like the LDS reads and waits, so the instruction order below IS the program order:
 // left to the scheduler, the reads of the next sub-step sank behind the rows that free their registers, the last
@@ -106,8 +106,9 @@ __device__ __forceinline__ void wait_frags(Frags<2>& f) {
 // NW = waves per workgroup, laid out 2 x NW/2; every wave tile is 128 x 64 (BN = 32 NW).
 template <int BN, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
-  constexpr int NI = 2;                                      // MFMA columns per wave (wave tile 128 x 64)
-  static_assert(BN == 32 * NW, "2 x NW/2 waves of 128 x 64");
+  constexpr int WN = BN / (NW / 2);                          // wave tile width: 64, or 128 for 4 waves on a 256-wide tile
+  constexpr int NI = WN / 32;                                // MFMA columns per wave
+  static_assert(NI == 2 || NI == 4, "wave tiles are 128 x 64 or 128 x 128");
   constexpr int NA = 32 / NW, NB = (BN / 8) / NW;            // DMA instructions per wave, step and operand
   constexpr int PER = (NA + NB) / 4;                         // DMA instructions per wave and sub-step
   static_assert((NA + NB) % 4 == 0 && PER <= 4, "DMA instructions are spread evenly over the four sub-steps");
@@ -149,6 +150,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   }
   Dma<NA> da;
   Dma<NB> db;
+  // DMA instruction j of an operand tile: wave w of NW fills LDS rows (NW j + w) * 8 .. + 7 of the slot (1 KB);
+  // lane l lands at row l / 8, physical chunk l % 8 (its offset selects the logical chunk
+  // (l % 8) ^ ((row >> 1) & 7) of that row).
+#define QL_DMA16(d, slot, j) dma16((d).rsrc, (slot) + (NW * (j) + wave) * 1024, (d).voff[j], (d).soff)
   // state for step k (clamped to the last step); K segment 0 first, then segment 1
   auto seek = [&](auto& d, const auto& rows, const auto& chunk, int cnt, int row0, int k, bool is_a) {
     const int kc = k < KT ? k : KT - 1;
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   // ds_read takes a 16-bit immediate: one base register per sub-step, operand and 64 KB window of the ring; the
   // slot within the window and the 32-row MFMA tile (4 KB apart, same swizzle) are immediates.
   const int wm = wave / (NW / 2), wn = wave % (NW / 2);
-  const int a_row = wm * 128 + (lane & 31), b_row = wn * 64 + (lane & 31), half = lane >> 5;
+  const int a_row = wm * 128 + (lane & 31), b_row = wn * WN + (lane & 31), half = lane >> 5;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
   uint32_t baseA[4][3], baseB[4][3];
 #pragma unroll
@@ -207,14 +212,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
 #pragma unroll
-    for (int j = 0; j < NA; ++j) dma16<NW>(da, lds + (2 * s) * kSlot, j, wave);
+    for (int j = 0; j < NA; ++j) QL_DMA16(da, lds + (2 * s) * kSlot, j);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) dma16<NW>(db, lds + (2 * s + 1) * kSlot, j, wave);
+    for (int j = 0; j < NB; ++j) QL_DMA16(db, lds + (2 * s + 1) * kSlot, j);
     advance(da, a_rows, a_chunk, NA, m0, s, true);
     advance(db, b_rows, b_chunk, NB, n0, s, false);
   }
 #pragma unroll
-  for (int j = 0; j < NA; ++j) dma16<NW>(da, lds + 4 * kSlot, j, wave);
+  for (int j = 0; j < NA; ++j) QL_DMA16(da, lds + 4 * kSlot, j);
   advance(da, a_rows, a_chunk, NA, m0, 2, true);
   // A(0), B(0) landed; A(1), B(1), A(2) (2 NA + NB instructions) in flight
   wait_vmcnt<2 * NA + NB>();
@@ -232,8 +237,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   // NB of B(k+2) into slot db_, then the NA of A(k+3) into slot da_.  One fragment read behind each of the first
   // 4 + NI MFMAs (issued in the MFMA's shadow, and landed long before the next wait); one DMA behind each row.
 #define QL_DMA_Q(q, da_, db_)                                                                               \
-  if ((q) < NB) dma16<NW>(db, lds + (db_) * kSlot, (q) < NB ? (q) : 0, wave);                               \
-  else dma16<NW>(da, lds + (da_) * kSlot, (q) >= NB ? (q) - NB : 0, wave);
+  if ((q) < NB) QL_DMA16(db, lds + (db_) * kSlot, (q) < NB ? (q) : 0);                               \
+  else QL_DMA16(da, lds + (da_) * kSlot, (q) >= NB ? (q) - NB : 0);
 #define QL_SUBSTEP(cur, nxt, sa, sb, kk, q0, da_, db_, with_dma)                                            \
   {                                                                                                         \
     wait_frags(cur);                                                                                        \
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   QL_SUBSTEP(f0, f1, SA, SB, 3, 0, 0, 0, false)
   // One iteration: the last sub-step of step k (tiles in slots S0 = 2k % 5 and S0 + 1) and the first three of
   // step k+1 (slots S0 + 2, S0 + 3), requesting B(k+2) into slot S0 and A(k+3) into slot S0 + 1.
-#define QL_ITER(S0)                                                                                         \
+#define QL_ITER(S0, FAST)                                                                                   \
   {                                                                                                         \
     constexpr int sa_ = ((S0) + 2) % NSLOT, sb_ = ((S0) + 3) % NSLOT, fa_ = (S0) % NSLOT, fb_ = ((S0) + 1) % NSLOT; \
     wait_frags(f1);                                           /* this wave has read all it needs of step k */ \
@@ -264,21 +269,33 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
     QL_SUBSTEP(f0, f1, sa_, sb_, 1, 1 * PER, fb_, fa_, true)                                                \
     QL_SUBSTEP(f1, f0, sa_, sb_, 2, 2 * PER, fb_, fa_, true)                                                \
     QL_SUBSTEP(f0, f1, sa_, sb_, 3, 3 * PER, fb_, fa_, true)                                                \
-    advance(db, b_rows, b_chunk, NB, n0, k + 2, false);                                                     \
-    advance(da, a_rows, a_chunk, NA, m0, k + 3, true);                                                      \
+    if (FAST) {                                                                                             \
+      db.soff += BK * 2;                                                                                    \
+      da.soff += BK * 2;                                                                                    \
+    } else {                                                                                                \
+      advance(db, b_rows, b_chunk, NB, n0, k + 2, false);                                                   \
+      advance(da, a_rows, a_chunk, NA, m0, k + 3, true);                                                    \
+    }                                                                                                       \
     ++k;                                                                                                    \
   }
 
   QL_HEAD(0, 1)                                               // step 0, sub-steps 0 .. 2 (no DMA: the ring is full)
   int k = 0;                                                 // f1 holds the fragments of sub-step 3 of step k
+  // Steady state: every tile requested and every state advanced in these five iterations stays inside K segment 0
+  // (the last advance moves A to step k + 8 < KT0), so the DMA state advances by one scalar add and no iteration
+  // carries the branches and register copies of the segment switch.
+#pragma unroll 1
+  while (k + 8 < p.KT0) {
+    QL_ITER(0, true) QL_ITER(2, true) QL_ITER(4, true) QL_ITER(1, true) QL_ITER(3, true)
+  }
 #pragma unroll 1
   while (k + 5 < KT) {
-    QL_ITER(0) QL_ITER(2) QL_ITER(4) QL_ITER(1) QL_ITER(3)
+    QL_ITER(0, false) QL_ITER(2, false) QL_ITER(4, false) QL_ITER(1, false) QL_ITER(3, false)
   }
-  if (k + 1 < KT) QL_ITER(0)
-  if (k + 1 < KT) QL_ITER(2)
-  if (k + 1 < KT) QL_ITER(4)
-  if (k + 1 < KT) QL_ITER(1)
+  if (k + 1 < KT) QL_ITER(0, false)
+  if (k + 1 < KT) QL_ITER(2, false)
+  if (k + 1 < KT) QL_ITER(4, false)
+  if (k + 1 < KT) QL_ITER(1, false)
   // the last sub-step of the last step; its fragments are in f1
   wait_frags(f1);
 #pragma unroll
@@ -289,6 +306,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
 #undef QL_HEAD
 #undef QL_SUBSTEP
 #undef QL_DMA_Q
+#undef QL_DMA16
 #undef QL_READ_A
 #undef QL_READ_B
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // drain the tail's redundant loads
@@ -301,7 +319,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
-    const int n = n0 + wn * 64 + ni * 32 + (lane & 31);
+    const int n = n0 + wn * WN + ni * 32 + (lane & 31);
     if (n >= p.N) continue;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
