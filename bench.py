@@ -11,7 +11,7 @@ Prints ONE JSON line: the metric is fwd+bwd TFLOP/s (algorithmic FLOPs 4*M*h*o +
 linear); `roofline` is the main MFMA GEMM kernel against the bf16 dense peak, timed with HIP events
 around every launch inside the timed region; `cpu_baseline` is the fp64 CPU oracle on a bounded
 sample of the same workload.  The other rows of the path (quantise, standalone dequant, few-token
-GEMV) are measured after the timed region and reported in `extra`.
+GEMV) and the main GEMM per shape are measured after the timed region and reported in `extra`.
 """
 from __future__ import annotations
 
@@ -293,6 +293,28 @@ def main():
                                    "fwd_us_per_linear": round(tf * 1e3 / 7, 2), "bwd_us_per_linear": round(tb * 1e3 / 7, 2),
                                    "fwd_eager_GBps": round(bytes_block / (tfe * 1e-3) * 1e-9, 1),
                                    "bwd_dx_eager_GBps": round(bytes_block / (tbe * 1e-3) * 1e-9, 1)}
+        # the main GEMM alone, per shape (dX = dY What^T, no adapter), beside torch.matmul on the same operands
+        # (the vendor GEMM library, for context: same shape, same data, same NT layout)
+        by_shape = {}
+        for (h, o) in sorted(set(linears)):
+            Wq = pool[0][linears.index((h, o))]
+            Wd = ql.qlora_nf4_dequant(Wq)
+            bwd = lambda: ql.qlora_linear_bwd(dY[o], None, Wq, None, None, s, dX=dX[h], need_dL=False, workspace=ws)
+            for _ in range(2):
+                bwd()
+            torch.cuda.synchronize()
+            ql.qlora_profile_gemm(True)
+            ql.qlora_profile_gemm_read()
+            for _ in range(8):
+                bwd()
+            torch.cuda.synchronize()
+            ql.qlora_profile_gemm(False)
+            g_ms, g_n, g_fl = ql.qlora_profile_gemm_read()
+            t_lib = _time_ms(torch, lambda: torch.matmul(dY[o], Wd.t(), out=dX[h]), 8)
+            by_shape[f"M{M}_N{h}_K{o}"] = {"gemm_nt_TFLOPs": round(g_fl / (g_ms * 1e-3) * 1e-12, 1),
+                                           "torch_matmul_TFLOPs": round(2.0 * M * h * o / (t_lib * 1e-3) * 1e-12, 1)}
+            del Wd
+        extra["gemm_by_shape"] = by_shape
         extra["gemv"] = {"bytes_per_weight": 0.51587, "note": "packed + 8-bit constants + c1 traffic only; weights "
                          "cycle through the resident pool; one pass over the pool captured in a HIP graph "
                          "(the eager figures include Python launch cost)", **gemv}
