@@ -103,7 +103,8 @@ __device__ __forceinline__ void wait_frags(Frags<4>& f) {
 
 // BN = 256 is the main configuration.  BN = 128 serves the columns left over when the 256-wide tiles do not fill
 // a whole number of rounds of the 256 CUs: half-width tiles finish that last, partly filled round in half the time.
-// NW = waves per workgroup, laid out 2 x NW/2; every wave tile is 128 x 64 (BN = 32 NW).
+// NW = waves per workgroup, laid out 2 x NW/2: wave tiles are 128 x 64 (the configurations launched), or 128 x 128
+// for 4 waves on the 256-wide tile (builds and measures the same; kept as the QL_GEMM_WAVES build option).
 template <int BN, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   constexpr int WN = BN / (NW / 2);                          // wave tile width: 64, or 128 for 4 waves on a 256-wide tile
