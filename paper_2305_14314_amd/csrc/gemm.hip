@@ -318,17 +318,29 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
     for (int j = 0; j < NI; ++j) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+a"(acc[i][j]));
 
   // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
+  // One 64-bit base per lane and MFMA column; a store's row offset is then a compile-time multiple of ldc, and
+  // tiles that lie wholly inside M (all but the last tile-row) skip the per-row bound checks: computing every
+  // address and bound from scratch cost 12 instructions per 2-byte store, three times the stores themselves.
+  const bool rows_inside = m0 + BM <= p.M;
+  const int m_lane = m0 + wm * 128 + 4 * half;              // first row this lane stores
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
     const int n = n0 + wn * WN + ni * 32 + (lane & 31);
     if (n >= p.N) continue;
+    uint16_t* const cb = p.C + (int64_t)m_lane * p.ldc + n;
+    if (rows_inside) {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+      for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 128 + mi * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        if (m < p.M) p.C[(int64_t)m * p.ldc + n] = bf16_bits(acc[mi][ni][v]);
-      }
+        for (int v = 0; v < 16; ++v) cb[(int64_t)(mi * 32 + 8 * (v >> 2) + (v & 3)) * p.ldc] = bf16_bits(acc[mi][ni][v]);
+    } else {
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = mi * 32 + 8 * (v >> 2) + (v & 3);
+          if (m_lane + row < p.M) cb[(int64_t)row * p.ldc] = bf16_bits(acc[mi][ni][v]);
+        }
     }
   }
 }
