@@ -264,8 +264,21 @@ def main():
                   ffn: torch.empty(m, ffn, device=dev, dtype=torch.bfloat16)}
             wsz = max(max(ql.qlora_linear_fwd_sizes(m, h, o, r), ql.qlora_linear_bwd_sizes(m, h, o, r))
                       for h, o in linears)
+            wsz = max(wsz, ql.qlora_linear_fwd_multi_sizes(m, d, [d] * 3, [r] * 3),
+                      ql.qlora_linear_fwd_multi_sizes(m, d, [ffn] * 2, [r] * 2))
             wss = ws[:wsz]
             kk = [0]
+            Yqkv = [torch.empty(m, d, device=dev, dtype=torch.bfloat16) for _ in range(3)]
+            Ygu = [torch.empty(m, ffn, device=dev, dtype=torch.bfloat16) for _ in range(2)]
+
+            def few_fwd_grouped():
+                # the layers of a block that read the same input in one launch each: q/k/v, then o, gate/up, down
+                blk = pool[kk[0] % len(pool)]
+                kk[0] += 1
+                ql.qlora_linear_fwd_multi(Xs[d], blk[0:3], L1[0:3], L2[0:3], [s] * 3, Ys=Yqkv, workspace=wss)
+                ql.qlora_linear_fwd(Xs[d], blk[3], L1[3], L2[3], s, Y=Ys[d], workspace=wss)
+                ql.qlora_linear_fwd_multi(Xs[d], blk[4:6], L1[4:6], L2[4:6], [s] * 2, Ys=Ygu, workspace=wss)
+                ql.qlora_linear_fwd(Xs[ffn], blk[6], L1[6], L2[6], s, Y=Ys[d], workspace=wss)
 
             def few_fwd():
                 blk = pool[kk[0] % len(pool)]
@@ -286,11 +299,16 @@ def main():
             tf = _time_graph_ms(torch, few_fwd, len(pool))
             kk[0] = 0
             tb = _time_graph_ms(torch, few_bwd, len(pool))
+            kk[0] = 0
+            tg = _time_graph_ms(torch, few_fwd_grouped, len(pool))
             gemv[f"tokens_{m}"] = {"fwd_GBps": round(bytes_block / (tf * 1e-3) * 1e-9, 1),
                                    "bwd_dx_GBps": round(bytes_block / (tb * 1e-3) * 1e-9, 1),
                                    "fwd_frac_hbm": round(bytes_block / (tf * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                                    "bwd_dx_frac_hbm": round(bytes_block / (tb * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                                    "fwd_us_per_linear": round(tf * 1e3 / 7, 2), "bwd_us_per_linear": round(tb * 1e3 / 7, 2),
+                                   "fwd_grouped_GBps": round(bytes_block / (tg * 1e-3) * 1e-9, 1),
+                                   "fwd_grouped_frac_hbm": round(bytes_block / (tg * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                                   "fwd_grouped_us_per_block": round(tg * 1e3, 2),
                                    "fwd_eager_GBps": round(bytes_block / (tfe * 1e-3) * 1e-9, 1),
                                    "bwd_dx_eager_GBps": round(bytes_block / (tbe * 1e-3) * 1e-9, 1)}
         # the main GEMM alone, per shape (dX = dY What^T, no adapter), beside torch.matmul on the same operands
@@ -317,7 +335,8 @@ def main():
         extra["gemm_by_shape"] = by_shape
         extra["gemv"] = {"bytes_per_weight": 0.51587, "note": "packed + 8-bit constants + c1 traffic only; weights "
                          "cycle through the resident pool; one pass over the pool captured in a HIP graph "
-                         "(the eager figures include Python launch cost)", **gemv}
+                         "(the eager figures include Python launch cost); fwd_grouped runs q/k/v and gate/up, which read the "
+                         "same input, as one launch each (4 launches per block instead of 7)", **gemv}
     out["extra"] = extra
 
     if not args.no_cpu_baseline:

@@ -161,6 +161,25 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
                               uint16_t* dX, uint16_t* dL1, uint16_t* dL2,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Forward of several QLoRA linear layers that read the SAME input (Eq. 5 applied per layer: the q / k / v or the
+ * gate / up projections of a decoder block, where the adapter sits on every linear layer -- Section 5 and the
+ * hyperparameter appendix):
+ *   Y[l] = X * doubleDequant(Wq[l]) + s[l] * (X * L1[l]) * L2[l],   l = 0 .. n-1,  1 <= n <= QLORA_MULTI_MAX.
+ * X: M x h with h = Wq[l].rows for every l (else QLORA_ERR_SHAPE); Wq is an array of n views; L1, L2, Y are host
+ * arrays of n device pointers, s and r host arrays of n values (r[l] = 0 skips layer l's adapter, and then L1[l],
+ * L2[l] are not read; L1 and L2 themselves may be NULL when every r[l] is 0).  At M <= 16 all layers run in ONE
+ * launch of the streaming kernel, so the fixed cost of a call is paid once; at larger M the layers run one after
+ * the other exactly as n calls of qlora_linear_fwd would.  Results meet the same tolerance as qlora_linear_fwd but
+ * need not be bit-identical to it (the contraction may be split differently).  Same rules for the workspace
+ * (counter header first, qlora_workspace_init once per buffer), alignment, ownership and errors. */
+#define QLORA_MULTI_MAX 4
+qlora_status qlora_linear_fwd_multi_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
+                                          size_t* workspace_bytes);
+qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf4_view* Wq,
+                                    const uint16_t* const* L1, const uint16_t* const* L2, const float* s,
+                                    int64_t M, const int32_t* r, uint16_t* const* Y,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid for the benchmark (not part of the method): while enabled, every launch of the
  * main MFMA GEMM kernel made by qlora_linear_fwd / qlora_linear_bwd is bracketed by a pair of HIP
  * events recorded on the call's stream.  qlora_profile_gemm_read waits for those events, returns

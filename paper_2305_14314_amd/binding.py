@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_PKG, "libqlora_hip.so")
 EXPORTS = [
     "qlora_status_string", "qlora_last_hip_error", "qlora_nf4_sizes", "qlora_nf4_quantize",
     "qlora_nf4_dequant", "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd",
-    "qlora_linear_bwd", "qlora_workspace_init", "qlora_profile_gemm", "qlora_profile_gemm_read",
+    "qlora_linear_bwd", "qlora_linear_fwd_multi_sizes", "qlora_linear_fwd_multi", "qlora_workspace_init",
+    "qlora_profile_gemm", "qlora_profile_gemm_read",
 ]
 
 
@@ -58,6 +59,9 @@ def lib():
                                    vp, c_size_t, vp]
     L.qlora_linear_bwd.argtypes = [vp, vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp,
                                    vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_linear_fwd_multi_sizes.argtypes = [c_int64, c_int32, c_int64, POINTER(c_int64), POINTER(c_int32), sp]
+    L.qlora_linear_fwd_multi.argtypes = [vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
+                                         c_int64, POINTER(c_int32), POINTER(vp), vp, c_size_t, vp]
     L.qlora_profile_gemm.argtypes = [ctypes.c_int]
     L.qlora_profile_gemm.restype = None
     L.qlora_profile_gemm_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64), POINTER(ctypes.c_double)]
@@ -195,6 +199,34 @@ def qlora_linear_fwd(X, Wq: NF4Weight, L1, L2, s, Y=None, T_save=None, workspace
     _check(lib().qlora_linear_fwd(_ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(Y), _ptr(T_save),
                                   _ptr(workspace), workspace.numel(), _stream(stream)))
     return Y
+
+
+MULTI_MAX = 4
+
+
+def qlora_linear_fwd_multi_sizes(M, h, os_, rs) -> int:
+    n = len(os_)
+    out = c_size_t(0)
+    _check(lib().qlora_linear_fwd_multi_sizes(M, n, h, (c_int64 * n)(*os_), (c_int32 * n)(*rs), byref(out)))
+    return int(out.value)
+
+
+def qlora_linear_fwd_multi(X, Wqs, L1s, L2s, ss, Ys=None, workspace=None, stream=None):
+    """Y[l] = X dequant(Wqs[l]) + ss[l] (X L1s[l]) L2s[l] for up to MULTI_MAX layers that read the same X (M, h);
+    at M <= 16 all of them in one launch.  L1s[l] / L2s[l] may be None (no adapter on that layer)."""
+    n = len(Wqs)
+    M, h = X.shape
+    rs = [0 if L1s[l] is None else L1s[l].shape[1] for l in range(n)]
+    if Ys is None:
+        Ys = [torch.empty((M, w.cols), dtype=torch.bfloat16, device=X.device) for w in Wqs]
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_fwd_multi_sizes(M, h, [w.cols for w in Wqs], rs), X.device, stream)
+    views = (qlora_nf4_view * n)(*[w.view() for w in Wqs])
+    ptrs = lambda ts: (c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
+    _check(lib().qlora_linear_fwd_multi(_ptr(X), n, views, ptrs(L1s), ptrs(L2s), (c_float * n)(*[float(s) for s in ss]),
+                                        M, (c_int32 * n)(*rs), ptrs(Ys), _ptr(workspace), workspace.numel(),
+                                        _stream(stream)))
+    return Ys
 
 
 def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1=None, dL2=None,

@@ -169,6 +169,41 @@ BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
   return p;
 }
 
+// Several layers on one X.  Few tokens: one launch, every layer with its own partial buffers.  Otherwise the layers
+// run one after the other through the single-layer path, sharing one workspace of the largest size.
+static_assert(QLORA_MULTI_MAX == qlora::kFewMaxLayers, "the header's limit is the kernel's");
+struct MultiPlan {
+  float* fpart[qlora::kFewMaxLayers];
+  float* lpart[qlora::kFewMaxLayers];
+  int splits;
+  bool few;
+  size_t bytes;
+};
+MultiPlan plan_fwd_multi(void* ws, int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r) {
+  MultiPlan p{};
+  int slabs = 0, r_max = 0, oi[qlora::kFewMaxLayers];
+  for (int l = 0; l < n; ++l) {
+    slabs += qlora::fewtok_fwd_slabs((int)o[l]);
+    if (r[l] > r_max) r_max = r[l];
+    oi[l] = (int)o[l];
+  }
+  p.few = M <= qlora::kFewTokens && slabs <= qlora::kFewMaxSlabs;
+  if (p.few) {
+    Carver c(ws);
+    p.splits = qlora::fewtok_multi_splits(n, (int)h, oi, r_max);
+    for (int l = 0; l < n; ++l) {
+      p.fpart[l] = c.take<float>((size_t)p.splits * M * o[l]);
+      p.lpart[l] = c.take<float>((size_t)qlora::fewtok_fwd_lparts((int)h, r[l]) * M * r[l] + 4);
+    }
+    p.bytes = c.off;
+  } else {
+    for (int l = 0; l < n; ++l) {
+      const size_t b = plan_fwd(nullptr, M, h, o[l], r[l]).bytes;
+      if (b > p.bytes) p.bytes = b;
+    }
+  }
+  return p;
+}
 
 }  // namespace
 
@@ -301,6 +336,50 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   // Y = X What + Ts L2 (Eq. 5): the adapter term is the second K segment of the same accumulators
   QL_TRY(gemm_nt_timed(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
                                st));
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_fwd_multi_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
+                                          size_t* workspace_bytes) {
+  if (!o || !r || !workspace_bytes) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_MULTI_MAX) return QLORA_ERR_SHAPE;
+  for (int l = 0; l < n; ++l)
+    if (qlora_status st = check_linear(M, h, o[l], r[l])) return st;
+  *workspace_bytes = plan_fwd_multi(nullptr, M, n, h, o, r).bytes;
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf4_view* Wq, const uint16_t* const* L1,
+                                    const uint16_t* const* L2, const float* s, int64_t M, const int32_t* r,
+                                    uint16_t* const* Y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!X || !Wq || !s || !r || !Y || !workspace) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_MULTI_MAX) return QLORA_ERR_SHAPE;
+  int64_t o[QLORA_MULTI_MAX];
+  const int64_t h = Wq[0].rows;
+  for (int l = 0; l < n; ++l) {
+    if (qlora_status st = check_view(&Wq[l])) return st;
+    if (Wq[l].rows != h) return QLORA_ERR_SHAPE;              // every layer reads the same X
+    o[l] = Wq[l].cols;
+    if (qlora_status st = check_linear(M, h, o[l], r[l])) return st;
+    if (!Y[l]) return QLORA_ERR_NULL;
+    if (r[l] > 0 && (!L1 || !L2 || !L1[l] || !L2[l])) return QLORA_ERR_NULL;
+    if (!aligned16(Y[l]) || (r[l] > 0 && (!aligned16(L1[l]) || !aligned16(L2[l])))) return QLORA_ERR_ALIGN;
+  }
+  if (!aligned16(X) || !aligned16(workspace)) return QLORA_ERR_ALIGN;
+  const MultiPlan p = plan_fwd_multi(workspace, M, n, h, o, r);
+  if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
+  if (!p.few) {
+    for (int l = 0; l < n; ++l)
+      if (qlora_status st = qlora_linear_fwd(X, &Wq[l], r[l] > 0 ? L1[l] : nullptr, r[l] > 0 ? L2[l] : nullptr, s[l], M,
+                                             r[l], Y[l], nullptr, workspace, workspace_bytes, hip_stream))
+        return st;
+    return QLORA_OK;
+  }
+  qlora::FewLayer layers[QLORA_MULTI_MAX];
+  for (int l = 0; l < n; ++l)
+    layers[l] = qlora::FewLayer{to_dev(&Wq[l]), r[l] > 0 ? L1[l] : nullptr, r[l] > 0 ? L2[l] : nullptr, r[l], s[l],
+                                p.fpart[l], p.lpart[l], Y[l]};
+  QL_TRY(qlora::launch_fewtok_fwd_multi(X, (int)M, n, layers, p.splits, (unsigned*)workspace, (hipStream_t)hip_stream));
   return QLORA_OK;
 }
 

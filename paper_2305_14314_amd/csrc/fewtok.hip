@@ -489,8 +489,9 @@ __device__ void lora_bwd_partial(const FewArgs& p, int wg, float* red /* [NT / 6
 // through a wave-private LDS strip.
 struct FwdStep { uint32_t pk[8]; u32x4 x; uint32_t code; float c1; };   // raw loads only: nothing here is consumed before compute()
 
+// `work` is this workgroup's position in the call's work list: the adapter partials first, then (split, slab) pairs.
 template <int MT, int NT>
-__global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
+__device__ __forceinline__ void fewtok_fwd_body(const FewArgs& p, const int work) {
   constexpr int NA = MT / 8;                                 // accumulator sets (and MFMAs per column phase)
   constexpr int kDepth = 3;
   constexpr int NW = NT / 64;                                // waves: 16 with 128 VGPRs each, or 8 with 256 (MT = 16)
@@ -500,7 +501,6 @@ __global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
   float* red = (float*)smem;
   float* unit = (float*)(smem + kUnitOff);
   __shared__ int flag;
-  const int work = work_index();
   if (work < p.n_lparts) {
     lora_fwd_partial<NT>(p, work, red);
     adapter_arrive<false, NT>(p, smem, &flag);
@@ -642,6 +642,32 @@ __global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
   }
   if (!arrive_last(p.ctr + slab, (unsigned)p.splits, &flag)) return;
   finalize_slab<false, NT>(p, slab, smem, p.ctr + kCtrShake + slab, &flag);
+}
+
+template <int MT, int NT>
+__global__ __launch_bounds__(NT) void fewtok_fwd_kernel(const FewArgs p) {
+  fewtok_fwd_body<MT, NT>(p, work_index());
+}
+
+// Several layers that read the same token rows (the q / k / v or the gate / up projections of a decoder block) in
+// one launch: the fixed cost of a call -- launch, arrival chain, output stage -- is paid once for all of them.
+// The work list holds every layer's adapter partials first, then every layer's (split, slab) pairs.
+struct FewMulti {
+  int n;
+  int a_first[kFewMaxLayers + 1];            // first adapter workgroup of layer l; [n] = their total
+  int w_first[kFewMaxLayers + 1];            // first (split, slab) workgroup of layer l; [n] = the grid size
+  FewArgs a[kFewMaxLayers];
+};
+
+template <int MT, int NT>
+__global__ __launch_bounds__(NT) void fewtok_fwd_multi_kernel(const FewMulti m) {
+  const int work = work_index();
+  const bool adapter = work < m.a_first[m.n];
+  const int* first = adapter ? m.a_first : m.w_first;
+  int l = 0;
+  while (l + 1 < m.n && work >= first[l + 1]) ++l;
+  const FewArgs p = m.a[l];
+  fewtok_fwd_body<MT, NT>(p, (adapter ? 0 : p.n_lparts) + work - first[l]);
 }
 
 // ---- backward main --------------------------------------------------------------------------------
@@ -818,6 +844,46 @@ hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* p
   const dim3 grid((unsigned)(a.n_slabs * splits + a.n_lparts));
   if (M <= 8) hipLaunchKernelGGL((fewtok_fwd_kernel<8, 1024>), grid, dim3(1024), 0, st, a);
   else hipLaunchKernelGGL((fewtok_fwd_kernel<16, 512>), grid, dim3(512), 0, st, a);
+  return hipGetLastError();
+}
+
+int fewtok_multi_splits(int n, int h, const int* o, int r_max) {
+  int slabs = 0, reserved = 0;
+  for (int l = 0; l < n; ++l) { slabs += fewtok_fwd_slabs(o[l]); reserved += fewtok_fwd_lparts(h, r_max > 0 ? 16 : 0); }
+  return pick_splits(slabs, (h + 15) / 16, 32, reserved);
+}
+
+hipError_t launch_fewtok_fwd_multi(const uint16_t* X, int M, int n, const FewLayer* layers, int splits, unsigned* ctr,
+                                   hipStream_t st) {
+  if (n < 1 || n > kFewMaxLayers) return hipErrorInvalidValue;
+  FewMulti m;
+  m.n = n;
+  int adapters = 0, slab0 = 0;
+  for (int l = 0; l < n; ++l) {
+    const FewLayer& y = layers[l];
+    FewArgs& a = m.a[l];
+    a.X = X; a.M = M; a.packed = y.w.packed; a.code = y.w.code; a.c1 = y.w.c1; a.mean = y.w.mean;
+    a.h = (int)y.w.rows; a.o = (int)y.w.cols; a.part = y.part;
+    const int steps = (a.h + 15) / 16;
+    a.per_split = ((steps + splits - 1) / splits) * 16;
+    a.n_slabs = fewtok_fwd_slabs(a.o); a.splits = splits;
+    a.L = y.L1; a.r = y.r; a.lpart = y.lpart; a.n_lparts = fewtok_fwd_lparts(a.h, y.r);
+    a.ctr = ctr + slab0;                                     // every layer its own range of slab counters
+    a.Bmat = y.L2; a.scale = y.scale; a.out = y.Y; a.hl = nullptr;
+    m.a_first[l] = adapters;
+    adapters += a.n_lparts;
+    slab0 += a.n_slabs;
+  }
+  if (slab0 > kFewMaxSlabs) return hipErrorInvalidValue;
+  m.a_first[n] = adapters;
+  int work = adapters;
+  for (int l = 0; l < n; ++l) { m.w_first[l] = work; work += m.a[l].n_slabs * splits; }
+  m.w_first[n] = work;
+  for (int l = n + 1; l <= kFewMaxLayers; ++l) { m.a_first[l] = adapters; m.w_first[l] = work; }
+  for (int l = n; l < kFewMaxLayers; ++l) m.a[l] = m.a[0];
+  const dim3 grid((unsigned)work);
+  if (M <= 8) hipLaunchKernelGGL((fewtok_fwd_multi_kernel<8, 1024>), grid, dim3(1024), 0, st, m);
+  else hipLaunchKernelGGL((fewtok_fwd_multi_kernel<16, 512>), grid, dim3(512), 0, st, m);
   return hipGetLastError();
 }
 

@@ -69,6 +69,18 @@ hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* p
 hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* part, int splits, const uint16_t* L1,
                              const uint16_t* L2, int r, float scale, float* lpart, unsigned* ctr, uint16_t* dX,
                              uint16_t* U_hl, hipStream_t st);
+// Forward of up to kFewMaxLayers layers that read the same X (M x h) in one launch; every layer brings its own
+// partial buffers; `ctr` as above (the layers' slabs together must not exceed kFewMaxSlabs).
+constexpr int kFewMaxLayers = 4;
+struct FewLayer {
+  NF4Dev w; const uint16_t* L1; const uint16_t* L2; int r; float scale;
+  float* part;                               // [splits][M][o]
+  float* lpart;                              // [fewtok_fwd_lparts][M][r]
+  uint16_t* Y;                               // M x o
+};
+int fewtok_multi_splits(int n, int h, const int* o, int r_max);
+hipError_t launch_fewtok_fwd_multi(const uint16_t* X, int M, int n, const FewLayer* layers, int splits, unsigned* ctr,
+                                   hipStream_t st);
 hipError_t launch_workspace_init(void* workspace, hipStream_t st);
 
 }  // namespace qlora

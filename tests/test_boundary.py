@@ -92,6 +92,41 @@ def test_linear_arguments_are_rejected_on_the_host(L):
     assert w(ctypes.c_void_p(0x1004), big, None) == -5
 
 
+def test_multi_layer_arguments_are_rejected_on_the_host(L):
+    """The several-layers-on-one-input forward validates before any HIP call: layer count, every layer's shape,
+    one common number of input features, pointers, alignment and workspace size."""
+    from paper_2305_14314_amd import QloraError, qlora_linear_fwd_multi_sizes, qlora_linear_fwd_sizes
+    from paper_2305_14314_amd.binding import WORKSPACE_HEADER_BYTES, qlora_nf4_view
+    for args, st in [((4, 64, [], []), -2), ((4, 64, [64] * 5, [0] * 5), -2), ((4, 64, [64, 96], [0, 0]), -3),
+                     ((4, 64, [64, 64], [0, 8]), -3), ((0, 64, [64], [0]), -2)]:
+        with pytest.raises(QloraError) as e:
+            qlora_linear_fwd_multi_sizes(*args)
+        assert e.value.status == st
+    assert qlora_linear_fwd_multi_sizes(4, 64, [64, 128], [0, 16]) > WORKSPACE_HEADER_BYTES
+    # many tokens: the layers run one after the other in one workspace of the largest single-layer size
+    assert qlora_linear_fwd_multi_sizes(300, 64, [64, 128], [0, 16]) == max(qlora_linear_fwd_sizes(300, 64, 64, 0),
+                                                                              qlora_linear_fwd_sizes(300, 64, 128, 16))
+    fake = ctypes.c_void_p(0x1000)
+    big = 1 << 30
+    n = 2
+    views = (qlora_nf4_view * n)(qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256),
+                                 qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 64, 64, 256))
+    ptrs = lambda *v: (ctypes.c_void_p * n)(*v)
+    s, r0, r16 = (ctypes.c_float * n)(1.0, 1.0), (ctypes.c_int32 * n)(0, 0), (ctypes.c_int32 * n)(0, 16)
+    f = L.qlora_linear_fwd_multi
+    ok_y = ptrs(0x1000, 0x1000)
+    assert f(None, n, views, None, None, s, 4, r0, ok_y, fake, big, None) == -1                         # X
+    assert f(fake, n, views, None, None, s, 4, r0, ptrs(0x1000, None), fake, big, None) == -1           # Y[1]
+    assert f(fake, n, views, None, None, s, 4, r16, ok_y, fake, big, None) == -1                        # L1 with r > 0
+    assert f(fake, n, views, ptrs(None, 0x1000), ptrs(None, None), s, 4, r16, ok_y, fake, big, None) == -1
+    assert f(fake, 0, views, None, None, s, 4, r0, ok_y, fake, big, None) == -2
+    assert f(fake, 5, views, None, None, s, 4, r0, ok_y, fake, big, None) == -2
+    assert f(fake, n, views, None, None, s, 4, r0, ok_y, fake, 64, None) == -4                          # too small
+    assert f(fake, n, views, None, None, s, 4, r0, ptrs(0x1000, 0x1008), fake, big, None) == -5
+    views[1].rows = 192                                                                                # another h
+    assert f(fake, n, views, None, None, s, 4, r0, ok_y, fake, big, None) == -2
+
+
 def test_constant_storage_order_is_a_permutation_that_keeps_groups_together():
     """The 8-bit constants are stored column-group-major (include/qlora.h).  The index map used by the parity
     tests and the one the binding offers agree, are permutations, and put the <= 4 constants of one row and one

@@ -117,3 +117,77 @@ def test_fewtok_counters_reset_and_repeat(oracle, synth):
             else:
                 assert torch.equal(Y.view(torch.int16), first[key[0]].view(torch.int16))
                 assert torch.equal(dX.view(torch.int16), first[key[1]].view(torch.int16))
+
+
+@pytest.mark.parametrize("M", [1, 5, 16])
+def test_multi_layer_forward_small(oracle, synth, M):
+    """Several layers on one input in one launch: three layers of different widths, one of them without an adapter,
+    one with rank 64; every output element against the oracle; the counter header is zero afterwards."""
+    import paper_2305_14314_amd as ql
+    h, outs, ranks, ss = 1024, [1024, 320, 2304], [16, 0, 64], [0.5, 1.0, 0.25]
+    hX = synth.normal_bf16((M, h), 1.0, 4000 + M)
+    X = dev_bf16(hX)
+    Wqs, L1s, L2s, refs = [], [], [], []
+    for l, (o, r) in enumerate(zip(outs, ranks)):
+        W = synth.normal_f32((h, o), synth.SIGMA_W, 4100 + l)
+        q = oracle.nf4_quantize(W)
+        Wqs.append(upload_quant(q))
+        hL1 = synth.normal_bf16((h, r), 0.05, 4200 + l) if r else None
+        hL2 = synth.normal_bf16((r, o), 0.05, 4300 + l) if r else None
+        L1s.append(dev_bf16(hL1) if r else None)
+        L2s.append(dev_bf16(hL2) if r else None)
+        refs.append(oracle.linear_fwd(hX, oracle.nf4_dequant(q), hL1, hL2, ss[l]))
+    ws = ql.workspace_alloc(ql.qlora_linear_fwd_multi_sizes(M, h, outs, ranks))
+    print(f"case multi M={M} h={h} o={outs} r={ranks}", flush=True)
+    Ys = ql.qlora_linear_fwd_multi(X, Wqs, L1s, L2s, ss, workspace=ws)
+    torch.cuda.synchronize()
+    for l in range(len(outs)):
+        _check(host_bits(Ys[l]), refs[l], f"multi M={M} layer {l} Y")
+    assert int(ws[:ql.binding.WORKSPACE_HEADER_BYTES].max()) == 0, "arrival counters are not back at zero"
+    # twice in a row on the same workspace: bit for bit the same
+    Ys2 = ql.qlora_linear_fwd_multi(X, Wqs, L1s, L2s, ss, workspace=ws)
+    torch.cuda.synchronize()
+    for a, b in zip(Ys, Ys2):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_multi_layer_forward_many_tokens_is_the_single_layer_path(synth):
+    """Above 16 tokens the layers run one after the other through qlora_linear_fwd: identical bits."""
+    import paper_2305_14314_amd as ql
+    M, h, outs, ranks, ss = 96, 512, [512, 192], [16, 32], [0.5, 2.0]
+    X = dev_bf16(synth.normal_bf16((M, h), 1.0, 5000))
+    Wqs = [ql.qlora_nf4_quantize(synth.normal_f32_device((h, o), synth.SIGMA_W, 5100 + l)) for l, o in enumerate(outs)]
+    L1s = [dev_bf16(synth.normal_bf16((h, r), 0.05, 5200 + l)) for l, r in enumerate(ranks)]
+    L2s = [dev_bf16(synth.normal_bf16((r, o), 0.05, 5300 + l)) for l, (r, o) in enumerate(zip(ranks, outs))]
+    Ys = ql.qlora_linear_fwd_multi(X, Wqs, L1s, L2s, ss)
+    torch.cuda.synchronize()
+    for l in range(2):
+        Y1 = ql.qlora_linear_fwd(X, Wqs[l], L1s[l], L2s[l], ss[l])
+        torch.cuda.synchronize()
+        assert torch.equal(Ys[l].view(torch.int16), Y1.view(torch.int16))
+
+
+@pytest.mark.parametrize("group", ["qkv", "gate_up"])
+def test_multi_layer_forward_65b_groups(oracle, synth, group):
+    """The groups of a 65B-shaped decoder block that share their input -- q / k / v (3 x 8192 x 8192) and gate / up
+    (2 x 8192 x 22016) -- at 1 and 16 tokens, r = 64: every output element of every layer against the oracle."""
+    import paper_2305_14314_amd as ql
+    cfg = synth.CONFIGS[4]
+    r, s = cfg["r"], cfg["alpha"] / cfg["r"]
+    h, o, n = (8192, 8192, 3) if group == "qkv" else (8192, 22016, 2)
+    Wqs, Whats, hL1, hL2 = [], [], [], []
+    for l in range(n):
+        Wd = synth.normal_f32_device((h, o), synth.SIGMA_W, 6000 + 10 * l + (0 if group == "qkv" else 5))
+        Wqs.append(ql.qlora_nf4_quantize(Wd))
+        del Wd
+        Whats.append(oracle.nf4_dequant(download_quant(Wqs[-1])))
+        hL1.append(synth.normal_bf16((h, r), cfg["sigma_l"], 6100 + l))
+        hL2.append(synth.normal_bf16((r, o), cfg["sigma_l"], 6200 + l))
+    L1s, L2s = [dev_bf16(a) for a in hL1], [dev_bf16(a) for a in hL2]
+    for M in (1, 16):
+        print(f"case multi {group} M={M}", flush=True)
+        hX = synth.normal_bf16((M, h), 1.0, 6300 + M)
+        Ys = ql.qlora_linear_fwd_multi(dev_bf16(hX), Wqs, L1s, L2s, [s] * n)
+        torch.cuda.synchronize()
+        for l in range(n):
+            _check(host_bits(Ys[l]), oracle.linear_fwd(hX, Whats[l], hL1[l], hL2[l], s), f"{group} M={M} layer {l} Y")
