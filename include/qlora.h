@@ -161,6 +161,18 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
                               uint16_t* dX, uint16_t* dL1, uint16_t* dL2,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same backward pass with gradient accumulation: the adapter gradients are ADDED, in fp32, to the caller's
+ * accumulators instead of being written as bf16 (Section 3 after Eq. 6 gives the gradients; an optimizer step over
+ * several micro-batches, as the batch sizes of the hyperparameter appendix imply, sums them before the update):
+ *   dL1_acc (h x r, fp32) += s * X^T * (dY * L2^T),     dL2_acc (r x o, fp32) += s * (X * L1)^T * dY.
+ * The caller zeroes the accumulators before the first micro-batch.  Either may be NULL; dX, T_saved, the workspace
+ * and every other rule are those of qlora_linear_bwd.  The sums are not rounded to bf16 on the way. */
+qlora_status qlora_linear_bwd_acc(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq,
+                                  const uint16_t* L1, const uint16_t* L2, float s,
+                                  int64_t M, int32_t r, const uint16_t* T_saved,
+                                  uint16_t* dX, float* dL1_acc, float* dL2_acc,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Forward of several QLoRA linear layers that read the SAME input (Eq. 5 applied per layer: the q / k / v or the
  * gate / up projections of a decoder block, where the adapter sits on every linear layer -- Section 5 and the
  * hyperparameter appendix):

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libqlora_hip.so")
 EXPORTS = [
     "qlora_status_string", "qlora_last_hip_error", "qlora_nf4_sizes", "qlora_nf4_quantize",
     "qlora_nf4_dequant", "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd",
-    "qlora_linear_bwd", "qlora_linear_fwd_multi_sizes", "qlora_linear_fwd_multi", "qlora_workspace_init",
+    "qlora_linear_bwd", "qlora_linear_bwd_acc", "qlora_linear_fwd_multi_sizes", "qlora_linear_fwd_multi", "qlora_workspace_init",
     "qlora_profile_gemm", "qlora_profile_gemm_read",
 ]
 
@@ -59,6 +59,7 @@ def lib():
                                    vp, c_size_t, vp]
     L.qlora_linear_bwd.argtypes = [vp, vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp,
                                    vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_linear_bwd_acc.argtypes = list(L.qlora_linear_bwd.argtypes)
     L.qlora_linear_fwd_multi_sizes.argtypes = [c_int64, c_int32, c_int64, POINTER(c_int64), POINTER(c_int32), sp]
     L.qlora_linear_fwd_multi.argtypes = [vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
                                          c_int64, POINTER(c_int32), POINTER(vp), vp, c_size_t, vp]
@@ -250,6 +251,26 @@ def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1
                                   _ptr(dX), _ptr(dL1), _ptr(dL2), _ptr(workspace), workspace.numel(),
                                   _stream(stream)))
     return dX, dL1, dL2
+
+
+def qlora_linear_bwd_acc(dY, X, Wq: NF4Weight, L1, L2, s, dL1_acc, dL2_acc, T_saved=None, dX=None, need_dX=True,
+                         workspace=None, stream=None):
+    """The backward pass with the adapter gradients added to the fp32 accumulators dL1_acc (h, r), dL2_acc (r, o)."""
+    M, o = dY.shape
+    h = Wq.rows
+    r = 0 if L1 is None else L1.shape[1]
+    dev = dY.device
+    if dX is None and need_dX:
+        dX = torch.empty((M, h), dtype=torch.bfloat16, device=dev)
+    for a in (dL1_acc, dL2_acc):
+        assert a is None or (a.dtype == torch.float32 and a.is_contiguous())
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_bwd_sizes(M, h, o, r), dev, stream)
+    v = Wq.view()
+    _check(lib().qlora_linear_bwd_acc(_ptr(dY), _ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(T_saved),
+                                      _ptr(dX), _ptr(dL1_acc), _ptr(dL2_acc), _ptr(workspace), workspace.numel(),
+                                      _stream(stream)))
+    return dX
 
 
 def qlora_profile_gemm(enable: bool):

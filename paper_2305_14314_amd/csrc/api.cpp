@@ -329,7 +329,7 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   if (r > 0) {
     // T = X L1 (Eq. 3): split-K partials, then Ts = bf16(s T) (rank zero-padded) and T_save = [hi | lo] of T
     QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.splits, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, nullptr, st));
   }
   QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
   if (r > 0) QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
@@ -383,21 +383,26 @@ qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf
   return QLORA_OK;
 }
 
-qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
-                              const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved,
-                              uint16_t* dX, uint16_t* dL1, uint16_t* dL2, void* workspace, size_t workspace_bytes,
-                              void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// The backward pass; the adapter gradients go to bf16 matrices (dL1, dL2) or are added to fp32 ones (aL1, aL2).
+qlora_status linear_bwd_impl(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
+                             const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved, uint16_t* dX,
+                             uint16_t* dL1, uint16_t* dL2, float* aL1, float* aL2, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
   if (qlora_status st = check_view(Wq)) return st;
   const int64_t h = Wq->rows, o = Wq->cols;
   if (qlora_status st = check_linear(M, h, o, r)) return st;
   if (!dY || !workspace) return QLORA_ERR_NULL;
-  if (r == 0) { dL1 = nullptr; dL2 = nullptr; }
+  if (r == 0) { dL1 = nullptr; dL2 = nullptr; aL1 = nullptr; aL2 = nullptr; }
   if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
-  if ((dL1 || dL2) && !X) return QLORA_ERR_NULL;
+  const bool want1 = dL1 || aL1, want2 = dL2 || aL2;
+  if ((want1 || want2) && !X) return QLORA_ERR_NULL;
   const BwdPlan p = plan_bwd(workspace, M, h, o, r);
   if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
   if (!aligned16(dY) || !aligned16(X) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
-      !aligned16(T_saved) || !aligned16(dX) || !aligned16(dL1) || !aligned16(dL2))
+      !aligned16(T_saved) || !aligned16(dX) || !aligned16(dL1) || !aligned16(dL2) || !aligned16(aL1) || !aligned16(aL2))
     return QLORA_ERR_ALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
   const qlora::NF4Dev W = to_dev(Wq);
@@ -406,11 +411,11 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
     // few tokens: one launch streams the packed weight once; U = dY L2^T comes from extra workgroups, is applied
     // by each slab's last arriver and left as a [hi | lo] pair for dL1
     QL_TRY(qlora::launch_fewtok_bwd(dY, (int)M, W, p.fpart, p.fsplits, L1, L2, r, s, p.lpart, (unsigned*)workspace, dX,
-                                    (r > 0 && dL1) ? p.Uhl : nullptr, st));
-  } else if (r > 0 && (dX || dL1)) {
+                                    (r > 0 && want1) ? p.Uhl : nullptr, st));
+  } else if (r > 0 && (dX || want1)) {
     // U = dY L2^T: Us = bf16(s U) feeds the adapter segment of dX, the [hi | lo] pair of U feeds dL1
     QL_TRY(qlora::launch_small_gemm(dY, o, false, L2, o, false, 0, 0, (int)M, r, (int)o, p.part, p.sU, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, p.Us, p.rp, p.rp, s, p.Uhl, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sU, (int)M, r, p.Us, p.rp, p.rp, s, p.Uhl, nullptr, st));
   }
   if (!p.few && dX) {
     const uint16_t* B1 = L1;
@@ -420,23 +425,42 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
     QL_TRY(gemm_nt_timed(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, r > 0 ? p.rp : 0, dX, h, (int)M, (int)h,
                                  st));
   }
-  if (dL1) {
+  if (want1) {
     // dL1 = s X^T U: contraction over the tokens, both operands stored token-major; U enters as hi + lo
     QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * r, true, 2, r, (int)h, r, (int)M, p.part, p.sL1, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, r, dL1, r, r, s, nullptr, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, r, dL1, r, r, s, nullptr, aL1, st));
   }
-  if (dL2) {
+  if (want2) {
     const uint16_t* T = T_saved;
     if (!T) {                                               // gradient checkpointing: recompute T = X L1
       QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.sT, st));
-      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, nullptr, 0, 0, 0.0f, p.Thl, st));
+      QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, nullptr, 0, 0, 0.0f, p.Thl, nullptr, st));
       T = p.Thl;
     }
     // dL2 = s T^T dY with T as hi + lo rows
     QL_TRY(qlora::launch_small_gemm(T, 2 * r, true, dY, o, true, 1, r, r, (int)o, (int)M, p.part, p.sL2, st));
-    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, r, (int)o, dL2, o, (int)o, s, nullptr, st));
+    QL_TRY(qlora::launch_small_finalize(p.part, p.sL2, r, (int)o, dL2, o, (int)o, s, nullptr, aL2, st));
   }
   return QLORA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
+                              const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved,
+                              uint16_t* dX, uint16_t* dL1, uint16_t* dL2, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  return linear_bwd_impl(dY, X, Wq, L1, L2, s, M, r, T_saved, dX, dL1, dL2, nullptr, nullptr, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+qlora_status qlora_linear_bwd_acc(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
+                                  const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved,
+                                  uint16_t* dX, float* dL1_acc, float* dL2_acc, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  return linear_bwd_impl(dY, X, Wq, L1, L2, s, M, r, T_saved, dX, nullptr, nullptr, dL1_acc, dL2_acc, workspace,
+                         workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -39,9 +39,9 @@ int small_gemm_splits(int I, int J, int K);
 hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb, int hl,
                              int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st);
 //   Sums the splits, then writes out0 = bf16(scale0 * sum) (w0 columns, zeros beyond J) and/or
-//   hl = [bf16(sum) | bf16(sum - bf16(sum))] (row stride 2 J).
+//   hl = [bf16(sum) | bf16(sum - bf16(sum))] (row stride 2 J) and/or adds scale0 * sum to the fp32 matrix acc (I x J).
 hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
-                                 float scale0, uint16_t* hl, hipStream_t st);
+                                 float scale0, uint16_t* hl, float* acc, hipStream_t st);
 //   dst[c][r] = src[r][c], rows r >= R zero-filled up to Rp.
 hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
                                 hipStream_t st);

@@ -167,9 +167,10 @@ __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallAr
 //   sum(i, j)  = sum over splits of part[s][i][j]
 //   out0[i][j] = bf16(scale0 * sum) for j < J, zero for J <= j < w0                    (row stride ld0)
 //   hl[i][j]   = bf16(sum),  hl[i][J + j] = bf16(sum - hl[i][j])                       (row stride 2 J)
+//   acc[i][j] += scale0 * sum                                      (fp32, row stride J: gradient accumulation)
 __global__ void small_finalize_kernel(const float* __restrict__ part, int splits, int I, int J,
                                       uint16_t* __restrict__ out0, int64_t ld0, int w0, float scale0,
-                                      uint16_t* __restrict__ hl) {
+                                      uint16_t* __restrict__ hl, float* __restrict__ acc) {
   const int wmax = (out0 && w0 > J) ? w0 : J;
   const int64_t total = (int64_t)I * wmax;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
@@ -180,6 +181,7 @@ __global__ void small_finalize_kernel(const float* __restrict__ part, int splits
       for (int sp = 0; sp < splits; ++sp) s += part[(int64_t)sp * I * J + (int64_t)i * J + j];
     }
     if (out0 && j < w0) out0[(int64_t)i * ld0 + j] = bf16_bits(s * scale0);
+    if (acc && j < J) acc[(int64_t)i * J + j] += s * scale0;
     if (hl && j < J) {
       const uint16_t hi = bf16_bits(s);
       hl[(int64_t)i * 2 * J + j] = hi;
@@ -242,12 +244,12 @@ hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint
 }
 
 hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
-                                 float scale0, uint16_t* hl, hipStream_t st) {
+                                 float scale0, uint16_t* hl, float* acc, hipStream_t st) {
   const int wmax = (out0 && w0 > J) ? w0 : J;
   int64_t blocks = ((int64_t)I * wmax + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, out0, ld0, w0,
-                     scale0, hl);
+                     scale0, hl, acc);
   return hipGetLastError();
 }
 

@@ -86,6 +86,10 @@ def test_linear_arguments_are_rejected_on_the_host(L):
     assert b(None, None, ctypes.byref(v), None, None, 1.0, 4, 0, None, fake, None, None, fake, big, None) == -1   # dY
     assert b(fake, None, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, fake, fake, None, fake, big, None) == -1  # dL1 needs X
     assert b(fake, None, ctypes.byref(v), None, None, 1.0, 4, 0, None, fake, None, None, fake, 64, None) == -4
+    a = L.qlora_linear_bwd_acc                    # same checks; the gradient outputs are fp32 accumulators
+    assert a(None, None, ctypes.byref(v), None, None, 1.0, 4, 0, None, fake, None, None, fake, big, None) == -1
+    assert a(fake, None, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, fake, fake, None, fake, big, None) == -1  # needs X
+    assert a(fake, fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, fake, ctypes.c_void_p(0x1004), None, fake, big, None) == -5
     w = L.qlora_workspace_init
     assert w(None, big, None) == -1
     assert w(fake, WORKSPACE_HEADER_BYTES - 1, None) == -4

@@ -116,6 +116,44 @@ def test_run_to_run_determinism(synth):
         assert torch.equal(u, v)
 
 
+@pytest.mark.parametrize("M,h,o,r", [(200, 512, 448, 16), (9, 320, 448, 64), (1024, 1024, 1024, 128)])
+def test_gradient_accumulation(oracle, synth, M, h, o, r):
+    """qlora_linear_bwd_acc over three micro-batches: the fp32 accumulators hold the sum of the oracle's three
+    gradients.  No bf16 rounding is involved, so the bound is far below the output tolerance: the operands are exact
+    bf16, T and U are carried with 16 significant bits (relative 2^-17 per product term) and the sums are fp32."""
+    import paper_2305_14314_amd as ql
+    s = 0.75
+    W = synth.normal_f32((h, o), synth.SIGMA_W, 7000)
+    q = oracle.nf4_quantize(W)
+    Wq = upload_quant(q)
+    hL1, hL2 = synth.normal_bf16((h, r), 0.05, 7001), synth.normal_bf16((r, o), 0.05, 7002)
+    L1, L2 = dev_bf16(hL1), dev_bf16(hL2)
+    a1 = torch.zeros((h, r), dtype=torch.float32, device="cuda")
+    a2 = torch.zeros((r, o), dtype=torch.float32, device="cuda")
+    r1 = np.zeros((h, r))
+    r2 = np.zeros((r, o))
+    dX_ref = None
+    for mb in range(3):
+        hX, hdY = synth.normal_bf16((M, h), 1.0, 7100 + mb), synth.normal_bf16((M, o), 1.0, 7200 + mb)
+        X, dY = dev_bf16(hX), dev_bf16(hdY)
+        T = torch.empty((M, 2 * r), dtype=torch.bfloat16, device="cuda") if mb != 1 else None   # one batch recomputes T
+        if T is not None:
+            ql.qlora_linear_fwd(X, Wq, L1, L2, s, T_save=T)
+        dX = ql.qlora_linear_bwd_acc(dY, X, Wq, L1, L2, s, a1, a2, T_saved=T)
+        dXb, _, _ = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s, T_saved=T)
+        torch.cuda.synchronize()
+        assert torch.equal(dX.view(torch.int16), dXb.view(torch.int16))      # dX does not depend on the variant
+        g1, g2 = oracle.linear_bwd_dl(hdY, hX, hL1, hL2, s)
+        r1 += g1
+        r2 += g2
+    for got, ref, tag in ((a1, r1, "dL1_acc"), (a2, r2, "dL2_acc")):
+        got = got.cpu().numpy().astype(np.float64)
+        rms = np.sqrt((ref ** 2).mean())
+        err = np.abs(got - ref).max()
+        print(f"  {tag}: max|err|/rms = {err / rms:.2e}", flush=True)
+        assert err <= 2e-4 * rms, f"{tag}: max|err| {err:.3g} > 2e-4 * rms {rms:.3g}"
+
+
 FULL = [(1, 0), (1, 4), (1, 6), (2, 0), (2, 4), (2, 6), (3, 0), (3, 4), (3, 6)]   # (config, layer): the distinct shapes
 
 
