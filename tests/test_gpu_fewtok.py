@@ -119,12 +119,13 @@ def test_fewtok_counters_reset_and_repeat(oracle, synth):
                 assert torch.equal(dX.view(torch.int16), first[key[1]].view(torch.int16))
 
 
-@pytest.mark.parametrize("M", [1, 5, 16])
-def test_multi_layer_forward_small(oracle, synth, M):
-    """Several layers on one input in one launch: three layers of different widths, one of them without an adapter,
-    one with rank 64; every output element against the oracle; the counter header is zero afterwards."""
+@pytest.mark.parametrize("M,n", [(1, 3), (5, 3), (16, 3), (3, 1), (8, 4), (16, 2)])
+def test_multi_layer_forward_small(oracle, synth, M, n):
+    """Several layers on one input in one launch: one to four layers of different widths, one of them without an
+    adapter, one with rank 64; every output element against the oracle; the counter header is zero afterwards."""
     import paper_2305_14314_amd as ql
-    h, outs, ranks, ss = 1024, [1024, 320, 2304], [16, 0, 64], [0.5, 1.0, 0.25]
+    h = 1024
+    outs, ranks, ss = [1024, 320, 2304, 64][:n], [16, 0, 64, 32][:n], [0.5, 1.0, 0.25, 2.0][:n]
     hX = synth.normal_bf16((M, h), 1.0, 4000 + M)
     X = dev_bf16(hX)
     Wqs, L1s, L2s, refs = [], [], [], []
