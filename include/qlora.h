@@ -105,6 +105,8 @@ qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int3
  * mean = correctly rounded fp32 mean of all c2; per run of 256 constants
  * c1 = absmax(c2 - mean) and code = E4M3(round-to-nearest-even, saturating)
  * of (c2 - mean) * fl32(448 / c1).
+ * W must be finite: an Inf or NaN is not detected and gives unspecified codes and
+ * constants for the tensor (all accesses stay in bounds).
  * scratch: device buffer of at least the size qlora_nf4_sizes reports. */
 qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
                                 int32_t blocksize, int32_t dq_blocksize,
