@@ -57,10 +57,11 @@ def _load():
     L.oracle_nf4_quantize.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp]
     L.oracle_nf4_dequant.argtypes = [vp, vp, vp, c_float, c_int64, c_int64, c_int32, c_int32, vp, vp]
     lin = [vp, vp, vp, vp, c_double, c_int64, c_int64, c_int64, c_int64, vp, c_int64, vp]
-    for name in ("oracle_linear_fwd", "oracle_linear_fwd_cols", "oracle_linear_bwd_dx",
-                 "oracle_linear_bwd_dx_cols"):
+    for name in ("oracle_linear_fwd_cols", "oracle_linear_bwd_dx_cols"):
         getattr(L, name).argtypes = lin
-    L.oracle_linear_bwd_dl.argtypes = [vp, vp, vp, vp, c_double, c_int64, c_int64, c_int64, c_int64, vp, vp]
+    for name in ("oracle_linear_fwd", "oracle_linear_bwd_dx"):
+        getattr(L, name).argtypes = lin[:-1] + [vp, vp]      # ..., D, out
+    L.oracle_linear_bwd_dl.argtypes = [vp, vp, vp, vp, c_double, c_int64, c_int64, c_int64, c_int64, vp, vp, vp]
     _lib = L
     return L
 
@@ -162,11 +163,20 @@ def _lin_args(A, What, L1, L2, M, h, o):
     return What, L1, L2, r
 
 
-def linear_fwd(X, What, L1, L2, s, rows=None, cols=None):
-    """Y = X What + s (X L1) L2 in fp64.  X/What/L1/L2 are bf16 bit patterns (uint16).
-    rows: token rows to compute (all columns), or cols: output columns (all rows)."""
+def dropout_multipliers(keep, p):
+    """LoRA dropout as a matrix of multipliers: 0 where an element of the adapter's input is dropped, 1/(1-p) where
+    it is kept (keep: boolean M x h)."""
+    return np.ascontiguousarray(np.asarray(keep, bool).astype(np.float64) / (1.0 - float(p)))
+
+
+def linear_fwd(X, What, L1, L2, s, rows=None, cols=None, D=None):
+    """Y = X What + s ((D o X) L1) L2 in fp64 (D: M x h multipliers of LoRA dropout, None = no dropout).
+    X/What/L1/L2 are bf16 bit patterns (uint16).
+    rows: token rows to compute (all columns), or cols: output columns (all rows; not with D)."""
     X = _arr(X, np.uint16)
     M, h = X.shape
+    D = None if D is None else _arr(D, np.float64, (M, h))
+    assert D is None or cols is None
     o = np.asarray(What).shape[1]
     What, L1, L2, r = _lin_args(X, What, L1, L2, M, h, o)
     L = _load()
@@ -180,15 +190,17 @@ def linear_fwd(X, What, L1, L2, s, rows=None, cols=None):
     ns = M if sel is None else sel.size
     Y = np.empty((ns, o), np.float64)
     _check(L.oracle_linear_fwd(_p(X), _p(What), _p(L1), _p(L2), float(s), M, h, o, r,
-                               _p(sel), ns, _p(Y)), "linear_fwd")
+                               _p(sel), ns, _p(D), _p(Y)), "linear_fwd")
     return Y
 
 
-def linear_bwd_dx(dY, What, L1, L2, s, rows=None, cols=None):
-    """dX = dY What^T + s (dY L2^T) L1^T in fp64."""
+def linear_bwd_dx(dY, What, L1, L2, s, rows=None, cols=None, D=None):
+    """dX = dY What^T + s D o ((dY L2^T) L1^T) in fp64 (D as in linear_fwd)."""
     dY = _arr(dY, np.uint16)
     M, o = dY.shape
     h = np.asarray(What).shape[0]
+    D = None if D is None else _arr(D, np.float64, (M, h))
+    assert D is None or cols is None
     What, L1, L2, r = _lin_args(dY, What, L1, L2, M, h, o)
     L = _load()
     if cols is not None:
@@ -201,12 +213,12 @@ def linear_bwd_dx(dY, What, L1, L2, s, rows=None, cols=None):
     ns = M if sel is None else sel.size
     dX = np.empty((ns, h), np.float64)
     _check(L.oracle_linear_bwd_dx(_p(dY), _p(What), _p(L1), _p(L2), float(s), M, h, o, r,
-                                  _p(sel), ns, _p(dX)), "linear_bwd_dx")
+                                  _p(sel), ns, _p(D), _p(dX)), "linear_bwd_dx")
     return dX
 
 
-def linear_bwd_dl(dY, X, L1, L2, s):
-    """dL1 = s X^T (dY L2^T), dL2 = s (X L1)^T dY in fp64."""
+def linear_bwd_dl(dY, X, L1, L2, s, D=None):
+    """dL1 = s Xd^T (dY L2^T), dL2 = s (Xd L1)^T dY in fp64, Xd = D o X (D as in linear_fwd)."""
     dY = _arr(dY, np.uint16)
     X = _arr(X, np.uint16)
     M, o = dY.shape
@@ -216,6 +228,7 @@ def linear_bwd_dl(dY, X, L1, L2, s):
     L2 = _arr(L2, np.uint16, (r, o))
     dL1 = np.empty((h, r), np.float64)
     dL2 = np.empty((r, o), np.float64)
+    D = None if D is None else _arr(D, np.float64, (M, h))
     _check(_load().oracle_linear_bwd_dl(_p(dY), _p(X), _p(L1), _p(L2), float(s), M, h, o, r,
-                                        _p(dL1), _p(dL2)), "linear_bwd_dl")
+                                        _p(D), _p(dL1), _p(dL2)), "linear_bwd_dl")
     return dL1, dL2

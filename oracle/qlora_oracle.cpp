@@ -282,7 +282,7 @@ static int check_lin(const void* a, const void* b, const void* out, int64_t M, i
 int oracle_linear_fwd(const uint16_t* X, const uint16_t* What,
                       const uint16_t* L1, const uint16_t* L2, double s,
                       int64_t M, int64_t h, int64_t o, int64_t r,
-                      const int64_t* row_sel, int64_t n_sel, double* Y) {
+                      const int64_t* row_sel, int64_t n_sel, const double* D, double* Y) {
   if (int e = check_lin(X, What, Y, M, h, o, r, L1, L2)) return e;
   if (!row_sel) n_sel = M;
   for (int64_t i = 0; i < n_sel; ++i) { const int64_t m = row_sel ? row_sel[i] : i; if (m < 0 || m >= M) return -2; }
@@ -296,9 +296,9 @@ int oracle_linear_fwd(const uint16_t* X, const uint16_t* What,
       const uint16_t* w = What + k * o;
       for (int64_t n = 0; n < o; ++n) y[n] += x * bf16_to_f64(w[n]);
     }
-    std::vector<double> t((size_t)r, 0.0);                  /* T = X L1 */
+    std::vector<double> t((size_t)r, 0.0);                  /* T = (D o X) L1 */
     for (int64_t k = 0; k < h; ++k) {
-      const double x = bf16_to_f64(X[m * h + k]);
+      const double x = bf16_to_f64(X[m * h + k]) * (D ? D[m * h + k] : 1.0);
       for (int64_t j = 0; j < r; ++j) t[(size_t)j] += x * bf16_to_f64(L1[k * r + j]);
     }
     for (int64_t n = 0; n < o; ++n) {                       /* + s (T L2) */
@@ -339,7 +339,7 @@ int oracle_linear_fwd_cols(const uint16_t* X, const uint16_t* What,
 int oracle_linear_bwd_dx(const uint16_t* dY, const uint16_t* What,
                          const uint16_t* L1, const uint16_t* L2, double s,
                          int64_t M, int64_t h, int64_t o, int64_t r,
-                         const int64_t* row_sel, int64_t n_sel, double* dX) {
+                         const int64_t* row_sel, int64_t n_sel, const double* D, double* dX) {
   if (int e = check_lin(dY, What, dX, M, h, o, r, L1, L2)) return e;
   if (!row_sel) n_sel = M;
   for (int64_t i = 0; i < n_sel; ++i) { const int64_t m = row_sel ? row_sel[i] : i; if (m < 0 || m >= M) return -2; }
@@ -359,7 +359,7 @@ int oracle_linear_bwd_dx(const uint16_t* dY, const uint16_t* What,
       for (int64_t n = 0; n < o; ++n) acc += bf16_to_f64(g[n]) * bf16_to_f64(w[n]);
       double lora = 0.0;                                    /* U L1^T */
       for (int64_t j = 0; j < r; ++j) lora += u[(size_t)j] * bf16_to_f64(L1[k * r + j]);
-      dX[i * h + k] = acc + s * lora;
+      dX[i * h + k] = acc + s * (D ? D[m * h + k] : 1.0) * lora;   /* the branch saw D o X */
     }
   }
   return 0;
@@ -397,7 +397,7 @@ int oracle_linear_bwd_dx_cols(const uint16_t* dY, const uint16_t* What,
 int oracle_linear_bwd_dl(const uint16_t* dY, const uint16_t* X,
                          const uint16_t* L1, const uint16_t* L2, double s,
                          int64_t M, int64_t h, int64_t o, int64_t r,
-                         double* dL1, double* dL2) {
+                         const double* D, double* dL1, double* dL2) {
   if (!dY || !X || !L1 || !L2 || !dL1 || !dL2) return -1;
   if (M <= 0 || h <= 0 || o <= 0 || r <= 0) return -2;
   std::vector<double> U((size_t)(M * r)), T((size_t)(M * r));
@@ -409,16 +409,16 @@ int oracle_linear_bwd_dl(const uint16_t* dY, const uint16_t* X,
       U[(size_t)(m * r + j)] = acc;
     }
     for (int64_t j = 0; j < r; ++j) T[(size_t)(m * r + j)] = 0.0;
-    for (int64_t k = 0; k < h; ++k) {                       /* T = X L1 */
-      const double x = bf16_to_f64(X[m * h + k]);
+    for (int64_t k = 0; k < h; ++k) {                       /* T = (D o X) L1 */
+      const double x = bf16_to_f64(X[m * h + k]) * (D ? D[m * h + k] : 1.0);
       for (int64_t j = 0; j < r; ++j) T[(size_t)(m * r + j)] += x * bf16_to_f64(L1[k * r + j]);
     }
   }
 #pragma omp parallel for schedule(static)
-  for (int64_t k = 0; k < h; ++k) {                         /* dL1 = s X^T U */
+  for (int64_t k = 0; k < h; ++k) {                         /* dL1 = s (D o X)^T U */
     std::vector<double> acc((size_t)r, 0.0);
     for (int64_t m = 0; m < M; ++m) {
-      const double x = bf16_to_f64(X[m * h + k]);
+      const double x = bf16_to_f64(X[m * h + k]) * (D ? D[m * h + k] : 1.0);
       for (int64_t j = 0; j < r; ++j) acc[(size_t)j] += x * U[(size_t)(m * r + j)];
     }
     for (int64_t j = 0; j < r; ++j) dL1[k * r + j] = s * acc[(size_t)j];

@@ -101,11 +101,18 @@ int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* 
 /* Eq. 5 with the scalar s of Eq. 3:  Y = X What + s (X L1) L2, all sums fp64,
  * no intermediate rounding.  What is the h x o bf16 matrix from
  * oracle_nf4_dequant.  Only the token rows listed in row_sel (n_sel of them,
- * NULL = all M rows in order) are computed; Y is n_sel x o fp64.  r may be 0. */
+ * NULL = all M rows in order) are computed; Y is n_sel x o fp64.  r may be 0.
+ *
+ * LoRA dropout (hyperparameter appendix: rate 0.1 up to 13B, 0.05 above; the
+ * paper gives the rate only, the placement is the one of the LoRA method it
+ * builds on: on the input of the adapter branch): D, if not NULL, is an M x h
+ * fp64 matrix of multipliers (0 for a dropped element, 1/(1-p) for a kept one)
+ * and the branch reads D o X:   Y = X What + s ((D o X) L1) L2.
+ * Placement: PARITY UNPINNED against the paper. */
 int oracle_linear_fwd(const uint16_t* X, const uint16_t* What,
                       const uint16_t* L1, const uint16_t* L2, double s,
                       int64_t M, int64_t h, int64_t o, int64_t r,
-                      const int64_t* row_sel, int64_t n_sel, double* Y);
+                      const int64_t* row_sel, int64_t n_sel, const double* D, double* Y);
 
 /* Same product, only for the output columns in col_sel; Y is M x n_sel. */
 int oracle_linear_fwd_cols(const uint16_t* X, const uint16_t* What,
@@ -114,12 +121,12 @@ int oracle_linear_fwd_cols(const uint16_t* X, const uint16_t* What,
                            const int64_t* col_sel, int64_t n_sel, double* Y);
 
 /* Backward through the frozen weight (Section 3, after Eq. 6):
- *   dX = dY What^T + s (dY L2^T) L1^T
+ *   dX = dY What^T + s D o ((dY L2^T) L1^T)          (D = all ones when NULL)
  * for the token rows in row_sel (NULL = all); dX is n_sel x h fp64. */
 int oracle_linear_bwd_dx(const uint16_t* dY, const uint16_t* What,
                          const uint16_t* L1, const uint16_t* L2, double s,
                          int64_t M, int64_t h, int64_t o, int64_t r,
-                         const int64_t* row_sel, int64_t n_sel, double* dX);
+                         const int64_t* row_sel, int64_t n_sel, const double* D, double* dX);
 
 /* Same, only for the input-feature columns in col_sel; dX is M x n_sel. */
 int oracle_linear_bwd_dx_cols(const uint16_t* dY, const uint16_t* What,
@@ -127,12 +134,13 @@ int oracle_linear_bwd_dx_cols(const uint16_t* dY, const uint16_t* What,
                               int64_t M, int64_t h, int64_t o, int64_t r,
                               const int64_t* col_sel, int64_t n_sel, double* dX);
 
-/* Adapter gradients (only dE/dL_i are formed, never dE/dW):
- *   dL1 = s X^T (dY L2^T)   (h x r),   dL2 = s (X L1)^T dY   (r x o),  fp64. */
+/* Adapter gradients (only dE/dL_i are formed, never dE/dW), fp64, with
+ * Xd = D o X (= X when D is NULL):
+ *   dL1 = s Xd^T (dY L2^T)   (h x r),   dL2 = s (Xd L1)^T dY   (r x o). */
 int oracle_linear_bwd_dl(const uint16_t* dY, const uint16_t* X,
                          const uint16_t* L1, const uint16_t* L2, double s,
                          int64_t M, int64_t h, int64_t o, int64_t r,
-                         double* dL1, double* dL2);
+                         const double* D, double* dL1, double* dL2);
 
 #ifdef __cplusplus
 }

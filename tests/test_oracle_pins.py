@@ -445,3 +445,92 @@ def test_backward_against_library_matmul(oracle, lin_case):
     z1, z2 = np.zeros_like(c["L1"]), np.zeros_like(c["L2"])
     assert np.all(oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], z2, s)[0] == 0)
     assert np.all(oracle.linear_bwd_dl(c["dY"], c["X"], z1, c["L2"], s)[1] == 0)
+
+
+# ----------------------------------------------------------------------------- LoRA dropout
+
+def test_dropout_reduces_to_known_cases(oracle, lin_case):
+    """LoRA dropout (hyperparameter appendix) acts on the input of the adapter branch only.  All multipliers 1 is no
+    dropout, bit for bit; all 0 removes the adapter; the frozen product never sees the mask; and the result equals
+    the library matmul on the masked, rescaled input."""
+    c = lin_case
+    M, h = c["M"], c["h"]
+    X, W, L1, L2, dY = (_bf16_f64(c[k]) for k in ("X", "W", "L1", "L2", "dY"))
+    s = c["s"]
+    ones, zeros = np.ones((M, h)), np.zeros((M, h))
+    base = oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], s)
+    np.testing.assert_array_equal(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], s, D=ones), base)
+    np.testing.assert_allclose(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], s, D=zeros), X @ W, atol=1e-12)
+    rng = np.random.default_rng(8)
+    keep = rng.random((M, h)) >= 0.25
+    D = oracle.dropout_multipliers(keep, 0.25)
+    assert set(np.unique(D)) == {0.0, 1.0 / 0.75} and np.array_equal(D != 0, keep)
+    Xd = X * D
+    np.testing.assert_allclose(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], s, D=D),
+                               X @ W + s * ((Xd @ L1) @ L2), rtol=0, atol=1e-12)
+    rows = np.array([5, 1], np.int64)
+    np.testing.assert_array_equal(oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], s, rows=rows, D=D),
+                                  oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], s, D=D)[rows])
+    got_dx = oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], s, D=D)
+    np.testing.assert_allclose(got_dx, dY @ W.T + s * D * ((dY @ L2.T) @ L1.T), rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], s, rows=rows, D=D), got_dx[rows])
+    dL1, dL2 = oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], c["L2"], s, D=D)
+    np.testing.assert_allclose(dL1, s * (Xd.T @ (dY @ L2.T)), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dL2, s * ((Xd @ L1).T @ dY), rtol=0, atol=1e-12)
+    # a dropped input element gets no gradient through the adapter, and gives none to its row of L1
+    m, k = np.argwhere(~keep)[0]
+    assert abs(got_dx[m, k] - (dY @ W.T)[m, k]) < 1e-12
+    only = np.zeros((M, h)); only[:, 3] = 2.0                          # everything dropped but feature 3
+    dL1_only, _ = oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], c["L2"], s, D=only)
+    assert np.all(dL1_only[np.arange(h) != 3] == 0) and np.any(dL1_only[3] != 0)
+
+
+def test_dropout_backward_by_exact_central_differences(oracle):
+    """With a fixed mask E = sum(Y * dY) is still linear in X, L1 and L2: central differences with step 1 on small
+    integers (multipliers 0 and 2, i.e. p = 1/2, keep every product exact) reproduce the three gradients."""
+    rng = np.random.default_rng(9)
+    M, h, o, r = 5, 12, 16, 3
+    ints = lambda shape, k: _bf16_bits(rng.integers(-k, k + 1, shape).astype(np.float32))
+    c = dict(s=0.25, X=ints((M, h), 6), W=ints((h, o), 4), L1=ints((h, r), 3), L2=ints((r, o), 3), dY=ints((M, o), 5))
+    keep = rng.random((M, h)) >= 0.5
+    keep[0, 0], keep[4, 11] = True, False
+    D = oracle.dropout_multipliers(keep, 0.5)
+    dX = oracle.linear_bwd_dx(c["dY"], c["W"], c["L1"], c["L2"], c["s"], D=D)
+    dL1, dL2 = oracle.linear_bwd_dl(c["dY"], c["X"], c["L1"], c["L2"], c["s"], D=D)
+
+    def energy(X=None, L1=None, L2=None):
+        Y = oracle.linear_fwd(c["X"] if X is None else X, c["W"], c["L1"] if L1 is None else L1,
+                              c["L2"] if L2 is None else L2, c["s"], D=D)
+        return float((Y * _bf16_f64(c["dY"])).sum())
+
+    def bump(bits, i, j, d):
+        a = _bf16_f64(bits).astype(np.float32).copy()
+        a[i, j] += d
+        return _bf16_bits(a)
+
+    for (i, j) in [(0, 0), (4, 11), (2, 5), (3, 7)]:                  # a kept and a dropped element among them
+        num = (energy(X=bump(c["X"], i, j, 1)) - energy(X=bump(c["X"], i, j, -1))) / 2
+        assert abs(num - dX[i, j]) < 1e-9
+    for (i, j) in [(0, 0), (11, 2), (6, 1)]:
+        num = (energy(L1=bump(c["L1"], i, j, 1)) - energy(L1=bump(c["L1"], i, j, -1))) / 2
+        assert abs(num - dL1[i, j]) < 1e-9
+    for (i, j) in [(0, 0), (2, 15), (1, 8)]:
+        num = (energy(L2=bump(c["L2"], i, j, 1)) - energy(L2=bump(c["L2"], i, j, -1))) / 2
+        assert abs(num - dL2[i, j]) < 1e-9
+
+
+def test_dropout_keeps_the_expectation(oracle, lin_case):
+    """Inverted dropout: averaged over many independent masks the adapter term returns to its no-dropout value
+    (the 1/(1-p) rescaling), within the sampling error."""
+    c = lin_case
+    rng = np.random.default_rng(10)
+    p, n = 0.1, 400
+    base = oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], c["s"])
+    acc = np.zeros_like(base)
+    for _ in range(n):
+        acc += oracle.linear_fwd(c["X"], c["W"], c["L1"], c["L2"], c["s"],
+                                 D=oracle.dropout_multipliers(rng.random((c["M"], c["h"])) >= p, p))
+    frozen = _bf16_f64(c["X"]) @ _bf16_f64(c["W"])
+    adapter = base - frozen
+    err = np.abs(acc / n - base).max()
+    assert err < 0.1 * np.abs(adapter).max(), (err, np.abs(adapter).max())
