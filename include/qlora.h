@@ -175,6 +175,35 @@ qlora_status qlora_linear_bwd_acc(const uint16_t* dY, const uint16_t* X, const q
                                   uint16_t* dX, float* dL1_acc, float* dL2_acc,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* LoRA dropout (hyperparameter appendix: rate 0.1 for models up to 13B, 0.05 for 33B and 65B).  The paper gives the
+ * rate only; the placement is the one of the LoRA method it builds on -- inverted dropout on the INPUT of the adapter
+ * branch, the frozen product never sees it:
+ *   Y   = X * doubleDequant(Wq) + s * ((D o X) * L1) * L2,      D[m][k] = keep(m, k) / (1 - p)
+ *   dX  = dY * doubleDequant(Wq)^T + s * D o ((dY * L2^T) * L1^T)
+ *   dL1 = s * (D o X)^T * (dY * L2^T),      dL2 = s * ((D o X) * L1)^T * dY.
+ * The random draw is the caller's: keep_mask (device, M*h/8 bytes) holds one bit per element of X, bit e % 8 of byte
+ * e / 8 for e = m*h + k, 1 = kept; the same mask must be passed to the forward and the backward call of a step.
+ * 0 <= p < 1 (else QLORA_ERR_SHAPE); keep_mask may be NULL only when r = 0, where the calls are the plain ones.
+ * T_save / T_saved hold (B o X) * L1 for the 0/1 mask B, as a [hi | lo] pair (the 1/(1-p) is applied with s).
+ * These calls always take the large-GEMM path (no few-token streaming kernel); workspaces are sized by
+ * qlora_linear_dropout_sizes (either out-pointer may be NULL).  The backward call takes both kinds of adapter
+ * gradient outputs of qlora_linear_bwd and qlora_linear_bwd_acc; any of them may be NULL.  Everything else --
+ * layouts, alignment, ownership, errors, tolerance -- as for qlora_linear_fwd / qlora_linear_bwd. */
+qlora_status qlora_linear_dropout_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* fwd_bytes,
+                                        size_t* bwd_bytes);
+qlora_status qlora_linear_fwd_dropout(const uint16_t* X, const qlora_nf4_view* Wq,
+                                      const uint16_t* L1, const uint16_t* L2, float s,
+                                      int64_t M, int32_t r, const uint8_t* keep_mask, float p,
+                                      uint16_t* Y, uint16_t* T_save,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+qlora_status qlora_linear_bwd_dropout(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq,
+                                      const uint16_t* L1, const uint16_t* L2, float s,
+                                      int64_t M, int32_t r, const uint8_t* keep_mask, float p,
+                                      const uint16_t* T_saved,
+                                      uint16_t* dX, uint16_t* dL1, uint16_t* dL2,
+                                      float* dL1_acc, float* dL2_acc,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Forward of several QLoRA linear layers that read the SAME input (Eq. 5 applied per layer: the q / k / v or the
  * gate / up projections of a decoder block, where the adapter sits on every linear layer -- Section 5 and the
  * hyperparameter appendix):

@@ -20,6 +20,7 @@ EXPORTS = [
     "qlora_nf4_dequant", "qlora_linear_fwd_sizes", "qlora_linear_bwd_sizes", "qlora_linear_fwd",
     "qlora_linear_bwd", "qlora_linear_bwd_acc", "qlora_linear_fwd_multi_sizes", "qlora_linear_fwd_multi", "qlora_workspace_init",
     "qlora_profile_gemm", "qlora_profile_gemm_read",
+    "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
 ]
 
 
@@ -63,6 +64,11 @@ def lib():
     L.qlora_linear_fwd_multi_sizes.argtypes = [c_int64, c_int32, c_int64, POINTER(c_int64), POINTER(c_int32), sp]
     L.qlora_linear_fwd_multi.argtypes = [vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
                                          c_int64, POINTER(c_int32), POINTER(vp), vp, c_size_t, vp]
+    L.qlora_linear_dropout_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp, sp]
+    L.qlora_linear_fwd_dropout.argtypes = [vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp, c_float,
+                                           vp, vp, vp, c_size_t, vp]
+    L.qlora_linear_bwd_dropout.argtypes = [vp, vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp, c_float,
+                                           vp, vp, vp, vp, vp, vp, vp, c_size_t, vp]
     L.qlora_profile_gemm.argtypes = [ctypes.c_int]
     L.qlora_profile_gemm.restype = None
     L.qlora_profile_gemm_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64), POINTER(ctypes.c_double)]
@@ -271,6 +277,62 @@ def qlora_linear_bwd_acc(dY, X, Wq: NF4Weight, L1, L2, s, dL1_acc, dL2_acc, T_sa
                                       _ptr(dX), _ptr(dL1_acc), _ptr(dL2_acc), _ptr(workspace), workspace.numel(),
                                       _stream(stream)))
     return dX
+
+
+def qlora_linear_dropout_sizes(M, h, o, r):
+    """(forward workspace bytes, backward workspace bytes) of the LoRA-dropout calls."""
+    f, b = c_size_t(0), c_size_t(0)
+    _check(lib().qlora_linear_dropout_sizes(M, h, o, r, byref(f), byref(b)))
+    return int(f.value), int(b.value)
+
+
+def pack_keep_mask(keep):
+    """Boolean (M, h) device tensor, True = kept -> the bit mask the C ABI takes (bit e % 8 of byte e // 8)."""
+    k = keep.reshape(-1, 8).to(torch.uint8)
+    w = torch.tensor([1, 2, 4, 8, 16, 32, 64, 128], dtype=torch.uint8, device=keep.device)
+    return (k * w).sum(dim=1, dtype=torch.int32).to(torch.uint8).contiguous()
+
+
+def qlora_linear_fwd_dropout(X, Wq: NF4Weight, L1, L2, s, keep_mask, p, Y=None, T_save=None, workspace=None, stream=None):
+    """Y = X dequant(Wq) + s ((D o X) L1) L2 with D = keep / (1 - p): LoRA dropout on the adapter's input.
+    keep_mask: uint8 device tensor of M * h / 8 bytes (pack_keep_mask)."""
+    M, h = X.shape
+    o = Wq.cols
+    r = 0 if L1 is None else L1.shape[1]
+    if Y is None:
+        Y = torch.empty((M, o), dtype=torch.bfloat16, device=X.device)
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_dropout_sizes(M, h, o, r)[0], X.device, stream)
+    v = Wq.view()
+    _check(lib().qlora_linear_fwd_dropout(_ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(keep_mask),
+                                          float(p), _ptr(Y), _ptr(T_save), _ptr(workspace), workspace.numel(),
+                                          _stream(stream)))
+    return Y
+
+
+def qlora_linear_bwd_dropout(dY, X, Wq: NF4Weight, L1, L2, s, keep_mask, p, T_saved=None, dX=None, dL1=None, dL2=None,
+                             dL1_acc=None, dL2_acc=None, need_dX=True, need_dL=True, workspace=None, stream=None):
+    """dX, dL1, dL2 under LoRA dropout (same mask as the forward call); with dL1_acc / dL2_acc the adapter gradients
+    are added to those fp32 accumulators instead."""
+    M, o = dY.shape
+    h = Wq.rows
+    r = 0 if L1 is None else L1.shape[1]
+    dev = dY.device
+    if dX is None and need_dX:
+        dX = torch.empty((M, h), dtype=torch.bfloat16, device=dev)
+    if r > 0 and need_dL and dL1_acc is None and dL2_acc is None:
+        if dL1 is None:
+            dL1 = torch.empty((h, r), dtype=torch.bfloat16, device=dev)
+        if dL2 is None:
+            dL2 = torch.empty((r, o), dtype=torch.bfloat16, device=dev)
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_dropout_sizes(M, h, o, r)[1], dev, stream)
+    v = Wq.view()
+    _check(lib().qlora_linear_bwd_dropout(_ptr(dY), _ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r,
+                                          _ptr(keep_mask), float(p), _ptr(T_saved), _ptr(dX), _ptr(dL1), _ptr(dL2),
+                                          _ptr(dL1_acc), _ptr(dL2_acc), _ptr(workspace), workspace.numel(),
+                                          _stream(stream)))
+    return dX, dL1, dL2
 
 
 def qlora_profile_gemm(enable: bool):

@@ -100,11 +100,11 @@ struct FwdPlan {
   bool few;
   size_t bytes;
 };
-FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
+FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r, bool allow_few = true) {
   FwdPlan p{};
   Carver c(ws);
   p.rp = (r + 63) / 64 * 64;
-  p.few = M <= qlora::kFewTokens && qlora::fewtok_fwd_slabs((int)o) <= qlora::kFewMaxSlabs;
+  p.few = allow_few && M <= qlora::kFewTokens && qlora::fewtok_fwd_slabs((int)o) <= qlora::kFewMaxSlabs;
   if (p.few) {
     p.fsplits = qlora::fewtok_fwd_splits((int)h, (int)o);
     p.fpart = c.take<float>((size_t)p.fsplits * M * o);
@@ -137,11 +137,11 @@ struct BwdPlan {
   bool few;
   size_t bytes;
 };
-BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r) {
+BwdPlan plan_bwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r, bool allow_few = true) {
   BwdPlan p{};
   Carver c(ws);
   p.rp = (r + 63) / 64 * 64;
-  p.few = M <= qlora::kFewTokens && qlora::fewtok_bwd_slabs((int)h) <= qlora::kFewMaxSlabs;
+  p.few = allow_few && M <= qlora::kFewTokens && qlora::fewtok_bwd_slabs((int)h) <= qlora::kFewMaxSlabs;
   if (p.few) {
     p.fsplits = qlora::fewtok_bwd_splits((int)h, (int)o);
     p.fpart = c.take<float>((size_t)p.fsplits * M * h);
@@ -303,15 +303,22 @@ qlora_status qlora_workspace_init(void* workspace, size_t workspace_bytes, void*
 
 #define QL_TRY(expr) do { if (hipError_t e_ = (expr)) return hip_status(e_); } while (0)
 
-qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1, const uint16_t* L2,
-                              float s, int64_t M, int32_t r, uint16_t* Y, uint16_t* T_save, void* workspace,
-                              size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// LoRA dropout: the kept elements' 1/(1-p) goes into the adapter's scale, the mask into the operand loads.
+inline float dropout_scale(float s, float p) { return (float)((double)s / (1.0 - (double)p)); }
+
+// The forward pass; keep_mask != NULL: LoRA dropout on the adapter's input (large-GEMM path whatever M).
+qlora_status linear_fwd_impl(const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1, const uint16_t* L2,
+                             float s, int64_t M, int32_t r, const uint8_t* keep_mask, uint16_t* Y, uint16_t* T_save,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (qlora_status st = check_view(Wq)) return st;
   const int64_t h = Wq->rows, o = Wq->cols;
   if (qlora_status st = check_linear(M, h, o, r)) return st;
   if (!X || !Y || !workspace) return QLORA_ERR_NULL;
   if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
-  const FwdPlan p = plan_fwd(workspace, M, h, o, r);
+  const FwdPlan p = plan_fwd(workspace, M, h, o, r, keep_mask == nullptr);
   if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
   if (!aligned16(X) || !aligned16(Y) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
       !aligned16(T_save))
@@ -328,7 +335,7 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   }
   if (r > 0) {
     // T = X L1 (Eq. 3): split-K partials, then Ts = bf16(s T) (rank zero-padded) and T_save = [hi | lo] of T
-    QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.splits, st));
+    QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.splits, st, keep_mask));
     QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, nullptr, st));
   }
   QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
@@ -337,6 +344,34 @@ qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const
   QL_TRY(gemm_nt_timed(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
                                st));
   return QLORA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+qlora_status qlora_linear_fwd(const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1, const uint16_t* L2,
+                              float s, int64_t M, int32_t r, uint16_t* Y, uint16_t* T_save, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  return linear_fwd_impl(X, Wq, L1, L2, s, M, r, nullptr, Y, T_save, workspace, workspace_bytes, hip_stream);
+}
+
+qlora_status qlora_linear_dropout_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* fwd_bytes,
+                                        size_t* bwd_bytes) {
+  if (qlora_status st = check_linear(M, h, o, r)) return st;
+  // without an adapter there is nothing to drop and the calls are the plain ones, few-token path included
+  if (fwd_bytes) *fwd_bytes = plan_fwd(nullptr, M, h, o, r, r == 0).bytes;
+  if (bwd_bytes) *bwd_bytes = plan_bwd(nullptr, M, h, o, r, r == 0).bytes;
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_fwd_dropout(const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
+                                      const uint16_t* L2, float s, int64_t M, int32_t r, const uint8_t* keep_mask,
+                                      float p, uint16_t* Y, uint16_t* T_save, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  if (!(p >= 0.0f && p < 1.0f)) return QLORA_ERR_SHAPE;
+  if (r > 0 && !keep_mask) return QLORA_ERR_NULL;
+  return linear_fwd_impl(X, Wq, L1, L2, r > 0 ? dropout_scale(s, p) : s, M, r, r > 0 ? keep_mask : nullptr, Y, T_save,
+                         workspace, workspace_bytes, hip_stream);
 }
 
 qlora_status qlora_linear_fwd_multi_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
@@ -388,9 +423,9 @@ qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf
 namespace {
 // The backward pass; the adapter gradients go to bf16 matrices (dL1, dL2) or are added to fp32 ones (aL1, aL2).
 qlora_status linear_bwd_impl(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq, const uint16_t* L1,
-                             const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved, uint16_t* dX,
-                             uint16_t* dL1, uint16_t* dL2, float* aL1, float* aL2, void* workspace,
-                             size_t workspace_bytes, void* hip_stream) {
+                             const uint16_t* L2, float s, int64_t M, int32_t r, const uint8_t* keep_mask,
+                             const uint16_t* T_saved, uint16_t* dX, uint16_t* dL1, uint16_t* dL2, float* aL1,
+                             float* aL2, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (qlora_status st = check_view(Wq)) return st;
   const int64_t h = Wq->rows, o = Wq->cols;
   if (qlora_status st = check_linear(M, h, o, r)) return st;
@@ -399,7 +434,7 @@ qlora_status linear_bwd_impl(const uint16_t* dY, const uint16_t* X, const qlora_
   if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
   const bool want1 = dL1 || aL1, want2 = dL2 || aL2;
   if ((want1 || want2) && !X) return QLORA_ERR_NULL;
-  const BwdPlan p = plan_bwd(workspace, M, h, o, r);
+  const BwdPlan p = plan_bwd(workspace, M, h, o, r, keep_mask == nullptr);
   if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
   if (!aligned16(dY) || !aligned16(X) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
       !aligned16(T_saved) || !aligned16(dX) || !aligned16(dL1) || !aligned16(dL2) || !aligned16(aL1) || !aligned16(aL2))
@@ -424,16 +459,18 @@ qlora_status linear_bwd_impl(const uint16_t* dY, const uint16_t* X, const qlora_
     // dX = dY What^T + Us L1^T
     QL_TRY(gemm_nt_timed(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, r > 0 ? p.rp : 0, dX, h, (int)M, (int)h,
                                  st));
+    // LoRA dropout: a dropped input element gets no gradient through the adapter
+    if (r > 0 && keep_mask) QL_TRY(qlora::launch_dropout_dx_fix(dX, (int)M, (int)h, keep_mask, p.Us, p.rp, L1, r, st));
   }
   if (want1) {
     // dL1 = s X^T U: contraction over the tokens, both operands stored token-major; U enters as hi + lo
-    QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * r, true, 2, r, (int)h, r, (int)M, p.part, p.sL1, st));
+    QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * r, true, 2, r, (int)h, r, (int)M, p.part, p.sL1, st, keep_mask));
     QL_TRY(qlora::launch_small_finalize(p.part, p.sL1, (int)h, r, dL1, r, r, s, nullptr, aL1, st));
   }
   if (want2) {
     const uint16_t* T = T_saved;
     if (!T) {                                               // gradient checkpointing: recompute T = X L1
-      QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.sT, st));
+      QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.sT, st, keep_mask));
       QL_TRY(qlora::launch_small_finalize(p.part, p.sT, (int)M, r, nullptr, 0, 0, 0.0f, p.Thl, nullptr, st));
       T = p.Thl;
     }
@@ -451,7 +488,7 @@ qlora_status qlora_linear_bwd(const uint16_t* dY, const uint16_t* X, const qlora
                               const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved,
                               uint16_t* dX, uint16_t* dL1, uint16_t* dL2, void* workspace, size_t workspace_bytes,
                               void* hip_stream) {
-  return linear_bwd_impl(dY, X, Wq, L1, L2, s, M, r, T_saved, dX, dL1, dL2, nullptr, nullptr, workspace,
+  return linear_bwd_impl(dY, X, Wq, L1, L2, s, M, r, nullptr, T_saved, dX, dL1, dL2, nullptr, nullptr, workspace,
                          workspace_bytes, hip_stream);
 }
 
@@ -459,8 +496,19 @@ qlora_status qlora_linear_bwd_acc(const uint16_t* dY, const uint16_t* X, const q
                                   const uint16_t* L2, float s, int64_t M, int32_t r, const uint16_t* T_saved,
                                   uint16_t* dX, float* dL1_acc, float* dL2_acc, void* workspace,
                                   size_t workspace_bytes, void* hip_stream) {
-  return linear_bwd_impl(dY, X, Wq, L1, L2, s, M, r, T_saved, dX, nullptr, nullptr, dL1_acc, dL2_acc, workspace,
-                         workspace_bytes, hip_stream);
+  return linear_bwd_impl(dY, X, Wq, L1, L2, s, M, r, nullptr, T_saved, dX, nullptr, nullptr, dL1_acc, dL2_acc,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+qlora_status qlora_linear_bwd_dropout(const uint16_t* dY, const uint16_t* X, const qlora_nf4_view* Wq,
+                                      const uint16_t* L1, const uint16_t* L2, float s, int64_t M, int32_t r,
+                                      const uint8_t* keep_mask, float p, const uint16_t* T_saved, uint16_t* dX,
+                                      uint16_t* dL1, uint16_t* dL2, float* dL1_acc, float* dL2_acc, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  if (!(p >= 0.0f && p < 1.0f)) return QLORA_ERR_SHAPE;
+  if (r > 0 && !keep_mask) return QLORA_ERR_NULL;
+  return linear_bwd_impl(dY, X, Wq, L1, L2, r > 0 ? dropout_scale(s, p) : s, M, r, r > 0 ? keep_mask : nullptr, T_saved,
+                         dX, dL1, dL2, dL1_acc, dL2_acc, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -36,8 +36,15 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
 //   hl = 1 / 2: A / B is a [hi | lo] pair (the lo half hl_off elements behind the hi half) and enters as hi + lo;
 //   supported: (ta, tb, hl) = (0,1,0), (0,0,0), (1,1,1), (1,1,2).
 int small_gemm_splits(int I, int J, int K);
+//   amask (LoRA dropout; only with (0,1,0) and (1,1,2), lda % 8 == 0): elements of A whose keep-bit -- bit e % 8 of byte
+//   e / 8, e the element's offset from A -- is clear enter as zero.
 hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb, int hl,
-                             int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st);
+                             int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st,
+                             const uint8_t* amask = nullptr);
+//   LoRA dropout: dX[m][k] -= sum_t Us[m][t] L1[k][t] (bf16 operands, fp32 sum, one more rounding to bf16) wherever the
+//   keep-bit of element (m, k) is clear.  dX is M x h, Us M x ld_us (first r columns used), L1 h x r.
+hipError_t launch_dropout_dx_fix(uint16_t* dX, int M, int h, const uint8_t* mask, const uint16_t* Us, int ld_us,
+                                 const uint16_t* L1, int r, hipStream_t st);
 //   Sums the splits, then writes out0 = bf16(scale0 * sum) (w0 columns, zeros beyond J) and/or
 //   hl = [bf16(sum) | bf16(sum - bf16(sum))] (row stride 2 J) and/or adds scale0 * sum to the fp32 matrix acc (I x J).
 hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,

@@ -9,6 +9,10 @@
 // an operand (HL = 1: A, HL = 2: B) the kernel loads both halves' tiles and issues two MFMAs per fragment of
 // the other operand into the same accumulators, so X (resp. dY) is streamed once.
 //
+// MASK: LoRA dropout on the adapter's input (hyperparameter appendix): operand A is X, and an element of X enters as
+// zero where its bit in the caller's keep-mask (bit e % 8 of byte e / 8 for the flat element index e = token * h + k)
+// is clear; the 1/(1-p) of the kept elements is folded into the scale of the finalize step.
+//
 // Operand layouts are template flags: TA = false means A is stored [i][k] (K-contiguous),
 // TA = true means A is stored [k][i] (the contraction index is the row index, as for X^T);
 // likewise TB for B ([j][k] or [k][j]).  K-contiguous tiles are kept in LDS XOR-swizzled in 16-byte
@@ -31,6 +35,7 @@ struct SmallArgs {
   const uint16_t* A; int64_t lda;
   const uint16_t* B; int64_t ldb;
   int64_t hl_off;            // HL != 0: element offset of the pair's lo half from its hi half (same row)
+  const uint8_t* amask;      // MASK: keep-bits of A's elements in storage order, one bit each
   float* part;
   int I, J, K, k_per_split;
 };
@@ -51,6 +56,32 @@ __device__ __forceinline__ u32x4 fetch_chunk(const uint16_t* __restrict__ src, i
     if (k < k_end && row < R) return *(const u32x4*)(src + (int64_t)k * ld + row);
     return z;
   }
+}
+
+// the same for operand A under a keep-mask: a chunk is 8 consecutive elements of storage, i.e. one mask byte
+template <bool T>
+__device__ __forceinline__ u32x4 fetch_chunk_masked(const uint16_t* __restrict__ src, const uint8_t* __restrict__ mask,
+                                                    int64_t ld, int r0, int R, int k0, int k_end, int c) {
+  u32x4 v = {0u, 0u, 0u, 0u};
+  int64_t off;
+  bool ok;
+  if constexpr (!T) {
+    const int row = r0 + (c >> 3), k = k0 + (c & 7) * 8;
+    ok = row < R && k < k_end;
+    off = (int64_t)row * ld + k;
+  } else {
+    const int k = k0 + (c >> 3), row = r0 + (c & 7) * 8;
+    ok = k < k_end && row < R;
+    off = (int64_t)k * ld + row;
+  }
+  if (ok) {
+    v = *(const u32x4*)(src + off);
+    const uint32_t b = mask[off >> 3];                       // ld and the chunk start are multiples of 8
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+      v[d] &= (((b >> (2 * d)) & 1u) ? 0x0000ffffu : 0u) | (((b >> (2 * d + 1)) & 1u) ? 0xffff0000u : 0u);
+  }
+  return v;
 }
 
 template <bool T>
@@ -84,9 +115,10 @@ __device__ __forceinline__ bf16x8 small_frag(const lds_char* tile, int row, int 
   }
 }
 
-template <bool TA, bool TB, int HL>
+template <bool TA, bool TB, int HL, bool MASK>
 __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallArgs p) {
   static_assert(HL == 0 || (HL == 1 && TA) || (HL == 2 && TB), "a [hi | lo] operand is stored token-major");
+  static_assert(!MASK || HL != 1, "the masked operand is X itself");
   __shared__ __attribute__((aligned(16))) char sA_[ST * kTPitch * 2];
   __shared__ __attribute__((aligned(16))) char sB_[ST * kTPitch * 2];
   __shared__ __attribute__((aligned(16))) char sC_[HL ? ST * kTPitch * 2 : 16];
@@ -114,7 +146,8 @@ __global__ __launch_bounds__(kSmallThreads) void small_gemm_kernel(const SmallAr
   auto fetch = [&](Regs& R, int k0) {                       // k0 >= k_end loads nothing and yields zeros
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      R.a[u] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0, k_end, tid + 256 * u);
+      if constexpr (MASK) R.a[u] = fetch_chunk_masked<TA>(p.A, p.amask, p.lda, i0, p.I, k0, k_end, tid + 256 * u);
+      else R.a[u] = fetch_chunk<TA>(p.A, p.lda, i0, p.I, k0, k_end, tid + 256 * u);
       R.b[u] = fetch_chunk<TB>(p.B, p.ldb, j0, p.J, k0, k_end, tid + 256 * u);
       if constexpr (HL != 0) R.c[u] = fetch_chunk<true>(lo_src, lo_ld, lo_r0, lo_R, k0, k_end, tid + 256 * u);
     }
@@ -228,17 +261,25 @@ int small_gemm_splits(int I, int J, int K) {
 }
 
 hipError_t launch_small_gemm(const uint16_t* A, int64_t lda, bool ta, const uint16_t* B, int64_t ldb, bool tb, int hl,
-                             int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st) {
+                             int64_t hl_off, int I, int J, int K, float* part, int splits, hipStream_t st,
+                             const uint8_t* amask) {
   SmallArgs a;
   a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.hl_off = hl_off; a.part = part; a.I = I; a.J = J; a.K = K;
+  a.amask = amask;
+  if (amask && lda % 8 != 0) return hipErrorInvalidValue;
   const int ksteps = (K + ST - 1) / ST;
   a.k_per_split = ((ksteps + splits - 1) / splits) * ST;
   dim3 grid((unsigned)((I + ST - 1) / ST), (unsigned)((J + ST - 1) / ST), (unsigned)splits);
   dim3 block(kSmallThreads);
-  if (!ta && tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, true, 0>), grid, block, 0, st, a);
-  else if (!ta && !tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, false, 0>), grid, block, 0, st, a);
-  else if (ta && tb && hl == 1) hipLaunchKernelGGL((small_gemm_kernel<true, true, 1>), grid, block, 0, st, a);
-  else if (ta && tb && hl == 2) hipLaunchKernelGGL((small_gemm_kernel<true, true, 2>), grid, block, 0, st, a);
+  if (amask) {
+    if (!ta && tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, true, 0, true>), grid, block, 0, st, a);
+    else if (ta && tb && hl == 2) hipLaunchKernelGGL((small_gemm_kernel<true, true, 2, true>), grid, block, 0, st, a);
+    else return hipErrorInvalidValue;
+  }
+  else if (!ta && tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, true, 0, false>), grid, block, 0, st, a);
+  else if (!ta && !tb && hl == 0) hipLaunchKernelGGL((small_gemm_kernel<false, false, 0, false>), grid, block, 0, st, a);
+  else if (ta && tb && hl == 1) hipLaunchKernelGGL((small_gemm_kernel<true, true, 1, false>), grid, block, 0, st, a);
+  else if (ta && tb && hl == 2) hipLaunchKernelGGL((small_gemm_kernel<true, true, 2, false>), grid, block, 0, st, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -250,6 +291,75 @@ hipError_t launch_small_finalize(const float* part, int splits, int I, int J, ui
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(small_finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, splits, I, J, out0, ld0, w0,
                      scale0, hl, acc);
+  return hipGetLastError();
+}
+
+// LoRA dropout, input gradient: the main GEMM has written dX = dY What^T + Us L1^T with Us = bf16(s/(1-p) dY L2^T),
+// which is right wherever the adapter saw the input element; a dropped element gets no gradient through the
+// adapter, so its adapter term -- recomputed here from the same bf16 operands -- is taken off again (one more
+// rounding for those elements).  A workgroup takes 256 mask bytes (2048 consecutive elements), lists the dropped
+// ones in LDS (a few per cent) and spreads them over its threads, eight lanes to a dot product of length r: with
+// one thread per mask byte nearly every wave would walk all eight bit positions for two or three useful lanes.
+__global__ __launch_bounds__(256) void dropout_dx_fix_kernel(uint16_t* __restrict__ dX, int64_t n_bytes, int h,
+                                                             const uint8_t* __restrict__ mask,
+                                                             const uint16_t* __restrict__ Us, int ld_us,
+                                                             const uint16_t* __restrict__ L1, int r) {
+  __shared__ uint16_t list[2048];
+  __shared__ int wave_cnt[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t q = (int64_t)blockIdx.x * 256 + tid;
+  const uint32_t drop = q < n_bytes ? (~(uint32_t)mask[q]) & 0xffu : 0u;
+  const int cnt = __builtin_popcount(drop);
+  // exclusive prefix sum of cnt over the workgroup: within the wave by shuffles, across the 4 waves through LDS
+  int incl = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int up = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += up;
+  }
+  if (lane == 63) wave_cnt[wave] = incl;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int c = wave_cnt[w];
+    if (w < wave) base += c;
+    total += c;
+  }
+  int pos = base + incl - cnt;
+  for (uint32_t d = drop; d != 0; d &= d - 1) list[pos++] = (uint16_t)(tid * 8 + (__builtin_ctz(d)));
+  __syncthreads();
+  // eight lanes per dropped element, 16 bytes of both rows per lane and step, summed by shuffles
+  const int64_t e_base = (int64_t)blockIdx.x * 2048;
+  const int sub = tid & 7;
+  for (int idx0 = 0; idx0 < total; idx0 += 32) {             // uniform trip count: the shuffles below need every lane
+    const int idx = idx0 + (tid >> 3);
+    const bool live = idx < total;
+    const int64_t e = e_base + list[live ? idx : 0];         // flat element index token * h + k
+    const int m = (int)(e / h), k = (int)(e - (int64_t)m * h);
+    const uint16_t* us = Us + (int64_t)m * ld_us;
+    const uint16_t* l1 = L1 + (int64_t)k * r;
+    float dot = 0.0f;
+    for (int t = 8 * sub; t < r; t += 64) {                  // r % 16 == 0: a lane's chunk is inside the row or not at all
+      const u32x4 a = *(const u32x4*)(us + t), w = *(const u32x4*)(l1 + t);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        dot = __builtin_fmaf(bf16_lo_to_f32(a[d]), bf16_lo_to_f32(w[d]), dot);
+        dot = __builtin_fmaf(bf16_lo_to_f32(a[d] >> 16), bf16_lo_to_f32(w[d] >> 16), dot);
+      }
+    }
+    dot += __shfl_xor(dot, 1, 64);
+    dot += __shfl_xor(dot, 2, 64);
+    dot += __shfl_xor(dot, 4, 64);
+    if (live && sub == 0) dX[e] = bf16_bits(bf16_lo_to_f32(dX[e]) - dot);
+  }
+}
+
+hipError_t launch_dropout_dx_fix(uint16_t* dX, int M, int h, const uint8_t* mask, const uint16_t* Us, int ld_us,
+                                 const uint16_t* L1, int r, hipStream_t st) {
+  const int64_t n = (int64_t)M * h / 8;
+  hipLaunchKernelGGL(dropout_dx_fix_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dX, n, h, mask, Us,
+                     ld_us, L1, r);
   return hipGetLastError();
 }
 

@@ -131,6 +131,36 @@ def test_multi_layer_arguments_are_rejected_on_the_host(L):
     assert f(fake, n, views, None, None, s, 4, r0, ok_y, fake, big, None) == -2
 
 
+def test_dropout_arguments_are_rejected_on_the_host(L):
+    """LoRA-dropout calls: the rate must lie in [0, 1), the mask is required exactly when there is an adapter, and
+    the workspace is the large-GEMM one whatever the number of tokens."""
+    from paper_2305_14314_amd import qlora_linear_bwd_sizes, qlora_linear_dropout_sizes, qlora_linear_fwd_sizes
+    from paper_2305_14314_amd.binding import qlora_nf4_view
+    fake = ctypes.c_void_p(0x1000)
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256)
+    big = 1 << 30
+    f = L.qlora_linear_fwd_dropout
+    assert f(fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 1.0, fake, None, fake, big, None) == -2      # p = 1
+    assert f(fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, -0.1, fake, None, fake, big, None) == -2
+    assert f(fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, float("nan"), fake, None, fake, big, None) == -2
+    assert f(fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, 0.1, fake, None, fake, big, None) == -1      # mask
+    assert f(None, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 0.1, fake, None, fake, big, None) == -1      # X
+    assert f(fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 0.1, fake, None, fake, 64, None) == -4
+    b = L.qlora_linear_bwd_dropout
+    assert b(fake, fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 1.5, None, fake, None, None, None, None, fake, big, None) == -2
+    assert b(fake, fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, 0.1, None, fake, None, None, None, None, fake, big, None) == -1
+    assert b(fake, None, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 0.1, None, fake, fake, None, None, None, fake, big, None) == -1  # dL1 needs X
+    assert b(fake, fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 0.1, None, fake, None, None, None, None, fake, 64, None) == -4
+    # 4 tokens: the plain calls would stream (small workspace), the dropout calls dequantise the whole weight
+    fb, bb = qlora_linear_dropout_sizes(4, 1024, 1024, 16)
+    assert fb >= 2 * 1024 * 1024 and bb >= 2 * 1024 * 1024
+    assert fb > qlora_linear_fwd_sizes(4, 1024, 1024, 16) and bb > qlora_linear_bwd_sizes(4, 1024, 1024, 16)
+    assert qlora_linear_dropout_sizes(300, 1024, 1024, 16) == (qlora_linear_fwd_sizes(300, 1024, 1024, 16),
+                                                                qlora_linear_bwd_sizes(300, 1024, 1024, 16))
+    assert qlora_linear_dropout_sizes(4, 1024, 1024, 0) == (qlora_linear_fwd_sizes(4, 1024, 1024, 0),
+                                                             qlora_linear_bwd_sizes(4, 1024, 1024, 0))
+
+
 def test_constant_storage_order_is_a_permutation_that_keeps_groups_together():
     """The 8-bit constants are stored column-group-major (include/qlora.h).  The index map used by the parity
     tests and the one the binding offers agree, are permutations, and put the <= 4 constants of one row and one
