@@ -56,6 +56,11 @@ def _load():
     L.oracle_e4m3_unit.restype = c_float
     L.oracle_nf4_quantize.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp]
     L.oracle_nf4_dequant.argtypes = [vp, vp, vp, c_float, c_int64, c_int64, c_int32, c_int32, vp, vp]
+    L.oracle_codebook4.argtypes = [ctypes.c_int, vp]
+    L.oracle_index4.argtypes = [vp, c_float]
+    L.oracle_index4.restype = ctypes.c_int
+    L.oracle_quantize4.argtypes = [vp] + list(L.oracle_nf4_quantize.argtypes)
+    L.oracle_dequant4.argtypes = [vp] + list(L.oracle_nf4_dequant.argtypes)
     lin = [vp, vp, vp, vp, c_double, c_int64, c_int64, c_int64, c_int64, vp, c_int64, vp]
     for name in ("oracle_linear_fwd_cols", "oracle_linear_bwd_dx_cols"):
         getattr(L, name).argtypes = lin
@@ -122,8 +127,23 @@ def e4m3_unit(code: int) -> np.float32:
     return np.float32(_load().oracle_e4m3_unit(int(code)))
 
 
-def nf4_quantize(W, blocksize: int = 64, dq_blocksize: int = 256):
-    """Returns dict(packed u8[P/2], code u8[n], c1 f32[n1], mean f32, c2 f32[n])."""
+KINDS = {"nf4": 0, "fp4_e2m1": 1, "fp4_e3m0": 2, "int4": 3}
+
+
+def codebook4(kind) -> np.ndarray:
+    """The 16 values (fp32, ascending, in [-1, 1]) of a 4-bit data type: 'nf4', 'fp4_e2m1', 'fp4_e3m0', 'int4'."""
+    out = np.empty(16, np.float32)
+    _check(_load().oracle_codebook4(KINDS[kind] if isinstance(kind, str) else int(kind), _p(out)), "codebook4")
+    return out
+
+
+def index4(table, xhat) -> int:
+    return int(_load().oracle_index4(_p(_arr(table, np.float32, (16,))), np.float32(xhat)))
+
+
+def nf4_quantize(W, blocksize: int = 64, dq_blocksize: int = 256, table=None):
+    """Returns dict(packed u8[P/2], code u8[n], c1 f32[n1], mean f32, c2 f32[n]).
+    table: the 16 values of another 4-bit data type (codebook4), None = NF4."""
     W = np.ascontiguousarray(W, dtype=np.float32)
     assert W.ndim == 2
     rows, cols = W.shape
@@ -137,10 +157,15 @@ def nf4_quantize(W, blocksize: int = 64, dq_blocksize: int = 256):
     c1 = np.empty(n1, np.float32)
     mean = np.empty(1, np.float32)
     c2 = np.empty(n, np.float32)
-    _check(_load().oracle_nf4_quantize(_p(W), rows, cols, blocksize, dq_blocksize,
-                                       _p(packed), _p(code), _p(c1), _p(mean), _p(c2)), "nf4_quantize")
+    if table is None:
+        _check(_load().oracle_nf4_quantize(_p(W), rows, cols, blocksize, dq_blocksize,
+                                           _p(packed), _p(code), _p(c1), _p(mean), _p(c2)), "nf4_quantize")
+    else:
+        table = _arr(table, np.float32, (16,))
+        _check(_load().oracle_quantize4(_p(table), _p(W), rows, cols, blocksize, dq_blocksize,
+                                        _p(packed), _p(code), _p(c1), _p(mean), _p(c2)), "quantize4")
     return dict(packed=packed, code=code, c1=c1, mean=np.float32(mean[0]), c2=c2,
-                rows=rows, cols=cols, blocksize=blocksize, dq_blocksize=dq_blocksize)
+                rows=rows, cols=cols, blocksize=blocksize, dq_blocksize=dq_blocksize, table=table)
 
 
 def nf4_dequant(q, return_c2hat: bool = False):
@@ -149,9 +174,12 @@ def nf4_dequant(q, return_c2hat: bool = False):
     n = rows * cols // q["blocksize"]
     out = np.empty((rows, cols), np.uint16)
     c2hat = np.empty(n, np.float32) if return_c2hat else None
-    _check(_load().oracle_nf4_dequant(_p(_arr(q["packed"], np.uint8)), _p(_arr(q["code"], np.uint8)),
-                                      _p(_arr(q["c1"], np.float32)), np.float32(q["mean"]), rows, cols,
-                                      q["blocksize"], q["dq_blocksize"], _p(out), _p(c2hat)), "nf4_dequant")
+    args = (_p(_arr(q["packed"], np.uint8)), _p(_arr(q["code"], np.uint8)), _p(_arr(q["c1"], np.float32)),
+            np.float32(q["mean"]), rows, cols, q["blocksize"], q["dq_blocksize"], _p(out), _p(c2hat))
+    if q.get("table") is None:
+        _check(_load().oracle_nf4_dequant(*args), "nf4_dequant")
+    else:
+        _check(_load().oracle_dequant4(_p(_arr(q["table"], np.float32, (16,))), *args), "dequant4")
     return (out, c2hat) if return_c2hat else out
 
 

@@ -102,14 +102,54 @@ void oracle_nf4_derive(double p_max, double out[16]) {
   }
 }
 
-int oracle_nf4_index(float xhat) {
+/* Nearest value of a non-decreasing 16-entry table, the lower index on an exact tie:
+ * the number of midpoints strictly below xhat. */
+static int index_in(const float* table, float xhat) {
   int idx = 0;
   for (int j = 0; j < 15; ++j) {
     /* the midpoint of two binary32 numbers is exact in binary64 */
-    const double mid = ((double)kNF4[j] + (double)kNF4[j + 1]) * 0.5;
+    const double mid = ((double)table[j] + (double)table[j + 1]) * 0.5;
     if ((double)xhat > mid) ++idx;
   }
   return idx;
+}
+
+int oracle_nf4_index(float xhat) { return index_in(kNF4, xhat); }
+
+int oracle_index4(const float* table, float xhat) { return table ? index_in(table, xhat) : -1; }
+
+/* The 4-bit data types the paper compares NF4 with (Section 4, the data-type table; Eq. 1 for the integer
+ * type), as 16 values in [-1, 1] in ascending order.  The paper names the float formats and gives no value
+ * table: each is enumerated here from its bit fields (sign, exponent, mantissa; exponent field 0 = subnormal,
+ * no infinities or NaNs) and divided by its largest magnitude, which removes the exponent bias.  Both float
+ * types have two zeros (entries 7 and 8); Int4 is round(7 x / absmax), 15 levels, entry 15 repeats the top. */
+int oracle_codebook4(int kind, float out[16]) {
+  if (!out) return -1;
+  double mag[8];
+  switch (kind) {
+    case 0: for (int i = 0; i < 16; ++i) out[i] = kNF4[i]; return 0;
+    case 1:                                            /* Float4 E2M1: e = 0: m/2;  e > 0: (1 + m/2) 2^(e-1) */
+      for (int c = 0; c < 8; ++c) {
+        const int e = c >> 1, m = c & 1;
+        mag[c] = e == 0 ? 0.5 * m : std::ldexp(1.0 + 0.5 * m, e - 1);
+      }
+      break;
+    case 2:                                            /* Float4 E3M0: e = 0: 0;  e > 0: 2^(e-1) */
+      for (int c = 0; c < 8; ++c) mag[c] = c == 0 ? 0.0 : std::ldexp(1.0, c - 1);
+      break;
+    case 3:                                            /* Int4: j / 7, j = -7 .. 7 */
+      for (int i = 0; i < 15; ++i) out[i] = (float)((double)(i - 7) / 7.0);
+      out[15] = 1.0f;
+      return 0;
+    default: return -2;
+  }
+  for (int c = 0; c < 8; ++c) {
+    const float v = (float)(mag[c] / mag[7]);
+    out[8 + c] = v;
+    out[7 - c] = -v;
+  }
+  out[7] = 0.0f;                                       /* the negative zero compares and multiplies as zero */
+  return 0;
 }
 
 uint16_t oracle_bf16_rne(float v) {
@@ -200,11 +240,11 @@ static float exact_mean_f32(const float* v, int64_t n) {
   return (float)std::ldexp((double)kept, drop - 149);
 }
 
-int oracle_nf4_quantize(const float* W, int64_t rows, int64_t cols,
-                        int32_t blocksize, int32_t dq_blocksize,
-                        uint8_t* packed, uint8_t* code, float* c1, float* mean,
-                        float* c2_out) {
-  if (!W || !packed || !code || !c1 || !mean) return -1;
+static int quantize4(const float* table, const float* W, int64_t rows, int64_t cols,
+                     int32_t blocksize, int32_t dq_blocksize,
+                     uint8_t* packed, uint8_t* code, float* c1, float* mean,
+                     float* c2_out) {
+  if (!table || !W || !packed || !code || !c1 || !mean) return -1;
   if (rows <= 0 || cols <= 0 || blocksize <= 0 || dq_blocksize <= 0) return -2;
   const int64_t P = rows * cols;
   if (P % blocksize != 0 || P % 2 != 0) return -2;
@@ -222,7 +262,7 @@ int oracle_nf4_quantize(const float* W, int64_t rows, int64_t cols,
     c2[(size_t)b] = amax;
     const float rc = (amax < FLT_MIN) ? 0.0f : fl32_div(1.0f, amax);   /* Eq. 1: c = range / absmax, range 1 */
     for (int i = 0; i < blocksize; ++i)
-      idx[(size_t)(b * blocksize + i)] = (uint8_t)oracle_nf4_index(fl32_mul(w[i], rc));
+      idx[(size_t)(b * blocksize + i)] = (uint8_t)index_in(table, fl32_mul(w[i], rc));
   }
   for (int64_t i = 0; i < P / 2; ++i)
     packed[i] = (uint8_t)(idx[(size_t)(2 * i)] | (idx[(size_t)(2 * i + 1)] << 4));
@@ -246,11 +286,25 @@ int oracle_nf4_quantize(const float* W, int64_t rows, int64_t cols,
   return 0;
 }
 
-int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* c1,
-                       float mean, int64_t rows, int64_t cols,
-                       int32_t blocksize, int32_t dq_blocksize,
-                       uint16_t* W_bf16, float* c2hat_out) {
-  if (!packed || !code || !c1 || !W_bf16) return -1;
+int oracle_nf4_quantize(const float* W, int64_t rows, int64_t cols,
+                        int32_t blocksize, int32_t dq_blocksize,
+                        uint8_t* packed, uint8_t* code, float* c1, float* mean,
+                        float* c2_out) {
+  return quantize4(kNF4, W, rows, cols, blocksize, dq_blocksize, packed, code, c1, mean, c2_out);
+}
+
+int oracle_quantize4(const float* table, const float* W, int64_t rows, int64_t cols,
+                     int32_t blocksize, int32_t dq_blocksize,
+                     uint8_t* packed, uint8_t* code, float* c1, float* mean,
+                     float* c2_out) {
+  return quantize4(table, W, rows, cols, blocksize, dq_blocksize, packed, code, c1, mean, c2_out);
+}
+
+static int dequant4(const float* table, const uint8_t* packed, const uint8_t* code, const float* c1,
+                    float mean, int64_t rows, int64_t cols,
+                    int32_t blocksize, int32_t dq_blocksize,
+                    uint16_t* W_bf16, float* c2hat_out) {
+  if (!table || !packed || !code || !c1 || !W_bf16) return -1;
   if (rows <= 0 || cols <= 0 || blocksize <= 0 || dq_blocksize <= 0) return -2;
   const int64_t P = rows * cols;
   if (P % blocksize != 0 || P % 2 != 0) return -2;
@@ -263,10 +317,24 @@ int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* 
     for (int i = 0; i < blocksize; ++i) {
       const int64_t e = b * blocksize + i;
       const int id = (packed[e >> 1] >> ((e & 1) * 4)) & 15;
-      W_bf16[e] = oracle_bf16_rne(fl32_mul(kNF4[id], c2hat));                          /* dequant(c2, W) */
+      W_bf16[e] = oracle_bf16_rne(fl32_mul(table[id], c2hat));                         /* dequant(c2, W) */
     }
   }
   return 0;
+}
+
+int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* c1,
+                       float mean, int64_t rows, int64_t cols,
+                       int32_t blocksize, int32_t dq_blocksize,
+                       uint16_t* W_bf16, float* c2hat_out) {
+  return dequant4(kNF4, packed, code, c1, mean, rows, cols, blocksize, dq_blocksize, W_bf16, c2hat_out);
+}
+
+int oracle_dequant4(const float* table, const uint8_t* packed, const uint8_t* code, const float* c1,
+                    float mean, int64_t rows, int64_t cols,
+                    int32_t blocksize, int32_t dq_blocksize,
+                    uint16_t* W_bf16, float* c2hat_out) {
+  return dequant4(table, packed, code, c1, mean, rows, cols, blocksize, dq_blocksize, W_bf16, c2hat_out);
 }
 
 /* ---- Eq. 5 / Eq. 3 and the backward products, fp64 triple loops ----------- */

@@ -98,6 +98,25 @@ int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* 
                        int32_t blocksize, int32_t dq_blocksize,
                        uint16_t* W_bf16, float* c2hat_out);
 
+/* The other 4-bit data types of the paper's comparison (Section 4: Int4, Float4 E2M1, Float4 E3M0 beside
+ * NFloat4) through the same blockwise scheme: only the 16-value table changes.  kind: 0 NF4 (Appendix E),
+ * 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4 (Eq. 1 with range [-7, 7]).  The paper prints no value tables for the
+ * float types: they are enumerated from the bit fields (exponent field 0 = subnormal, no infinities / NaNs) and
+ * normalised by the largest magnitude -- PARITY UNPINNED against the paper, pinned against that definition.
+ * Returns 0, -1 (NULL) or -2 (unknown kind). */
+int oracle_codebook4(int kind, float out[16]);
+/* Nearest entry of a non-decreasing 16-value table, the lower index on an exact tie. */
+int oracle_index4(const float* table, float xhat);
+/* oracle_nf4_quantize / oracle_nf4_dequant with the table as an argument. */
+int oracle_quantize4(const float* table, const float* W, int64_t rows, int64_t cols,
+                     int32_t blocksize, int32_t dq_blocksize,
+                     uint8_t* packed, uint8_t* code, float* c1, float* mean,
+                     float* c2_out);
+int oracle_dequant4(const float* table, const uint8_t* packed, const uint8_t* code, const float* c1,
+                    float mean, int64_t rows, int64_t cols,
+                    int32_t blocksize, int32_t dq_blocksize,
+                    uint16_t* W_bf16, float* c2hat_out);
+
 /* Eq. 5 with the scalar s of Eq. 3:  Y = X What + s (X L1) L2, all sums fp64,
  * no intermediate rounding.  What is the h x o bf16 matrix from
  * oracle_nf4_dequant.  Only the token rows listed in row_sel (n_sel of them,

@@ -534,3 +534,77 @@ def test_dropout_keeps_the_expectation(oracle, lin_case):
     adapter = base - frozen
     err = np.abs(acc / n - base).max()
     assert err < 0.1 * np.abs(adapter).max(), (err, np.abs(adapter).max())
+
+
+# ----------------------------------------------------------------------------- other 4-bit data types
+
+def test_codebooks_of_the_compared_data_types(oracle):
+    """Section 4 compares NF4 with Int4, Float4 E2M1 and Float4 E3M0 under the same blockwise scheme.  E2M1's
+    magnitudes are the published ones of the format (0, 0.5, 1, 1.5, 2, 3, 4, 6), E3M0 has an exponent only
+    (powers of two), Int4 is Eq. 1 with the range [-7, 7]; every table is normalised to [-1, 1], ascending,
+    antisymmetric, and NF4 through the table argument is the NF4 path."""
+    e2m1 = np.array([0, 0.5, 1, 1.5, 2, 3, 4, 6]) / 6
+    t = oracle.codebook4("fp4_e2m1").astype(np.float64)
+    np.testing.assert_allclose(t[8:], e2m1, rtol=0, atol=3e-8)
+    np.testing.assert_array_equal(t[:8], -t[:7:-1])
+    t = oracle.codebook4("fp4_e3m0").astype(np.float64)
+    np.testing.assert_array_equal(t[9:], 2.0 ** np.arange(-6, 1))
+    assert t[7] == 0 and t[8] == 0 and np.array_equal(t[:8], -t[:7:-1])
+    t = oracle.codebook4("int4").astype(np.float64)
+    np.testing.assert_allclose(t[:15], np.arange(-7, 8) / 7, rtol=0, atol=3e-8)
+    assert t[15] == 1.0
+    np.testing.assert_array_equal(oracle.codebook4("nf4"), oracle.nf4_table())
+    for k in oracle.KINDS:
+        t = oracle.codebook4(k)
+        assert t.dtype == np.float32 and np.all(np.diff(t) >= 0) and t[0] == -1 and t[15] == 1
+    with pytest.raises(ValueError):
+        oracle.codebook4(4)
+
+
+def test_index4_is_nearest_value_bruteforce(oracle):
+    """For any non-decreasing table the index points at the nearest value, the lower one on an exact tie; where a
+    value occurs twice (the two zeros of the float types) either copy decodes the same."""
+    rng = np.random.default_rng(12)
+    tables = [oracle.codebook4(k) for k in oracle.KINDS]
+    tables.append(np.sort(rng.uniform(-1, 1, 16)).astype(np.float32))
+    for t in tables:
+        t64 = t.astype(np.float64)
+        xs = np.concatenate([rng.uniform(-1.05, 1.05, 400), t64, (t64[:-1] + t64[1:]) / 2]).astype(np.float32)
+        for x in xs:
+            d = np.abs(t64 - np.float64(x))
+            got, want = oracle.index4(t, x), int(np.argmin(d))           # argmin returns the first minimum
+            assert t64[got] == t64[want], (x, t)
+            if np.all(np.diff(t64) > 0):
+                assert got == want, (x, t)
+    # Int4 is Eq. 1: round(7 x / absmax), away from the ties
+    t = oracle.codebook4("int4")
+    for x in rng.uniform(-1, 1, 500).astype(np.float32):
+        if abs(7 * float(x) - np.floor(7 * float(x)) - 0.5) > 1e-3:
+            assert oracle.index4(t, x) - 7 == int(np.round(7 * float(x)))
+
+
+def test_quantize4_round_trip_and_ranking(oracle):
+    """Through the table argument NF4 reproduces the NF4 path bit for bit; every data type's round-trip error stays
+    within half its widest gap times the block's absmax; and on normally distributed weights NF4 has the smallest
+    mean error of the four (Section 3: quantile quantisation is optimal for normal data; Section 4: NF4 > FP4 > Int4)."""
+    rng = np.random.default_rng(13)
+    W = rng.standard_normal((128, 1024)).astype(np.float32)
+    q0 = oracle.nf4_quantize(W)
+    q1 = oracle.nf4_quantize(W, table=oracle.codebook4("nf4"))
+    for k in ("packed", "code", "c1"):
+        np.testing.assert_array_equal(q0[k], q1[k])
+    np.testing.assert_array_equal(oracle.nf4_dequant(q0), oracle.nf4_dequant(q1))
+    err = {}
+    for kind in oracle.KINDS:
+        t = oracle.codebook4(kind)
+        q = oracle.nf4_quantize(W, table=t)
+        What, c2hat = oracle.nf4_dequant(q, return_c2hat=True)
+        What = _bf16_f64(What)
+        gap = np.diff(t.astype(np.float64)).max()
+        c2 = np.repeat(q["c2"].astype(np.float64), 64).reshape(W.shape)
+        c2h = np.repeat(c2hat.astype(np.float64), 64).reshape(W.shape)
+        # nearest value within gap/2 of x = w/c2; then c2 is replaced by its 8-bit reconstruction and the product rounded to bf16
+        bound = gap / 2 * c2 + np.abs(c2h - c2) + 2.0 ** -8 * np.abs(What) + 1e-6
+        assert np.all(np.abs(What - W) <= bound), kind
+        err[kind] = np.abs(What - W).mean()
+    assert err["nf4"] < min(err["fp4_e2m1"], err["fp4_e3m0"], err["int4"]), err
