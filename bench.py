@@ -256,6 +256,20 @@ def main():
                             "frac_hbm": round(el * 2.5159 / (t * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                             "bytes_per_element": 2.5159}
         del outb
+        # the data types of the paper's comparison (Section 4) on one 8192 x 8192 N(0, 0.02) tensor: round-trip error
+        # of quantise + doubleDequant in units of sigma (NF4 is the smallest), and the rate of the quantise pass
+        # when the decision thresholds arrive at run time
+        Wn = synth.normal_f32_device((d, d), synth.SIGMA_W, 424242)
+        types = {}
+        for name, dt in (("nf4", ql.NF4), ("fp4_e2m1", ql.FP4_E2M1), ("fp4_e3m0", ql.FP4_E3M0), ("int4", ql.INT4)):
+            Wq_t = ql.qlora_quantize_4bit(Wn, dt)
+            err = (ql.qlora_nf4_dequant(Wq_t).float() - Wn).abs().mean().item() / synth.SIGMA_W
+            t = _time_ms(torch, lambda: ql.qlora_quantize_4bit(Wn, dt, out=Wq_t), 5)
+            types[name] = {"mean_abs_err_over_sigma": round(err, 4),
+                           "quantize_GBps": round(d * d * 4.5159 / (t * 1e-3) * 1e-9, 1)}
+            del Wq_t
+        del Wn
+        extra["data_types"] = types
         # few-token regime (workload configs[4]): forward and input gradient at 1, 4, 16 tokens
         gemv = {}
         for m in cfg_few_tokens():

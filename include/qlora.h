@@ -88,7 +88,22 @@ typedef struct {
   int64_t cols;          /* o, out-features */
   int32_t blocksize;     /* 64  */
   int32_t dq_blocksize;  /* 256 */
+  int32_t dtype;         /* QLORA_NF4 (0) or one of the other 4-bit data types below */
+  int32_t reserved;      /* 0 */
 } qlora_nf4_view;
+
+/* The 4-bit data types of the paper's comparison (Section 4: Int4, Float4 E2M1, Float4 E3M0 beside NFloat4).  All go
+ * through the same blockwise scheme, storage layout and kernels; only the 16-value table differs, so a view of any
+ * of them can be passed wherever a qlora_nf4_view is taken.  The paper prints a table for NF4 only (Appendix E).
+ * The float types are the values of their bit fields (sign, exponent, mantissa; exponent field 0 is subnormal, no
+ * infinities or NaNs) divided by the largest magnitude -- E2M1: +-{0, 1/12, 1/6, 1/4, 1/3, 1/2, 2/3, 1}, E3M0:
+ * +-{0, 1/64, 1/32, ..., 1/2, 1}, each with two zeros -- and Int4 is Eq. 1 with the range [-7, 7]: j/7, 15 levels
+ * (code 15 repeats the top value and is never produced).  Quantisation picks the nearest value, the lower code on an
+ * exact tie, as for NF4. */
+enum { QLORA_NF4 = 0, QLORA_FP4_E2M1 = 1, QLORA_FP4_E3M0 = 2, QLORA_INT4 = 3 };
+
+/* The 16 values of a data type, ascending, as fp32 (host array).  QLORA_ERR_UNSUPPORTED for an unknown type. */
+qlora_status qlora_codebook_4bit(int32_t dtype, float* values16);
 
 /* Byte sizes of the buffers of a quantised rows x cols tensor and of the scratch
  * qlora_nf4_quantize needs.  Any out-pointer may be NULL.
@@ -112,6 +127,13 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
                                 int32_t blocksize, int32_t dq_blocksize,
                                 uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
                                 void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* The same with one of the other 4-bit data types (Section 4); dtype = QLORA_NF4 is qlora_nf4_quantize.  The
+ * buffers, their sizes and the Double Quantization of the constants do not depend on the data type. */
+qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
+                                 int32_t blocksize, int32_t dq_blocksize, int32_t dtype,
+                                 uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
+                                 void* scratch, size_t scratch_bytes, void* hip_stream);
 
 /* doubleDequant (Eq. 6, Eq. 2): W_bf16[rows x cols] =
  *   bf16_rne( NF4[index] * fl32( fl32(E4M3(code)/448 * c1) + mean ) ). */

@@ -21,6 +21,7 @@ EXPORTS = [
     "qlora_linear_bwd", "qlora_linear_bwd_acc", "qlora_linear_fwd_multi_sizes", "qlora_linear_fwd_multi", "qlora_workspace_init",
     "qlora_profile_gemm", "qlora_profile_gemm_read",
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
+    "qlora_codebook_4bit", "qlora_quantize_4bit",
 ]
 
 
@@ -32,7 +33,8 @@ class QloraError(RuntimeError):
 
 class qlora_nf4_view(Structure):
     _fields_ = [("packed", c_void_p), ("c2_code", c_void_p), ("c1", c_void_p), ("c2_mean", c_void_p),
-                ("rows", c_int64), ("cols", c_int64), ("blocksize", c_int32), ("dq_blocksize", c_int32)]
+                ("rows", c_int64), ("cols", c_int64), ("blocksize", c_int32), ("dq_blocksize", c_int32),
+                ("dtype", c_int32), ("reserved", c_int32)]
 
 
 _lib = None
@@ -53,6 +55,8 @@ def lib():
     L.qlora_last_hip_error.restype = ctypes.c_int
     L.qlora_nf4_sizes.argtypes = [c_int64, c_int64, c_int32, c_int32, sp, sp, sp, sp]
     L.qlora_nf4_quantize.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_quantize_4bit.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_codebook_4bit.argtypes = [c_int32, vp]
     L.qlora_nf4_dequant.argtypes = [POINTER(qlora_nf4_view), vp, vp]
     L.qlora_linear_fwd_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp]
     L.qlora_linear_bwd_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp]
@@ -96,14 +100,16 @@ def _stream(stream=None):
 class NF4Weight:
     """Device buffers of one quantised h x o weight plus the view struct the C ABI takes."""
 
-    def __init__(self, rows, cols, packed, code, c1, mean, blocksize=64, dq_blocksize=256):
+    def __init__(self, rows, cols, packed, code, c1, mean, blocksize=64, dq_blocksize=256, dtype=0):
         self.rows, self.cols = int(rows), int(cols)
         self.blocksize, self.dq_blocksize = int(blocksize), int(dq_blocksize)
         self.packed, self.code, self.c1, self.mean = packed, code, c1, mean
+        self.dtype = int(dtype)                               # NF4 = 0, or FP4_E2M1 / FP4_E3M0 / INT4
 
     def view(self) -> qlora_nf4_view:
         return qlora_nf4_view(self.packed.data_ptr(), self.code.data_ptr(), self.c1.data_ptr(),
-                              self.mean.data_ptr(), self.rows, self.cols, self.blocksize, self.dq_blocksize)
+                              self.mean.data_ptr(), self.rows, self.cols, self.blocksize, self.dq_blocksize,
+                              self.dtype, 0)
 
     @property
     def nbytes(self) -> int:
@@ -139,7 +145,22 @@ def nf4_alloc(rows, cols, device, blocksize=64, dq_blocksize=256) -> NF4Weight:
                      torch.empty(1, dtype=torch.float32, device=device), blocksize, dq_blocksize)
 
 
-def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None, out=None) -> NF4Weight:
+NF4, FP4_E2M1, FP4_E3M0, INT4 = 0, 1, 2, 3
+
+
+def qlora_codebook_4bit(dtype):
+    """The 16 fp32 values of a 4-bit data type (NF4, FP4_E2M1, FP4_E3M0, INT4), ascending, as a list."""
+    out = (c_float * 16)()
+    _check(lib().qlora_codebook_4bit(int(dtype), out))
+    return list(out)
+
+
+def qlora_quantize_4bit(W, dtype, blocksize=64, dq_blocksize=256, scratch=None, stream=None, out=None) -> NF4Weight:
+    """qlora_nf4_quantize with one of the other 4-bit data types of the paper's comparison."""
+    return qlora_nf4_quantize(W, blocksize, dq_blocksize, scratch, stream, out, dtype=dtype)
+
+
+def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None, out=None, dtype=0) -> NF4Weight:
     """W: fp32 device tensor (h, o).  Returns the quantised weight (in `out` if given, else new buffers)."""
     assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
     rows, cols = W.shape
@@ -151,8 +172,14 @@ def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=N
     packed, code, c1, mean = out.packed, out.code, out.c1, out.mean
     if scratch is None:
         scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
-    _check(lib().qlora_nf4_quantize(_ptr(W), rows, cols, blocksize, dq_blocksize, _ptr(packed), _ptr(code),
-                                    _ptr(c1), _ptr(mean), _ptr(scratch), scratch.numel(), _stream(stream)))
+    if dtype == 0:
+        _check(lib().qlora_nf4_quantize(_ptr(W), rows, cols, blocksize, dq_blocksize, _ptr(packed), _ptr(code),
+                                        _ptr(c1), _ptr(mean), _ptr(scratch), scratch.numel(), _stream(stream)))
+    else:
+        _check(lib().qlora_quantize_4bit(_ptr(W), rows, cols, blocksize, dq_blocksize, int(dtype), _ptr(packed),
+                                         _ptr(code), _ptr(c1), _ptr(mean), _ptr(scratch), scratch.numel(),
+                                         _stream(stream)))
+    out.dtype = int(dtype)
     return out
 
 

@@ -7,6 +7,7 @@
 
 #include <vector>
 
+#include "common.hpp"
 #include "launch.hpp"
 
 namespace {
@@ -60,11 +61,12 @@ qlora_status check_view(const qlora_nf4_view* v) {
   if (qlora_status st = check_quant_shape(v->rows, v->cols, v->blocksize, v->dq_blocksize)) return st;
   if (!aligned16(v->packed) || !aligned16(v->c2_code) || !aligned16(v->c1) || ((uintptr_t)v->c2_mean & 3u))
     return QLORA_ERR_ALIGN;
+  if (v->dtype < 0 || v->dtype >= qlora::kNumTypes4) return QLORA_ERR_UNSUPPORTED;
   return QLORA_OK;
 }
 
 inline qlora::NF4Dev to_dev(const qlora_nf4_view* v) {
-  return qlora::NF4Dev{v->packed, v->c2_code, v->c1, v->c2_mean, v->rows, v->cols};
+  return qlora::NF4Dev{v->packed, v->c2_code, v->c1, v->c2_mean, v->rows, v->cols, v->dtype};
 }
 
 qlora_status check_linear(int64_t M, int64_t h, int64_t o, int32_t r) {
@@ -260,8 +262,25 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
                                 int32_t blocksize, int32_t dq_blocksize,
                                 uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
                                 void* scratch, size_t scratch_bytes, void* hip_stream) {
+  return qlora_quantize_4bit(W, rows, cols, blocksize, dq_blocksize, QLORA_NF4, packed, c2_code, c1, c2_mean, scratch,
+                             scratch_bytes, hip_stream);
+}
+
+qlora_status qlora_codebook_4bit(int32_t dtype, float* values16) {
+  if (!values16) return QLORA_ERR_NULL;
+  if (dtype < 0 || dtype >= qlora::kNumTypes4) return QLORA_ERR_UNSUPPORTED;
+  const qlora::Table4 t = qlora::table4_host(dtype);
+  for (int i = 0; i < 16; ++i) values16[i] = t.v[i];
+  return QLORA_OK;
+}
+
+qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
+                                 int32_t blocksize, int32_t dq_blocksize, int32_t dtype,
+                                 uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
+                                 void* scratch, size_t scratch_bytes, void* hip_stream) {
   if (!W || !packed || !c2_code || !c1 || !c2_mean || !scratch) return QLORA_ERR_NULL;
   if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
+  if (dtype < 0 || dtype >= qlora::kNumTypes4) return QLORA_ERR_UNSUPPORTED;
   size_t need = 0;
   qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize, nullptr, nullptr, nullptr, &need);
   if (scratch_bytes < need) return QLORA_ERR_WORKSPACE;
@@ -269,7 +288,7 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
       ((uintptr_t)c2_mean & 3u))
     return QLORA_ERR_ALIGN;
   return hip_status(qlora::launch_quantize(W, rows, cols, packed, c2_code, c1, c2_mean, scratch,
-                                           (hipStream_t)hip_stream));
+                                           (hipStream_t)hip_stream, dtype));
 }
 
 qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void* hip_stream) {

@@ -109,6 +109,58 @@ __device__ __forceinline__ uint32_t nf4_index(float x, const Nf4Bucket* table) {
   return e.base + (x > e.thr ? 1u : 0u);
 }
 
+// ---- the other 4-bit data types of the paper's comparison (Section 4) --------------------------
+// Int4 (Eq. 1 with the range [-7, 7]), Float4 E2M1 and Float4 E3M0 go through the same blockwise scheme as NF4:
+// only the 16-value table differs.  The paper prints no tables for the float types; they are the values of the bit
+// fields (sign, exponent, mantissa; exponent field 0 = subnormal, no infinities or NaNs) divided by the largest
+// magnitude, which removes the exponent bias.  Tables are ascending; the float types hold zero twice (entries 7, 8),
+// Int4 has 15 levels and repeats the top one.  Thresholds are built as for NF4: midpoint rounded toward -infinity.
+constexpr int kNumTypes4 = 4;                // 0 NF4, 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4
+struct Table4 { float v[16]; };
+struct Thresholds4 { float t[15]; };
+
+inline Table4 table4_host(int dtype) {
+  Table4 tab{};
+  if (dtype == 0) {
+    for (int i = 0; i < 16; ++i) tab.v[i] = nf4_value(i);
+  } else if (dtype == 3) {
+    for (int i = 0; i < 15; ++i) tab.v[i] = (float)((double)(i - 7) / 7.0);
+    tab.v[15] = 1.0f;
+  } else {
+    const double e2m1[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+    const double e3m0[8] = {0.0, 1.0, 2.0, 4.0, 8.0, 16.0, 32.0, 64.0};
+    const double* mag = dtype == 1 ? e2m1 : e3m0;
+    for (int c = 0; c < 8; ++c) {
+      const float v = (float)(mag[c] / mag[7]);
+      tab.v[8 + c] = v;
+      tab.v[7 - c] = c == 0 ? 0.0f : -v;
+    }
+  }
+  return tab;
+}
+
+inline Thresholds4 thresholds4_host(const Table4& tab) {
+  Thresholds4 th{};
+  for (int j = 0; j < 15; ++j) {
+    const double mid = ((double)tab.v[j] + (double)tab.v[j + 1]) * 0.5;       // exact
+    float t = (float)mid;
+    if ((double)t > mid) t = __builtin_nextafterf(t, -__builtin_huge_valf());
+    th.t[j] = t;
+  }
+  return th;
+}
+
+// Nearest-value index for thresholds known only at run time: binary search over the 15 non-decreasing thresholds
+// kept in LDS (`t`, 16 floats; selects between elements of a by-value argument would become a lane-indexed read
+// of it, i.e. scratch memory).  Returns the number of thresholds strictly below x.
+__device__ __forceinline__ uint32_t index_search4(float x, const float* t) {
+  uint32_t lo = 0;
+#pragma unroll
+  for (uint32_t step = 8; step >= 1; step >>= 1)
+    if (x > t[lo + step - 1]) lo += step;
+  return lo;
+}
+
 // ---- bf16 ------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {   // RNE, lo in bits 15:0
   bf16x2 v;

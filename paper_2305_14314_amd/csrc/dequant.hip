@@ -8,15 +8,27 @@ namespace qlora {
 
 constexpr int kDeqThreads = 256;
 
+// The 16 values of the data type into LDS: NF4 from constants; another type (Section 4) from the argument, copied
+// by one thread with constant indices (a lane-indexed read of a by-value argument would go through scratch).
+__device__ __forceinline__ void init_lut16(float* lut, int dtype, const Table4& tab) {
+  if (dtype == 0) {
+    if (threadIdx.x < 16) {
+      constexpr float t[16] = {QLORA_NF4_VALUES};
+      lut[threadIdx.x] = t[threadIdx.x];
+    }
+  } else if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lut[i] = tab.v[i];
+  }
+}
+
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
-    const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr) {
+    const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr,
+    const int dtype, const Table4 tab) {
   __shared__ float lut[16];
   __shared__ float unit[256];
-  if (threadIdx.x < 16) {
-    constexpr float t[16] = {QLORA_NF4_VALUES};
-    lut[threadIdx.x] = t[threadIdx.x];
-  }
+  init_lut16(lut, dtype, tab);
   unit[threadIdx.x] = e4m3_unit(threadIdx.x);               // 256 threads, 256 codes
   __syncthreads();
   const float mean = *mean_ptr;
@@ -45,13 +57,11 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 // form 128-byte runs along k.  No LDS staging of data.
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
-    const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out) {
+    const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out, const int dtype,
+    const Table4 tab) {
   __shared__ float lut[16];
   __shared__ float unit[256];
-  if (threadIdx.x < 16) {
-    constexpr float t[16] = {QLORA_NF4_VALUES};
-    lut[threadIdx.x] = t[threadIdx.x];
-  }
+  init_lut16(lut, dtype, tab);
   unit[threadIdx.x] = e4m3_unit(threadIdx.x);
   __syncthreads();
   const float mean = *mean_ptr;
@@ -92,7 +102,7 @@ hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipS
   const int h = (int)w.rows, o = (int)w.cols;
   dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64));
   hipLaunchKernelGGL(dequant_nf4_t_kernel, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
-                     w.c1, w.mean, out, h, o, ld_out);
+                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype));
   return hipGetLastError();
 }
 
@@ -103,7 +113,7 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(dequant_nf4_kernel, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
                      (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
-                     (uint32_t)(w.cols / 64));
+                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype));
   return hipGetLastError();
 }
 

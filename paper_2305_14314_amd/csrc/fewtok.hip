@@ -51,15 +51,34 @@ constexpr int kStripOff = kUnitOff + 1024;                   // float[kWaves][2]
 constexpr int kSmemBytes = kStripOff + kWaves * 256;
 static_assert(kLutBytes <= kRedBytes && kSmemBytes <= 160 * 1024, "LDS map");
 
+// dtype 0: NF4 from constants.  Another 4-bit data type (Section 4): its 16 values come with the arguments and are
+// staged in LDS by one thread first (`stage`, 16 floats) -- a lane-indexed read of a by-value argument would go
+// through scratch memory.
 template <int NT>
-__device__ __forceinline__ void init_pair_lut(f32x2* lut2 /* [256][32] */, float* unit /* [256] */) {
-  constexpr float t[16] = {QLORA_NF4_VALUES};
-  for (int e = threadIdx.x; e < 256 * kLutCopies; e += NT) {
-    const int b = e / kLutCopies;
-    f32x2 v;
-    v[0] = t[b & 15];
-    v[1] = t[b >> 4];
-    lut2[e] = v;
+__device__ __forceinline__ void init_pair_lut(f32x2* lut2 /* [256][32] */, float* unit /* [256] */, int dtype,
+                                              const Table4& tab, float* stage) {
+  if (dtype == 0) {
+    constexpr float t[16] = {QLORA_NF4_VALUES};
+    for (int e = threadIdx.x; e < 256 * kLutCopies; e += NT) {
+      const int b = e / kLutCopies;
+      f32x2 v;
+      v[0] = t[b & 15];
+      v[1] = t[b >> 4];
+      lut2[e] = v;
+    }
+  } else {
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) stage[i] = tab.v[i];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 256 * kLutCopies; e += NT) {
+      const int b = e / kLutCopies;
+      f32x2 v;
+      v[0] = stage[b & 15];
+      v[1] = stage[b >> 4];
+      lut2[e] = v;
+    }
   }
   if (threadIdx.x < 256) unit[threadIdx.x] = e4m3_unit(threadIdx.x);
 }
@@ -85,6 +104,7 @@ __device__ __forceinline__ f32x2 pair_lookup_b(const f32x2* lut2, uint32_t pk, u
 struct FewArgs {
   const uint16_t* X; int M;                  // tokens x contraction dim (X for forward, dY for backward)
   const uint8_t* packed; const uint8_t* code; const float* c1; const float* mean;
+  int dtype; Table4 tab;                     // data type of the weight (0 = NF4) and, for the others, its 16 values
   int h, o;
   float* part;                               // [splits][M][N]
   int per_split;                             // contraction elements per split
@@ -556,7 +576,7 @@ __device__ __forceinline__ void fewtok_fwd_body(const FewArgs& p, const int work
   FwdStep buf[kDepth];
 #pragma unroll
   for (int d = 0; d < kDepth; ++d) load_step(buf[d], kb0 + d * stride);
-  init_pair_lut<NT>(lut2, unit);
+  init_pair_lut<NT>(lut2, unit, p.dtype, p.tab, (float*)(smem + kStripOff));
   __syncthreads();
 
   f32x4 acc[NA][8];
@@ -744,7 +764,7 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
   BwdStep buf[kBwdDepth];
 #pragma unroll
   for (int d = 0; d < kBwdDepth; ++d) load_step(buf[d], kb0 + d * stride);   // in flight while the table is built
-  init_pair_lut<NT>(lut2, unit);
+  init_pair_lut<NT>(lut2, unit, p.dtype, p.tab, (float*)(smem + kStripOff));
   __syncthreads();
 
   f32x4 acc[4];
@@ -834,6 +854,7 @@ hipError_t launch_fewtok_fwd(const uint16_t* X, int M, const NF4Dev& w, float* p
                              uint16_t* T_hl, hipStream_t st) {
   FewArgs a;
   a.X = X; a.M = M; a.packed = w.packed; a.code = w.code; a.c1 = w.c1; a.mean = w.mean;
+  a.dtype = w.dtype; a.tab = table4_host(w.dtype);
   a.h = (int)w.rows; a.o = (int)w.cols; a.part = part;
   const int steps = (a.h + 15) / 16;
   a.per_split = ((steps + splits - 1) / splits) * 16;
@@ -863,6 +884,7 @@ hipError_t launch_fewtok_fwd_multi(const uint16_t* X, int M, int n, const FewLay
     const FewLayer& y = layers[l];
     FewArgs& a = m.a[l];
     a.X = X; a.M = M; a.packed = y.w.packed; a.code = y.w.code; a.c1 = y.w.c1; a.mean = y.w.mean;
+    a.dtype = y.w.dtype; a.tab = table4_host(y.w.dtype);
     a.h = (int)y.w.rows; a.o = (int)y.w.cols; a.part = y.part;
     const int steps = (a.h + 15) / 16;
     a.per_split = ((steps + splits - 1) / splits) * 16;
@@ -892,6 +914,7 @@ hipError_t launch_fewtok_bwd(const uint16_t* dY, int M, const NF4Dev& w, float* 
                              uint16_t* U_hl, hipStream_t st) {
   FewArgs a;
   a.X = dY; a.M = M; a.packed = w.packed; a.code = w.code; a.c1 = w.c1; a.mean = w.mean;
+  a.dtype = w.dtype; a.tab = table4_host(w.dtype);
   a.h = (int)w.rows; a.o = (int)w.cols; a.part = part;
   const int steps = (a.o + 127) / 128;
   // a split's column range is a whole number of 128-byte lines (256 columns): a line straddling two splits is

@@ -14,12 +14,13 @@ struct NF4Dev {            // device views of one quantised h x o weight
   const float* c1;
   const float* mean;
   int64_t rows, cols;      // h, o
+  int dtype;               // 0 NF4; 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4 (the data types of the paper's comparison)
 };
 
 // quantize.hip
 constexpr size_t kQuantBinsBytes = 256 * sizeof(unsigned long long);
 hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
-                           float* mean, void* scratch, hipStream_t st);
+                           float* mean, void* scratch, hipStream_t st, int dtype = 0);
 
 // dequant.hip
 hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);

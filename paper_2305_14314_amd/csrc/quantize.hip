@@ -22,14 +22,21 @@ constexpr int kQUnroll = 4;
 __global__ void zero_bins_kernel(unsigned long long* bins) { bins[threadIdx.x] = 0ull; }
 
 // One float4 per lane per step; 16 consecutive lanes hold one 64-block.
+// OTHER: one of the other 4-bit data types (Section 4); its decision thresholds arrive as an argument.
+template <bool OTHER>
 __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
     const float4* __restrict__ W, int64_t n_vec4,          // n_vec4 = elements / 4
     uint16_t* __restrict__ packed16,                       // one 16-bit store per lane: 4 nibbles
-    float* __restrict__ c2_out, unsigned long long* __restrict__ bins) {
+    float* __restrict__ c2_out, unsigned long long* __restrict__ bins, const Thresholds4 thr) {
   __shared__ unsigned long long lbins[256];
   __shared__ __attribute__((aligned(256))) Nf4Bucket buckets[32];
+  __shared__ float th[16];
   lbins[threadIdx.x] = 0ull;
   nf4_bucket_table_init(buckets, threadIdx.x);
+  if (OTHER && threadIdx.x == 0) {
+#pragma unroll
+    for (int j = 0; j < 15; ++j) th[j] = thr.t[j];
+  }
   __syncthreads();
 
   // kQUnroll independent float4 loads are issued before any is used: a wave keeps 4 KB in flight, which
@@ -52,10 +59,18 @@ __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
       amax = row16_max(amax);                                 // c2 of this lane's block
       // Eq. 1: the constant is range/absmax (range 1); elements are multiplied by it.
       const float rc = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(1.0f, amax);
-      const uint32_t i0 = nf4_index(__fmul_rn(w.x, rc), buckets);
-      const uint32_t i1 = nf4_index(__fmul_rn(w.y, rc), buckets);
-      const uint32_t i2 = nf4_index(__fmul_rn(w.z, rc), buckets);
-      const uint32_t i3 = nf4_index(__fmul_rn(w.w, rc), buckets);
+      uint32_t i0, i1, i2, i3;
+      if constexpr (OTHER) {
+        i0 = index_search4(__fmul_rn(w.x, rc), th);
+        i1 = index_search4(__fmul_rn(w.y, rc), th);
+        i2 = index_search4(__fmul_rn(w.z, rc), th);
+        i3 = index_search4(__fmul_rn(w.w, rc), th);
+      } else {
+        i0 = nf4_index(__fmul_rn(w.x, rc), buckets);
+        i1 = nf4_index(__fmul_rn(w.y, rc), buckets);
+        i2 = nf4_index(__fmul_rn(w.z, rc), buckets);
+        i3 = nf4_index(__fmul_rn(w.w, rc), buckets);
+      }
       packed16[v] = (uint16_t)(i0 | (i1 << 4) | (i2 << 8) | (i3 << 12));
       if ((threadIdx.x & 15) == 0) {
         c2_out[v >> 4] = amax;
@@ -167,7 +182,9 @@ __global__ __launch_bounds__(kDqBlock) void dq_encode_kernel(const float* __rest
 }
 
 hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
-                           float* mean, void* scratch, hipStream_t st) {
+                           float* mean, void* scratch, hipStream_t st, int dtype) {
+  if (dtype < 0 || dtype >= kNumTypes4) return hipErrorInvalidValue;
+  const Thresholds4 thr = thresholds4_host(table4_host(dtype));
   const int64_t elems = rows * cols;
   const int64_t n = elems / kBlock;
   unsigned long long* bins = (unsigned long long*)scratch;           // 256 x u64
@@ -177,8 +194,12 @@ hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* 
   const int64_t cap = 256 * 16;                                      // 16 workgroups per CU
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(zero_bins_kernel, dim3(1), dim3(256), 0, st, bins);
-  hipLaunchKernelGGL(quantize_nf4_kernel, dim3((unsigned)blocks), dim3(kQThreads), 0, st,
-                     (const float4*)W, n_vec4, (uint16_t*)packed, c2, bins);
+  if (dtype == 0)
+    hipLaunchKernelGGL(quantize_nf4_kernel<false>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
+                       n_vec4, (uint16_t*)packed, c2, bins, thr);
+  else
+    hipLaunchKernelGGL(quantize_nf4_kernel<true>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
+                       n_vec4, (uint16_t*)packed, c2, bins, thr);
   hipLaunchKernelGGL(dq_mean_kernel, dim3(1), dim3(64), 0, st, bins, (uint32_t)n, mean);
   const int64_t n1 = (n + kDqBlock - 1) / kDqBlock;
   hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)n1), dim3(kDqBlock), 0, st, c2, n, mean, code, c1,

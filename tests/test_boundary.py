@@ -161,6 +161,29 @@ def test_dropout_arguments_are_rejected_on_the_host(L):
                                                              qlora_linear_bwd_sizes(4, 1024, 1024, 0))
 
 
+def test_data_type_tables_and_their_validation(L, oracle):
+    """The library's tables of the 4-bit data types equal the oracle's bit for bit (host call, no GPU), unknown
+    types are refused, and a view carries its type."""
+    import numpy as np
+    from paper_2305_14314_amd import qlora_codebook_4bit
+    from paper_2305_14314_amd.binding import QloraError, qlora_nf4_view
+    for name, dtype in (("nf4", 0), ("fp4_e2m1", 1), ("fp4_e3m0", 2), ("int4", 3)):
+        mine = np.array(qlora_codebook_4bit(dtype), np.float32)
+        assert np.array_equal(mine.view(np.uint32), oracle.codebook4(name).view(np.uint32)), name
+    for bad in (-1, 4):
+        with pytest.raises(QloraError) as e:
+            qlora_codebook_4bit(bad)
+        assert e.value.status == -3
+    fake = ctypes.c_void_p(0x1000)
+    assert L.qlora_codebook_4bit(0, None) == -1
+    assert L.qlora_quantize_4bit(fake, 4, 64, 64, 256, 7, fake, fake, fake, fake, fake, 1 << 20, None) == -3
+    assert L.qlora_quantize_4bit(None, 4, 64, 64, 256, 1, fake, fake, fake, fake, fake, 1 << 20, None) == -1
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256, 4, 0)
+    assert L.qlora_nf4_dequant(ctypes.byref(v), fake, None) == -3
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256)       # eight fields: NF4
+    assert v.dtype == 0
+
+
 def test_constant_storage_order_is_a_permutation_that_keeps_groups_together():
     """The 8-bit constants are stored column-group-major (include/qlora.h).  The index map used by the parity
     tests and the one the binding offers agree, are permutations, and put the <= 4 constants of one row and one

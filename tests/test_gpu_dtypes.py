@@ -1,0 +1,84 @@
+"""GPU parity for the other 4-bit data types of the paper's comparison (Int4, Float4 E2M1, Float4 E3M0): the same
+kernels with another 16-value table.  Quantisation and dequantisation bit-exact against the oracle (ties and
+duplicate values included), the linear layer within the GEMM tolerance on both the large-GEMM and the few-token
+path."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import code_to_flat, dev_bf16, dev_f32, host_bits, host_u8, host_u32, upload_quant
+from test_gpu_linear import _check
+
+pytestmark = pytest.mark.gpu
+
+KINDS = [("fp4_e2m1", 1), ("fp4_e3m0", 2), ("int4", 3)]
+
+
+def _cases(oracle, synth, kind):
+    yield "normal", synth.normal_f32((257, 192), 0.02, 9000)
+    yield "unit-normal", synth.normal_f32((64, 512), 1.0, 9001)
+    w = synth.normal_f32((128, 256), 0.02, 9002)
+    w.reshape(-1)[:64 * 3] = 0.0                                          # all-zero blocks
+    yield "zero-blocks", w
+    # every decision point of the table, and its fp32 neighbours, in blocks whose absmax is exactly 1
+    t = oracle.codebook4(kind).astype(np.float64)
+    mids = ((t[:-1] + t[1:]) / 2).astype(np.float32)
+    pts = np.concatenate([mids, np.nextafter(mids, np.float32(2)), np.nextafter(mids, np.float32(-2)), t.astype(np.float32)])
+    flat = np.zeros((4 * 64,), np.float32)
+    flat[:len(pts)] = pts
+    flat[63::64] = 1.0                                                    # absmax 1 in every block
+    yield "decision-points", flat.reshape(1, -1).copy()
+
+
+@pytest.mark.parametrize("kind,dtype", KINDS)
+def test_quantize_dequant_bit_exact(oracle, synth, kind, dtype):
+    import paper_2305_14314_amd as ql
+    table = oracle.codebook4(kind)
+    assert np.array_equal(np.array(ql.qlora_codebook_4bit(dtype), np.float32).view(np.uint32), table.view(np.uint32))
+    for tag, W in _cases(oracle, synth, kind):
+        print("case", kind, tag, W.shape, flush=True)
+        q = oracle.nf4_quantize(W, table=table)
+        Wq = ql.qlora_quantize_4bit(dev_f32(W), dtype)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host_u8(Wq.packed), q["packed"], err_msg=f"{kind} {tag}: packed")
+        assert host_u32(Wq.mean)[0] == np.float32(q["mean"]).view(np.uint32)
+        np.testing.assert_array_equal(host_u32(Wq.c1), q["c1"].view(np.uint32))
+        np.testing.assert_array_equal(code_to_flat(host_u8(Wq.code), Wq.rows, Wq.cols), q["code"])
+        got = host_bits(ql.qlora_nf4_dequant(Wq))
+        np.testing.assert_array_equal(got, oracle.nf4_dequant(q), err_msg=f"{kind} {tag}: dequantised bf16")
+
+
+@pytest.mark.parametrize("kind,dtype", KINDS)
+@pytest.mark.parametrize("M,h,o,r", [(300, 448, 576, 32), (5, 192, 320, 16), (16, 1024, 1024, 64)])
+def test_linear_other_types(oracle, synth, kind, dtype, M, h, o, r):
+    """Forward and backward on a weight of another data type: M = 300 takes the dequantise + GEMM path, M = 5 and 16
+    the few-token streaming kernels (8- and 16-token variants), all against the oracle on its own dequantised weight."""
+    import paper_2305_14314_amd as ql
+    s = 0.5
+    table = oracle.codebook4(kind)
+    q = oracle.nf4_quantize(synth.normal_f32((h, o), synth.SIGMA_W, 9100 + M), table=table)
+    What = oracle.nf4_dequant(q)
+    Wq = upload_quant(q)
+    Wq.dtype = dtype
+    hX, hdY = synth.normal_bf16((M, h), 1.0, 9101), synth.normal_bf16((M, o), 1.0, 9102)
+    hL1, hL2 = synth.normal_bf16((h, r), 0.05, 9103), synth.normal_bf16((r, o), 0.05, 9104)
+    X, dY, L1, L2 = dev_bf16(hX), dev_bf16(hdY), dev_bf16(hL1), dev_bf16(hL2)
+    print(f"case {kind} linear M={M} h={h} o={o} r={r}", flush=True)
+    Y = ql.qlora_linear_fwd(X, Wq, L1, L2, s)
+    dX, dL1, dL2 = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s)
+    Ym = ql.qlora_linear_fwd_multi(X, [Wq, Wq], [L1, None], [L2, None], [s, 1.0])
+    torch.cuda.synchronize()
+    _check(host_bits(Y), oracle.linear_fwd(hX, What, hL1, hL2, s), f"{kind} Y")
+    _check(host_bits(dX), oracle.linear_bwd_dx(hdY, What, hL1, hL2, s), f"{kind} dX")
+    r1, r2 = oracle.linear_bwd_dl(hdY, hX, hL1, hL2, s)
+    _check(host_bits(dL1), r1, f"{kind} dL1", few_terms=M < 64)
+    _check(host_bits(dL2), r2, f"{kind} dL2", few_terms=M < 64)
+    _check(host_bits(Ym[0]), oracle.linear_fwd(hX, What, hL1, hL2, s), f"{kind} multi Y0")
+    _check(host_bits(Ym[1]), oracle.linear_fwd(hX, What, None, None, 1.0), f"{kind} multi Y1")
+    # the table matters: the same codes read as NF4 are far from this reference
+    Wq.dtype = 0
+    Ynf4 = ql.qlora_linear_fwd(X, Wq, None, None, s)
+    torch.cuda.synchronize()
+    ref = oracle.linear_fwd(hX, What, None, None, s)
+    got = (host_bits(Ynf4).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.abs(got - ref).max() > 10 * 2e-2 * np.sqrt((ref ** 2).mean())
