@@ -8,32 +8,38 @@
 // or L1): the adapter rides as extra K-steps of the same accumulators, so the output is rounded
 // to bf16 exactly once.
 //
-// Design for gfx950 (256 CUs in 8 XCDs, 160 KB LDS, MFMA 32x32x16 bf16 = 32 cycles per SIMD):
-//  * 256 x 256 output tile per workgroup of 8 waves (2 x 4), each wave 128 x 64 as 4 x 2 MFMA tiles: 128 fp32
-//    accumulators per lane (AGPRs).  Two waves per SIMD: one can issue MFMAs while the other waits.
+// Design for gfx950 (256 CUs in 8 XCDs, 160 KB LDS):
+//  * 256 x 256 output tile per workgroup of 4 waves (2 x 2), each wave 128 x 128 as 8 x 8 tiles of MFMA 16x16x32
+//    bf16: 256 fp32 accumulators per lane (all AGPRs), one wave per SIMD.  The kernel is bound by the board's power
+//    limit, not by issue slots: on the same Gaussian operands a register-only loop of 16x16x32 MFMAs sustains 6 %
+//    more FLOP/s than one of 32x32x16 MFMAs (an accumulator is read and written once per 32 k instead of once
+//    per 16), and the square wave tile reads a third less LDS per MFMA than 128 x 64.  Against 8 waves of 128 x 64
+//    with 32x32x16 the same kernel measures 7 - 11 % faster per product, bit-identical results.
 //  * K-step 64: a tile row is one whole 128-byte line.  With 32-wide steps every DMA instruction fetched 16 half
 //    lines, each line was pulled from L2 twice (the L1 does not keep it for a step) and the MFMA pipes measured
 //    67 % busy; the same kernel fetching whole lines (and nothing else changed) ran 5 - 17 % faster.
 //  * Operand tiles (256 rows x 128 B = 32 KB) arrive by buffer_load_dwordx4 ... lds (no VGPR staging) into a ring
 //    of five 32 KB slots -- all 160 KB of the CU -- in the order A(0) B(0) A(1) B(1) A(2) ...: tile n sits in slot
 //    n % 5.  While step k is computed, A(k+1), B(k+1) and A(k+2) are resident or landing.
-//  * One barrier per K-step, before its LAST 16-wide sub-step (by then a wave holds the step's last fragments in
-//    registers): it publishes the tiles of step k+1 -- so the first fragments of step k+1 are read during that
-//    last sub-step and the MFMA stream continues across the step boundary -- and frees the two slots of step k,
-//    into which B(k+2) and A(k+3) are requested over the following four sub-steps, one DMA instruction behind a
-//    row of MFMAs (waves issue in order: a burst of DMAs would stall the MFMA stream).  B thus has one step
-//    (about 1 us) and A two steps to arrive.
+//  * A K-step is two 32-wide sub-steps (one MFMA 16x16x32 per accumulator tile each).  One barrier per K-step,
+//    before its LAST sub-step (by then a wave holds the step's last fragments in registers): it publishes the
+//    tiles of step k+1 -- so the first fragments of step k+1 are read during that last sub-step and the MFMA
+//    stream continues across the step boundary -- and frees the two slots of step k, into which B(k+2) and A(k+3)
+//    are requested over the following two sub-steps, one DMA instruction behind a row of MFMAs (waves issue in
+//    order: a burst of DMAs would stall the MFMA stream).  B thus has one step (about 1 us) and A two steps to
+//    arrive.
 //  * Addresses cost no vector ALU instruction in the loop (VALU instructions share the MFMA's issue port): a DMA
 //    instruction takes a buffer resource based at the tile's first row, a per-lane byte offset that never
 //    changes and a scalar offset that advances by 128 per step; a fragment read takes one of a few base
 //    registers plus a 16-bit immediate (slot, MFMA tile).
-//  * Fragment reads are software-pipelined one 16-wide sub-step ahead, one read behind each of the first MFMAs of
-//    a sub-step; reads, MFMAs and waits are volatile asm so that this order is the program order, with
+//  * Fragment reads are software-pipelined one sub-step ahead, one read behind each of the first MFMAs of a
+//    sub-step; reads, MFMAs and waits are volatile asm so that this order is the program order, with
 //    hand-placed s_waitcnt (the compiler's automatic waits cannot tell a DMA into one slot from a read of another
 //    across the loop back-edge and would drain all DMAs every iteration).
 //  * LDS rows are 128 bytes (64 k); the eight 16-byte chunks of row r sit at chunk ^ ((r >> 1) & 7).  LDS has 64
-//    banks: a ds_read_b128 is served 16 lanes (256 bytes) per cycle; 16 consecutive rows alternate between the
-//    two halves of the bank space and the swizzle spreads the 8 rows of each half over its 8 sixteen-byte groups.
+//    banks: a ds_read_b128 is served 16 lanes (256 bytes) per cycle -- the 16 rows of one operand tile at one
+//    logical chunk -- which alternate between the two halves of the bank space while the swizzle spreads the 8
+//    rows of each half over its 8 sixteen-byte groups: no bank conflicts (counter-checked).
 //  * Workgroup ids are remapped so each XCD (which receives every 8th id) works on a contiguous
 //    range of the tile order, and tiles are ordered in groups of GM tile-rows, so the 32 tiles
 //    resident on an XCD share A and B tiles in that XCD's L2.
@@ -52,7 +58,7 @@ constexpr int BM = 256, BK = 64, NSLOT = 5;                  // BN is 256, or 12
 constexpr int kSlot = BM * BK * 2;                           // 32 KB: one 256-row operand tile
 constexpr int GM = 4;                                       // tile-rows per raster group
 #ifndef QL_GEMM_WAVES
-#define QL_GEMM_WAVES 8
+#define QL_GEMM_WAVES 4
 #endif
 constexpr int kMainWaves = QL_GEMM_WAVES;                    // waves per workgroup of the main (BN = 256) kernel
 
@@ -66,7 +72,7 @@ struct GemmArgs {
   int n_begin;                                               // first output column of this launch
 };
 
-template <int NI> struct Frags { bf16x8 a[4], b[NI]; };
+template <int NI> struct Frags { bf16x8 a[8], b[NI]; };      // 16-row / 16-column MFMA operand tiles of one 32-wide sub-step
 
 // One operand's DMA state.  The tile's rows are addressed through a buffer resource based at the tile's first
 // row: a per-lane byte offset that never changes (row * ld + chunk) plus a scalar byte offset that advances by one
@@ -87,32 +93,34 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, lchar* dst, i
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 #define QL_LDS_READ(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm))
-__device__ __forceinline__ void wait_frags(Frags<2>& f) {
-  asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]));
-}
 __device__ __forceinline__ void wait_frags(Frags<4>& f) {
   asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]),
-                 "+v"(f.b[3]));
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.a[4]), "+v"(f.a[5]), "+v"(f.a[6]),
+                 "+v"(f.a[7]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]), "+v"(f.b[3]));
+}
+__device__ __forceinline__ void wait_frags(Frags<8>& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.a[4]), "+v"(f.a[5]), "+v"(f.a[6]),
+                 "+v"(f.a[7]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]), "+v"(f.b[3]), "+v"(f.b[4]), "+v"(f.b[5]),
+                 "+v"(f.b[6]), "+v"(f.b[7]));
 }
 // The MFMAs are volatile asm like the LDS reads and waits, so the instruction order below IS the program order:
 // left to the scheduler, the reads of the next sub-step sank behind the rows that free their registers, the last
 // ones three MFMAs before the wait that needs them, and every sub-step began with an exposed LDS latency.
-#define QL_MFMA(c, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b))
+#define QL_MFMA(c, a, b) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b))
 
 // BN = 256 is the main configuration.  BN = 128 serves the columns left over when the 256-wide tiles do not fill
 // a whole number of rounds of the 256 CUs: half-width tiles finish that last, partly filled round in half the time.
-// NW = waves per workgroup, laid out 2 x NW/2: wave tiles are 128 x 64 (the configurations launched), or 128 x 128
-// for 4 waves on the 256-wide tile (builds and measures the same; kept as the QL_GEMM_WAVES build option).
+// NW = waves per workgroup, laid out 2 x NW/2: wave tiles are 128 x 128 (main configuration, 4 waves) or 128 x 64
+// (the half-width tail; also 8 waves on the 256-wide tile, the QL_GEMM_WAVES = 8 build option).
 template <int BN, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   constexpr int WN = BN / (NW / 2);                          // wave tile width: 64, or 128 for 4 waves on a 256-wide tile
-  constexpr int NI = WN / 32;                                // MFMA columns per wave
-  static_assert(NI == 2 || NI == 4, "wave tiles are 128 x 64 or 128 x 128");
+  constexpr int NI = WN / 16;                                // MFMA columns per wave
+  static_assert(NI == 4 || NI == 8, "wave tiles are 128 x 64 or 128 x 128");
   constexpr int NA = 32 / NW, NB = (BN / 8) / NW;            // DMA instructions per wave, step and operand
-  constexpr int PER = (NA + NB) / 4;                         // DMA instructions per wave and sub-step
-  static_assert((NA + NB) % 4 == 0 && PER <= 4, "DMA instructions are spread evenly over the four sub-steps");
+  constexpr int PER = (NA + NB) / 2;                         // DMA instructions per wave and sub-step
+  static_assert((NA + NB) % 2 == 0 && PER <= 8, "DMA instructions are spread evenly over the two sub-steps");
   __shared__ __attribute__((aligned(1024))) char smem[NSLOT * kSlot];             // 160 KB
   lchar* const lds = (lchar*)smem;
 
@@ -174,36 +182,38 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   };
 
   // ---- per-lane LDS addresses of the fragments --------------------------------------------------
-  // Sub-step kk (16 k) of a tile: logical chunk 2 kk + half of row r, at physical chunk (2 kk + half) ^ ((r >> 1) & 7).
+  // Sub-step kk (32 k) of a tile: logical chunks 4 kk .. 4 kk + 3 of row r, at physical chunk (4 kk + g) ^ ((r >> 1) & 7).
   // ds_read takes a 16-bit immediate: one base register per sub-step, operand and 64 KB window of the ring; the
   // slot within the window and the 32-row MFMA tile (4 KB apart, same swizzle) are immediates.
   const int wm = wave / (NW / 2), wn = wave % (NW / 2);
-  const int a_row = wm * 128 + (lane & 31), b_row = wn * WN + (lane & 31), half = lane >> 5;
+  // MFMA 16x16x32: lane (i = lane % 16, g = lane / 16) holds row i of a 16-row operand tile at k = 8 g .. 8 g + 7 of
+  // the 32-wide sub-step kk, i.e. logical chunk 4 kk + g.  16-row tiles are 2 KB apart and share the swizzle.
+  const int a_row = wm * 128 + (lane & 15), b_row = wn * WN + (lane & 15), g4 = lane >> 4;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-  uint32_t baseA[4][3], baseB[4][3];
+  uint32_t baseA[2][3], baseB[2][3];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
+  for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
     for (int w = 0; w < 3; ++w) {
-      baseA[kk][w] = lds0 + w * 65536 + a_row * 128 + (((2 * kk + half) ^ ((a_row >> 1) & 7)) * 16);
-      baseB[kk][w] = lds0 + w * 65536 + b_row * 128 + (((2 * kk + half) ^ ((b_row >> 1) & 7)) * 16);
+      baseA[kk][w] = lds0 + w * 65536 + a_row * 128 + (((4 * kk + g4) ^ ((a_row >> 1) & 7)) * 16);
+      baseB[kk][w] = lds0 + w * 65536 + b_row * 128 + (((4 * kk + g4) ^ ((b_row >> 1) & 7)) * 16);
     }
-#define QL_READ_A(dst, slot, kk, i) QL_LDS_READ(dst, baseA[kk][(slot) >> 1], ((slot) & 1) * kSlot + (i) * 4096)
-#define QL_READ_B(dst, slot, kk, i) QL_LDS_READ(dst, baseB[kk][(slot) >> 1], ((slot) & 1) * kSlot + (i) * 4096)
+#define QL_READ_A(dst, slot, kk, i) QL_LDS_READ(dst, baseA[kk][(slot) >> 1], ((slot) & 1) * kSlot + (i) * 2048)
+#define QL_READ_B(dst, slot, kk, i) QL_LDS_READ(dst, baseB[kk][(slot) >> 1], ((slot) & 1) * kSlot + (i) * 2048)
 
-  f32x16 acc[4][NI];
+  f32x4 acc[8][NI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
   // The MFMAs below are inline asm, invisible to the compiler's hazard recogniser: a vector-ALU write of an
   // accumulator register needs 2 wait states before an MFMA reads it as its addend.  Pin every initialisation
   // in front of a few idle cycles (without this the compiler sank the zeroing of one accumulator right in front
   // of its first MFMA, which then read the register's old contents).
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j) asm volatile("s_nop 3" : "+a"(acc[i][j]));
 
@@ -228,38 +238,35 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
 
   Frags<NI> f0, f1;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 8; ++i) {
     QL_READ_A(f0.a[i], 0, 0, i);
     if (i < NI) QL_READ_B(f0.b[i], 1, 0, i);
   }
 
-  // One 16-wide sub-step: multiply fragments `cur` while fetching fragments `nxt` (sub-step kk of the tiles in
+  // One 32-wide sub-step: multiply fragments `cur` while fetching fragments `nxt` (sub-step kk of the tiles in
   // slots sa, sb) and issuing this sub-step's share q0 .. q0 + PER - 1 of the step's DMA instructions: first the
   // NB of B(k+2) into slot db_, then the NA of A(k+3) into slot da_.  One fragment read behind each of the first
-  // 4 + NI MFMAs (issued in the MFMA's shadow, and landed long before the next wait); one DMA behind each row.
+  // 8 + NI MFMAs (issued in the MFMA's shadow, and landed long before the next wait); one DMA behind each row.
 #define QL_DMA_Q(q, da_, db_)                                                                               \
   if ((q) < NB) QL_DMA16(db, lds + (db_) * kSlot, (q) < NB ? (q) : 0);                               \
   else QL_DMA16(da, lds + (da_) * kSlot, (q) >= NB ? (q) - NB : 0);
 #define QL_SUBSTEP(cur, nxt, sa, sb, kk, q0, da_, db_, with_dma)                                            \
   {                                                                                                         \
     wait_frags(cur);                                                                                        \
-    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
+    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                      \
       _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) {                                                \
         QL_MFMA(acc[i_][ni_], cur.a[i_], cur.b[ni_]);                                                       \
-        const int r_ = i_ * NI + ni_;                        /* MFMA number; reads 0 .. 3 + NI: a[], then b[] */ \
-        if (r_ < 4) QL_READ_A(nxt.a[r_ & 3], sa, kk, r_ & 3);                                               \
-        else if (r_ < 4 + NI) QL_READ_B(nxt.b[(r_ - 4) % NI], sb, kk, (r_ - 4) % NI);                       \
+        const int r_ = i_ * NI + ni_;                        /* MFMA number; reads 0 .. 7 + NI: a[], then b[] */ \
+        if (r_ < 8) QL_READ_A(nxt.a[r_ & 7], sa, kk, r_ & 7);                                               \
+        else if (r_ < 8 + NI) QL_READ_B(nxt.b[(r_ - 8) % NI], sb, kk, (r_ - 8) % NI);                       \
       }                                                                                                     \
       if ((with_dma) && i_ < PER) { QL_DMA_Q((q0) + i_, da_, db_) }                                         \
     }                                                                                                       \
   }
-  // Sub-steps 0 .. 2 of a step whose tiles sit in slots SA, SB (fragments of sub-step 0 are in f0).
-#define QL_HEAD(SA, SB)                                                                                     \
-  QL_SUBSTEP(f0, f1, SA, SB, 1, 0, 0, 0, false)                                                             \
-  QL_SUBSTEP(f1, f0, SA, SB, 2, 0, 0, 0, false)                                                             \
-  QL_SUBSTEP(f0, f1, SA, SB, 3, 0, 0, 0, false)
-  // One iteration: the last sub-step of step k (tiles in slots S0 = 2k % 5 and S0 + 1) and the first three of
-  // step k+1 (slots S0 + 2, S0 + 3), requesting B(k+2) into slot S0 and A(k+3) into slot S0 + 1.
+  // Sub-step 0 of a step whose tiles sit in slots SA, SB (its fragments are in f0).
+#define QL_HEAD(SA, SB) QL_SUBSTEP(f0, f1, SA, SB, 1, 0, 0, 0, false)
+  // One iteration: the second sub-step of step k (tiles in slots S0 = 2k % 5 and S0 + 1) and the first of step k+1
+  // (slots S0 + 2, S0 + 3), requesting B(k+2) into slot S0 and A(k+3) into slot S0 + 1.
 #define QL_ITER(S0, FAST)                                                                                   \
   {                                                                                                         \
     constexpr int sa_ = ((S0) + 2) % NSLOT, sb_ = ((S0) + 3) % NSLOT, fa_ = (S0) % NSLOT, fb_ = ((S0) + 1) % NSLOT; \
@@ -268,8 +275,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
     asm volatile("s_barrier" ::: "memory");                   /* ... and everyone's; slots of step k are free */ \
     QL_SUBSTEP(f1, f0, sa_, sb_, 0, 0 * PER, fb_, fa_, true)                                                \
     QL_SUBSTEP(f0, f1, sa_, sb_, 1, 1 * PER, fb_, fa_, true)                                                \
-    QL_SUBSTEP(f1, f0, sa_, sb_, 2, 2 * PER, fb_, fa_, true)                                                \
-    QL_SUBSTEP(f0, f1, sa_, sb_, 3, 3 * PER, fb_, fa_, true)                                                \
     if (FAST) {                                                                                             \
       db.soff += BK * 2;                                                                                    \
       da.soff += BK * 2;                                                                                    \
@@ -280,8 +285,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
     ++k;                                                                                                    \
   }
 
-  QL_HEAD(0, 1)                                               // step 0, sub-steps 0 .. 2 (no DMA: the ring is full)
-  int k = 0;                                                 // f1 holds the fragments of sub-step 3 of step k
+  QL_HEAD(0, 1)                                               // step 0, sub-step 0 (no DMA: the ring is full)
+  int k = 0;                                                 // f1 holds the fragments of the last sub-step of step k
   // Steady state: every tile requested and every state advanced in these five iterations stays inside K segment 0
   // (the last advance moves A to step k + 8 < KT0), so the DMA state advances by one scalar add and no iteration
   // carries the branches and register copies of the segment switch.
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   // the last sub-step of the last step; its fragments are in f1
   wait_frags(f1);
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) QL_MFMA(acc[i][ni], f1.a[i], f1.b[ni]);
 #undef QL_ITER
@@ -313,32 +318,32 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // drain the tail's redundant loads
   // likewise the other way: an MFMA's result may be read by the vector ALU only 18 wait states after its issue
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+a"(acc[i][j]));
 
-  // ---- epilogue: one rounding to bf16; lane owns column n, rows 8*(v/4) + 4*half + v%4 ----------
+  // ---- epilogue: one rounding to bf16; lane owns column n, rows 16 mi + 4 (lane / 16) + v ---------
   // One 64-bit base per lane and MFMA column; a store's row offset is then a compile-time multiple of ldc, and
   // tiles that lie wholly inside M (all but the last tile-row) skip the per-row bound checks: computing every
   // address and bound from scratch cost 12 instructions per 2-byte store, three times the stores themselves.
   const bool rows_inside = m0 + BM <= p.M;
-  const int m_lane = m0 + wm * 128 + 4 * half;              // first row this lane stores
+  const int m_lane = m0 + wm * 128 + 4 * g4;                // first row this lane stores: D rows 4 g + v, column lane % 16
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) {
-    const int n = n0 + wn * WN + ni * 32 + (lane & 31);
+    const int n = n0 + wn * WN + ni * 16 + (lane & 15);
     if (n >= p.N) continue;
     uint16_t* const cb = p.C + (int64_t)m_lane * p.ldc + n;
     if (rows_inside) {
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
+      for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) cb[(int64_t)(mi * 32 + 8 * (v >> 2) + (v & 3)) * p.ldc] = bf16_bits(acc[mi][ni][v]);
+        for (int v = 0; v < 4; ++v) cb[(int64_t)(mi * 16 + v) * p.ldc] = bf16_bits(acc[mi][ni][v]);
     } else {
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
+      for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = mi * 32 + 8 * (v >> 2) + (v & 3);
+        for (int v = 0; v < 4; ++v) {
+          const int row = mi * 16 + v;
           if (m_lane + row < p.M) cb[(int64_t)row * p.ldc] = bf16_bits(acc[mi][ni][v]);
         }
     }
