@@ -255,7 +255,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
     wait_frags(cur);                                                                                        \
     _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                      \
       _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) {                                                \
-        QL_MFMA(acc[i_][ni_], cur.a[i_], cur.b[ni_]);                                                       \
+        QL_MFMA(acc[i_][ni_], cur.b[ni_], cur.a[i_]);        /* D = (B tile) (A tile)^T: see the epilogue */      \
         const int r_ = i_ * NI + ni_;                        /* MFMA number; reads 0 .. 7 + NI: a[], then b[] */ \
         if (r_ < 8) QL_READ_A(nxt.a[r_ & 7], sa, kk, r_ & 7);                                               \
         else if (r_ < 8 + NI) QL_READ_B(nxt.b[(r_ - 8) % NI], sb, kk, (r_ - 8) % NI);                       \
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) QL_MFMA(acc[i][ni], f1.a[i], f1.b[ni]);
+    for (int ni = 0; ni < NI; ++ni) QL_MFMA(acc[i][ni], f1.b[ni], f1.a[i]);
 #undef QL_ITER
 #undef QL_HEAD
 #undef QL_SUBSTEP
@@ -322,30 +322,27 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NI; ++j) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+a"(acc[i][j]));
 
-  // ---- epilogue: one rounding to bf16; lane owns column n, rows 16 mi + 4 (lane / 16) + v ---------
-  // One 64-bit base per lane and MFMA column; a store's row offset is then a compile-time multiple of ldc, and
-  // tiles that lie wholly inside M (all but the last tile-row) skip the per-row bound checks: computing every
-  // address and bound from scratch cost 12 instructions per 2-byte store, three times the stores themselves.
+  // ---- epilogue: one rounding to bf16 ------------------------------------------------------------
+  // The MFMAs take the weight-side fragment as their first operand, so an accumulator tile is the TRANSPOSE of
+  // the output tile: lane (j = lane % 16, g = lane / 16) holds output row 16 mi + j and the four consecutive
+  // columns 16 ni + 4 g .. + 3, which go out as one 8-byte store (a quarter of the store instructions of the
+  // untransposed tile, whose lanes hold four rows of one column).  One 64-bit base per lane; tiles that lie wholly
+  // inside M (all but the last tile-row) skip the per-row bound checks.  N % 4 == 0: a group of four columns is
+  // inside or outside as a whole.
   const bool rows_inside = m0 + BM <= p.M;
-  const int m_lane = m0 + wm * 128 + 4 * g4;                // first row this lane stores: D rows 4 g + v, column lane % 16
+  const int m_lane = m0 + wm * 128 + (lane & 15);            // first row this lane stores
+  const int n_lane = n0 + wn * WN + 4 * g4;                  // its first column
+  uint16_t* const cb = p.C + (int64_t)m_lane * p.ldc + n_lane;
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) {
-    const int n = n0 + wn * WN + ni * 16 + (lane & 15);
-    if (n >= p.N) continue;
-    uint16_t* const cb = p.C + (int64_t)m_lane * p.ldc + n;
-    if (rows_inside) {
+  for (int mi = 0; mi < 8; ++mi) {
+    if (!rows_inside && m_lane + mi * 16 >= p.M) continue;
 #pragma unroll
-      for (int mi = 0; mi < 8; ++mi)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) cb[(int64_t)(mi * 16 + v) * p.ldc] = bf16_bits(acc[mi][ni][v]);
-    } else {
-#pragma unroll
-      for (int mi = 0; mi < 8; ++mi)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int row = mi * 16 + v;
-          if (m_lane + row < p.M) cb[(int64_t)row * p.ldc] = bf16_bits(acc[mi][ni][v]);
-        }
+    for (int ni = 0; ni < NI; ++ni) {
+      if (n_lane + ni * 16 >= p.N) continue;
+      uint2 q;
+      q.x = pack_bf16x2(acc[mi][ni][0], acc[mi][ni][1]);
+      q.y = pack_bf16x2(acc[mi][ni][2], acc[mi][ni][3]);
+      *(uint2*)(cb + (int64_t)(mi * 16) * p.ldc + ni * 16) = q;
     }
   }
 }
@@ -356,6 +353,7 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
                           const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                           uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
   if (K0 <= 0 || K0 % BK != 0 || K1 < 0 || K1 % BK != 0) return hipErrorInvalidValue;
+  if (N % 4 != 0 || ldc % 4 != 0 || ((uintptr_t)C & 7u)) return hipErrorInvalidValue;    // 8-byte output stores
   // a tile's rows are addressed with 32-bit byte offsets from its first row
   const int64_t ld_max = std::max(std::max(lda0, ldb0), std::max(K1 ? lda1 : 0, K1 ? ldb1 : 0));
   if (256 * ld_max * 2 + (int64_t)(K0 > K1 ? K0 : K1) * 2 >= (1ll << 31)) return hipErrorInvalidValue;
