@@ -82,9 +82,10 @@ def test_config0_full(oracle, synth):
 
 
 @pytest.mark.parametrize("M,h,o,r", [(300, 448, 576, 32), (1, 64, 64, 16), (17, 128, 320, 64), (513, 256, 192, 128),
-                                      (64, 1024, 64, 256)])
+                                      (64, 1024, 64, 256), (65, 64, 128, 16), (257, 64, 64, 64), (700, 192, 832, 48)])
 def test_ragged_shapes(oracle, synth, M, h, o, r):
-    """Token counts and feature sizes that do not fill the 256-wide tiles, several ranks."""
+    """Token counts and feature sizes that do not fill the 256-wide tiles, several ranks; h = 64 is a single K-step
+    of the large GEMM (shorter than its prefetch ring), o = 832 leaves a 64-column remainder in the last tile."""
     import paper_2305_14314_amd as ql
     L = synth.make_layer(0, 0, M=M, h=h, o=o, r=r)
     _run_case(oracle, ql, L, f"ragged M={M} h={h} o={o} r={r}")
