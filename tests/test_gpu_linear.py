@@ -193,3 +193,24 @@ def test_full_size_sampled(oracle, synth, config, layer):
         r1, r2 = oracle.linear_bwd_dl(hdY, hX, hL1, hL2, s)
         _check(host_bits(dL1), r1, "dL1")
         _check(host_bits(dL2), r2, "dL2")
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.choice([1, 2, 7, 15, 16, 17, 31, 64, 100, 255, 256, 257, 400, 600]))
+        h = 64 * int(rng.integers(1, 25))
+        o = 64 * int(rng.integers(1, 25))
+        r = int(rng.choice([0, 16, 32, 48, 64, 80, 128, 256]))
+        out.append((M, h, o, r))
+    return out
+
+
+@pytest.mark.parametrize("M,h,o,r", _random_shapes(24, 20240521))
+def test_random_shapes(oracle, synth, M, h, o, r):
+    """Seeded random token counts (both sides of the few-token threshold and of the 256-row tile), feature sizes
+    (multiples of 64 up to 1536) and ranks: forward, input gradient and adapter gradients against the oracle."""
+    import paper_2305_14314_amd as ql
+    L = synth.make_layer(0, 0, M=M, h=h, o=o, r=max(r, 16))
+    _run_case(oracle, ql, L, f"random M={M} h={h} o={o} r={r}", with_lora=r > 0)
