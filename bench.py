@@ -270,6 +270,31 @@ def main():
             del Wq_t
         del Wn
         extra["data_types"] = types
+        # the training-loop variants of the same step (same pool, same shapes): LoRA dropout at the rate the paper
+        # uses for 65B (seeded keep-masks, one per input width) and adapter gradients accumulated in fp32
+        p_drop = 0.05
+        gen_m = torch.Generator(device=dev)
+        gen_m.manual_seed(synth.BASE_SEED + 1)
+        masks = {w: ql.pack_keep_mask(torch.rand(M, w, device=dev, generator=gen_m) >= p_drop) for w in (d, ffn)}
+        ws_drop = ql.workspace_alloc(max(max(ql.qlora_linear_dropout_sizes(M, h, o, r)) for h, o in linears), dev)
+        a1 = [torch.zeros(h, r, dtype=torch.float32, device=dev) for h, o in linears]
+        a2 = [torch.zeros(r, o, dtype=torch.float32, device=dev) for h, o in linears]
+        kd = [0]
+
+        def step_dropout():
+            block = pool[kd[0] % len(pool)]
+            kd[0] += 1
+            for li, (h, o) in enumerate(linears):
+                ql.qlora_linear_fwd_dropout(X[h], block[li], L1[li], L2[li], s, masks[h], p_drop, Y=Y[o], T_save=T[li],
+                                            workspace=ws_drop)
+            for li in reversed(range(len(linears))):
+                h, o = linears[li]
+                ql.qlora_linear_bwd_dropout(dY[o], X[h], block[li], L1[li], L2[li], s, masks[h], p_drop, T_saved=T[li],
+                                            dX=dX[h], dL1_acc=a1[li], dL2_acc=a2[li], workspace=ws_drop)
+        t = _time_ms(torch, step_dropout, 5, warmup=1)
+        extra["step_with_dropout_and_fp32_accumulation"] = {
+            "ms_per_step": round(t, 4), "TFLOPs": round(flops_step / (t * 1e-3) * 1e-12, 2), "p": p_drop}
+        del masks, ws_drop, a1, a2
         # few-token regime (workload configs[4]): forward and input gradient at 1, 4, 16 tokens
         gemv = {}
         for m in cfg_few_tokens():
