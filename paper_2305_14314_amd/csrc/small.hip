@@ -329,29 +329,50 @@ __global__ __launch_bounds__(256) void dropout_dx_fix_kernel(uint16_t* __restric
   int pos = base + incl - cnt;
   for (uint32_t d = drop; d != 0; d &= d - 1) list[pos++] = (uint16_t)(tid * 8 + (__builtin_ctz(d)));
   __syncthreads();
-  // eight lanes per dropped element, 16 bytes of both rows per lane and step, summed by shuffles
+  // eight lanes per dropped element, 16 bytes of both rows per lane and step, summed by shuffles; two elements per
+  // lane group and iteration, so that the loads of the second are in flight while the first is summed
   const int64_t e_base = (int64_t)blockIdx.x * 2048;
   const int sub = tid & 7;
-  for (int idx0 = 0; idx0 < total; idx0 += 32) {             // uniform trip count: the shuffles below need every lane
-    const int idx = idx0 + (tid >> 3);
-    const bool live = idx < total;
-    const int64_t e = e_base + list[live ? idx : 0];         // flat element index token * h + k
-    const int m = (int)(e / h), k = (int)(e - (int64_t)m * h);
-    const uint16_t* us = Us + (int64_t)m * ld_us;
-    const uint16_t* l1 = L1 + (int64_t)k * r;
-    float dot = 0.0f;
-    for (int t = 8 * sub; t < r; t += 64) {                  // r % 16 == 0: a lane's chunk is inside the row or not at all
-      const u32x4 a = *(const u32x4*)(us + t), w = *(const u32x4*)(l1 + t);
+  for (int idx0 = 0; idx0 < total; idx0 += 64) {             // uniform trip count: the shuffles below need every lane
+    int64_t e[2];
+    bool live[2];
+    float dot[2], old[2];
+    u32x4 a[2], w[2];
+    const uint16_t* us[2];
+    const uint16_t* l1[2];
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        dot = __builtin_fmaf(bf16_lo_to_f32(a[d]), bf16_lo_to_f32(w[d]), dot);
-        dot = __builtin_fmaf(bf16_lo_to_f32(a[d] >> 16), bf16_lo_to_f32(w[d] >> 16), dot);
-      }
+    for (int z = 0; z < 2; ++z) {
+      const int idx = idx0 + 32 * z + (tid >> 3);
+      live[z] = idx < total;
+      e[z] = e_base + list[live[z] ? idx : 0];               // flat element index token * h + k
+      const int m = (int)(e[z] / h), k = (int)(e[z] - (int64_t)m * h);
+      us[z] = Us + (int64_t)m * ld_us;
+      l1[z] = L1 + (int64_t)k * r;
+      const bool in = 8 * sub < r;                           // r % 16 == 0: a lane's chunk is inside the row or not at all
+      a[z] = *(const u32x4*)(us[z] + (in ? 8 * sub : 0));
+      w[z] = *(const u32x4*)(l1[z] + (in ? 8 * sub : 0));
+      old[z] = bf16_lo_to_f32(dX[e[z]]);
+      dot[z] = 0.0f;
+      if (!in) { a[z] = u32x4{0u, 0u, 0u, 0u}; }
     }
-    dot += __shfl_xor(dot, 1, 64);
-    dot += __shfl_xor(dot, 2, 64);
-    dot += __shfl_xor(dot, 4, 64);
-    if (live && sub == 0) dX[e] = bf16_bits(bf16_lo_to_f32(dX[e]) - dot);
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+      for (int t = 8 * sub;;) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          dot[z] = __builtin_fmaf(bf16_lo_to_f32(a[z][d]), bf16_lo_to_f32(w[z][d]), dot[z]);
+          dot[z] = __builtin_fmaf(bf16_lo_to_f32(a[z][d] >> 16), bf16_lo_to_f32(w[z][d] >> 16), dot[z]);
+        }
+        t += 64;
+        if (t >= r) break;
+        a[z] = *(const u32x4*)(us[z] + t);
+        w[z] = *(const u32x4*)(l1[z] + t);
+      }
+      dot[z] += __shfl_xor(dot[z], 1, 64);
+      dot[z] += __shfl_xor(dot[z], 2, 64);
+      dot[z] += __shfl_xor(dot[z], 4, 64);
+      if (live[z] && sub == 0) dX[e[z]] = bf16_bits(old[z] - dot[z]);
+    }
   }
 }
 
