@@ -20,7 +20,9 @@
  *   - Return value: QLORA_OK or a negative qlora_status.  Arguments are checked
  *     on the host before any HIP call is made; on an argument error nothing is
  *     launched and no output is touched.  No exception or abort crosses the ABI.
- *   - Outputs are overwritten, never accumulated into.  Inputs must be finite.
+ *   - Outputs are overwritten, never accumulated into -- except the fp32
+ *     gradient accumulators of qlora_linear_bwd_acc / qlora_linear_bwd_dropout,
+ *     which exist to be added to.  Inputs must be finite.
  *   - Workspace / scratch contents are undefined on entry and on exit, with one
  *     exception: the first QLORA_WORKSPACE_HEADER_BYTES of a qlora_linear_*
  *     workspace hold arrival counters of the few-token kernels.  They must be
