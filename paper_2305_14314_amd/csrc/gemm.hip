@@ -254,9 +254,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   {                                                                                                         \
     wait_frags(cur);                                                                                        \
     _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                      \
-      _Pragma("unroll") for (int ni_ = 0; ni_ < NI; ++ni_) {                                                \
+      _Pragma("unroll") for (int nj_ = 0; nj_ < NI; ++nj_) {                                                \
+        const int ni_ = (i_ & 1) ? NI - 1 - nj_ : nj_;       /* serpentine: consecutive MFMAs share an operand */ \
         QL_MFMA(acc[i_][ni_], cur.b[ni_], cur.a[i_]);        /* D = (B tile) (A tile)^T: see the epilogue */      \
-        const int r_ = i_ * NI + ni_;                        /* MFMA number; reads 0 .. 7 + NI: a[], then b[] */ \
+        const int r_ = i_ * NI + nj_;                        /* MFMA number; reads 0 .. 7 + NI: a[], then b[] */ \
         if (r_ < 8) QL_READ_A(nxt.a[r_ & 7], sa, kk, r_ & 7);                                               \
         else if (r_ < 8 + NI) QL_READ_B(nxt.b[(r_ - 8) % NI], sb, kk, (r_ - 8) % NI);                       \
       }                                                                                                     \
