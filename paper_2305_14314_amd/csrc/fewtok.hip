@@ -164,11 +164,11 @@ __device__ __forceinline__ bool arrive_last(unsigned* c, unsigned total, volatil
 // hundred KB and are normally long done; when they are a little late (the smallest layers, cold adapter matrices)
 // the split waits for them -- a BOUNDED number of polls, so every wave exits whatever happens -- and only then
 // counts itself in.  Whoever completes the count owns the output stage: true = this workgroup.
-__device__ __forceinline__ bool meet_adapter(unsigned* shake, unsigned n_adapter, volatile int* flag) {
+__device__ __forceinline__ bool meet_adapter(unsigned* shake, unsigned n_adapter, volatile int* flag, unsigned early) {
   __syncthreads();                                           // everybody has read the previous flag
   if (threadIdx.x == 0) {
-    int mine = 0;
-    for (int it = 0; it < kSpinLimit; ++it) {
+    int mine = early == n_adapter;                           // seen complete already (the count cannot change any more)
+    for (int it = 0; !mine && it < kSpinLimit; ++it) {
       if (__hip_atomic_load(shake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_adapter) { mine = 1; break; }
       __builtin_amdgcn_s_sleep(16);
     }
@@ -240,6 +240,9 @@ __device__ void finalize_slab(const FewArgs& p, int slab, char* smem, unsigned* 
     }
   };
   if (p.r > 0) stage_load(0, p.r < RC ? p.r : RC);           // without an adapter Bmat may be NULL: no load at all
+  // a first look at the adapter's count, in flight together with the loads of the split partials below
+  unsigned early = 0u;
+  if (p.r > 0 && shake && threadIdx.x == 0) early = __hip_atomic_load(shake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
   float acc[P][4], lora[P][4];
 #pragma unroll
@@ -262,7 +265,7 @@ __device__ void finalize_slab(const FewArgs& p, int slab, char* smem, unsigned* 
     }
   }
   if (p.r > 0) {
-    if (shake && !meet_adapter(shake, (unsigned)p.n_lparts, flag)) return;         // the adapter came after the bounded wait: the slab is its
+    if (shake && !meet_adapter(shake, (unsigned)p.n_lparts, flag, early)) return;         // the adapter came after the bounded wait: the slab is its
     for (int e = threadIdx.x; e < p.M * p.r; e += NT) {
       float t = 0.0f;
       for (int q0 = 0; q0 < p.n_lparts; q0 += 8) {           // 8 loads in flight, then a fixed-order sum
