@@ -208,3 +208,32 @@ def test_constant_storage_order_is_a_permutation_that_keeps_groups_together():
         codes = torch.from_numpy((lib_order % 251).astype(np.uint8))
         Wq = NF4Weight(rows, cols, None, codes, None, None)
         assert np.array_equal(Wq.code_flat().numpy(), (flat % 251).astype(np.uint8))
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(L, tmp_path):
+    """include/qlora.h compiles as C99 with -pedantic, and a C program linked against the library gets the footprint
+    of Section 3, a data-type table and a status string through the host-only entry points (no GPU touched)."""
+    import shutil
+    import subprocess
+    from paper_2305_14314_amd import binding
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text('#include "qlora.h"\n#include <stdio.h>\n'
+                   'int main(void) {\n'
+                   '  size_t pb = 0, cb = 0, c1b = 0, sb = 0;\n'
+                   '  float t[16];\n'
+                   '  qlora_status a = qlora_nf4_sizes(8192, 22016, 64, 256, &pb, &cb, &c1b, &sb);\n'
+                   '  qlora_status b = qlora_codebook_4bit(QLORA_FP4_E3M0, t);\n'
+                   '  printf("%d %lu %lu %lu %d %g %g %s\\n", (int)a, (unsigned long)pb, (unsigned long)cb, (unsigned long)c1b,\n'
+                   '         (int)b, t[9], t[15], qlora_status_string(QLORA_ERR_ALIGN));\n'
+                   '  return 0;\n}\n')
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lqlora_hip", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=7)
+    P = 8192 * 22016
+    assert out[:7] == ["0", str(P // 2), str(P // 64), str(4 * P // (64 * 256)), "0", "0.015625", "1"]
+    assert out[7].startswith("QLORA_ERR_ALIGN")
