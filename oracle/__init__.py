@@ -61,6 +61,7 @@ def _load():
     L.oracle_index4.restype = ctypes.c_int
     L.oracle_quantize4.argtypes = [vp] + list(L.oracle_nf4_quantize.argtypes)
     L.oracle_dequant4.argtypes = [vp] + list(L.oracle_nf4_dequant.argtypes)
+    L.oracle_dequant4_nodq.argtypes = [vp, vp, vp, c_int64, c_int64, c_int32, vp]
     lin = [vp, vp, vp, vp, c_double, c_int64, c_int64, c_int64, c_int64, vp, c_int64, vp]
     for name in ("oracle_linear_fwd_cols", "oracle_linear_bwd_dx_cols"):
         getattr(L, name).argtypes = lin
@@ -143,11 +144,16 @@ def index4(table, xhat) -> int:
 
 def nf4_quantize(W, blocksize: int = 64, dq_blocksize: int = 256, table=None):
     """Returns dict(packed u8[P/2], code u8[n], c1 f32[n1], mean f32, c2 f32[n]).
-    table: the 16 values of another 4-bit data type (codebook4), None = NF4."""
+    table: the 16 values of another 4-bit data type (codebook4), None = NF4.
+    dq_blocksize = 0: no Double Quantization -- the result carries the fp32 constants c2 only (code, c1, mean None)."""
     W = np.ascontiguousarray(W, dtype=np.float32)
     assert W.ndim == 2
     rows, cols = W.shape
     P = rows * cols
+    if dq_blocksize == 0:
+        q = nf4_quantize(W, blocksize, 256, table)           # the first step does not depend on the second
+        q.update(code=None, c1=None, mean=None, dq_blocksize=0)
+        return q
     if blocksize <= 0 or dq_blocksize <= 0 or P % blocksize or P % 2:
         raise ValueError("oracle nf4_quantize: bad shape / blocksize")
     n = P // blocksize
@@ -173,6 +179,11 @@ def nf4_dequant(q, return_c2hat: bool = False):
     rows, cols = q["rows"], q["cols"]
     n = rows * cols // q["blocksize"]
     out = np.empty((rows, cols), np.uint16)
+    if q["dq_blocksize"] == 0:
+        table = nf4_table() if q.get("table") is None else _arr(q["table"], np.float32, (16,))
+        _check(_load().oracle_dequant4_nodq(_p(table), _p(_arr(q["packed"], np.uint8)), _p(_arr(q["c2"], np.float32)),
+                                            rows, cols, q["blocksize"], _p(out)), "dequant4_nodq")
+        return (out, _arr(q["c2"], np.float32).copy()) if return_c2hat else out
     c2hat = np.empty(n, np.float32) if return_c2hat else None
     args = (_p(_arr(q["packed"], np.uint8)), _p(_arr(q["code"], np.uint8)), _p(_arr(q["c1"], np.float32)),
             np.float32(q["mean"]), rows, cols, q["blocksize"], q["dq_blocksize"], _p(out), _p(c2hat))

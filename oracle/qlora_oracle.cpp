@@ -323,6 +323,22 @@ static int dequant4(const float* table, const uint8_t* packed, const uint8_t* co
   return 0;
 }
 
+/* Without Double Quantization (Section 3: the constants then cost 32/64 = 0.5 bit per parameter): the fp32
+ * constants c2 are used as they are, w_i = bf16_rne(fl32(table[idx_i] * c2[i / blocksize])). */
+int oracle_dequant4_nodq(const float* table, const uint8_t* packed, const float* c2,
+                         int64_t rows, int64_t cols, int32_t blocksize, uint16_t* W_bf16) {
+  if (!table || !packed || !c2 || !W_bf16) return -1;
+  if (rows <= 0 || cols <= 0 || blocksize <= 0) return -2;
+  const int64_t P = rows * cols;
+  if (P % blocksize != 0 || P % 2 != 0) return -2;
+#pragma omp parallel for schedule(static)
+  for (int64_t e = 0; e < P; ++e) {
+    const int id = (packed[e >> 1] >> ((e & 1) * 4)) & 15;
+    W_bf16[e] = oracle_bf16_rne(fl32_mul(table[id], c2[e / blocksize]));
+  }
+  return 0;
+}
+
 int oracle_nf4_dequant(const uint8_t* packed, const uint8_t* code, const float* c1,
                        float mean, int64_t rows, int64_t cols,
                        int32_t blocksize, int32_t dq_blocksize,

@@ -117,6 +117,13 @@ int oracle_dequant4(const float* table, const uint8_t* packed, const uint8_t* co
                     int32_t blocksize, int32_t dq_blocksize,
                     uint16_t* W_bf16, float* c2hat_out);
 
+/* doubleDequant's second step alone, for weights stored WITHOUT Double Quantization (Section 3 prices the fp32
+ * constants at 0.5 bit per parameter; Double Quantization is what brings them to 0.127):
+ *   w_i = bf16_rne(fl32(table[idx_i] * c2[i / blocksize])),  c2 the fp32 absmax constants of oracle_quantize4
+ * (its c2_out).  table: the 16 values of the data type (oracle_codebook4). */
+int oracle_dequant4_nodq(const float* table, const uint8_t* packed, const float* c2,
+                         int64_t rows, int64_t cols, int32_t blocksize, uint16_t* W_bf16);
+
 /* Eq. 5 with the scalar s of Eq. 3:  Y = X What + s (X L1) L2, all sums fp64,
  * no intermediate rounding.  What is the h x o bf16 matrix from
  * oracle_nf4_dequant.  Only the token rows listed in row_sel (n_sel of them,

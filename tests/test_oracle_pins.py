@@ -608,3 +608,38 @@ def test_quantize4_round_trip_and_ranking(oracle):
         assert np.all(np.abs(What - W) <= bound), kind
         err[kind] = np.abs(What - W).mean()
     assert err["nf4"] < min(err["fp4_e2m1"], err["fp4_e3m0"], err["int4"]), err
+
+
+# ----------------------------------------------------------------------------- without Double Quantization
+
+def test_without_double_quantization(oracle):
+    """Section 3: fp32 constants at blocksize 64 cost 32/64 = 0.5 bit per parameter, Double Quantization brings that
+    to 0.127.  Without it the weights are nf4[idx] * c2 rounded to bf16 (checked against numpy's fp32 product and the
+    library bf16 cast), the indices are those of the double-quantised tensor, and the reconstruction can only be
+    closer: the double-quantised constants differ from c2 by at most half an 8-bit step of their run."""
+    import torch
+    rng = np.random.default_rng(14)
+    W = (rng.standard_normal((96, 512)) * 0.02).astype(np.float32)
+    q0 = oracle.nf4_quantize(W, dq_blocksize=0)
+    q1 = oracle.nf4_quantize(W)
+    assert q0["code"] is None and q0["c1"] is None and q0["dq_blocksize"] == 0
+    np.testing.assert_array_equal(q0["packed"], q1["packed"])
+    np.testing.assert_array_equal(q0["c2"], np.abs(W.reshape(-1, 64)).max(axis=1))
+    bits = (4 * q0["packed"].size * 2 + 32 * q0["c2"].size) / W.size
+    assert bits == 4.5
+    idx = np.empty(W.size, np.uint8)
+    idx[0::2], idx[1::2] = q0["packed"] & 15, q0["packed"] >> 4
+    prod = oracle.nf4_table()[idx].reshape(-1, 64) * q0["c2"][:, None]          # numpy fp32 multiply
+    want = torch.from_numpy(prod.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.nf4_dequant(q0)
+    np.testing.assert_array_equal(got.reshape(-1, 64), want)
+    e0 = np.abs(_bf16_f64(got) - W).mean()
+    e1 = np.abs(_bf16_f64(oracle.nf4_dequant(q1)) - W).mean()
+    assert e0 <= e1 * 1.001, (e0, e1)
+    # another data type without Double Quantization
+    t = oracle.codebook4("int4")
+    q2 = oracle.nf4_quantize(W, dq_blocksize=0, table=t)
+    idx[0::2], idx[1::2] = q2["packed"] & 15, q2["packed"] >> 4
+    prod = t[idx].reshape(-1, 64) * q2["c2"][:, None]
+    want = torch.from_numpy(prod.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(oracle.nf4_dequant(q2).reshape(-1, 64), want)
