@@ -268,6 +268,11 @@ def main():
             types[name] = {"mean_abs_err_over_sigma": round(err, 4),
                            "quantize_GBps": round(d * d * 4.5159 / (t * 1e-3) * 1e-9, 1)}
             del Wq_t
+        Wq_t = ql.qlora_nf4_quantize(Wn, dq_blocksize=0)                 # NF4 without Double Quantization: 4.5 bit
+        types["nf4_without_dq"] = {
+            "mean_abs_err_over_sigma": round((ql.qlora_nf4_dequant(Wq_t).float() - Wn).abs().mean().item() / synth.SIGMA_W, 4),
+            "bits_per_param": Wq_t.nbytes * 8 / (d * d)}
+        del Wq_t
         del Wn
         extra["data_types"] = types
         # the training-loop variants of the same step (same pool, same shapes): LoRA dropout at the rate the paper

@@ -46,7 +46,7 @@ enum {
   QLORA_OK = 0,
   QLORA_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   QLORA_ERR_SHAPE = -2,       /* non-positive size, cols not a multiple of blocksize, ...    */
-  QLORA_ERR_UNSUPPORTED = -3, /* blocksize != 64, dq_blocksize != 256, r not supported, ...  */
+  QLORA_ERR_UNSUPPORTED = -3, /* blocksize != 64, dq_blocksize not 256 or 0, r not supported, ... */
   QLORA_ERR_WORKSPACE = -4,   /* workspace / scratch smaller than the *_sizes call reports   */
   QLORA_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                            */
   QLORA_ERR_HIP = -6          /* a kernel launch failed; see qlora_last_hip_error()          */
@@ -80,6 +80,13 @@ int qlora_last_hip_error(void);
  *             b = row*bpr + blk uses c1[b / dq_blocksize].
  *   c2_mean : one fp32, the mean that was subtracted from c2 (per tensor).
  * cols must be a multiple of blocksize, so a block never straddles two rows.
+ *
+ * Without Double Quantization (dq_blocksize = 0; Section 3 prices the fp32 constants at 32/64 = 0.5 bit per
+ * parameter, 4.5 bit in all): `c1` holds the n fp32 first-level constants c2 themselves, in flattened block order,
+ * and c2_code / c2_mean are not read (may be NULL).  Such a weight is accepted by quantise, dequantise and the
+ * linear-layer calls, which then take the large-GEMM path at any M -- the few-token streaming kernels read
+ * double-quantised constants; size the workspaces with qlora_linear_dropout_sizes -- and refused with
+ * QLORA_ERR_UNSUPPORTED by qlora_linear_fwd_multi at M <= 16.
  */
 typedef struct {
   const uint8_t* packed;
@@ -109,7 +116,8 @@ qlora_status qlora_codebook_4bit(int32_t dtype, float* values16);
 
 /* Byte sizes of the buffers of a quantised rows x cols tensor and of the scratch
  * qlora_nf4_quantize needs.  Any out-pointer may be NULL.
- * 4 + 8/64 + 32/(64*256) = 4.127 bits per parameter (Section 3). */
+ * 4 + 8/64 + 32/(64*256) = 4.127 bits per parameter (Section 3); with dq_blocksize = 0
+ * (no Double Quantization) code_bytes is 0 and c1_bytes = 4 * rows*cols/blocksize: 4.5 bits. */
 qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
                              size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
                              size_t* scratch_bytes);
@@ -124,6 +132,8 @@ qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int3
  * of (c2 - mean) * fl32(448 / c1).
  * W must be finite: an Inf or NaN is not detected and gives unspecified codes and
  * constants for the tensor (all accesses stay in bounds).
+ * dq_blocksize = 0 stops after the first step: c1 receives the n constants c2, and
+ * c2_code / c2_mean (may be NULL) are not written.
  * scratch: device buffer of at least the size qlora_nf4_sizes reports. */
 qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
                                 int32_t blocksize, int32_t dq_blocksize,

@@ -107,12 +107,14 @@ class NF4Weight:
         self.dtype = int(dtype)                               # NF4 = 0, or FP4_E2M1 / FP4_E3M0 / INT4
 
     def view(self) -> qlora_nf4_view:
-        return qlora_nf4_view(self.packed.data_ptr(), self.code.data_ptr(), self.c1.data_ptr(),
-                              self.mean.data_ptr(), self.rows, self.cols, self.blocksize, self.dq_blocksize,
-                              self.dtype, 0)
+        ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+        return qlora_nf4_view(ptr(self.packed), ptr(self.code), ptr(self.c1), ptr(self.mean), self.rows, self.cols,
+                              self.blocksize, self.dq_blocksize, self.dtype, 0)
 
     @property
     def nbytes(self) -> int:
+        if self.dq_blocksize == 0:                            # no Double Quantization: c1 holds the fp32 constants c2
+            return self.packed.numel() + 4 * self.c1.numel()
         return self.packed.numel() + self.code.numel() + 4 * self.c1.numel() + 4
 
     def code_flat(self):
@@ -207,6 +209,15 @@ def qlora_linear_bwd_sizes(M, h, o, r) -> int:
 WORKSPACE_HEADER_BYTES = 16384
 
 
+def _fwd_bytes(Wq, M, h, o, r):
+    """Workspace of a forward call: a weight without Double Quantization always takes the large-GEMM path."""
+    return qlora_linear_fwd_sizes(M, h, o, r) if Wq.dq_blocksize else qlora_linear_dropout_sizes(M, h, o, r)[0]
+
+
+def _bwd_bytes(Wq, M, h, o, r):
+    return qlora_linear_bwd_sizes(M, h, o, r) if Wq.dq_blocksize else qlora_linear_dropout_sizes(M, h, o, r)[1]
+
+
 def qlora_workspace_init(workspace, stream=None):
     """Zeroes the counter header of a workspace buffer: once per buffer, before its first use."""
     _check(lib().qlora_workspace_init(_ptr(workspace), workspace.numel(), _stream(stream)))
@@ -228,7 +239,7 @@ def qlora_linear_fwd(X, Wq: NF4Weight, L1, L2, s, Y=None, T_save=None, workspace
     if Y is None:
         Y = torch.empty((M, o), dtype=torch.bfloat16, device=X.device)
     if workspace is None:
-        workspace = workspace_alloc(qlora_linear_fwd_sizes(M, h, o, r), X.device, stream)
+        workspace = workspace_alloc(_fwd_bytes(Wq, M, h, o, r), X.device, stream)
     v = Wq.view()
     _check(lib().qlora_linear_fwd(_ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(Y), _ptr(T_save),
                                   _ptr(workspace), workspace.numel(), _stream(stream)))
@@ -278,7 +289,7 @@ def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1
         if dL2 is None:
             dL2 = torch.empty((r, o), dtype=torch.bfloat16, device=dev)
     if workspace is None:
-        workspace = workspace_alloc(qlora_linear_bwd_sizes(M, h, o, r), dev, stream)
+        workspace = workspace_alloc(_bwd_bytes(Wq, M, h, o, r), dev, stream)
     v = Wq.view()
     _check(lib().qlora_linear_bwd(_ptr(dY), _ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(T_saved),
                                   _ptr(dX), _ptr(dL1), _ptr(dL2), _ptr(workspace), workspace.numel(),
@@ -298,7 +309,7 @@ def qlora_linear_bwd_acc(dY, X, Wq: NF4Weight, L1, L2, s, dL1_acc, dL2_acc, T_sa
     for a in (dL1_acc, dL2_acc):
         assert a is None or (a.dtype == torch.float32 and a.is_contiguous())
     if workspace is None:
-        workspace = workspace_alloc(qlora_linear_bwd_sizes(M, h, o, r), dev, stream)
+        workspace = workspace_alloc(_bwd_bytes(Wq, M, h, o, r), dev, stream)
     v = Wq.view()
     _check(lib().qlora_linear_bwd_acc(_ptr(dY), _ptr(X), byref(v), _ptr(L1), _ptr(L2), float(s), M, r, _ptr(T_saved),
                                       _ptr(dX), _ptr(dL1_acc), _ptr(dL2_acc), _ptr(workspace), workspace.numel(),

@@ -25,22 +25,27 @@ __device__ __forceinline__ void init_lut16(float* lut, int dtype, const Table4& 
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr,
-    const int dtype, const Table4 tab) {
+    const int dtype, const Table4 tab, const bool dq) {
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
   unit[threadIdx.x] = e4m3_unit(threadIdx.x);               // 256 threads, 256 codes
   __syncthreads();
-  const float mean = *mean_ptr;
+  const float mean = dq ? *mean_ptr : 0.0f;
 
   const int64_t stride = (int64_t)gridDim.x * kDeqThreads;
   for (int64_t d = (int64_t)blockIdx.x * kDeqThreads + threadIdx.x; d < n_dwords; d += stride) {
     const uint32_t p = packed[d];
     const uint32_t blk = (uint32_t)(d >> 3);                // 8 dwords per 64-block
-    const uint32_t row = blk / bpr;
-    const uint8_t cd = code[code_pos(rows, (int)bpr, row, (int)(blk - row * bpr))];
-    // dequant(c1, c2): two separately rounded fp32 steps
-    const float c2 = __fadd_rn(__fmul_rn(unit[cd], c1[blk >> 8]), mean);
+    float c2;
+    if (dq) {
+      const uint32_t row = blk / bpr;
+      const uint8_t cd = code[code_pos(rows, (int)bpr, row, (int)(blk - row * bpr))];
+      // dequant(c1, c2): two separately rounded fp32 steps
+      c2 = __fadd_rn(__fmul_rn(unit[cd], c1[blk >> 8]), mean);
+    } else {
+      c2 = c1[blk];                                           // no Double Quantization: the fp32 constant itself
+    }
     uint4 o;
     o.x = pack_bf16x2(__fmul_rn(lut[p & 15u], c2), __fmul_rn(lut[(p >> 4) & 15u], c2));
     o.y = pack_bf16x2(__fmul_rn(lut[(p >> 8) & 15u], c2), __fmul_rn(lut[(p >> 12) & 15u], c2));
@@ -58,13 +63,13 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out, const int dtype,
-    const Table4 tab) {
+    const Table4 tab, const bool dq) {
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
   unit[threadIdx.x] = e4m3_unit(threadIdx.x);
   __syncthreads();
-  const float mean = *mean_ptr;
+  const float mean = dq ? *mean_ptr : 0.0f;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int kg = lane >> 3, ng = lane & 7;
@@ -81,7 +86,8 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const bool ok = k < h;
     const int64_t blk = (int64_t)(ok ? k : 0) * blocks_per_row + n_blk;
     p[j] = ok ? packed[blk * 8 + ng] : 0x77777777u;         // index 7 is the exact zero
-    c2[j] = ok ? __fadd_rn(__fmul_rn(unit[code[code_pos(h, blocks_per_row, k, n_blk)]], c1[blk >> 8]), mean) : 0.0f;
+    if (dq) c2[j] = ok ? __fadd_rn(__fmul_rn(unit[code[code_pos(h, blocks_per_row, k, n_blk)]], c1[blk >> 8]), mean) : 0.0f;
+    else c2[j] = ok ? c1[blk] : 0.0f;
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -102,7 +108,7 @@ hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipS
   const int h = (int)w.rows, o = (int)w.cols;
   dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64));
   hipLaunchKernelGGL(dequant_nf4_t_kernel, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
-                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype));
+                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype), w.dq);
   return hipGetLastError();
 }
 
@@ -113,7 +119,7 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(dequant_nf4_kernel, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
                      (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
-                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype));
+                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype), w.dq);
   return hipGetLastError();
 }
 

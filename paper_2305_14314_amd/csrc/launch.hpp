@@ -15,12 +15,14 @@ struct NF4Dev {            // device views of one quantised h x o weight
   const float* mean;
   int64_t rows, cols;      // h, o
   int dtype;               // 0 NF4; 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4 (the data types of the paper's comparison)
+  bool dq;                 // Double Quantization; false: `c1` holds the rows * cols / 64 fp32 constants c2, code and mean unused
 };
 
 // quantize.hip
 constexpr size_t kQuantBinsBytes = 256 * sizeof(unsigned long long);
+//   dq = false: no Double Quantization; the fp32 constants c2 go to `c1` (rows * cols / 64 floats), code and mean untouched.
 hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
-                           float* mean, void* scratch, hipStream_t st, int dtype = 0);
+                           float* mean, void* scratch, hipStream_t st, int dtype = 0, bool dq = true);
 
 // dequant.hip
 hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);

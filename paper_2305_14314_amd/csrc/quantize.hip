@@ -182,13 +182,14 @@ __global__ __launch_bounds__(kDqBlock) void dq_encode_kernel(const float* __rest
 }
 
 hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
-                           float* mean, void* scratch, hipStream_t st, int dtype) {
+                           float* mean, void* scratch, hipStream_t st, int dtype, bool dq) {
   if (dtype < 0 || dtype >= kNumTypes4) return hipErrorInvalidValue;
   const Thresholds4 thr = thresholds4_host(table4_host(dtype));
   const int64_t elems = rows * cols;
   const int64_t n = elems / kBlock;
   unsigned long long* bins = (unsigned long long*)scratch;           // 256 x u64
-  float* c2 = (float*)((char*)scratch + 256 * sizeof(unsigned long long));
+  // without Double Quantization the first-level constants are the result and go straight to the caller's buffer
+  float* c2 = dq ? (float*)((char*)scratch + 256 * sizeof(unsigned long long)) : c1;
   const int64_t n_vec4 = elems / 4;
   int64_t blocks = (n_vec4 + kQThreads - 1) / kQThreads;
   const int64_t cap = 256 * 16;                                      // 16 workgroups per CU
@@ -200,6 +201,7 @@ hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* 
   else
     hipLaunchKernelGGL(quantize_nf4_kernel<true>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
                        n_vec4, (uint16_t*)packed, c2, bins, thr);
+  if (!dq) return hipGetLastError();
   hipLaunchKernelGGL(dq_mean_kernel, dim3(1), dim3(64), 0, st, bins, (uint32_t)n, mean);
   const int64_t n1 = (n + kDqBlock - 1) / kDqBlock;
   hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)n1), dim3(kDqBlock), 0, st, c2, n, mean, code, c1,

@@ -184,6 +184,23 @@ def test_data_type_tables_and_their_validation(L, oracle):
     assert v.dtype == 0
 
 
+def test_sizes_without_double_quantization(L):
+    """dq_blocksize = 0: no code bytes, one fp32 constant per block (4.5 bit per parameter, Section 3), and a view
+    needs only its packed indices and constants."""
+    from paper_2305_14314_amd import qlora_nf4_sizes
+    from paper_2305_14314_amd.binding import qlora_nf4_view
+    pb, cb, c1b, sb = qlora_nf4_sizes(8192, 8192, 64, 0)
+    P = 8192 * 8192
+    assert (pb, cb, c1b) == (P // 2, 0, 4 * P // 64) and (pb + cb + c1b) * 8 / P == 4.5
+    fake = ctypes.c_void_p(0x1000)
+    v = qlora_nf4_view(0x1000, None, 0x1000, None, 128, 128, 64, 0)
+    assert L.qlora_nf4_dequant(ctypes.byref(v), None, None) == -1            # the view passes, the output is missing
+    v = qlora_nf4_view(0x1000, None, None, None, 128, 128, 64, 0)
+    assert L.qlora_nf4_dequant(ctypes.byref(v), fake, None) == -1            # the constants are still required
+    # no code / mean buffers needed: the call gets past the NULL checks and stops at the (deliberately) small scratch
+    assert L.qlora_nf4_quantize(fake, 4, 64, 64, 0, fake, None, fake, None, fake, 8, None) == -4
+
+
 def test_constant_storage_order_is_a_permutation_that_keeps_groups_together():
     """The 8-bit constants are stored column-group-major (include/qlora.h).  The index map used by the parity
     tests and the one the binding offers agree, are permutations, and put the <= 4 constants of one row and one

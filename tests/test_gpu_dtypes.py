@@ -82,3 +82,40 @@ def test_linear_other_types(oracle, synth, kind, dtype, M, h, o, r):
     ref = oracle.linear_fwd(hX, What, None, None, s)
     got = (host_bits(Ynf4).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
     assert np.abs(got - ref).max() > 10 * 2e-2 * np.sqrt((ref ** 2).mean())
+
+
+@pytest.mark.parametrize("kind,dtype", [("nf4", 0), ("int4", 3)])
+def test_without_double_quantization(oracle, synth, kind, dtype):
+    """dq_blocksize = 0: the fp32 constants are kept (4.5 bit per parameter).  Quantise and dequantise bit-exact; the
+    linear layer at 300 and at 5 tokens (the latter through the large-GEMM path: the streaming kernels read
+    double-quantised constants) against the oracle; the several-layers forward refuses such a weight at few tokens."""
+    import paper_2305_14314_amd as ql
+    table = oracle.codebook4(kind)
+    h, o, r, s = 448, 576, 32, 0.5
+    W = synth.normal_f32((h, o), synth.SIGMA_W, 9200)
+    q = oracle.nf4_quantize(W, dq_blocksize=0, table=table)
+    Wq = ql.qlora_nf4_quantize(dev_f32(W), dq_blocksize=0, dtype=dtype)
+    torch.cuda.synchronize()
+    assert Wq.dq_blocksize == 0 and Wq.code.numel() == 0 and Wq.nbytes * 8 / (h * o) == 4.5
+    np.testing.assert_array_equal(host_u8(Wq.packed), q["packed"])
+    np.testing.assert_array_equal(host_u32(Wq.c1), q["c2"].view(np.uint32))
+    What = oracle.nf4_dequant(q)
+    np.testing.assert_array_equal(host_bits(ql.qlora_nf4_dequant(Wq)), What)
+    hL1, hL2 = synth.normal_bf16((h, r), 0.05, 9201), synth.normal_bf16((r, o), 0.05, 9202)
+    L1, L2 = dev_bf16(hL1), dev_bf16(hL2)
+    for M in (300, 5):
+        print(f"case no-DQ {kind} M={M}", flush=True)
+        hX, hdY = synth.normal_bf16((M, h), 1.0, 9203 + M), synth.normal_bf16((M, o), 1.0, 9204 + M)
+        X, dY = dev_bf16(hX), dev_bf16(hdY)
+        Y = ql.qlora_linear_fwd(X, Wq, L1, L2, s)
+        dX, dL1, dL2 = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s)
+        torch.cuda.synchronize()
+        _check(host_bits(Y), oracle.linear_fwd(hX, What, hL1, hL2, s), f"no-DQ {kind} M={M} Y")
+        _check(host_bits(dX), oracle.linear_bwd_dx(hdY, What, hL1, hL2, s), f"no-DQ {kind} M={M} dX")
+        r1, r2 = oracle.linear_bwd_dl(hdY, hX, hL1, hL2, s)
+        _check(host_bits(dL1), r1, "dL1", few_terms=M < 64)
+        _check(host_bits(dL2), r2, "dL2", few_terms=M < 64)
+    ws = ql.workspace_alloc(ql.qlora_linear_dropout_sizes(5, h, o, r)[0])
+    with pytest.raises(ql.QloraError) as e:
+        ql.qlora_linear_fwd_multi(X, [Wq], [L1], [L2], [s], workspace=ws)
+    assert e.value.status == -3
