@@ -22,10 +22,12 @@ __device__ __forceinline__ void init_lut16(float* lut, int dtype, const Table4& 
   }
 }
 
+template <bool DQ>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr,
-    const int dtype, const Table4 tab, const bool dq) {
+    const int dtype, const Table4 tab) {
+  constexpr bool dq = DQ;                                    // Double Quantization, or the fp32 constants as they are
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
@@ -60,10 +62,12 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 // 64-block per row.  A lane loads one packed dword (8 n) from each of 8 consecutive rows and
 // writes, for each of its 8 columns, the 8 k-consecutive bf16 as one 16-byte store, so stores
 // form 128-byte runs along k.  No LDS staging of data.
+template <bool DQ>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out, const int dtype,
-    const Table4 tab, const bool dq) {
+    const Table4 tab) {
+  constexpr bool dq = DQ;
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
@@ -107,8 +111,12 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
 hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st) {
   const int h = (int)w.rows, o = (int)w.cols;
   dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64));
-  hipLaunchKernelGGL(dequant_nf4_t_kernel, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
-                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype), w.dq);
+  if (w.dq)
+    hipLaunchKernelGGL(dequant_nf4_t_kernel<true>, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
+                       w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype));
+  else
+    hipLaunchKernelGGL(dequant_nf4_t_kernel<false>, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
+                       w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype));
   return hipGetLastError();
 }
 
@@ -117,9 +125,14 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
   int64_t blocks = (n_dwords + kDeqThreads - 1) / kDeqThreads;
   const int64_t cap = 256 * 32;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(dequant_nf4_kernel, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
-                     (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
-                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype), w.dq);
+  if (w.dq)
+    hipLaunchKernelGGL(dequant_nf4_kernel<true>, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
+                       (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
+                       (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype));
+  else
+    hipLaunchKernelGGL(dequant_nf4_kernel<false>, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
+                       (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
+                       (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype));
   return hipGetLastError();
 }
 
