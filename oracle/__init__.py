@@ -62,6 +62,9 @@ def _load():
     L.oracle_quantize4.argtypes = [vp] + list(L.oracle_nf4_quantize.argtypes)
     L.oracle_dequant4.argtypes = [vp] + list(L.oracle_nf4_dequant.argtypes)
     L.oracle_dequant4_nodq.argtypes = [vp, vp, vp, c_int64, c_int64, c_int32, vp]
+    L.oracle_quantize_int8.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp]
+    L.oracle_dequant_int8.argtypes = [vp, vp, c_int64, c_int64, c_int32, vp]
+    L.oracle_dq_constants.argtypes = [vp, vp, c_float, c_int64, c_int32, vp]
     lin = [vp, vp, vp, vp, c_double, c_int64, c_int64, c_int64, c_int64, vp, c_int64, vp]
     for name in ("oracle_linear_fwd_cols", "oracle_linear_bwd_dx_cols"):
         getattr(L, name).argtypes = lin
@@ -192,6 +195,43 @@ def nf4_dequant(q, return_c2hat: bool = False):
     else:
         _check(_load().oracle_dequant4(_p(_arr(q["table"], np.float32, (16,))), *args), "dequant4")
     return (out, c2hat) if return_c2hat else out
+
+
+def int8_quantize(W, blocksize: int = 64, dq_blocksize: int = 256):
+    """Eq. 1: blockwise 8-bit integers.  Returns dict(q8 i8[P], code, c1, mean (None without Double Quantization),
+    c2 f32[n], ...)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    rows, cols = W.shape
+    P = rows * cols
+    if blocksize <= 0 or dq_blocksize < 0 or P % blocksize:
+        raise ValueError("oracle int8_quantize: bad shape / blocksize")
+    n = P // blocksize
+    q8 = np.empty(P, np.int8)
+    c2 = np.empty(n, np.float32)
+    dq = dq_blocksize != 0
+    code = np.empty(n, np.uint8) if dq else None
+    c1 = np.empty(-(-n // dq_blocksize), np.float32) if dq else None
+    mean = np.empty(1, np.float32) if dq else None
+    _check(_load().oracle_quantize_int8(_p(W), rows, cols, blocksize, dq_blocksize, _p(q8), _p(code), _p(c1),
+                                        _p(mean), _p(c2)), "int8_quantize")
+    return dict(q8=q8, code=code, c1=c1, mean=None if mean is None else np.float32(mean[0]), c2=c2, rows=rows,
+                cols=cols, blocksize=blocksize, dq_blocksize=dq_blocksize)
+
+
+def int8_dequant(q):
+    """Eq. 2 on the result of int8_quantize.  Returns bf16 bit patterns u16[rows, cols]."""
+    rows, cols = q["rows"], q["cols"]
+    n = rows * cols // q["blocksize"]
+    if q["dq_blocksize"] == 0:
+        c2hat = _arr(q["c2"], np.float32)
+    else:
+        c2hat = np.empty(n, np.float32)
+        _check(_load().oracle_dq_constants(_p(_arr(q["code"], np.uint8)), _p(_arr(q["c1"], np.float32)),
+                                           np.float32(q["mean"]), n, q["dq_blocksize"], _p(c2hat)), "dq_constants")
+    out = np.empty((rows, cols), np.uint16)
+    _check(_load().oracle_dequant_int8(_p(_arr(q["q8"], np.int8)), _p(c2hat), rows, cols, q["blocksize"], _p(out)),
+           "int8_dequant")
+    return out
 
 
 def _lin_args(A, What, L1, L2, M, h, o):

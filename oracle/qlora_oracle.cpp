@@ -323,6 +323,87 @@ static int dequant4(const float* table, const uint8_t* packed, const uint8_t* co
   return 0;
 }
 
+/* ---- 8-bit integers: Eq. 1 and Eq. 2 as printed ------------------------------
+ * Eq. 1:  X^Int8 = round(127 / absmax(X) * X) = round(c * X), per block of `blocksize` elements, with
+ *         c = fl32(127 / absmax) (0 for an all-zero or subnormal block, or when the quotient overflows) and
+ *         round = to nearest, ties to even, of the fp32 product fl32(c * x); the result lies in [-127, 127].
+ * The constants absmax then go through Double Quantization exactly as for the 4-bit types (dq_blocksize = 0:
+ * they are kept as fp32).
+ * Eq. 2:  dequant(c, X^Int8) = X^Int8 / c = X^Int8 * absmax / 127, evaluated as
+ *         w = bf16_rne(fl32(q * fl32(c2hat / 127))),  c2hat the (de-double-quantised) absmax of the block. */
+static void dq_constants(const std::vector<float>& c2, int64_t n, int32_t dq_blocksize, uint8_t* code, float* c1,
+                         float* mean) {
+  const float mu = exact_mean_f32(c2.data(), n);
+  *mean = mu;
+  const int64_t n1 = (n + dq_blocksize - 1) / dq_blocksize;
+  for (int64_t B = 0; B < n1; ++B) {
+    const int64_t lo = B * dq_blocksize;
+    const int64_t hi = (lo + dq_blocksize < n) ? lo + dq_blocksize : n;
+    float amax = 0.0f;
+    for (int64_t b = lo; b < hi; ++b) amax = std::fmax(amax, std::fabs(fl32_sub(c2[(size_t)b], mu)));
+    c1[B] = amax;
+    float rc1 = (amax < FLT_MIN) ? 0.0f : fl32_div(448.0f, amax);
+    if (!std::isfinite(rc1)) rc1 = 0.0f;
+    for (int64_t b = lo; b < hi; ++b)
+      code[b] = oracle_e4m3_encode(fl32_mul(fl32_sub(c2[(size_t)b], mu), rc1));
+  }
+}
+
+int oracle_quantize_int8(const float* W, int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
+                         int8_t* q8, uint8_t* code, float* c1, float* mean, float* c2_out) {
+  if (!W || !q8 || !c2_out) return -1;
+  if (dq_blocksize != 0 && (!code || !c1 || !mean)) return -1;
+  if (rows <= 0 || cols <= 0 || blocksize <= 0 || dq_blocksize < 0) return -2;
+  const int64_t P = rows * cols;
+  if (P % blocksize != 0) return -2;
+  const int64_t n = P / blocksize;
+  for (int64_t i = 0; i < P; ++i) if (!std::isfinite(W[i])) return -3;
+  std::vector<float> c2((size_t)n);
+#pragma omp parallel for schedule(static)
+  for (int64_t b = 0; b < n; ++b) {
+    const float* w = W + b * blocksize;
+    float amax = 0.0f;
+    for (int i = 0; i < blocksize; ++i) amax = std::fmax(amax, std::fabs(w[i]));
+    c2[(size_t)b] = amax;
+    float c = (amax < FLT_MIN) ? 0.0f : fl32_div(127.0f, amax);
+    if (!std::isfinite(c)) c = 0.0f;
+    for (int i = 0; i < blocksize; ++i) {
+      double v = std::nearbyint((double)fl32_mul(c, w[i]));    /* default rounding mode: ties to even */
+      if (v > 127.0) v = 127.0;
+      if (v < -127.0) v = -127.0;
+      q8[b * blocksize + i] = (int8_t)v;
+    }
+  }
+  std::memcpy(c2_out, c2.data(), (size_t)n * sizeof(float));
+  if (dq_blocksize != 0) dq_constants(c2, n, dq_blocksize, code, c1, mean);
+  return 0;
+}
+
+/* c2hat: the n reconstructed constants (oracle_nf4_dequant's c2hat_out, or c2 itself without Double Quantization) */
+int oracle_dequant_int8(const int8_t* q8, const float* c2hat, int64_t rows, int64_t cols, int32_t blocksize,
+                        uint16_t* W_bf16) {
+  if (!q8 || !c2hat || !W_bf16) return -1;
+  if (rows <= 0 || cols <= 0 || blocksize <= 0) return -2;
+  const int64_t P = rows * cols;
+  if (P % blocksize != 0) return -2;
+#pragma omp parallel for schedule(static)
+  for (int64_t e = 0; e < P; ++e) {
+    const float step = fl32_div(c2hat[e / blocksize], 127.0f);
+    W_bf16[e] = oracle_bf16_rne(fl32_mul((float)q8[e], step));
+  }
+  return 0;
+}
+
+/* the reconstructed constants alone: c2hat[b] = fl32(fl32(unit(code[b]) * c1[b / dq_blocksize]) + mean) */
+int oracle_dq_constants(const uint8_t* code, const float* c1, float mean, int64_t n, int32_t dq_blocksize,
+                        float* c2hat) {
+  if (!code || !c1 || !c2hat) return -1;
+  if (n <= 0 || dq_blocksize <= 0) return -2;
+  for (int64_t b = 0; b < n; ++b)
+    c2hat[b] = fl32_add(fl32_mul(oracle_e4m3_unit(code[b]), c1[b / dq_blocksize]), mean);
+  return 0;
+}
+
 /* Without Double Quantization (Section 3: the constants then cost 32/64 = 0.5 bit per parameter): the fp32
  * constants c2 are used as they are, w_i = bf16_rne(fl32(table[idx_i] * c2[i / blocksize])). */
 int oracle_dequant4_nodq(const float* table, const uint8_t* packed, const float* c2,

@@ -117,6 +117,19 @@ int oracle_dequant4(const float* table, const uint8_t* packed, const uint8_t* co
                     int32_t blocksize, int32_t dq_blocksize,
                     uint16_t* W_bf16, float* c2hat_out);
 
+/* 8-bit integers, Eq. 1 and Eq. 2 as printed (the paper's example of blockwise quantisation and its Int8 baseline):
+ *   q = clamp(round_to_nearest_even(fl32(c * x)), -127, 127),  c = fl32(127 / absmax(block))  (0 if that is not a
+ *   finite positive number);  the constants absmax are double-quantised like those of the 4-bit types
+ *   (dq_blocksize = 0: kept, code / c1 / mean may be NULL);  c2_out (n fp32) receives them in any case.
+ *   w = bf16_rne(fl32(q * fl32(c2hat / 127))).
+ * oracle_dq_constants reconstructs c2hat from the double-quantised constants. */
+int oracle_quantize_int8(const float* W, int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
+                         int8_t* q8, uint8_t* code, float* c1, float* mean, float* c2_out);
+int oracle_dequant_int8(const int8_t* q8, const float* c2hat, int64_t rows, int64_t cols, int32_t blocksize,
+                        uint16_t* W_bf16);
+int oracle_dq_constants(const uint8_t* code, const float* c1, float mean, int64_t n, int32_t dq_blocksize,
+                        float* c2hat);
+
 /* doubleDequant's second step alone, for weights stored WITHOUT Double Quantization (Section 3 prices the fp32
  * constants at 0.5 bit per parameter; Double Quantization is what brings them to 0.127):
  *   w_i = bf16_rne(fl32(table[idx_i] * c2[i / blocksize])),  c2 the fp32 absmax constants of oracle_quantize4

@@ -643,3 +643,51 @@ def test_without_double_quantization(oracle):
     prod = t[idx].reshape(-1, 64) * q2["c2"][:, None]
     want = torch.from_numpy(prod.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     np.testing.assert_array_equal(oracle.nf4_dequant(q2).reshape(-1, 64), want)
+
+
+# ----------------------------------------------------------------------------- 8-bit integers (Eq. 1, Eq. 2)
+
+def test_int8_is_equation_1_and_2(oracle):
+    """Eq. 1 / Eq. 2 with numpy: q = rint(127 / absmax * x) per block (numpy's rint rounds ties to even), the range is
+    [-127, 127] with absmax hitting +-127, zeros stay zero, the round trip is within half a step, the constants go
+    through the same Double Quantization as the 4-bit types', and without it the reconstruction is q * absmax / 127."""
+    import torch
+    rng = np.random.default_rng(15)
+    W = (rng.standard_normal((64, 512)) * 0.02).astype(np.float32)
+    W.reshape(-1)[:64] = 0.0                                              # an all-zero block
+    q = oracle.int8_quantize(W, dq_blocksize=0)
+    Wb = W.reshape(-1, 64)
+    c2 = np.abs(Wb).max(axis=1)
+    np.testing.assert_array_equal(q["c2"], c2)
+    with np.errstate(divide="ignore"):
+        c = np.where(c2 > 0, np.float32(127) / c2, np.float32(0)).astype(np.float32)
+    want = np.rint((c[:, None] * Wb).astype(np.float32)).clip(-127, 127).astype(np.int8)
+    np.testing.assert_array_equal(q["q8"].reshape(-1, 64), want)
+    assert q["q8"].min() == -127 and q["q8"].max() == 127 and np.all(q["q8"][:64] == 0)
+    assert np.all(np.abs(q["q8"].reshape(-1, 64)).max(axis=1)[1:] == 127)
+    got = _bf16_f64(oracle.int8_dequant(q)).reshape(-1, 64)
+    step = (c2 / np.float32(127)).astype(np.float32)
+    ref = torch.from_numpy((q["q8"].reshape(-1, 64).astype(np.float32) * step[:, None]).astype(np.float32))
+    np.testing.assert_array_equal(oracle.int8_dequant(q).reshape(-1, 64),
+                                  ref.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    assert np.all(np.abs(got - Wb) <= 0.5 * step[:, None].astype(np.float64) * (1 + 2.0 ** -20) + 2.0 ** -8 * np.abs(got) + 1e-12)  # half a step + half a bf16 ulp
+    # with Double Quantization the constants are those of the NF4 path on the same tensor
+    qd = oracle.int8_quantize(W)
+    qn = oracle.nf4_quantize(W)
+    for k in ("code", "c1", "c2"):
+        np.testing.assert_array_equal(qd[k], qn[k])
+    assert np.float32(qd["mean"]).view(np.uint32) == np.float32(qn["mean"]).view(np.uint32)
+    np.testing.assert_array_equal(qd["q8"], q["q8"])
+    e_dq = np.abs(_bf16_f64(oracle.int8_dequant(qd)) - W).mean()
+    e_nf4 = np.abs(_bf16_f64(oracle.nf4_dequant(qn)) - W).mean()
+    assert e_dq < 0.2 * e_nf4                                            # 8 bits against 4
+
+
+def test_int8_ties_and_clamp(oracle):
+    """A block whose absmax is 127 has c = 1, so the codes are the inputs rounded: halves go to the even neighbour,
+    and the sign is kept."""
+    w = np.zeros((1, 64), np.float32)
+    w[0, :9] = [127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, -126.5]
+    q = oracle.int8_quantize(w, dq_blocksize=0)
+    assert list(q["q8"][:9]) == [127, 0, 2, 2, 0, -2, -2, 126, -126]
+    np.testing.assert_array_equal(_bf16_f64(oracle.int8_dequant(q))[0, :4], [127.0, 0.0, 2.0, 2.0])
