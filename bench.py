@@ -273,6 +273,16 @@ def main():
             "mean_abs_err_over_sigma": round((ql.qlora_nf4_dequant(Wq_t).float() - Wn).abs().mean().item() / synth.SIGMA_W, 4),
             "bits_per_param": Wq_t.nbytes * 8 / (d * d)}
         del Wq_t
+        Wq_t = ql.qlora_quantize_int8(Wn)                                # Eq. 1 / Eq. 2 as printed: 8-bit integers
+        t = _time_ms(torch, lambda: ql.qlora_quantize_int8(Wn, out=Wq_t), 5, warmup=1)
+        Wd_t = torch.empty((d, d), dtype=torch.bfloat16, device=dev)
+        t2 = _time_ms(torch, lambda: ql.qlora_nf4_dequant(Wq_t, out=Wd_t), 5, warmup=1)
+        types["int8"] = {
+            "mean_abs_err_over_sigma": round((ql.qlora_nf4_dequant(Wq_t).float() - Wn).abs().mean().item() / synth.SIGMA_W, 5),
+            "bits_per_param": round(Wq_t.nbytes * 8 / (d * d), 4),
+            "quantize_GBps": round(d * d * (4 + 1.0159) / (t * 1e-3) * 1e-9, 1),
+            "dequant_GBps": round(d * d * (1.0159 + 2) / (t2 * 1e-3) * 1e-9, 1)}
+        del Wq_t, Wd_t
         del Wn
         extra["data_types"] = types
         # the training-loop variants of the same step (same pool, same shapes): LoRA dropout at the rate the paper

@@ -87,6 +87,10 @@ int qlora_last_hip_error(void);
  * linear-layer calls, which then take the large-GEMM path at any M -- the few-token streaming kernels read
  * double-quantised constants; size the workspaces with qlora_linear_dropout_sizes -- and refused with
  * QLORA_ERR_UNSUPPORTED by qlora_linear_fwd_multi at M <= 16.
+ *
+ * 8-bit integers (dtype = QLORA_INT8; Eq. 1 and Eq. 2 as printed): `packed` holds one signed byte per weight,
+ * rows*cols bytes in flattened order, the constants are stored as above (with or without Double Quantization).
+ * Accepted and refused exactly like a weight without Double Quantization: large-GEMM path at any M.
  */
 typedef struct {
   const uint8_t* packed;
@@ -97,7 +101,7 @@ typedef struct {
   int64_t cols;          /* o, out-features */
   int32_t blocksize;     /* 64  */
   int32_t dq_blocksize;  /* 256 */
-  int32_t dtype;         /* QLORA_NF4 (0) or one of the other 4-bit data types below */
+  int32_t dtype;         /* QLORA_NF4 (0) or one of the other data types below */
   int32_t reserved;      /* 0 */
 } qlora_nf4_view;
 
@@ -109,9 +113,10 @@ typedef struct {
  * +-{0, 1/64, 1/32, ..., 1/2, 1}, each with two zeros -- and Int4 is Eq. 1 with the range [-7, 7]: j/7, 15 levels
  * (code 15 repeats the top value and is never produced).  Quantisation picks the nearest value, the lower code on an
  * exact tie, as for NF4. */
-enum { QLORA_NF4 = 0, QLORA_FP4_E2M1 = 1, QLORA_FP4_E3M0 = 2, QLORA_INT4 = 3 };
+enum { QLORA_NF4 = 0, QLORA_FP4_E2M1 = 1, QLORA_FP4_E3M0 = 2, QLORA_INT4 = 3, QLORA_INT8 = 4 };
 
-/* The 16 values of a data type, ascending, as fp32 (host array).  QLORA_ERR_UNSUPPORTED for an unknown type. */
+/* The 16 values of a 4-bit data type, ascending, as fp32 (host array).  QLORA_ERR_UNSUPPORTED for an unknown type
+ * and for QLORA_INT8, which has no table. */
 qlora_status qlora_codebook_4bit(int32_t dtype, float* values16);
 
 /* Byte sizes of the buffers of a quantised rows x cols tensor and of the scratch
@@ -121,6 +126,12 @@ qlora_status qlora_codebook_4bit(int32_t dtype, float* values16);
 qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
                              size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
                              size_t* scratch_bytes);
+
+/* The same for any data type of the enum: QLORA_INT8 stores rows*cols bytes in `packed`, everything else is as
+ * for NF4 (the constants do not depend on the data type). */
+qlora_status qlora_quant_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize, int32_t dtype,
+                               size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
+                               size_t* scratch_bytes);
 
 /* Blockwise NF4 quantisation with Double Quantization (Eq. 1; Section 3,
  * "4-bit NormalFloat Quantization" step (3) and "Double Quantization").
@@ -145,6 +156,17 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
 qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
                                  int32_t blocksize, int32_t dq_blocksize, int32_t dtype,
                                  uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
+                                 void* scratch, size_t scratch_bytes, void* hip_stream);
+
+/* Blockwise 8-bit integers, Eq. 1 as printed: per block c2 = absmax, c = fl32(127 / c2) (0 when c2 < FLT_MIN or the
+ * quotient overflows), q8 = round-to-nearest-even(fl32(c * w)) clamped to [-127, 127]; the constants c2 then go through
+ * Double Quantization as in qlora_nf4_quantize (dq_blocksize = 0: kept as fp32 in c1).  q8: rows*cols signed bytes.
+ * Dequantisation (qlora_nf4_dequant and the linear-layer calls on a view with dtype = QLORA_INT8) is Eq. 2:
+ * w = bf16_rne(fl32(q8 * fl32(c2hat / 127))).  scratch: the size qlora_quant_sizes reports.  Not a 4-bit type:
+ * qlora_quantize_4bit refuses QLORA_INT8. */
+qlora_status qlora_quantize_int8(const float* W, int64_t rows, int64_t cols,
+                                 int32_t blocksize, int32_t dq_blocksize,
+                                 int8_t* q8, uint8_t* c2_code, float* c1, float* c2_mean,
                                  void* scratch, size_t scratch_bytes, void* hip_stream);
 
 /* doubleDequant (Eq. 6, Eq. 2): W_bf16[rows x cols] =

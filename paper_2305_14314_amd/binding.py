@@ -21,7 +21,7 @@ EXPORTS = [
     "qlora_linear_bwd", "qlora_linear_bwd_acc", "qlora_linear_fwd_multi_sizes", "qlora_linear_fwd_multi", "qlora_workspace_init",
     "qlora_profile_gemm", "qlora_profile_gemm_read",
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
-    "qlora_codebook_4bit", "qlora_quantize_4bit",
+    "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
 ]
 
 
@@ -57,6 +57,8 @@ def lib():
     L.qlora_nf4_quantize.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
     L.qlora_quantize_4bit.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
     L.qlora_codebook_4bit.argtypes = [c_int32, vp]
+    L.qlora_quant_sizes.argtypes = [c_int64, c_int64, c_int32, c_int32, c_int32, sp, sp, sp, sp]
+    L.qlora_quantize_int8.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
     L.qlora_nf4_dequant.argtypes = [POINTER(qlora_nf4_view), vp, vp]
     L.qlora_linear_fwd_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp]
     L.qlora_linear_bwd_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp]
@@ -104,10 +106,13 @@ class NF4Weight:
         self.rows, self.cols = int(rows), int(cols)
         self.blocksize, self.dq_blocksize = int(blocksize), int(dq_blocksize)
         self.packed, self.code, self.c1, self.mean = packed, code, c1, mean
-        self.dtype = int(dtype)                               # NF4 = 0, or FP4_E2M1 / FP4_E3M0 / INT4
+        self.dtype = int(dtype)                               # NF4 = 0, or FP4_E2M1 / FP4_E3M0 / INT4 / INT8
 
     def view(self) -> qlora_nf4_view:
         ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+        per_byte = 1 if self.dtype == 4 else 2                # weights per byte of `packed`: INT8 one, the 4-bit types two
+        if self.packed.numel() * per_byte != self.rows * self.cols:
+            raise ValueError("NF4Weight: size of `packed` does not match rows, cols and dtype")
         return qlora_nf4_view(ptr(self.packed), ptr(self.code), ptr(self.c1), ptr(self.mean), self.rows, self.cols,
                               self.blocksize, self.dq_blocksize, self.dtype, 0)
 
@@ -138,16 +143,41 @@ def qlora_nf4_sizes(rows, cols, blocksize=64, dq_blocksize=256):
     return tuple(int(x.value) for x in out)
 
 
-def nf4_alloc(rows, cols, device, blocksize=64, dq_blocksize=256) -> NF4Weight:
+def qlora_quant_sizes(rows, cols, blocksize=64, dq_blocksize=256, dtype=0):
+    """(packed_bytes, code_bytes, c1_bytes, scratch_bytes) for any data type (INT8: one byte per weight)."""
+    out = [c_size_t(0) for _ in range(4)]
+    _check(lib().qlora_quant_sizes(rows, cols, blocksize, dq_blocksize, int(dtype), *[byref(x) for x in out]))
+    return tuple(int(x.value) for x in out)
+
+
+def nf4_alloc(rows, cols, device, blocksize=64, dq_blocksize=256, dtype=0) -> NF4Weight:
     """Uninitialised device buffers for a quantised rows x cols weight."""
-    pb, cb, c1b, _ = qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize)
-    return NF4Weight(rows, cols, torch.empty(pb, dtype=torch.uint8, device=device),
-                     torch.empty(cb, dtype=torch.uint8, device=device),
-                     torch.empty(c1b // 4, dtype=torch.float32, device=device),
-                     torch.empty(1, dtype=torch.float32, device=device), blocksize, dq_blocksize)
+    pb, cb, c1b, _ = qlora_quant_sizes(rows, cols, blocksize, dq_blocksize, dtype)
+    w = NF4Weight(rows, cols, torch.empty(pb, dtype=torch.uint8, device=device),
+                  torch.empty(cb, dtype=torch.uint8, device=device),
+                  torch.empty(c1b // 4, dtype=torch.float32, device=device),
+                  torch.empty(1, dtype=torch.float32, device=device), blocksize, dq_blocksize)
+    w.dtype = int(dtype)
+    return w
 
 
-NF4, FP4_E2M1, FP4_E3M0, INT4 = 0, 1, 2, 3
+NF4, FP4_E2M1, FP4_E3M0, INT4, INT8 = 0, 1, 2, 3, 4
+
+
+def qlora_quantize_int8(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None, out=None) -> NF4Weight:
+    """Blockwise 8-bit integers (Eq. 1).  The result's `packed` holds the signed bytes (as uint8 storage)."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
+    rows, cols = W.shape
+    sb = qlora_quant_sizes(rows, cols, blocksize, dq_blocksize, INT8)[3]
+    if out is None:
+        out = nf4_alloc(rows, cols, W.device, blocksize, dq_blocksize, INT8)
+    assert (out.rows, out.cols, out.blocksize, out.dq_blocksize, out.dtype) == (rows, cols, blocksize, dq_blocksize, INT8)
+    assert out.packed.numel() == rows * cols
+    if scratch is None:
+        scratch = torch.empty(sb, dtype=torch.uint8, device=W.device)
+    _check(lib().qlora_quantize_int8(_ptr(W), rows, cols, blocksize, dq_blocksize, _ptr(out.packed), _ptr(out.code),
+                                     _ptr(out.c1), _ptr(out.mean), _ptr(scratch), scratch.numel(), _stream(stream)))
+    return out
 
 
 def qlora_codebook_4bit(dtype):
@@ -171,6 +201,7 @@ def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=N
     if out is None:
         out = nf4_alloc(rows, cols, dev, blocksize, dq_blocksize)
     assert (out.rows, out.cols, out.blocksize, out.dq_blocksize) == (rows, cols, blocksize, dq_blocksize)
+    assert 0 <= int(dtype) < INT8 and out.packed.numel() == rows * cols // 2
     packed, code, c1, mean = out.packed, out.code, out.c1, out.mean
     if scratch is None:
         scratch = torch.empty(sb, dtype=torch.uint8, device=dev)
@@ -211,11 +242,13 @@ WORKSPACE_HEADER_BYTES = 16384
 
 def _fwd_bytes(Wq, M, h, o, r):
     """Workspace of a forward call: a weight without Double Quantization always takes the large-GEMM path."""
-    return qlora_linear_fwd_sizes(M, h, o, r) if Wq.dq_blocksize else qlora_linear_dropout_sizes(M, h, o, r)[0]
+    few = Wq.dq_blocksize and Wq.dtype != INT8
+    return qlora_linear_fwd_sizes(M, h, o, r) if few else qlora_linear_dropout_sizes(M, h, o, r)[0]
 
 
 def _bwd_bytes(Wq, M, h, o, r):
-    return qlora_linear_bwd_sizes(M, h, o, r) if Wq.dq_blocksize else qlora_linear_dropout_sizes(M, h, o, r)[1]
+    few = Wq.dq_blocksize and Wq.dtype != INT8
+    return qlora_linear_bwd_sizes(M, h, o, r) if few else qlora_linear_dropout_sizes(M, h, o, r)[1]
 
 
 def qlora_workspace_init(workspace, stream=None):

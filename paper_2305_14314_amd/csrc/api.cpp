@@ -62,9 +62,13 @@ qlora_status check_view(const qlora_nf4_view* v) {
   if (qlora_status st = check_quant_shape(v->rows, v->cols, v->blocksize, v->dq_blocksize)) return st;
   if (!aligned16(v->packed) || !aligned16(v->c1) || (dq && (!aligned16(v->c2_code) || ((uintptr_t)v->c2_mean & 3u))))
     return QLORA_ERR_ALIGN;
-  if (v->dtype < 0 || v->dtype >= qlora::kNumTypes4) return QLORA_ERR_UNSUPPORTED;
+  if (v->dtype < 0 || v->dtype >= qlora::kNumTypes) return QLORA_ERR_UNSUPPORTED;
   return QLORA_OK;
 }
+
+// The few-token streaming kernels read 4-bit indices and double-quantised constants; every other storage goes
+// through dequantise + GEMM whatever the token count.
+inline bool streams_few(const qlora_nf4_view* v) { return v->dq_blocksize != 0 && v->dtype != qlora::kTypeInt8; }
 
 inline qlora::NF4Dev to_dev(const qlora_nf4_view* v) {
   return qlora::NF4Dev{v->packed, v->c2_code, v->c1, v->c2_mean, v->rows, v->cols, v->dtype, v->dq_blocksize != 0};
@@ -250,10 +254,18 @@ qlora_status qlora_profile_gemm_read(double* total_ms, int64_t* launches, double
 qlora_status qlora_nf4_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
                              size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
                              size_t* scratch_bytes) {
+  return qlora_quant_sizes(rows, cols, blocksize, dq_blocksize, QLORA_NF4, packed_bytes, code_bytes, c1_bytes,
+                           scratch_bytes);
+}
+
+qlora_status qlora_quant_sizes(int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize, int32_t dtype,
+                               size_t* packed_bytes, size_t* code_bytes, size_t* c1_bytes,
+                               size_t* scratch_bytes) {
   if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
+  if (dtype < 0 || dtype >= qlora::kNumTypes) return QLORA_ERR_UNSUPPORTED;
   const int64_t P = rows * cols, n = P / blocksize;
   const int64_t n1 = dq_blocksize ? (n + dq_blocksize - 1) / dq_blocksize : n;   // without DQ the c1 buffer holds the n constants c2
-  if (packed_bytes) *packed_bytes = (size_t)(P / 2);
+  if (packed_bytes) *packed_bytes = dtype == qlora::kTypeInt8 ? (size_t)P : (size_t)(P / 2);
   if (code_bytes) *code_bytes = dq_blocksize ? (size_t)n : 0;
   if (c1_bytes) *c1_bytes = (size_t)n1 * sizeof(float);
   if (scratch_bytes) *scratch_bytes = qlora::kQuantBinsBytes + (dq_blocksize ? (size_t)n * sizeof(float) : 0);
@@ -292,6 +304,23 @@ qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
     return QLORA_ERR_ALIGN;
   return hip_status(qlora::launch_quantize(W, rows, cols, packed, c2_code, c1, c2_mean, scratch,
                                            (hipStream_t)hip_stream, dtype, dq));
+}
+
+qlora_status qlora_quantize_int8(const float* W, int64_t rows, int64_t cols,
+                                 int32_t blocksize, int32_t dq_blocksize,
+                                 int8_t* q8, uint8_t* c2_code, float* c1, float* c2_mean,
+                                 void* scratch, size_t scratch_bytes, void* hip_stream) {
+  const bool dq = dq_blocksize != 0;
+  if (!W || !q8 || !c1 || !scratch || (dq && (!c2_code || !c2_mean))) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
+  size_t need = 0;
+  qlora_quant_sizes(rows, cols, blocksize, dq_blocksize, QLORA_INT8, nullptr, nullptr, nullptr, &need);
+  if (scratch_bytes < need) return QLORA_ERR_WORKSPACE;
+  if (!aligned16(W) || !aligned16(q8) || !aligned16(c1) || !aligned16(scratch) ||
+      (dq && (!aligned16(c2_code) || ((uintptr_t)c2_mean & 3u))))
+    return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_quantize(W, rows, cols, (uint8_t*)q8, c2_code, c1, c2_mean, scratch,
+                                           (hipStream_t)hip_stream, qlora::kTypeInt8, dq));
 }
 
 qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void* hip_stream) {
@@ -340,7 +369,7 @@ qlora_status linear_fwd_impl(const uint16_t* X, const qlora_nf4_view* Wq, const 
   if (qlora_status st = check_linear(M, h, o, r)) return st;
   if (!X || !Y || !workspace) return QLORA_ERR_NULL;
   if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
-  const FwdPlan p = plan_fwd(workspace, M, h, o, r, keep_mask == nullptr && Wq->dq_blocksize != 0);
+  const FwdPlan p = plan_fwd(workspace, M, h, o, r, keep_mask == nullptr && streams_few(Wq));
   if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
   if (!aligned16(X) || !aligned16(Y) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
       !aligned16(T_save))
@@ -425,7 +454,7 @@ qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf
   if (!aligned16(X) || !aligned16(workspace)) return QLORA_ERR_ALIGN;
   if (M <= qlora::kFewTokens)
     for (int l = 0; l < n; ++l)
-      if (Wq[l].dq_blocksize == 0) return QLORA_ERR_UNSUPPORTED;   // the streaming kernels read double-quantised constants
+      if (!streams_few(&Wq[l])) return QLORA_ERR_UNSUPPORTED;      // the streaming kernels read 4-bit indices and double-quantised constants
   const MultiPlan p = plan_fwd_multi(workspace, M, n, h, o, r);
   if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
   if (!p.few) {
@@ -459,7 +488,7 @@ qlora_status linear_bwd_impl(const uint16_t* dY, const uint16_t* X, const qlora_
   if (r > 0 && (!L1 || !L2)) return QLORA_ERR_NULL;
   const bool want1 = dL1 || aL1, want2 = dL2 || aL2;
   if ((want1 || want2) && !X) return QLORA_ERR_NULL;
-  const BwdPlan p = plan_bwd(workspace, M, h, o, r, keep_mask == nullptr && Wq->dq_blocksize != 0);
+  const BwdPlan p = plan_bwd(workspace, M, h, o, r, keep_mask == nullptr && streams_few(Wq));
   if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
   if (!aligned16(dY) || !aligned16(X) || !aligned16(workspace) || !aligned16(L1) || !aligned16(L2) ||
       !aligned16(T_saved) || !aligned16(dX) || !aligned16(dL1) || !aligned16(dL2) || !aligned16(aL1) || !aligned16(aL2))

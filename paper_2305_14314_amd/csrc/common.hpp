@@ -116,12 +116,16 @@ __device__ __forceinline__ uint32_t nf4_index(float x, const Nf4Bucket* table) {
 // magnitude, which removes the exponent bias.  Tables are ascending; the float types hold zero twice (entries 7, 8),
 // Int4 has 15 levels and repeats the top one.  Thresholds are built as for NF4: midpoint rounded toward -infinity.
 constexpr int kNumTypes4 = 4;                // 0 NF4, 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4
+// 8-bit integers (Eq. 1 and Eq. 2 as printed: q = round(127 / absmax * x), x^ = q * absmax / 127): one signed byte
+// per weight, no table; the constants absmax are stored like those of the 4-bit types.
+constexpr int kTypeInt8 = 4;
+constexpr int kNumTypes = 5;
 struct Table4 { float v[16]; };
 struct Thresholds4 { float t[15]; };
 
 inline Table4 table4_host(int dtype) {
   Table4 tab{};
-  if (dtype == 0) {
+  if (dtype == 0 || dtype == kTypeInt8) {        // Int8 reads no table
     for (int i = 0; i < 16; ++i) tab.v[i] = nf4_value(i);
   } else if (dtype == 3) {
     for (int i = 0; i < 15; ++i) tab.v[i] = (float)((double)(i - 7) / 7.0);

@@ -22,12 +22,18 @@ __device__ __forceinline__ void init_lut16(float* lut, int dtype, const Table4& 
   }
 }
 
-template <bool DQ>
+// signed byte j of a dword as fp32
+__device__ __forceinline__ float s8_to_f32(uint32_t p, int j) { return (float)((int)(p << (24 - 8 * j)) >> 24); }
+
+// I8: 8-bit integers, Eq. 2 as printed: w = q * absmax / 127, as bf16(fl32(q * fl32(c2 / 127))).  A lane then reads
+// 8 bytes instead of 4; `packed` and `n_dwords` count in lane-sized units (8 weights) either way.
+template <bool DQ, bool I8>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
-    const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
+    const void* __restrict__ packed_v, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr,
     const int dtype, const Table4 tab) {
   constexpr bool dq = DQ;                                    // Double Quantization, or the fp32 constants as they are
+  const uint32_t* __restrict__ packed = (const uint32_t*)packed_v;
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
@@ -37,8 +43,14 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 
   const int64_t stride = (int64_t)gridDim.x * kDeqThreads;
   for (int64_t d = (int64_t)blockIdx.x * kDeqThreads + threadIdx.x; d < n_dwords; d += stride) {
-    const uint32_t p = packed[d];
-    const uint32_t blk = (uint32_t)(d >> 3);                // 8 dwords per 64-block
+    uint32_t p, ph = 0;
+    if constexpr (I8) {
+      const uint2 pp = ((const uint2*)packed_v)[d];
+      p = pp.x; ph = pp.y;
+    } else {
+      p = packed[d];
+    }
+    const uint32_t blk = (uint32_t)(d >> 3);                // 8 lanes per 64-block
     float c2;
     if (dq) {
       const uint32_t row = blk / bpr;
@@ -49,10 +61,18 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
       c2 = c1[blk];                                           // no Double Quantization: the fp32 constant itself
     }
     uint4 o;
-    o.x = pack_bf16x2(__fmul_rn(lut[p & 15u], c2), __fmul_rn(lut[(p >> 4) & 15u], c2));
-    o.y = pack_bf16x2(__fmul_rn(lut[(p >> 8) & 15u], c2), __fmul_rn(lut[(p >> 12) & 15u], c2));
-    o.z = pack_bf16x2(__fmul_rn(lut[(p >> 16) & 15u], c2), __fmul_rn(lut[(p >> 20) & 15u], c2));
-    o.w = pack_bf16x2(__fmul_rn(lut[(p >> 24) & 15u], c2), __fmul_rn(lut[p >> 28], c2));
+    if constexpr (I8) {
+      const float step = __fdiv_rn(c2, 127.0f);
+      o.x = pack_bf16x2(__fmul_rn(s8_to_f32(p, 0), step), __fmul_rn(s8_to_f32(p, 1), step));
+      o.y = pack_bf16x2(__fmul_rn(s8_to_f32(p, 2), step), __fmul_rn(s8_to_f32(p, 3), step));
+      o.z = pack_bf16x2(__fmul_rn(s8_to_f32(ph, 0), step), __fmul_rn(s8_to_f32(ph, 1), step));
+      o.w = pack_bf16x2(__fmul_rn(s8_to_f32(ph, 2), step), __fmul_rn(s8_to_f32(ph, 3), step));
+    } else {
+      o.x = pack_bf16x2(__fmul_rn(lut[p & 15u], c2), __fmul_rn(lut[(p >> 4) & 15u], c2));
+      o.y = pack_bf16x2(__fmul_rn(lut[(p >> 8) & 15u], c2), __fmul_rn(lut[(p >> 12) & 15u], c2));
+      o.z = pack_bf16x2(__fmul_rn(lut[(p >> 16) & 15u], c2), __fmul_rn(lut[(p >> 20) & 15u], c2));
+      o.w = pack_bf16x2(__fmul_rn(lut[(p >> 24) & 15u], c2), __fmul_rn(lut[p >> 28], c2));
+    }
     out[d] = o;
   }
 }
@@ -62,12 +82,13 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 // 64-block per row.  A lane loads one packed dword (8 n) from each of 8 consecutive rows and
 // writes, for each of its 8 columns, the 8 k-consecutive bf16 as one 16-byte store, so stores
 // form 128-byte runs along k.  No LDS staging of data.
-template <bool DQ>
+template <bool DQ, bool I8>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
-    const uint32_t* __restrict__ packed, const uint8_t* __restrict__ code, const float* __restrict__ c1,
+    const void* __restrict__ packed_v, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out, const int dtype,
     const Table4 tab) {
   constexpr bool dq = DQ;
+  const uint32_t* __restrict__ packed = (const uint32_t*)packed_v;
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
@@ -82,22 +103,33 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
   const int k_base = blockIdx.y * 64 + kg * 8;
   const int blocks_per_row = o >> 6;
 
-  uint32_t p[8];
+  uint32_t p[8], ph[8];
   float c2[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int k = k_base + j;
     const bool ok = k < h;
     const int64_t blk = (int64_t)(ok ? k : 0) * blocks_per_row + n_blk;
-    p[j] = ok ? packed[blk * 8 + ng] : 0x77777777u;         // index 7 is the exact zero
+    if constexpr (I8) {                                       // 8 bytes = this lane's 8 columns of row k
+      const uint2 pp = ((const uint2*)packed_v)[blk * 8 + ng];
+      p[j] = ok ? pp.x : 0u;
+      ph[j] = ok ? pp.y : 0u;
+    } else {
+      p[j] = ok ? packed[blk * 8 + ng] : 0x77777777u;         // index 7 is the exact zero
+      ph[j] = 0u;
+    }
     if (dq) c2[j] = ok ? __fadd_rn(__fmul_rn(unit[code[code_pos(h, blocks_per_row, k, n_blk)]], c1[blk >> 8]), mean) : 0.0f;
     else c2[j] = ok ? c1[blk] : 0.0f;
+    if constexpr (I8) c2[j] = __fdiv_rn(c2[j], 127.0f);       // Eq. 2: the step absmax / 127
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     float v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = __fmul_rn(lut[(p[j] >> (4 * e)) & 15u], c2[j]);
+    for (int j = 0; j < 8; ++j) {
+      if constexpr (I8) v[j] = __fmul_rn(s8_to_f32(e < 4 ? p[j] : ph[j], e & 3), c2[j]);
+      else v[j] = __fmul_rn(lut[(p[j] >> (4 * e)) & 15u], c2[j]);
+    }
     uint4 q;
     q.x = pack_bf16x2(v[0], v[1]);
     q.y = pack_bf16x2(v[2], v[3]);
@@ -111,12 +143,13 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
 hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st) {
   const int h = (int)w.rows, o = (int)w.cols;
   dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64));
-  if (w.dq)
-    hipLaunchKernelGGL(dequant_nf4_t_kernel<true>, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
-                       w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype));
-  else
-    hipLaunchKernelGGL(dequant_nf4_t_kernel<false>, grid, dim3(kDeqThreads), 0, st, (const uint32_t*)w.packed, w.code,
-                       w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype));
+  const bool i8 = w.dtype == kTypeInt8;
+#define QL_DEQ_T(DQ, I8)                                                                                        \
+  hipLaunchKernelGGL((dequant_nf4_t_kernel<DQ, I8>), grid, dim3(kDeqThreads), 0, st, (const void*)w.packed, w.code, \
+                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype))
+  if (w.dq) { if (i8) QL_DEQ_T(true, true); else QL_DEQ_T(true, false); }
+  else      { if (i8) QL_DEQ_T(false, true); else QL_DEQ_T(false, false); }
+#undef QL_DEQ_T
   return hipGetLastError();
 }
 
@@ -125,14 +158,14 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
   int64_t blocks = (n_dwords + kDeqThreads - 1) / kDeqThreads;
   const int64_t cap = 256 * 32;
   if (blocks > cap) blocks = cap;
-  if (w.dq)
-    hipLaunchKernelGGL(dequant_nf4_kernel<true>, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
-                       (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
-                       (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype));
-  else
-    hipLaunchKernelGGL(dequant_nf4_kernel<false>, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,
-                       (const uint32_t*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,
-                       (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype));
+  const bool i8 = w.dtype == kTypeInt8;
+#define QL_DEQ(DQ, I8)                                                                                      \
+  hipLaunchKernelGGL((dequant_nf4_kernel<DQ, I8>), dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,        \
+                     (const void*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,  \
+                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype))
+  if (w.dq) { if (i8) QL_DEQ(true, true); else QL_DEQ(true, false); }
+  else      { if (i8) QL_DEQ(false, true); else QL_DEQ(false, false); }
+#undef QL_DEQ
   return hipGetLastError();
 }
 

@@ -22,12 +22,14 @@ constexpr int kQUnroll = 4;
 __global__ void zero_bins_kernel(unsigned long long* bins) { bins[threadIdx.x] = 0ull; }
 
 // One float4 per lane per step; 16 consecutive lanes hold one 64-block.
-// OTHER: one of the other 4-bit data types (Section 4); its decision thresholds arrive as an argument.
-template <bool OTHER>
+// MODE 0: NF4.  1: one of the other 4-bit data types (Section 4); its decision thresholds arrive as an argument.
+// 2: 8-bit integers, Eq. 1 as printed: q = round_to_nearest_even(fl32(127 / absmax) * x), one signed byte per weight.
+template <int MODE>
 __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
     const float4* __restrict__ W, int64_t n_vec4,          // n_vec4 = elements / 4
-    uint16_t* __restrict__ packed16,                       // one 16-bit store per lane: 4 nibbles
+    void* __restrict__ packed,                             // one store per lane: 4 nibbles (16 bit) or 4 bytes
     float* __restrict__ c2_out, unsigned long long* __restrict__ bins, const Thresholds4 thr) {
+  constexpr bool OTHER = MODE == 1;
   __shared__ unsigned long long lbins[256];
   __shared__ __attribute__((aligned(256))) Nf4Bucket buckets[32];
   __shared__ float th[16];
@@ -58,9 +60,18 @@ __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
                                    __builtin_fmaxf(__builtin_fabsf(w.z), __builtin_fabsf(w.w)));
       amax = row16_max(amax);                                 // c2 of this lane's block
       // Eq. 1: the constant is range/absmax (range 1); elements are multiplied by it.
-      const float rc = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(1.0f, amax);
-      uint32_t i0, i1, i2, i3;
-      if constexpr (OTHER) {
+      float rc = (amax < __FLT_MIN__) ? 0.0f : __fdiv_rn(MODE == 2 ? 127.0f : 1.0f, amax);
+      if constexpr (MODE == 2) {
+        if (__builtin_isinf(rc)) rc = 0.0f;                   // 127 / absmax beyond fp32: the block quantises to zeros
+        auto q8 = [&](float x) -> uint32_t {                  // the product lies in [-127, 127] up to rounding: clamp anyway
+          const float t = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(__fmul_rn(x, rc)), -127.0f), 127.0f);
+          return (uint32_t)(int)t & 0xffu;
+        };
+        ((uint32_t*)packed)[v] = q8(w.x) | (q8(w.y) << 8) | (q8(w.z) << 16) | (q8(w.w) << 24);
+      }
+      uint32_t i0 = 0, i1 = 0, i2 = 0, i3 = 0;
+      if constexpr (MODE == 2) {
+      } else if constexpr (OTHER) {
         i0 = index_search4(__fmul_rn(w.x, rc), th);
         i1 = index_search4(__fmul_rn(w.y, rc), th);
         i2 = index_search4(__fmul_rn(w.z, rc), th);
@@ -71,7 +82,7 @@ __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
         i2 = nf4_index(__fmul_rn(w.z, rc), buckets);
         i3 = nf4_index(__fmul_rn(w.w, rc), buckets);
       }
-      packed16[v] = (uint16_t)(i0 | (i1 << 4) | (i2 << 8) | (i3 << 12));
+      if constexpr (MODE != 2) ((uint16_t*)packed)[v] = (uint16_t)(i0 | (i1 << 4) | (i2 << 8) | (i3 << 12));
       if ((threadIdx.x & 15) == 0) {
         c2_out[v >> 4] = amax;
         const uint32_t u32 = __builtin_bit_cast(uint32_t, amax);
@@ -183,7 +194,7 @@ __global__ __launch_bounds__(kDqBlock) void dq_encode_kernel(const float* __rest
 
 hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
                            float* mean, void* scratch, hipStream_t st, int dtype, bool dq) {
-  if (dtype < 0 || dtype >= kNumTypes4) return hipErrorInvalidValue;
+  if (dtype < 0 || dtype >= kNumTypes) return hipErrorInvalidValue;
   const Thresholds4 thr = thresholds4_host(table4_host(dtype));
   const int64_t elems = rows * cols;
   const int64_t n = elems / kBlock;
@@ -196,11 +207,14 @@ hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* 
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(zero_bins_kernel, dim3(1), dim3(256), 0, st, bins);
   if (dtype == 0)
-    hipLaunchKernelGGL(quantize_nf4_kernel<false>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
-                       n_vec4, (uint16_t*)packed, c2, bins, thr);
+    hipLaunchKernelGGL(quantize_nf4_kernel<0>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
+                       n_vec4, (void*)packed, c2, bins, thr);
+  else if (dtype == kTypeInt8)
+    hipLaunchKernelGGL(quantize_nf4_kernel<2>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
+                       n_vec4, (void*)packed, c2, bins, thr);
   else
-    hipLaunchKernelGGL(quantize_nf4_kernel<true>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
-                       n_vec4, (uint16_t*)packed, c2, bins, thr);
+    hipLaunchKernelGGL(quantize_nf4_kernel<1>, dim3((unsigned)blocks), dim3(kQThreads), 0, st, (const float4*)W,
+                       n_vec4, (void*)packed, c2, bins, thr);
   if (!dq) return hipGetLastError();
   hipLaunchKernelGGL(dq_mean_kernel, dim3(1), dim3(64), 0, st, bins, (uint32_t)n, mean);
   const int64_t n1 = (n + kDqBlock - 1) / kDqBlock;

@@ -178,10 +178,41 @@ def test_data_type_tables_and_their_validation(L, oracle):
     assert L.qlora_codebook_4bit(0, None) == -1
     assert L.qlora_quantize_4bit(fake, 4, 64, 64, 256, 7, fake, fake, fake, fake, fake, 1 << 20, None) == -3
     assert L.qlora_quantize_4bit(None, 4, 64, 64, 256, 1, fake, fake, fake, fake, fake, 1 << 20, None) == -1
-    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256, 4, 0)
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256, 5, 0)
     assert L.qlora_nf4_dequant(ctypes.byref(v), fake, None) == -3
+    # Int8 is a data type of a view, but has no table and is not a 4-bit type
+    assert L.qlora_quantize_4bit(fake, 4, 64, 64, 256, 4, fake, fake, fake, fake, fake, 1 << 20, None) == -3
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256, 4, 0)
+    assert L.qlora_nf4_dequant(ctypes.byref(v), None, None) == -1           # the view passes, the output is missing
     v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256)       # eight fields: NF4
     assert v.dtype == 0
+
+
+def test_int8_sizes_and_validation(L):
+    """8-bit integers: one byte per weight, the constants as for the 4-bit types (8.127 bit per parameter with Double
+    Quantization, 8.5 without); argument checks of the quantise call (host only: every call stops at validation)."""
+    from paper_2305_14314_amd import INT8, qlora_nf4_sizes, qlora_quant_sizes
+    from paper_2305_14314_amd.binding import QloraError
+    P = 8192 * 8192
+    pb, cb, c1b, sb = qlora_quant_sizes(8192, 8192, 64, 256, INT8)
+    assert (pb, cb, c1b) == (P, P // 64, 4 * P // (64 * 256)) and sb == qlora_nf4_sizes(8192, 8192)[3]
+    assert abs((pb + cb + c1b) * 8 / P - 8.127) < 1e-3
+    pb, cb, c1b, _ = qlora_quant_sizes(8192, 8192, 64, 0, INT8)
+    assert (pb + cb + c1b) * 8 / P == 8.5
+    assert qlora_quant_sizes(8192, 8192, 64, 256, 0) == qlora_nf4_sizes(8192, 8192, 64, 256)
+    with pytest.raises(QloraError) as e:
+        qlora_quant_sizes(64, 64, 64, 256, 5)
+    assert e.value.status == -3
+    fake = ctypes.c_void_p(0x1000)
+    q = L.qlora_quantize_int8
+    assert q(None, 4, 64, 64, 256, fake, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert q(fake, 4, 64, 64, 256, None, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert q(fake, 4, 64, 64, 256, fake, None, fake, fake, fake, 1 << 20, None) == -1
+    assert q(fake, 4, 64, 64, 0, fake, None, fake, None, fake, 8, None) == -4        # no DQ: code / mean may be NULL
+    assert q(fake, 4, 60, 64, 256, fake, fake, fake, fake, fake, 1 << 20, None) == -2
+    assert q(fake, 4, 64, 32, 256, fake, fake, fake, fake, fake, 1 << 20, None) == -3
+    assert q(fake, 4, 64, 64, 256, fake, fake, fake, fake, fake, 8, None) == -4
+    assert q(ctypes.c_void_p(0x1004), 4, 64, 64, 256, fake, fake, fake, fake, fake, 1 << 20, None) == -5
 
 
 def test_sizes_without_double_quantization(L):

@@ -119,3 +119,78 @@ def test_without_double_quantization(oracle, synth, kind, dtype):
     with pytest.raises(ql.QloraError) as e:
         ql.qlora_linear_fwd_multi(X, [Wq], [L1], [L2], [s], workspace=ws)
     assert e.value.status == -3
+
+
+def _int8_cases(synth):
+    yield "normal", synth.normal_f32((257, 192), 0.02, 9300)
+    yield "unit-normal", synth.normal_f32((64, 512), 1.0, 9301)
+    w = synth.normal_f32((128, 256), 0.02, 9302)
+    w.reshape(-1)[:64 * 3] = 0.0                                          # all-zero blocks
+    w.reshape(-1)[64 * 5:64 * 6] *= np.float32(1e-36)                     # 127 / absmax overflows fp32: zeros
+    yield "zero-and-tiny-blocks", w
+    # blocks with absmax 127 (c = 1): every half-integer and its fp32 neighbours, both signs -> ties to even
+    k = np.arange(0, 42, dtype=np.float32) * 3 + 0.5
+    pts = np.concatenate([k, np.nextafter(k, np.float32(1e9)), np.nextafter(k, np.float32(-1e9))])
+    pts = np.concatenate([pts, -pts])
+    flat = np.zeros((5 * 64,), np.float32)
+    idx = np.arange(len(pts))
+    flat[idx + idx // 63] = pts                                           # 63 points per block, the last slot stays free
+    flat[63::64] = 127.0
+    yield "ties", flat.reshape(1, -1).copy()
+
+
+@pytest.mark.parametrize("dq_blocksize", [256, 0])
+def test_int8_quantize_dequant_bit_exact(oracle, synth, dq_blocksize):
+    """Eq. 1 / Eq. 2 with 8-bit integers: the bytes, the constants (double-quantised or kept) and the dequantised bf16
+    weights equal the oracle's bit for bit; the 4-bit entry points refuse the type."""
+    import paper_2305_14314_amd as ql
+    for tag, W in _int8_cases(synth):
+        print("case int8", tag, W.shape, "dq", dq_blocksize, flush=True)
+        q = oracle.int8_quantize(W, dq_blocksize=dq_blocksize)
+        Wq = ql.qlora_quantize_int8(dev_f32(W), dq_blocksize=dq_blocksize)
+        torch.cuda.synchronize()
+        assert Wq.dtype == ql.INT8 and Wq.packed.numel() == W.size
+        np.testing.assert_array_equal(host_u8(Wq.packed).view(np.int8), q["q8"], err_msg=f"int8 {tag}: bytes")
+        if dq_blocksize:
+            assert host_u32(Wq.mean)[0] == np.float32(q["mean"]).view(np.uint32)
+            np.testing.assert_array_equal(host_u32(Wq.c1), q["c1"].view(np.uint32))
+            np.testing.assert_array_equal(code_to_flat(host_u8(Wq.code), Wq.rows, Wq.cols), q["code"])
+        else:
+            np.testing.assert_array_equal(host_u32(Wq.c1), q["c2"].view(np.uint32))
+        np.testing.assert_array_equal(host_bits(ql.qlora_nf4_dequant(Wq)), oracle.int8_dequant(q),
+                                      err_msg=f"int8 {tag}: dequantised bf16")
+    with pytest.raises(ql.QloraError) as e:
+        ql.qlora_codebook_4bit(ql.INT8)
+    assert e.value.status == -3
+    bits = 8 + (8 / 64 + 32 / (64 * 256) if dq_blocksize else 0.5)
+    assert abs(Wq.nbytes * 8 / W.size - bits) < 1e-3 + (32 + 32) / W.size
+
+
+@pytest.mark.parametrize("dq_blocksize", [256, 0])
+@pytest.mark.parametrize("M,h,o,r", [(300, 448, 576, 32), (5, 192, 320, 16)])
+def test_int8_linear(oracle, synth, dq_blocksize, M, h, o, r):
+    """Forward and backward on an Int8 weight (dequantise + GEMM at any token count; the transposed dequantisation
+    feeds the forward product, the plain one the backward) against the oracle on its own dequantised weight."""
+    import paper_2305_14314_amd as ql
+    s = 0.5
+    W = synth.normal_f32((h, o), synth.SIGMA_W, 9310 + M)
+    q = oracle.int8_quantize(W, dq_blocksize=dq_blocksize)
+    What = oracle.int8_dequant(q)
+    Wq = ql.qlora_quantize_int8(dev_f32(W), dq_blocksize=dq_blocksize)
+    hX, hdY = synth.normal_bf16((M, h), 1.0, 9311), synth.normal_bf16((M, o), 1.0, 9312)
+    hL1, hL2 = synth.normal_bf16((h, r), 0.05, 9313), synth.normal_bf16((r, o), 0.05, 9314)
+    X, dY, L1, L2 = dev_bf16(hX), dev_bf16(hdY), dev_bf16(hL1), dev_bf16(hL2)
+    print(f"case int8 linear M={M} h={h} o={o} r={r} dq={dq_blocksize}", flush=True)
+    Y = ql.qlora_linear_fwd(X, Wq, L1, L2, s)
+    dX, dL1, dL2 = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s)
+    torch.cuda.synchronize()
+    _check(host_bits(Y), oracle.linear_fwd(hX, What, hL1, hL2, s), "int8 Y")
+    _check(host_bits(dX), oracle.linear_bwd_dx(hdY, What, hL1, hL2, s), "int8 dX")
+    r1, r2 = oracle.linear_bwd_dl(hdY, hX, hL1, hL2, s)
+    _check(host_bits(dL1), r1, "int8 dL1", few_terms=M < 64)
+    _check(host_bits(dL2), r2, "int8 dL2", few_terms=M < 64)
+    if M <= 16:
+        ws = ql.workspace_alloc(ql.qlora_linear_dropout_sizes(M, h, o, r)[0])
+        with pytest.raises(ql.QloraError) as e:
+            ql.qlora_linear_fwd_multi(X, [Wq], [L1], [L2], [s], workspace=ws)
+        assert e.value.status == -3
