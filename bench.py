@@ -236,6 +236,16 @@ def main():
 
     extra = {}
     if not args.no_extra:
+        # the same steps without the HIP events around the GEMM launches: each recorded event is a marker of its own
+        # on the stream and costs a bubble of 4-5 us before and after the kernel it brackets (28 per step)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(args.warmup + args.steps + k)
+        torch.cuda.synchronize()
+        ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
+        extra["step_without_gemm_events"] = {"ms_per_step": round(ms_plain, 4),
+                                             "TFLOPs": round(flops_step / (ms_plain * 1e-3) * 1e-12, 2)}
         if quant_elems:
             extra["quantize"] = {"GBps": round(quant_elems * 4.5159 / (t_quant_ms * 1e-3) * 1e-9, 1),
                                  "frac_hbm": round(quant_elems * 4.5159 / (t_quant_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),

@@ -25,8 +25,9 @@ hipError_t gemm_nt_timed(const uint16_t* A0, const uint16_t* B0, int64_t lda0, i
   if (!g_prof.enabled)
     return qlora::launch_gemm_nt(A0, B0, lda0, ldb0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
   GemmProfile::Rec r{};
-  if (hipError_t e = hipEventCreate(&r.start)) return e;
-  if (hipError_t e = hipEventCreate(&r.stop)) return e;
+  // timing-only events: no system-scope fence (and the cache write-back it implies) when they complete
+  if (hipError_t e = hipEventCreateWithFlags(&r.start, hipEventDisableSystemFence)) return e;
+  if (hipError_t e = hipEventCreateWithFlags(&r.stop, hipEventDisableSystemFence)) { (void)hipEventDestroy(r.start); return e; }
   r.flops = 2.0 * (double)M * (double)N * (double)(K0 + K1);
   (void)hipEventRecord(r.start, st);
   const hipError_t e = qlora::launch_gemm_nt(A0, B0, lda0, ldb0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
