@@ -98,8 +98,8 @@ struct Carver {
 };
 
 struct FwdPlan {
-  uint16_t* Wt;      // o x h     dequantised weight, transposed (K-contiguous for the forward)
-  uint16_t* L2t;     // o x rp    L2^T, rank zero-padded to a multiple of 64
+  uint16_t* Wt;      // o x (h + rp)   dequantised weight, transposed (K-contiguous for the forward), and behind it in
+                     //                every row L2^T with the rank zero-padded to a multiple of 64: both K segments
   uint16_t* Ts;      // M x rp    bf16(s * X L1)
   float* part;       // split-K partials of X L1
   float* fpart;      // few-token path: split partials of X What
@@ -121,10 +121,9 @@ FwdPlan plan_fwd(void* ws, int64_t M, int64_t h, int64_t o, int32_t r, bool allo
     p.bytes = c.off;
     return p;
   }
-  p.Wt = c.take<uint16_t>((size_t)h * o);
+  p.Wt = c.take<uint16_t>((size_t)(h + (r > 0 ? p.rp : 0)) * o);
   if (r > 0) {
     p.splits = qlora::small_gemm_splits((int)M, r, (int)h);
-    p.L2t = c.take<uint16_t>((size_t)o * p.rp);
     p.Ts = c.take<uint16_t>((size_t)M * p.rp);
     p.part = c.take<float>((size_t)p.splits * M * r);
   }
@@ -390,10 +389,10 @@ qlora_status linear_fwd_impl(const uint16_t* X, const qlora_nf4_view* Wq, const 
     QL_TRY(qlora::launch_small_gemm(X, h, false, L1, r, true, 0, 0, (int)M, r, (int)h, p.part, p.splits, st, keep_mask));
     QL_TRY(qlora::launch_small_finalize(p.part, p.splits, (int)M, r, p.Ts, p.rp, p.rp, s, T_save, nullptr, st));
   }
-  QL_TRY(qlora::launch_dequant_t(W, p.Wt, h, st));
-  if (r > 0) QL_TRY(qlora::launch_transpose_pad(L2, o, r, (int)o, p.L2t, p.rp, st));
+  const int64_t ldw = h + (r > 0 ? p.rp : 0);               // one row of Wt: What^T[n][0 .. h), then L2^T[n][0 .. rp)
+  QL_TRY(qlora::launch_dequant_t(W, p.Wt, ldw, st, r > 0 ? L2 : nullptr, r, r > 0 ? p.rp : 0));
   // Y = X What + Ts L2 (Eq. 5): the adapter term is the second K segment of the same accumulators
-  QL_TRY(gemm_nt_timed(X, p.Wt, h, h, (int)h, p.Ts, p.L2t, p.rp, p.rp, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
+  QL_TRY(gemm_nt_timed(X, p.Wt, h, ldw, (int)h, p.Ts, p.Wt + h, p.rp, ldw, r > 0 ? p.rp : 0, Y, o, (int)M, (int)o,
                                st));
   return QLORA_OK;
 }

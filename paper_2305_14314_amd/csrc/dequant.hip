@@ -82,13 +82,47 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 // 64-block per row.  A lane loads one packed dword (8 n) from each of 8 consecutive rows and
 // writes, for each of its 8 columns, the 8 k-consecutive bf16 as one 16-byte store, so stores
 // form 128-byte runs along k.  No LDS staging of data.
+//
+// Workgroup rows beyond the weight's (blockIdx.y >= ceil(h / 64)) transpose the adapter's L2 (r x o, bf16) the same
+// way into columns h .. h + rp - 1 of `out` (rows t >= r are written as zeros), so that one buffer of row stride
+// ld_out >= h + rp holds both K segments of the forward product's weight-side operand and no launch of its own is
+// spent on a 1 MB transpose.
 template <bool DQ, bool I8>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const void* __restrict__ packed_v, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out, const int dtype,
-    const Table4 tab) {
+    const Table4 tab, const uint16_t* __restrict__ L2, int r) {
   constexpr bool dq = DQ;
   const uint32_t* __restrict__ packed = (const uint32_t*)packed_v;
+  const int w_rows = (h + 63) >> 6;                          // workgroup rows of the weight
+  if ((int)blockIdx.y >= w_rows) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int kg = lane >> 3, ng = lane & 7;
+    const int n_blk = blockIdx.x * 4 + wave;
+    if (n_blk * 64 >= o) return;
+    const int t_base = ((int)blockIdx.y - w_rows) * 64 + kg * 8;
+    const int n_first = n_blk * 64 + ng * 8;
+    uint4 row[8];                                            // row[j] = L2[t_base + j][n_first .. n_first + 7]
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int t = t_base + j;
+      row[j] = (t < r) ? *(const uint4*)(L2 + (int64_t)t * o + n_first) : uint4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      auto el = [&](int j) -> uint32_t {                     // element e of row j
+        const uint32_t d = (e >> 1) == 0 ? row[j].x : (e >> 1) == 1 ? row[j].y : (e >> 1) == 2 ? row[j].z : row[j].w;
+        return (e & 1) ? d >> 16 : d & 0xffffu;
+      };
+      uint4 q;
+      q.x = el(0) | (el(1) << 16);
+      q.y = el(2) | (el(3) << 16);
+      q.z = el(4) | (el(5) << 16);
+      q.w = el(6) | (el(7) << 16);
+      *(uint4*)(out + (int64_t)(n_first + e) * ld_out + h + t_base) = q;
+    }
+    return;
+  }
   __shared__ float lut[16];
   __shared__ float unit[256];
   init_lut16(lut, dtype, tab);
@@ -140,13 +174,16 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
   }
 }
 
-hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st) {
+hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st, const uint16_t* L2, int r,
+                            int rp) {
   const int h = (int)w.rows, o = (int)w.cols;
-  dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64));
+  if (L2 == nullptr) { r = 0; rp = 0; }
+  if (rp % 64 != 0 || r > rp || ld_out < h + rp || ld_out % 8 != 0) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64 + rp / 64));
   const bool i8 = w.dtype == kTypeInt8;
 #define QL_DEQ_T(DQ, I8)                                                                                        \
   hipLaunchKernelGGL((dequant_nf4_t_kernel<DQ, I8>), grid, dim3(kDeqThreads), 0, st, (const void*)w.packed, w.code, \
-                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype))
+                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype), L2, r)
   if (w.dq) { if (i8) QL_DEQ_T(true, true); else QL_DEQ_T(true, false); }
   else      { if (i8) QL_DEQ_T(false, true); else QL_DEQ_T(false, false); }
 #undef QL_DEQ_T

@@ -27,7 +27,10 @@ hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* 
 // dequant.hip
 hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);
 // out[n][k] = dequant(W)[k][n] with row stride ld_out (elements); requires h % 8 == 0.
-hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st);
+// L2 != NULL (r x o bf16, rp = r rounded up to a multiple of 64, ld_out >= h + rp): the same launch also writes
+// out[n][h + t] = L2[t][n] for t < r and zeros for r <= t < rp.
+hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st,
+                            const uint16_t* L2 = nullptr, int r = 0, int rp = 0);
 
 // gemm.hip: C[M x N] = A0 B0^T + A1 B1^T, all operands K-contiguous bf16, K0 and K1 multiples of 64.
 hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
@@ -52,9 +55,6 @@ hipError_t launch_dropout_dx_fix(uint16_t* dX, int M, int h, const uint8_t* mask
 //   hl = [bf16(sum) | bf16(sum - bf16(sum))] (row stride 2 J) and/or adds scale0 * sum to the fp32 matrix acc (I x J).
 hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
                                  float scale0, uint16_t* hl, float* acc, hipStream_t st);
-//   dst[c][r] = src[r][c], rows r >= R zero-filled up to Rp.
-hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
-                                hipStream_t st);
 hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st);
 
 // fewtok.hip: few-token (M <= 16) streaming path, one launch per call: fp32 split partials of the frozen product,

@@ -223,22 +223,6 @@ __global__ void small_finalize_kernel(const float* __restrict__ part, int splits
   }
 }
 
-// dst[c][r] = src[r][c] for r < R, zero for R <= r < Rp.  src is R x C (ld = lds_), dst is C x Rp.
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int64_t ld_src, int R,
-                                                            int C, uint16_t* __restrict__ dst, int Rp) {
-  __shared__ uint16_t tile[64][65];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-    const int r = r0 + e / 64, c = c0 + e % 64;
-    tile[e / 64][e % 64] = (r < R && c < C) ? src[(int64_t)r * ld_src + c] : (uint16_t)0;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-    const int c = c0 + e / 64, r = r0 + e % 64;
-    if (c < C && r < Rp) dst[(int64_t)c * Rp + r] = tile[e % 64][e / 64];
-  }
-}
-
 // dst[row][0..Cp) = src[row][0..C) followed by zeros
 __global__ void copy_pad_kernel(const uint16_t* __restrict__ src, int R, int C, uint16_t* __restrict__ dst, int Cp) {
   const int64_t total = (int64_t)R * Cp;
@@ -381,13 +365,6 @@ hipError_t launch_dropout_dx_fix(uint16_t* dX, int M, int h, const uint8_t* mask
   const int64_t n = (int64_t)M * h / 8;
   hipLaunchKernelGGL(dropout_dx_fix_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dX, n, h, mask, Us,
                      ld_us, L1, r);
-  return hipGetLastError();
-}
-
-hipError_t launch_transpose_pad(const uint16_t* src, int64_t ld_src, int R, int C, uint16_t* dst, int Rp,
-                                hipStream_t st) {
-  dim3 grid((unsigned)((C + 63) / 64), (unsigned)((Rp + 63) / 64));
-  hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, st, src, ld_src, R, C, dst, Rp);
   return hipGetLastError();
 }
 
