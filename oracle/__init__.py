@@ -42,6 +42,7 @@ def _load():
     L.oracle_num_threads.restype = ctypes.c_int
     L.oracle_nf4_table.argtypes = [vp]
     L.oracle_nf4_derive.argtypes = [c_double, vp]
+    L.oracle_nfk_derive.argtypes = [c_int32, vp]
     L.oracle_normal_quantile.argtypes = [c_double]
     L.oracle_normal_quantile.restype = c_double
     L.oracle_nf4_index.argtypes = [c_float]
@@ -131,7 +132,14 @@ def e4m3_unit(code: int) -> np.float32:
     return np.float32(_load().oracle_e4m3_unit(int(code)))
 
 
-KINDS = {"nf4": 0, "fp4_e2m1": 1, "fp4_e3m0": 2, "int4": 3}
+KINDS = {"nf4": 0, "fp4_e2m1": 1, "fp4_e3m0": 2, "int4": 3, "nf3": 5, "nf2": 6}
+
+
+def nfk_derive(k: int) -> np.ndarray:
+    """k-bit NormalFloat values (k = 2, 3, 4) from normal quantiles, fp64: 2^k values ascending, padded with +1 to 16."""
+    out = np.empty(16, np.float64)
+    _check(_load().oracle_nfk_derive(int(k), _p(out)), "nfk_derive")
+    return out
 
 
 def codebook4(kind) -> np.ndarray:

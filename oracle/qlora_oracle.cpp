@@ -102,6 +102,33 @@ void oracle_nf4_derive(double p_max, double out[16]) {
   }
 }
 
+/* k-bit NormalFloat for k = 2, 3, 4 (Section 3, "4-bit NormalFloat Quantization": the construction is stated for
+ * general k): 2^(k-1) evenly spaced probabilities from 1/2 to p_max give the negative side (the zero among them is
+ * dropped), 2^(k-1) + 1 give the positive side, all quantiles divided by the top one: 2^k values with one exact zero.
+ * The paper gives neither p_max nor a table for k != 4; the reading here is the tail mass that reproduces the printed
+ * k = 4 table, written for general k:  1 - p_max = (1 / 2^(k+1) + 1 / (2^(k+1) - 2)) / 2.
+ * out: the 2^k values ascending, then +1 repeated up to 16 entries (codes >= 2^k are never produced). */
+int oracle_nfk_derive(int k, double out[16]) {
+  if (!out) return -1;
+  if (k < 2 || k > 4) return -2;
+  const int n_neg = 1 << (k - 1), n_pos = n_neg + 1;
+  const double two = (double)(1 << (k + 1));
+  const double p_max = 1.0 - 0.5 * (1.0 / two + 1.0 / (two - 2.0));
+  const double top = oracle_normal_quantile(p_max);
+  for (int i = 1; i < n_neg; ++i) {
+    const double p = 0.5 + (p_max - 0.5) * (double)i / (double)(n_neg - 1);
+    out[n_neg - 1 - i] = -oracle_normal_quantile(p) / top;
+  }
+  for (int i = 0; i < n_pos; ++i) {
+    const double p = 0.5 + (p_max - 0.5) * (double)i / (double)(n_pos - 1);
+    out[n_neg - 1 + i] = (i == 0) ? 0.0 : oracle_normal_quantile(p) / top;
+  }
+  out[0] = -1.0;
+  out[(1 << k) - 1] = 1.0;
+  for (int i = 1 << k; i < 16; ++i) out[i] = 1.0;
+  return 0;
+}
+
 /* Nearest value of a non-decreasing 16-entry table, the lower index on an exact tie:
  * the number of midpoints strictly below xhat. */
 static int index_in(const float* table, float xhat) {
@@ -141,6 +168,12 @@ int oracle_codebook4(int kind, float out[16]) {
       for (int i = 0; i < 15; ++i) out[i] = (float)((double)(i - 7) / 7.0);
       out[15] = 1.0f;
       return 0;
+    case 5: case 6: {                                  /* NF3, NF2: the derived quantiles, rounded once to fp32 */
+      double d[16];
+      if (oracle_nfk_derive(kind == 5 ? 3 : 2, d)) return -2;
+      for (int i = 0; i < 16; ++i) out[i] = (float)d[i];
+      return 0;
+    }
     default: return -2;
   }
   for (int c = 0; c < 8; ++c) {

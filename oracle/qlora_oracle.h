@@ -123,6 +123,11 @@ int oracle_dequant4(const float* table, const uint8_t* packed, const uint8_t* co
  *   (dq_blocksize = 0: kept, code / c1 / mean may be NULL);  c2_out (n fp32) receives them in any case.
  *   w = bf16_rne(fl32(q * fl32(c2hat / 127))).
  * oracle_dq_constants reconstructs c2hat from the double-quantised constants. */
+/* k-bit NormalFloat values for k = 2, 3, 4 from N(0,1) quantiles (Section 3; p_max for k != 4 is a reading, see the
+ * source): 2^k values ascending, then +1 repeated up to 16 entries.  oracle_codebook4 kinds 5 (NF3) and 6 (NF2) are
+ * these rounded to fp32. */
+int oracle_nfk_derive(int k, double out[16]);
+
 int oracle_quantize_int8(const float* W, int64_t rows, int64_t cols, int32_t blocksize, int32_t dq_blocksize,
                          int8_t* q8, uint8_t* code, float* c1, float* mean, float* c2_out);
 int oracle_dequant_int8(const int8_t* q8, const float* c2hat, int64_t rows, int64_t cols, int32_t blocksize,

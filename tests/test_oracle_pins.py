@@ -691,3 +691,50 @@ def test_int8_ties_and_clamp(oracle):
     q = oracle.int8_quantize(w, dq_blocksize=0)
     assert list(q["q8"][:9]) == [127, 0, 2, 2, 0, -2, -2, 126, -126]
     np.testing.assert_array_equal(_bf16_f64(oracle.int8_dequant(q))[0, :4], [127.0, 0.0, 2.0, 2.0])
+
+
+# ----------------------------------------------------------------------------- k-bit NormalFloat, k = 2, 3 (Section 3)
+
+def test_nfk_construction(oracle):
+    """The general-k construction: k = 4 gives back the derivation that matches the printed table; for k = 2, 3 every
+    value is the stated quantile (library normal quantile), there are 2^k distinct ascending values with one exact
+    zero, one more positive than negative, ends at -1 and +1, and the 16-entry table is padded with +1."""
+    from scipy.stats import norm
+    d4 = oracle.nfk_derive(4)
+    np.testing.assert_array_equal(d4, oracle.nf4_derive(1.0 - 0.5 * (1.0 / 32.0 + 1.0 / 30.0)))
+    assert np.abs(d4 - oracle.nf4_table().astype(np.float64)).max() <= 2e-7
+    for k in (2, 3):
+        d = oracle.nfk_derive(k)
+        n = 1 << k
+        n_neg, n_pos = n // 2, n // 2 + 1
+        p_max = 1.0 - 0.5 * (1.0 / (2 * n) + 1.0 / (2 * n - 2))
+        top = norm.ppf(p_max)
+        want = [-norm.ppf(0.5 + (p_max - 0.5) * i / (n_neg - 1)) / top for i in range(n_neg - 1, 0, -1)]
+        want += [norm.ppf(0.5 + (p_max - 0.5) * i / (n_pos - 1)) / top for i in range(n_pos)]
+        assert len(want) == n
+        np.testing.assert_allclose(d[:n], want, rtol=0, atol=1e-12)
+        assert np.all(np.diff(d[:n]) > 0) and d[0] == -1.0 and d[n - 1] == 1.0 and d[n_neg - 1] == 0.0
+        assert (d[:n] < 0).sum() == n_neg - 1 and (d[:n] > 0).sum() == n_neg
+        assert np.all(d[n:] == 1.0)
+        tab = oracle.codebook4("nf3" if k == 3 else "nf2")
+        np.testing.assert_array_equal(tab, d.astype(np.float32))
+    # NF2 in closed form: {-1, 0, Q((1/2 + p_max) / 2) / Q(p_max), 1}
+    p2 = 1.0 - 0.5 * (1.0 / 8 + 1.0 / 6)
+    np.testing.assert_allclose(oracle.nfk_derive(2)[:4], [-1.0, 0.0, norm.ppf((0.5 + p2) / 2) / norm.ppf(p2), 1.0], atol=1e-12)
+
+
+def test_nfk_error_ordering_and_codes(oracle):
+    """On normal data fewer bits cost more error (NF2 > NF3 > NF4), a k-bit NormalFloat beats the k-bit integer grid of
+    Eq. 1 (the paper's argument for quantile quantisation), and codes >= 2^k never occur."""
+    rng = np.random.default_rng(16)
+    W = (rng.standard_normal((128, 512)) * 0.02).astype(np.float32)
+    err = {}
+    for name, k in (("nf2", 2), ("nf3", 3), ("nf4", 4)):
+        q = oracle.nf4_quantize(W, table=oracle.codebook4(name))
+        codes = np.concatenate([q["packed"] & 15, q["packed"] >> 4])
+        assert codes.max() == (1 << k) - 1 and codes.min() == 0
+        err[name] = np.abs(_bf16_f64(oracle.nf4_dequant(q)) - W).mean()
+    assert err["nf2"] > 1.5 * err["nf3"] > 1.5 * 1.5 * err["nf4"]
+    int3 = np.array([j / 3.0 for j in range(-3, 4)] + [1.0] * 9, np.float32)      # Eq. 1 with the range [-3, 3]
+    q = oracle.nf4_quantize(W, table=int3)
+    assert err["nf3"] < np.abs(_bf16_f64(oracle.nf4_dequant(q)) - W).mean()
