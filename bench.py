@@ -271,7 +271,8 @@ def main():
         # when the decision thresholds arrive at run time
         Wn = synth.normal_f32_device((d, d), synth.SIGMA_W, 424242)
         types = {}
-        for name, dt in (("nf4", ql.NF4), ("fp4_e2m1", ql.FP4_E2M1), ("fp4_e3m0", ql.FP4_E3M0), ("int4", ql.INT4)):
+        for name, dt in (("nf4", ql.NF4), ("fp4_e2m1", ql.FP4_E2M1), ("fp4_e3m0", ql.FP4_E3M0), ("int4", ql.INT4),
+                         ("nf3", ql.NF3), ("nf2", ql.NF2)):
             Wq_t = ql.qlora_quantize_4bit(Wn, dt)
             err = (ql.qlora_nf4_dequant(Wq_t).float() - Wn).abs().mean().item() / synth.SIGMA_W
             t = _time_ms(torch, lambda: ql.qlora_quantize_4bit(Wn, dt, out=Wq_t), 5)

@@ -113,10 +113,18 @@ typedef struct {
  * +-{0, 1/64, 1/32, ..., 1/2, 1}, each with two zeros -- and Int4 is Eq. 1 with the range [-7, 7]: j/7, 15 levels
  * (code 15 repeats the top value and is never produced).  Quantisation picks the nearest value, the lower code on an
  * exact tie, as for NF4. */
-enum { QLORA_NF4 = 0, QLORA_FP4_E2M1 = 1, QLORA_FP4_E3M0 = 2, QLORA_INT4 = 3, QLORA_INT8 = 4 };
+enum { QLORA_NF4 = 0, QLORA_FP4_E2M1 = 1, QLORA_FP4_E3M0 = 2, QLORA_INT4 = 3, QLORA_INT8 = 4, QLORA_NF3 = 5, QLORA_NF2 = 6 };
 
-/* The 16 values of a 4-bit data type, ascending, as fp32 (host array).  QLORA_ERR_UNSUPPORTED for an unknown type
- * and for QLORA_INT8, which has no table. */
+/* k-bit NormalFloat for k = 3 and 2 (Section 3 gives the construction for general k and prints the k = 4 table only):
+ * 2^(k-1) evenly spaced probabilities from 1/2 to p_max on the negative side (the zero among them dropped), 2^(k-1) + 1
+ * on the positive side, the normal quantiles divided by the top one, rounded to fp32.  p_max is not in the paper: the
+ * tail mass 1 - p_max = (1 / 2^(k+1) + 1 / (2^(k+1) - 2)) / 2 is the one that reproduces the printed k = 4 table.
+ * QLORA_NF3 and QLORA_NF2 are table types like the 4-bit ones: 16-entry tables whose entries from 2^k on repeat +1, the
+ * codes sit in the same 4-bit containers (codes >= 2^k are never produced), so they show the error of fewer levels,
+ * not a smaller footprint. */
+
+/* The 16 values of a table data type (the 4-bit ones, QLORA_NF3, QLORA_NF2), ascending, as fp32 (host array).
+ * QLORA_ERR_UNSUPPORTED for an unknown type and for QLORA_INT8, which has no table. */
 qlora_status qlora_codebook_4bit(int32_t dtype, float* values16);
 
 /* Byte sizes of the buffers of a quantised rows x cols tensor and of the scratch
@@ -151,7 +159,8 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
                                 uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
                                 void* scratch, size_t scratch_bytes, void* hip_stream);
 
-/* The same with one of the other 4-bit data types (Section 4); dtype = QLORA_NF4 is qlora_nf4_quantize.  The
+/* The same with one of the other table data types (Section 4's 4-bit ones, QLORA_NF3, QLORA_NF2); dtype = QLORA_NF4
+ * is qlora_nf4_quantize.  The
  * buffers, their sizes and the Double Quantization of the constants do not depend on the data type. */
 qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
                                  int32_t blocksize, int32_t dq_blocksize, int32_t dtype,

@@ -161,7 +161,7 @@ def nf4_alloc(rows, cols, device, blocksize=64, dq_blocksize=256, dtype=0) -> NF
     return w
 
 
-NF4, FP4_E2M1, FP4_E3M0, INT4, INT8 = 0, 1, 2, 3, 4
+NF4, FP4_E2M1, FP4_E3M0, INT4, INT8, NF3, NF2 = 0, 1, 2, 3, 4, 5, 6
 
 
 def qlora_quantize_int8(W, blocksize=64, dq_blocksize=256, scratch=None, stream=None, out=None) -> NF4Weight:
@@ -201,7 +201,7 @@ def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=N
     if out is None:
         out = nf4_alloc(rows, cols, dev, blocksize, dq_blocksize)
     assert (out.rows, out.cols, out.blocksize, out.dq_blocksize) == (rows, cols, blocksize, dq_blocksize)
-    assert 0 <= int(dtype) < INT8 and out.packed.numel() == rows * cols // 2
+    assert int(dtype) in (NF4, FP4_E2M1, FP4_E3M0, INT4, NF3, NF2) and out.packed.numel() == rows * cols // 2
     packed, code, c1, mean = out.packed, out.code, out.c1, out.mean
     if scratch is None:
         scratch = torch.empty(sb, dtype=torch.uint8, device=dev)

@@ -282,7 +282,7 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
 
 qlora_status qlora_codebook_4bit(int32_t dtype, float* values16) {
   if (!values16) return QLORA_ERR_NULL;
-  if (dtype < 0 || dtype >= qlora::kNumTypes4) return QLORA_ERR_UNSUPPORTED;
+  if (!qlora::is_table_type(dtype)) return QLORA_ERR_UNSUPPORTED;
   const qlora::Table4 t = qlora::table4_host(dtype);
   for (int i = 0; i < 16; ++i) values16[i] = t.v[i];
   return QLORA_OK;
@@ -295,7 +295,7 @@ qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
   const bool dq = dq_blocksize != 0;
   if (!W || !packed || !c1 || !scratch || (dq && (!c2_code || !c2_mean))) return QLORA_ERR_NULL;
   if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
-  if (dtype < 0 || dtype >= qlora::kNumTypes4) return QLORA_ERR_UNSUPPORTED;
+  if (!qlora::is_table_type(dtype)) return QLORA_ERR_UNSUPPORTED;
   size_t need = 0;
   qlora_nf4_sizes(rows, cols, blocksize, dq_blocksize, nullptr, nullptr, nullptr, &need);
   if (scratch_bytes < need) return QLORA_ERR_WORKSPACE;

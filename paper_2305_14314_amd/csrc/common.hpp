@@ -115,16 +115,54 @@ __device__ __forceinline__ uint32_t nf4_index(float x, const Nf4Bucket* table) {
 // fields (sign, exponent, mantissa; exponent field 0 = subnormal, no infinities or NaNs) divided by the largest
 // magnitude, which removes the exponent bias.  Tables are ascending; the float types hold zero twice (entries 7, 8),
 // Int4 has 15 levels and repeats the top one.  Thresholds are built as for NF4: midpoint rounded toward -infinity.
-constexpr int kNumTypes4 = 4;                // 0 NF4, 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4
+// data type ids: 0 NF4, 1 Float4 E2M1, 2 Float4 E3M0, 3 Int4
 // 8-bit integers (Eq. 1 and Eq. 2 as printed: q = round(127 / absmax * x), x^ = q * absmax / 127): one signed byte
 // per weight, no table; the constants absmax are stored like those of the 4-bit types.
 constexpr int kTypeInt8 = 4;
-constexpr int kNumTypes = 5;
+// k-bit NormalFloat for k = 3 and 2 (Section 3 states the construction for general k): 2^k values in a 16-entry table
+// whose tail repeats +1, stored in the 4-bit containers of the other types (codes >= 2^k never occur).
+constexpr int kTypeNF3 = 5, kTypeNF2 = 6;
+constexpr int kNumTypes = 7;
+inline bool is_table_type(int dtype) { return dtype >= 0 && dtype < kNumTypes && dtype != kTypeInt8; }
 struct Table4 { float v[16]; };
 struct Thresholds4 { float t[15]; };
 
+// Standard normal quantile for 1/2 <= p < 1 (host): Newton's iteration on Phi(x) = p from x = 0.  Phi is increasing
+// and concave on x >= 0, so the iterates rise monotonically to the root and converge quadratically.
+inline double normal_quantile_upper_host(double p) {
+  double x = 0.0;
+  for (int it = 0; it < 60; ++it) {
+    const double cdf = 0.5 * __builtin_erfc(-x * 0.70710678118654752440);
+    const double pdf = 0.39894228040143267794 * __builtin_exp(-0.5 * x * x);
+    const double dx = (p - cdf) / pdf;
+    x += dx;
+    if (__builtin_fabs(dx) < 1e-16 * (1.0 + x)) break;
+  }
+  return x;
+}
+
+// NFk: 2^(k-1) evenly spaced probabilities from 1/2 to p_max on the negative side (the zero is dropped), 2^(k-1) + 1
+// on the positive side, quantiles divided by the top one.  The paper gives no p_max; the tail mass
+// (1 / 2^(k+1) + 1 / (2^(k+1) - 2)) / 2 is the one that reproduces its printed 4-bit table.
+inline Table4 nfk_table_host(int k) {
+  Table4 tab{};
+  const int n_neg = 1 << (k - 1), n_pos = n_neg + 1, n = 1 << k;
+  const double two = (double)(2 * n);
+  const double p_max = 1.0 - 0.5 * (1.0 / two + 1.0 / (two - 2.0));
+  const double top = normal_quantile_upper_host(p_max);
+  for (int i = 1; i < n_neg - 1; ++i)
+    tab.v[n_neg - 1 - i] = (float)(-normal_quantile_upper_host(0.5 + (p_max - 0.5) * (double)i / (double)(n_neg - 1)) / top);
+  for (int i = 1; i < n_pos - 1; ++i)
+    tab.v[n_neg - 1 + i] = (float)(normal_quantile_upper_host(0.5 + (p_max - 0.5) * (double)i / (double)(n_pos - 1)) / top);
+  tab.v[0] = -1.0f;
+  tab.v[n_neg - 1] = 0.0f;
+  for (int i = n - 1; i < 16; ++i) tab.v[i] = 1.0f;
+  return tab;
+}
+
 inline Table4 table4_host(int dtype) {
   Table4 tab{};
+  if (dtype == kTypeNF3 || dtype == kTypeNF2) return nfk_table_host(dtype == kTypeNF3 ? 3 : 2);
   if (dtype == 0 || dtype == kTypeInt8) {        // Int8 reads no table
     for (int i = 0; i < 16; ++i) tab.v[i] = nf4_value(i);
   } else if (dtype == 3) {

@@ -167,10 +167,10 @@ def test_data_type_tables_and_their_validation(L, oracle):
     import numpy as np
     from paper_2305_14314_amd import qlora_codebook_4bit
     from paper_2305_14314_amd.binding import QloraError, qlora_nf4_view
-    for name, dtype in (("nf4", 0), ("fp4_e2m1", 1), ("fp4_e3m0", 2), ("int4", 3)):
+    for name, dtype in (("nf4", 0), ("fp4_e2m1", 1), ("fp4_e3m0", 2), ("int4", 3), ("nf3", 5), ("nf2", 6)):
         mine = np.array(qlora_codebook_4bit(dtype), np.float32)
         assert np.array_equal(mine.view(np.uint32), oracle.codebook4(name).view(np.uint32)), name
-    for bad in (-1, 4):
+    for bad in (-1, 4, 7):
         with pytest.raises(QloraError) as e:
             qlora_codebook_4bit(bad)
         assert e.value.status == -3
@@ -178,7 +178,7 @@ def test_data_type_tables_and_their_validation(L, oracle):
     assert L.qlora_codebook_4bit(0, None) == -1
     assert L.qlora_quantize_4bit(fake, 4, 64, 64, 256, 7, fake, fake, fake, fake, fake, 1 << 20, None) == -3
     assert L.qlora_quantize_4bit(None, 4, 64, 64, 256, 1, fake, fake, fake, fake, fake, 1 << 20, None) == -1
-    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256, 5, 0)
+    v = qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256, 7, 0)
     assert L.qlora_nf4_dequant(ctypes.byref(v), fake, None) == -3
     # Int8 is a data type of a view, but has no table and is not a 4-bit type
     assert L.qlora_quantize_4bit(fake, 4, 64, 64, 256, 4, fake, fake, fake, fake, fake, 1 << 20, None) == -3
@@ -201,8 +201,9 @@ def test_int8_sizes_and_validation(L):
     assert (pb + cb + c1b) * 8 / P == 8.5
     assert qlora_quant_sizes(8192, 8192, 64, 256, 0) == qlora_nf4_sizes(8192, 8192, 64, 256)
     with pytest.raises(QloraError) as e:
-        qlora_quant_sizes(64, 64, 64, 256, 5)
+        qlora_quant_sizes(64, 64, 64, 256, 7)
     assert e.value.status == -3
+    assert qlora_quant_sizes(8192, 8192, 64, 256, 5) == qlora_nf4_sizes(8192, 8192, 64, 256)   # NF3: 4-bit containers
     fake = ctypes.c_void_p(0x1000)
     q = L.qlora_quantize_int8
     assert q(None, 4, 64, 64, 256, fake, fake, fake, fake, fake, 1 << 20, None) == -1

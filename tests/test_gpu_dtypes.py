@@ -11,7 +11,7 @@ from test_gpu_linear import _check
 
 pytestmark = pytest.mark.gpu
 
-KINDS = [("fp4_e2m1", 1), ("fp4_e3m0", 2), ("int4", 3)]
+KINDS = [("fp4_e2m1", 1), ("fp4_e3m0", 2), ("int4", 3), ("nf3", 5), ("nf2", 6)]
 
 
 def _cases(oracle, synth, kind):
