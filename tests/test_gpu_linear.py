@@ -214,3 +214,63 @@ def test_random_shapes(oracle, synth, M, h, o, r):
     import paper_2305_14314_amd as ql
     L = synth.make_layer(0, 0, M=M, h=h, o=o, r=max(r, 16))
     _run_case(oracle, ql, L, f"random M={M} h={h} o={o} r={r}", with_lora=r > 0)
+
+
+def test_training_step_graph_replay(synth):
+    """The large-GEMM path under HIP graph capture: forward with T saved, backward with all three gradients, the
+    dropout variants with fp32 accumulation.  Every replay -- with eager work, scribbled workspace and synchronisations
+    in between -- reproduces the eager result bit for bit (the path holds kernels only: nothing a graph replays badly)."""
+    import paper_2305_14314_amd as ql
+    M, h, o, r, s, p = 300, 448, 576, 32, 0.5, 0.1
+    Wq = ql.qlora_nf4_quantize(synth.normal_f32_device((h, o), synth.SIGMA_W, 7100))
+    L1 = dev_bf16(synth.normal_bf16((h, r), 0.05, 7101))
+    L2 = dev_bf16(synth.normal_bf16((r, o), 0.05, 7102))
+    X = dev_bf16(synth.normal_bf16((M, h), 1.0, 7103))
+    dY = dev_bf16(synth.normal_bf16((M, o), 1.0, 7104))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7105)
+    mask = ql.pack_keep_mask(torch.rand(M, h, device="cuda", generator=gen) >= p)
+    nbytes = max(ql.qlora_linear_fwd_sizes(M, h, o, r), ql.qlora_linear_bwd_sizes(M, h, o, r),
+                 *ql.qlora_linear_dropout_sizes(M, h, o, r))
+    ws = ql.workspace_alloc(nbytes)
+    hdr = ql.binding.WORKSPACE_HEADER_BYTES
+    bufs = dict(Y=torch.empty(M, o, dtype=torch.bfloat16, device="cuda"), T=torch.empty(M, 2 * r, dtype=torch.bfloat16, device="cuda"),
+                dX=torch.empty(M, h, dtype=torch.bfloat16, device="cuda"), dL1=torch.empty_like(L1), dL2=torch.empty_like(L2),
+                Yd=torch.empty(M, o, dtype=torch.bfloat16, device="cuda"), dXd=torch.empty(M, h, dtype=torch.bfloat16, device="cuda"),
+                a1=torch.zeros(h, r, dtype=torch.float32, device="cuda"), a2=torch.zeros(r, o, dtype=torch.float32, device="cuda"))
+
+    def step():
+        ql.qlora_linear_fwd(X, Wq, L1, L2, s, Y=bufs["Y"], T_save=bufs["T"], workspace=ws)
+        ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s, T_saved=bufs["T"], dX=bufs["dX"], dL1=bufs["dL1"], dL2=bufs["dL2"],
+                            workspace=ws)
+        ql.qlora_linear_fwd_dropout(X, Wq, L1, L2, s, mask, p, Y=bufs["Yd"], workspace=ws)
+        ql.qlora_linear_bwd_dropout(dY, X, Wq, L1, L2, s, mask, p, dX=bufs["dXd"], dL1_acc=bufs["a1"], dL2_acc=bufs["a2"],
+                                    workspace=ws)
+
+    def clear():
+        for k, t in bufs.items():
+            t.zero_()
+
+    clear()
+    step()
+    torch.cuda.synchronize()
+    want = {k: t.clone() for k, t in bufs.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for it in range(3):
+        clear()
+        ws[hdr:].random_(0, 255)                             # stale contents behind the counter header must not matter
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k, t in bufs.items():
+            assert torch.equal(t.view(torch.int32 if t.dtype == torch.float32 else torch.int16),
+                               want[k].view(torch.int32 if t.dtype == torch.float32 else torch.int16)), f"replay {it}: {k} differs"
+        assert int(ws[:hdr].max()) == 0
