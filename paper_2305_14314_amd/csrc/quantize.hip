@@ -16,8 +16,18 @@
 
 namespace qlora {
 
+// Loads in flight: kQUnroll float4 per lane, kQWgsPerCu workgroups per CU (grid-stride beyond that).  Measured on
+// 8192 x 22016 tensors read cold (GB/s of algorithmic bytes): unroll x workgroups 2 x 6 and 3 x 4: 4.42 - 4.45;
+// 1 x 6: 4.40; 2 x 8: 4.28; 4 x 16 (the first choice): 4.06; 2 x 32: 3.83 -- past ~48 KB in flight per CU more requests
+// only queue up in front of the memory channels.
+#ifndef QL_Q_UNROLL
+#define QL_Q_UNROLL 2
+#endif
+#ifndef QL_Q_WGS_PER_CU
+#define QL_Q_WGS_PER_CU 6
+#endif
 constexpr int kQThreads = 256;
-constexpr int kQUnroll = 4;
+constexpr int kQUnroll = QL_Q_UNROLL;
 
 __global__ void zero_bins_kernel(unsigned long long* bins) { bins[threadIdx.x] = 0ull; }
 
@@ -41,8 +51,7 @@ __global__ __launch_bounds__(kQThreads) void quantize_nf4_kernel(
   }
   __syncthreads();
 
-  // kQUnroll independent float4 loads are issued before any is used: a wave keeps 4 KB in flight, which
-  // the HBM latency-bandwidth product needs at 8 waves per SIMD.
+  // kQUnroll independent float4 loads are issued before any is used.
   const int64_t stride = (int64_t)gridDim.x * kQThreads;
   for (int64_t v0 = (int64_t)blockIdx.x * kQThreads + threadIdx.x; v0 < n_vec4; v0 += kQUnroll * stride) {
     float4 wv[kQUnroll];
@@ -203,7 +212,7 @@ hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* 
   float* c2 = dq ? (float*)((char*)scratch + 256 * sizeof(unsigned long long)) : c1;
   const int64_t n_vec4 = elems / 4;
   int64_t blocks = (n_vec4 + kQThreads - 1) / kQThreads;
-  const int64_t cap = 256 * 16;                                      // 16 workgroups per CU
+  const int64_t cap = 256 * QL_Q_WGS_PER_CU;                         // workgroups per CU
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(zero_bins_kernel, dim3(1), dim3(256), 0, st, bins);
   if (dtype == 0)
