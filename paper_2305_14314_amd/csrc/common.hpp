@@ -162,7 +162,10 @@ inline Table4 nfk_table_host(int k) {
 
 inline Table4 table4_host(int dtype) {
   Table4 tab{};
-  if (dtype == kTypeNF3 || dtype == kTypeNF2) return nfk_table_host(dtype == kTypeNF3 ? 3 : 2);
+  if (dtype == kTypeNF3 || dtype == kTypeNF2) {              // derived once per process, not per launch
+    static const Table4 nf3 = nfk_table_host(3), nf2 = nfk_table_host(2);
+    return dtype == kTypeNF3 ? nf3 : nf2;
+  }
   if (dtype == 0 || dtype == kTypeInt8) {        // Int8 reads no table
     for (int i = 0; i < 16; ++i) tab.v[i] = nf4_value(i);
   } else if (dtype == 3) {
