@@ -57,10 +57,7 @@ namespace {
 constexpr int BM = 256, BK = 64, NSLOT = 5;                  // BN is 256, or 128 for the tail launch (template parameter)
 constexpr int kSlot = BM * BK * 2;                           // 32 KB: one 256-row operand tile
 constexpr int GM = 4;                                       // tile-rows per raster group
-#ifndef QL_GEMM_WAVES
-#define QL_GEMM_WAVES 4
-#endif
-constexpr int kMainWaves = QL_GEMM_WAVES;                    // waves per workgroup of the main (BN = 256) kernel
+constexpr int kMainWaves = 4;                                // waves per workgroup of the main (BN = 256) kernel
 
 typedef __attribute__((address_space(3))) char lchar;
 
@@ -112,7 +109,7 @@ __device__ __forceinline__ void wait_frags(Frags<8>& f) {
 // BN = 256 is the main configuration.  BN = 128 serves the columns left over when the 256-wide tiles do not fill
 // a whole number of rounds of the 256 CUs: half-width tiles finish that last, partly filled round in half the time.
 // NW = waves per workgroup, laid out 2 x NW/2: wave tiles are 128 x 128 (main configuration, 4 waves) or 128 x 64
-// (the half-width tail; also 8 waves on the 256-wide tile, the QL_GEMM_WAVES = 8 build option).
+// (the half-width tail).
 template <int BN, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   constexpr int WN = BN / (NW / 2);                          // wave tile width: 64, or 128 for 4 waves on a 256-wide tile

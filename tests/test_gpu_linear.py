@@ -14,8 +14,8 @@ TOL = 2e-2
 def _check(got_bits, ref, tag, few_terms=False):
     """max|err| <= 2e-2 * rms(ref).  few_terms: the output is a sum of only a handful of products
     (adapter gradients at a few tokens), its distribution is heavy-tailed and the largest entries'
-    own bf16 rounding (2^-9 relative) can exceed 2e-2 * rms; such entries must then be within one
-    bf16 rounding step of the reference instead."""
+    own bf16 rounding can exceed 2e-2 * rms; such entries must then be within one bf16 step (2^-8
+    relative, the bound tested below) of the reference instead.  Prints how many entries needed it."""
     got = bits_f64(got_bits).reshape(ref.shape)
     rms = np.sqrt((ref ** 2).mean())
     aerr = np.abs(got - ref)
@@ -23,6 +23,9 @@ def _check(got_bits, ref, tag, few_terms=False):
     print(f"  {tag}: max|err|/rms = {err / rms if rms > 0 else 0.0:.4f}", flush=True)
     assert np.isfinite(got).all(), tag
     if few_terms:
+        relaxed = int(np.count_nonzero(aerr > TOL * rms))
+        if relaxed:
+            print(f"  {tag}: {relaxed} of {aerr.size} entries beyond 2e-2 * rms, held to one bf16 step", flush=True)
         assert np.all(aerr <= np.maximum(TOL * rms, 2.0 ** -8 * np.abs(ref))), tag
         return
     assert err <= TOL * rms, f"{tag}: max|err| {err:.4g} > {TOL} * rms {rms:.4g}"

@@ -15,7 +15,7 @@ def test_nf4_index_schemes_agree(tmp_path):
     if not (os.path.exists(hipcc) or shutil.which(hipcc)):
         pytest.skip("hipcc not available")
     exe = str(tmp_path / "nf4_index_check")
-    src = os.path.join(CSRC, "host_checks", "nf4_index_check.cpp")
+    src = os.path.join(ROOT, "tests", "host_checks", "nf4_index_check.cpp")
     subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-ffp-contract=off", "-x", "hip", "-I", CSRC,
                     src, "-o", exe], check=True, capture_output=True)
     out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout

@@ -683,6 +683,33 @@ def test_int8_is_equation_1_and_2(oracle):
     assert e_dq < 0.2 * e_nf4                                            # 8 bits against 4
 
 
+def test_int8_dq_constants_are_those_of_double_dequant(oracle):
+    """With Double Quantization the 8-bit-integer path rebuilds its constants with the same two fp32 steps as
+    doubleDequant (Eq. 6): bit for bit the c2hat that nf4_dequant reports for the NF4 quantisation of the same tensor
+    (itself pinned against numpy / torch pieces above), and again from numpy fp32 pieces here -- table value / 448
+    times c1, rounded, plus mean, rounded.  The dequantised weights are then q * fl32(c2hat / 127) with the library
+    bf16 cast."""
+    import torch
+    rng = np.random.default_rng(16)
+    W = (rng.standard_normal((96, 512)) * 0.02).astype(np.float32)
+    W[5] *= 40.0                                                          # a run of constants far from the mean
+    qd = oracle.int8_quantize(W)
+    qn = oracle.nf4_quantize(W)
+    _, c2hat_nf4 = oracle.nf4_dequant(qn, return_c2hat=True)
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()   # library E4M3 decode
+    unit = (lib / np.float32(448)).astype(np.float32)
+    c1 = np.repeat(qd["c1"], 256)[:qd["code"].size]
+    c2hat_np = ((unit[qd["code"]] * c1).astype(np.float32) + np.float32(qd["mean"])).astype(np.float32)
+    np.testing.assert_array_equal(c2hat_np.view(np.uint32), c2hat_nf4.view(np.uint32))
+    step = (c2hat_np / np.float32(127)).astype(np.float32)
+    ref = torch.from_numpy((qd["q8"].reshape(-1, 64).astype(np.float32) * step[:, None]).astype(np.float32))
+    np.testing.assert_array_equal(oracle.int8_dequant(qd).reshape(-1, 64),
+                                  ref.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    # a planted mistake in the constants (one fused rounding instead of two) must show: the pin is not vacuous
+    fused = (unit[qd["code"]].astype(np.float64) * c1.astype(np.float64) + np.float64(qd["mean"])).astype(np.float32)
+    assert np.any(fused.view(np.uint32) != c2hat_np.view(np.uint32))
+
+
 def test_int8_ties_and_clamp(oracle):
     """A block whose absmax is 127 has c = 1, so the codes are the inputs rounded: halves go to the even neighbour,
     and the sign is kept."""
