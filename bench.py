@@ -11,7 +11,8 @@ Prints ONE JSON line: the metric is fwd+bwd TFLOP/s (algorithmic FLOPs 4*M*h*o +
 linear); `roofline` is the main MFMA GEMM kernel against the bf16 dense peak, timed with HIP events
 around every launch inside the timed region; `cpu_baseline` is the fp64 CPU oracle on a bounded
 sample of the same workload.  The other rows of the path (quantise, standalone dequant, few-token
-GEMV) and the main GEMM per shape are measured after the timed region and reported in `extra`.
+GEMV), the 7B- and 13B-shaped blocks and the main GEMM per shape are measured after the timed region
+and reported in `extra`.
 """
 from __future__ import annotations
 
@@ -28,6 +29,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 PEAK_HBM_GBS = 8000.0
+SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes")
 
 
 def _ensure_built():
@@ -85,9 +87,9 @@ def _read_traffic():
     return None
 
 
-def cpu_baseline(seconds_target=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the workload:
-    forward and input-gradient rows of the 8192 x 8192 linear (fp64, OpenMP)."""
+def cpu_baseline(seconds_target=16.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload: forward and input-gradient
+    rows of the 8192 x 8192 linear (fp64, OpenMP), and quantise + doubleDequant of one 8192 x 22016 tensor."""
     import oracle
     from paper_2305_14314_amd import synth
     h = o = 8192
@@ -108,9 +110,98 @@ def cpu_baseline(seconds_target=20.0):
         secs += time.perf_counter() - t0
         flops += 2 * (2.0 * rows * h * o + 2.0 * rows * r * (h + o))
         reps += 1
+    del W, q, What
+    Wg = synth.normal_f32((8192, 22016), synth.SIGMA_W, synth.tensor_seed(3, 4, "W"))
+    t0 = time.perf_counter()
+    qg = oracle.nf4_quantize(Wg)
+    t_q = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.nf4_dequant(qg)
+    t_d = time.perf_counter() - t0
+    el = Wg.size
     return {"value": flops / secs * 1e-12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{reps} x (Y and dX for {rows} token rows of the 8192x8192 linear, r=64), fp64 loops, "
-                      f"{secs:.1f} s"}
+                      f"{secs:.1f} s",
+            "quantize_dequant_8192x22016": {"quantize_s": round(t_q, 3), "dequant_s": round(t_d, 3),
+                                            "quantize_GBps": round(el * 4.5159 / t_q * 1e-9, 3),
+                                            "dequant_GBps": round(el * 2.5159 / t_d * 1e-9, 3)}}
+
+
+class Block:
+    """Resident operands of one workload (a decoder block's seven linears at M tokens) and its fwd+bwd step."""
+
+    def __init__(self, torch, ql, synth, cfg_index, pool_blocks, dev, time_quant=False):
+        cfg = synth.CONFIGS[cfg_index]
+        self.torch, self.ql = torch, ql
+        self.M, self.r = cfg["M"], cfg["r"]
+        self.s = cfg["alpha"] / self.r
+        self.linears = cfg["linears"]
+        M, r, linears = self.M, self.r, self.linears
+        widths = sorted({w for hw in linears for w in hw})
+        # weights are drawn on the device, one tensor at a time, quantised into preallocated buffers and discarded;
+        # the quantise row is timed here: HIP events around the calls of a block, back to back on the stream
+        self.pool = [[ql.nf4_alloc(h, o, dev) for h, o in linears] for _ in range(pool_blocks)]
+        self.t_quant_ms, self.quant_elems = 0.0, 0
+        scratch = torch.empty(max(ql.qlora_nf4_sizes(h, o)[3] for h, o in linears), dtype=torch.uint8, device=dev)
+        for b in range(pool_blocks):
+            Ws = [synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(cfg_index, li, "W") + b, dev)
+                  for li, (h, o) in enumerate(linears)]
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for li in range(len(linears)):
+                ql.qlora_nf4_quantize(Ws[li], scratch=scratch, out=self.pool[b][li])
+            e1.record()
+            torch.cuda.synchronize()
+            if b > 0 and time_quant:                            # the first block warms up
+                self.t_quant_ms += e0.elapsed_time(e1)
+                self.quant_elems += sum(h * o for h, o in linears)
+            del Ws
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.BASE_SEED + (0 if cfg_index == 3 else cfg_index))
+        self.rnd = lambda *shape, sd=1.0: (torch.randn(*shape, device=dev, dtype=torch.float32, generator=gen) * sd).to(
+            torch.bfloat16)
+        rnd = self.rnd
+        empty = lambda *shape: torch.empty(*shape, device=dev, dtype=torch.bfloat16)
+        self.X = {w: rnd(M, w) for w in widths}
+        self.dY = {w: rnd(M, w) for w in widths}
+        self.L1 = [rnd(h, r, sd=cfg["sigma_l"]) for h, o in linears]
+        self.L2 = [rnd(r, o, sd=cfg["sigma_l"]) for h, o in linears]
+        self.Y = {w: empty(M, w) for w in widths}
+        self.dX = {w: empty(M, w) for w in widths}
+        self.T = [empty(M, 2 * r) for _ in linears]
+        self.dL1 = [torch.empty_like(a) for a in self.L1]
+        self.dL2 = [torch.empty_like(a) for a in self.L2]
+        ws_bytes = max(max(ql.qlora_linear_fwd_sizes(M, h, o, r), ql.qlora_linear_bwd_sizes(M, h, o, r)) for h, o in linears)
+        self.ws = ql.workspace_alloc(ws_bytes, dev)
+        self.flops_step = sum(4.0 * M * h * o + 6.0 * M * r * (h + o) for h, o in linears)
+
+    def step(self, k):
+        ql, s = self.ql, self.s
+        block = self.pool[k % len(self.pool)]
+        for li, (h, o) in enumerate(self.linears):
+            ql.qlora_linear_fwd(self.X[h], block[li], self.L1[li], self.L2[li], s, Y=self.Y[o], T_save=self.T[li],
+                                workspace=self.ws)
+        for li in reversed(range(len(self.linears))):
+            h, o = self.linears[li]
+            ql.qlora_linear_bwd(self.dY[o], self.X[h], block[li], self.L1[li], self.L2[li], s, T_saved=self.T[li],
+                                dX=self.dX[h], dL1=self.dL1[li], dL2=self.dL2[li], workspace=self.ws)
+
+    def timed_steps(self, steps, warmup, first=0):
+        """(ms per step from the host clock, GEMM ms, launches, FLOPs from HIP events around every main-GEMM launch)"""
+        torch, ql = self.torch, self.ql
+        for k in range(warmup):
+            self.step(first + k)
+        torch.cuda.synchronize()
+        ql.qlora_profile_gemm(True)
+        t0 = time.perf_counter()
+        for k in range(steps):
+            self.step(first + warmup + k)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ql.qlora_profile_gemm(False)
+        gemm_ms, launches, gemm_flops = ql.qlora_profile_gemm_read()
+        return (t1 - t0) * 1e3 / steps, gemm_ms, launches, gemm_flops
 
 
 def main():
@@ -121,6 +212,9 @@ def main():
     ap.add_argument("--pool-blocks", type=int, default=80, help="differently-seeded weight blocks resident in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--sections", default="all",
+                    help="comma-separated parts of `extra` to run, of " + ",".join(SECTIONS) + " (default all); "
+                         "profiling runs name the part whose kernels they want")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy, the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -129,6 +223,7 @@ def main():
         sys.stderr.write("bench.py: this build is single-GPU; --gpus must be 1 (tokens would shard across GPUs with one "
                          "sum of the adapter gradients per step; that path is not built)\n")
         sys.exit(2)
+    want = lambda name: not args.no_extra and (args.sections == "all" or name in args.sections.split(","))
 
     _ensure_built()
     import torch
@@ -141,60 +236,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    cfg = synth.CONFIGS[3]
-    M, r = cfg["M"], cfg["r"]
-    s = cfg["alpha"] / r
-    linears = cfg["linears"]
+    B = Block(torch, ql, synth, 3, args.pool_blocks, dev, time_quant=True)
+    M, r, s, linears, pool = B.M, B.r, B.s, B.linears, B.pool
     d, ffn = 8192, 22016
-
-    # ---- resident pool: quantise `pool_blocks` blocks of 7 tensors with this library -------------
-    # Weights are drawn on the device, one tensor at a time (a block is 3.2 GB of fp32), quantised into
-    # preallocated buffers and discarded.  The quantise row is timed here: HIP events around each call of a
-    # block, calls of one block back to back on the stream (the fp32 sources of a block are resident first).
-    pool = [[ql.nf4_alloc(h, o, dev) for h, o in linears] for _ in range(args.pool_blocks)]
-    t_quant_ms, quant_elems = 0.0, 0
-    scratch = torch.empty(max(ql.qlora_nf4_sizes(h, o)[3] for h, o in linears), dtype=torch.uint8, device=dev)
-    for b in range(args.pool_blocks):
-        Ws = [synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(3, li, "W") + b, dev)
-              for li, (h, o) in enumerate(linears)]
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for li in range(len(linears)):
-            ql.qlora_nf4_quantize(Ws[li], scratch=scratch, out=pool[b][li])
-        e1.record()
-        torch.cuda.synchronize()
-        if b > 0:                                       # the first block warms up
-            t_quant_ms += e0.elapsed_time(e1)
-            quant_elems += sum(h * o for h, o in linears)
-        del Ws
-
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(synth.BASE_SEED)
-    rnd = lambda *shape, sd=1.0: (torch.randn(*shape, device=dev, dtype=torch.float32, generator=gen) * sd).to(
-        torch.bfloat16)
-    X = {d: rnd(M, d), ffn: rnd(M, ffn)}
-    dY = {d: rnd(M, d), ffn: rnd(M, ffn)}
-    L1 = [rnd(h, r, sd=cfg["sigma_l"]) for h, o in linears]
-    L2 = [rnd(r, o, sd=cfg["sigma_l"]) for h, o in linears]
-    Y = {d: torch.empty(M, d, device=dev, dtype=torch.bfloat16), ffn: torch.empty(M, ffn, device=dev, dtype=torch.bfloat16)}
-    dX = {d: torch.empty(M, d, device=dev, dtype=torch.bfloat16), ffn: torch.empty(M, ffn, device=dev, dtype=torch.bfloat16)}
-    T = [torch.empty(M, 2 * r, device=dev, dtype=torch.bfloat16) for _ in linears]
-    dL1 = [torch.empty_like(a) for a in L1]
-    dL2 = [torch.empty_like(a) for a in L2]
-    ws_bytes = max(max(ql.qlora_linear_fwd_sizes(M, h, o, r), ql.qlora_linear_bwd_sizes(M, h, o, r)) for h, o in linears)
-    ws = ql.workspace_alloc(ws_bytes, dev)
-
-    def step(k):
-        block = pool[k % len(pool)]
-        for li, (h, o) in enumerate(linears):
-            ql.qlora_linear_fwd(X[h], block[li], L1[li], L2[li], s, Y=Y[o], T_save=T[li], workspace=ws)
-        for li in reversed(range(len(linears))):
-            h, o = linears[li]
-            ql.qlora_linear_bwd(dY[o], X[h], block[li], L1[li], L2[li], s, T_saved=T[li], dX=dX[h], dL1=dL1[li],
-                                dL2=dL2[li], workspace=ws)
-
-    flops_step = sum(4.0 * M * h * o + 6.0 * M * r * (h + o) for h, o in linears)
+    X, dY, L1, L2, Y, dX, T, ws = B.X, B.dY, B.L1, B.L2, B.Y, B.dX, B.T, B.ws
+    flops_step = B.flops_step
 
     if args.pmc_calibration:
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -203,20 +249,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for k in range(args.warmup):
-        step(k)
-    torch.cuda.synchronize()
-    ql.qlora_profile_gemm(True)
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(args.warmup + k)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ql.qlora_profile_gemm(False)
-    gemm_ms, gemm_launches, gemm_flops = ql.qlora_profile_gemm_read()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step, gemm_ms, gemm_launches, gemm_flops = B.timed_steps(args.steps, args.warmup)
     tflops = flops_step / (ms_per_step * 1e-3) * 1e-12
-
     achieved = gemm_flops / (gemm_ms * 1e-3) * 1e-12 if gemm_ms > 0 else 0.0
     out = {
         "metric": "QLoRA linear fwd+bwd TFLOP/s (% bf16 MFMA peak); 4-bit GEMV HBM GB/s",
@@ -229,28 +263,31 @@ def main():
                    "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": _read_traffic(), "launches": gemm_launches,
+                     "traffic": _read_traffic(),
+                     "traffic_source": "profiles/gemm_nt_llama65b_pmc.txt (rocprofv3 --pmc runs of this command, "
+                                       "committed; not measured in this run)",
+                     "launches": gemm_launches,
                      "avg_launch_ms": round(gemm_ms / max(1, gemm_launches), 5),
                      "flops_per_launch": gemm_flops / max(1, gemm_launches)},
     }
 
     extra = {}
-    if not args.no_extra:
+    if want("plain"):
         # the same steps without the HIP events around the GEMM launches: each recorded event is a marker of its own
         # on the stream and costs a bubble of 4-5 us before and after the kernel it brackets (28 per step)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(args.steps):
-            step(args.warmup + args.steps + k)
+            B.step(args.warmup + args.steps + k)
         torch.cuda.synchronize()
         ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
         extra["step_without_gemm_events"] = {"ms_per_step": round(ms_plain, 4),
                                              "TFLOPs": round(flops_step / (ms_plain * 1e-3) * 1e-12, 2)}
-        if quant_elems:
-            extra["quantize"] = {"GBps": round(quant_elems * 4.5159 / (t_quant_ms * 1e-3) * 1e-9, 1),
-                                 "frac_hbm": round(quant_elems * 4.5159 / (t_quant_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
-                                 "elements": quant_elems, "ms": round(t_quant_ms, 3),
-                                 "bytes_per_element": 4.5159}
+    if want("quantize") and B.quant_elems:
+        gbs_q = B.quant_elems * 4.5159 / (B.t_quant_ms * 1e-3) * 1e-9
+        extra["quantize"] = {"GBps": round(gbs_q, 1), "frac_hbm": round(gbs_q / PEAK_HBM_GBS, 4),
+                             "elements": B.quant_elems, "ms": round(B.t_quant_ms, 3), "bytes_per_element": 4.5159}
+    if want("dequant"):
         # standalone doubleDequant over the pool (cold weights): 0.5159 B read + 2 B written per element
         outb = torch.empty(ffn * d, dtype=torch.bfloat16, device=dev)
         k = [0]
@@ -266,6 +303,7 @@ def main():
                             "frac_hbm": round(el * 2.5159 / (t * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                             "bytes_per_element": 2.5159}
         del outb
+    if want("types"):
         # the data types of the paper's comparison (Section 4) on one 8192 x 8192 N(0, 0.02) tensor: round-trip error
         # of quantise + doubleDequant in units of sigma (NF4 is the smallest), and the rate of the quantise pass
         # when the decision thresholds arrive at run time
@@ -296,6 +334,7 @@ def main():
         del Wq_t, Wd_t
         del Wn
         extra["data_types"] = types
+    if want("dropout"):
         # the training-loop variants of the same step (same pool, same shapes): LoRA dropout at the rate the paper
         # uses for 65B (seeded keep-masks, one per input width) and adapter gradients accumulated in fp32
         p_drop = 0.05
@@ -321,61 +360,92 @@ def main():
         extra["step_with_dropout_and_fp32_accumulation"] = {
             "ms_per_step": round(t, 4), "TFLOPs": round(flops_step / (t * 1e-3) * 1e-12, 2), "p": p_drop}
         del masks, ws_drop, a1, a2
+    if want("gemv"):
         # few-token regime (workload configs[4]): forward and input gradient at 1, 4, 16 tokens
         gemv = {}
+        rnd = B.rnd
         for m in cfg_few_tokens():
             Xs = {d: rnd(m, d), ffn: rnd(m, ffn)}
             Ys = {d: torch.empty(m, d, device=dev, dtype=torch.bfloat16),
                   ffn: torch.empty(m, ffn, device=dev, dtype=torch.bfloat16)}
+            hs, os_ = [h for h, o in linears], [o for h, o in linears]
             wsz = max(max(ql.qlora_linear_fwd_sizes(m, h, o, r), ql.qlora_linear_bwd_sizes(m, h, o, r))
                       for h, o in linears)
             wsz = max(wsz, ql.qlora_linear_fwd_multi_sizes(m, d, [d] * 3, [r] * 3),
-                      ql.qlora_linear_fwd_multi_sizes(m, d, [ffn] * 2, [r] * 2))
+                      ql.qlora_linear_fwd_multi_sizes(m, d, [ffn] * 2, [r] * 2),
+                      ql.qlora_linear_list_sizes(m, hs, os_, [r] * 7, False),
+                      ql.qlora_linear_list_sizes(m, hs, os_, [r] * 7, True))
             wss = ws[:wsz]
             kk = [0]
             Yqkv = [torch.empty(m, d, device=dev, dtype=torch.bfloat16) for _ in range(3)]
             Ygu = [torch.empty(m, ffn, device=dev, dtype=torch.bfloat16) for _ in range(2)]
+            Yl = [torch.empty(m, o, device=dev, dtype=torch.bfloat16) for h, o in linears]
+            dXl = [torch.empty(m, h, device=dev, dtype=torch.bfloat16) for h, o in linears]
+            Xl = [Xs[h] for h, o in linears]
+            dYl = [Xs[o] for h, o in linears]
+
+            def next_block():
+                blk = pool[kk[0] % len(pool)]
+                kk[0] += 1
+                return blk
 
             def few_fwd_grouped():
                 # the layers of a block that read the same input in one launch each: q/k/v, then o, gate/up, down
-                blk = pool[kk[0] % len(pool)]
-                kk[0] += 1
+                blk = next_block()
                 ql.qlora_linear_fwd_multi(Xs[d], blk[0:3], L1[0:3], L2[0:3], [s] * 3, Ys=Yqkv, workspace=wss)
                 ql.qlora_linear_fwd(Xs[d], blk[3], L1[3], L2[3], s, Y=Ys[d], workspace=wss)
                 ql.qlora_linear_fwd_multi(Xs[d], blk[4:6], L1[4:6], L2[4:6], [s] * 2, Ys=Ygu, workspace=wss)
                 ql.qlora_linear_fwd(Xs[ffn], blk[6], L1[6], L2[6], s, Y=Ys[d], workspace=wss)
 
             def few_fwd():
-                blk = pool[kk[0] % len(pool)]
-                kk[0] += 1
+                blk = next_block()
                 for li, (h, o) in enumerate(linears):
                     ql.qlora_linear_fwd(Xs[h], blk[li], L1[li], L2[li], s, Y=Ys[o], workspace=wss)
 
             def few_bwd():
-                blk = pool[kk[0] % len(pool)]
-                kk[0] += 1
+                blk = next_block()
                 for li, (h, o) in enumerate(linears):
                     ql.qlora_linear_bwd(Xs[o], None, blk[li], L1[li], L2[li], s, dX=Ys[h], need_dL=False,
                                         workspace=wss)
+
+            def few_fwd_list():                              # the block's seven linears as one persistent launch
+                ql.qlora_linear_fwd_list(Xl, next_block(), L1, L2, [s] * 7, Ys=Yl, workspace=wss)
+
+            def few_bwd_list():
+                ql.qlora_linear_bwd_list(dYl, next_block(), L1, L2, [s] * 7, dXs=dXl, workspace=wss)
+
             bytes_block = sum(h * o * 0.51587 for h, o in linears)
+            gbs = lambda t_ms: bytes_block / (t_ms * 1e-3) * 1e-9
             tfe = _time_ms(torch, few_fwd, 2 * len(pool))
             tbe = _time_ms(torch, few_bwd, 2 * len(pool))
-            kk[0] = 0
-            tf = _time_graph_ms(torch, few_fwd, len(pool))
-            kk[0] = 0
-            tb = _time_graph_ms(torch, few_bwd, len(pool))
-            kk[0] = 0
-            tg = _time_graph_ms(torch, few_fwd_grouped, len(pool))
-            gemv[f"tokens_{m}"] = {"fwd_GBps": round(bytes_block / (tf * 1e-3) * 1e-9, 1),
-                                   "bwd_dx_GBps": round(bytes_block / (tb * 1e-3) * 1e-9, 1),
-                                   "fwd_frac_hbm": round(bytes_block / (tf * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
-                                   "bwd_dx_frac_hbm": round(bytes_block / (tb * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
-                                   "fwd_us_per_linear": round(tf * 1e3 / 7, 2), "bwd_us_per_linear": round(tb * 1e3 / 7, 2),
-                                   "fwd_grouped_GBps": round(bytes_block / (tg * 1e-3) * 1e-9, 1),
-                                   "fwd_grouped_frac_hbm": round(bytes_block / (tg * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
-                                   "fwd_grouped_us_per_block": round(tg * 1e3, 2),
-                                   "fwd_eager_GBps": round(bytes_block / (tfe * 1e-3) * 1e-9, 1),
-                                   "bwd_dx_eager_GBps": round(bytes_block / (tbe * 1e-3) * 1e-9, 1)}
+            res = {}
+            for name, fn in (("single", few_fwd), ("single_bwd", few_bwd), ("grouped", few_fwd_grouped),
+                             ("list", few_fwd_list), ("list_bwd", few_bwd_list)):
+                kk[0] = 0
+                res[name] = _time_graph_ms(torch, fn, len(pool))
+            # the headline few-token figures are the list launches: one call per block and direction
+            gemv[f"tokens_{m}"] = {"fwd_GBps": round(gbs(res["list"]), 1), "bwd_dx_GBps": round(gbs(res["list_bwd"]), 1),
+                                   "fwd_frac_hbm": round(gbs(res["list"]) / PEAK_HBM_GBS, 4),
+                                   "bwd_dx_frac_hbm": round(gbs(res["list_bwd"]) / PEAK_HBM_GBS, 4),
+                                   "fwd_us_per_block": round(res["list"] * 1e3, 2),
+                                   "bwd_us_per_block": round(res["list_bwd"] * 1e3, 2),
+                                   "fwd_single_calls_GBps": round(gbs(res["single"]), 1),
+                                   "fwd_single_calls_frac_hbm": round(gbs(res["single"]) / PEAK_HBM_GBS, 4),
+                                   "bwd_dx_single_calls_GBps": round(gbs(res["single_bwd"]), 1),
+                                   "bwd_dx_single_calls_frac_hbm": round(gbs(res["single_bwd"]) / PEAK_HBM_GBS, 4),
+                                   "fwd_single_us_per_linear": round(res["single"] * 1e3 / 7, 2),
+                                   "bwd_single_us_per_linear": round(res["single_bwd"] * 1e3 / 7, 2),
+                                   "fwd_grouped_GBps": round(gbs(res["grouped"]), 1),
+                                   "fwd_grouped_frac_hbm": round(gbs(res["grouped"]) / PEAK_HBM_GBS, 4),
+                                   "fwd_grouped_us_per_block": round(res["grouped"] * 1e3, 2),
+                                   "fwd_eager_GBps": round(gbs(tfe), 1), "bwd_dx_eager_GBps": round(gbs(tbe), 1)}
+        extra["gemv"] = {"bytes_per_weight": 0.51587, "note": "packed + 8-bit constants + c1 traffic only; weights "
+                         "cycle through the resident pool; one pass over the pool captured in a HIP graph (the eager "
+                         "figures include Python launch cost); fwd / bwd_dx: the seven linears of a block as ONE "
+                         "launch (qlora_linear_fwd_list / _bwd_list, every layer with its own input); single_calls: "
+                         "seven launches; grouped: q/k/v and gate/up, which read the same input, as one launch each "
+                         "(4 launches per block)", **gemv}
+    if want("gemm_shapes"):
         # the main GEMM alone, per shape (dX = dY What^T, no adapter), beside torch.matmul on the same operands
         # (the vendor GEMM library, for context: same shape, same data, same NT layout)
         by_shape = {}
@@ -398,10 +468,21 @@ def main():
                                            "torch_matmul_TFLOPs": round(2.0 * M * h * o / (t_lib * 1e-3) * 1e-12, 1)}
             del Wd
         extra["gemm_by_shape"] = by_shape
-        extra["gemv"] = {"bytes_per_weight": 0.51587, "note": "packed + 8-bit constants + c1 traffic only; weights "
-                         "cycle through the resident pool; one pass over the pool captured in a HIP graph "
-                         "(the eager figures include Python launch cost); fwd_grouped runs q/k/v and gate/up, which read the "
-                         "same input, as one launch each (4 launches per block instead of 7)", **gemv}
+    if want("configs"):
+        # the 7B- and 13B-shaped blocks at 8192 tokens (workloads configs[1], configs[2]): the same fwd + bwd step
+        cfgs = {}
+        for ci in (1, 2):
+            Bc = Block(torch, ql, synth, ci, min(8, args.pool_blocks), dev)
+            ms, g_ms, g_n, g_fl = Bc.timed_steps(max(4, args.steps // 2), 2)
+            tf = Bc.flops_step / (ms * 1e-3) * 1e-12
+            cfgs[synth.CONFIGS[ci]["name"]] = {
+                "tokens": Bc.M, "ms_per_step": round(ms, 4), "TFLOPs": round(tf, 2),
+                "pct_of_bf16_peak": round(100.0 * tf / PEAK_BF16_TFLOPS, 2), "flops_per_step": Bc.flops_step,
+                "gemm_TFLOPs": round(g_fl / (g_ms * 1e-3) * 1e-12, 2) if g_ms > 0 else None,
+                "gemm_frac": round(g_fl / (g_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4) if g_ms > 0 else None}
+            del Bc
+            torch.cuda.empty_cache()
+        extra["other_configs"] = cfgs
     out["extra"] = extra
 
     if not args.no_cpu_baseline:

@@ -49,7 +49,8 @@ enum {
   QLORA_ERR_UNSUPPORTED = -3, /* blocksize != 64, dq_blocksize not 256 or 0, r not supported, ... */
   QLORA_ERR_WORKSPACE = -4,   /* workspace / scratch smaller than the *_sizes call reports   */
   QLORA_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                            */
-  QLORA_ERR_HIP = -6          /* a kernel launch failed; see qlora_last_hip_error()          */
+  QLORA_ERR_HIP = -6,         /* a kernel launch failed; see qlora_last_hip_error()          */
+  QLORA_ERR_STATE = -7        /* qlora_workspace_check: a kernel found the counter header dirty */
 };
 
 /* Human-readable name of a status code (static storage, never NULL). */
@@ -287,6 +288,46 @@ qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf
                                     const uint16_t* const* L1, const uint16_t* const* L2, const float* s,
                                     int64_t M, const int32_t* r, uint16_t* const* Y,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Forward of a LIST of independent QLoRA linear layers at a few tokens in ONE launch (Eq. 5 applied per layer; the
+ * adapter sits on every linear layer of a decoder block -- Section 5 and the hyperparameter appendix):
+ *   Y[l] = X[l] * doubleDequant(Wq[l]) + s[l] * (X[l] * L1[l]) * L2[l],   l = 0 .. n-1,  1 <= n <= QLORA_LIST_MAX.
+ * Unlike qlora_linear_fwd_multi every layer has its own input X[l] (M x Wq[l].rows) and any shape; the layers must not
+ * depend on each other (a layer's input is never another layer's output of the same call).  X, L1, L2, Y are host
+ * arrays of n device pointers, Wq an array of n views, s and r host arrays of n values (r[l] = 0: no adapter, L1[l]
+ * and L2[l] are not read).  At M <= 16 one persistent kernel streams all layers' packed weights back to back -- the
+ * fixed cost of a launch is paid once and every compute unit gets the same number of bytes -- and all views must be
+ * double-quantised 4-bit weights of one data type (else QLORA_ERR_UNSUPPORTED); at larger M the layers run one
+ * after the other exactly as n calls of qlora_linear_fwd.  Results meet the tolerance of qlora_linear_fwd but need
+ * not be bit-identical to it.  Workspace rules as for qlora_linear_fwd (counter header first).
+ * qlora_linear_bwd_list is the input gradient of the same list (no adapter gradients):
+ *   dX[l] = dY[l] * doubleDequant(Wq[l])^T + s[l] * (dY[l] * L2[l]^T) * L1[l]^T,   dY[l]: M x Wq[l].cols. */
+#define QLORA_LIST_MAX 8
+qlora_status qlora_linear_fwd_list_sizes(int64_t M, int32_t n, const int64_t* h, const int64_t* o, const int32_t* r,
+                                         size_t* workspace_bytes);
+qlora_status qlora_linear_bwd_list_sizes(int64_t M, int32_t n, const int64_t* h, const int64_t* o, const int32_t* r,
+                                         size_t* workspace_bytes);
+qlora_status qlora_linear_fwd_list(int32_t n, const uint16_t* const* X, const qlora_nf4_view* Wq,
+                                   const uint16_t* const* L1, const uint16_t* const* L2, const float* s,
+                                   int64_t M, const int32_t* r, uint16_t* const* Y,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+qlora_status qlora_linear_bwd_list(int32_t n, const uint16_t* const* dY, const qlora_nf4_view* Wq,
+                                   const uint16_t* const* L1, const uint16_t* const* L2, const float* s,
+                                   int64_t M, const int32_t* r, uint16_t* const* dX,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Has a few-token kernel found the counter header of this workspace in a state no call leaves behind (not zeroed
+ * before first use, written by the caller, left half-way by an abandoned call)?  The arrival words of the list
+ * kernels carry a per-call tag, so stale contents are noticed by the kernel that meets them: it raises a sticky
+ * status word in the header, every wave still exits, and the outputs of that call are unspecified.  This call
+ * SYNCHRONISES hip_stream (the one entry point that does), reads the word and returns QLORA_ERR_STATE if it is set,
+ * QLORA_OK otherwise.  qlora_workspace_init clears it. */
+qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Testing aid: how many times a slab's last contributor polls for the adapter's partial sums before it hands the
+ * slab's output stage to the adapter's workgroups (default 64; 0 = never wait, so that hand-over path can be
+ * exercised).  Process-wide; affects the few-token list kernels only; results are the same bits either way. */
+void qlora_fewtok_poll_limit(int32_t polls);
 
 /* Measurement aid for the benchmark (not part of the method): while enabled, every launch of the
  * main MFMA GEMM kernel made by qlora_linear_fwd / qlora_linear_bwd is bracketed by a pair of HIP

@@ -22,6 +22,8 @@ EXPORTS = [
     "qlora_profile_gemm", "qlora_profile_gemm_read",
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
+    "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
+    "qlora_workspace_check", "qlora_fewtok_poll_limit",
 ]
 
 
@@ -75,11 +77,19 @@ def lib():
                                            vp, vp, vp, c_size_t, vp]
     L.qlora_linear_bwd_dropout.argtypes = [vp, vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp, c_float,
                                            vp, vp, vp, vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_linear_fwd_list_sizes.argtypes = [c_int64, c_int32, POINTER(c_int64), POINTER(c_int64), POINTER(c_int32), sp]
+    L.qlora_linear_bwd_list_sizes.argtypes = list(L.qlora_linear_fwd_list_sizes.argtypes)
+    L.qlora_linear_fwd_list.argtypes = [c_int32, POINTER(vp), POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp),
+                                        POINTER(c_float), c_int64, POINTER(c_int32), POINTER(vp), vp, c_size_t, vp]
+    L.qlora_linear_bwd_list.argtypes = list(L.qlora_linear_fwd_list.argtypes)
+    L.qlora_workspace_check.argtypes = [vp, c_size_t, vp]
+    L.qlora_fewtok_poll_limit.argtypes = [c_int32]
+    L.qlora_fewtok_poll_limit.restype = None
     L.qlora_profile_gemm.argtypes = [ctypes.c_int]
     L.qlora_profile_gemm.restype = None
     L.qlora_profile_gemm_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64), POINTER(ctypes.c_double)]
     for name in EXPORTS:
-        if name not in ("qlora_status_string", "qlora_last_hip_error", "qlora_profile_gemm"):
+        if name not in ("qlora_status_string", "qlora_last_hip_error", "qlora_profile_gemm", "qlora_fewtok_poll_limit"):
             getattr(L, name).restype = c_int32
     _lib = L
     return L
@@ -305,6 +315,57 @@ def qlora_linear_fwd_multi(X, Wqs, L1s, L2s, ss, Ys=None, workspace=None, stream
                                         M, (c_int32 * n)(*rs), ptrs(Ys), _ptr(workspace), workspace.numel(),
                                         _stream(stream)))
     return Ys
+
+
+LIST_MAX = 8
+
+
+def qlora_linear_list_sizes(M, hs, os_, rs, backward=False) -> int:
+    n = len(hs)
+    out = c_size_t(0)
+    fn = lib().qlora_linear_bwd_list_sizes if backward else lib().qlora_linear_fwd_list_sizes
+    _check(fn(M, n, (c_int64 * n)(*hs), (c_int64 * n)(*os_), (c_int32 * n)(*rs), byref(out)))
+    return int(out.value)
+
+
+def _list_call(fn, ins, Wqs, L1s, L2s, ss, outs, out_dim, workspace, stream, backward):
+    n = len(Wqs)
+    M = ins[0].shape[0]
+    rs = [0 if L1s[l] is None else L1s[l].shape[1] for l in range(n)]
+    if outs is None:
+        outs = [torch.empty((M, out_dim(w)), dtype=torch.bfloat16, device=ins[0].device) for w in Wqs]
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_list_sizes(M, [w.rows for w in Wqs], [w.cols for w in Wqs], rs, backward),
+                                    ins[0].device, stream)
+    views = (qlora_nf4_view * n)(*[w.view() for w in Wqs])
+    ptrs = lambda ts: (c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
+    _check(fn(n, ptrs(ins), views, ptrs(L1s), ptrs(L2s), (c_float * n)(*[float(s) for s in ss]), M, (c_int32 * n)(*rs),
+              ptrs(outs), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return outs
+
+
+def qlora_linear_fwd_list(Xs, Wqs, L1s, L2s, ss, Ys=None, workspace=None, stream=None):
+    """Y[l] = X[l] dequant(Wqs[l]) + ss[l] (X[l] L1s[l]) L2s[l] for up to LIST_MAX independent layers, each with its own
+    input of M tokens; at M <= 16 all of them in one persistent launch."""
+    return _list_call(lib().qlora_linear_fwd_list, Xs, Wqs, L1s, L2s, ss, Ys, lambda w: w.cols, workspace, stream, False)
+
+
+def qlora_linear_bwd_list(dYs, Wqs, L1s, L2s, ss, dXs=None, workspace=None, stream=None):
+    """dX[l] = dY[l] dequant(Wqs[l])^T + ss[l] (dY[l] L2s[l]^T) L1s[l]^T for up to LIST_MAX independent layers."""
+    return _list_call(lib().qlora_linear_bwd_list, dYs, Wqs, L1s, L2s, ss, dXs, lambda w: w.rows, workspace, stream, True)
+
+
+def qlora_workspace_check(workspace, stream=None) -> bool:
+    """Synchronises the stream; True if no kernel has found the workspace's counter header dirty since it was initialised."""
+    st = lib().qlora_workspace_check(_ptr(workspace), workspace.numel(), _stream(stream))
+    if st == -7:
+        return False
+    _check(st)
+    return True
+
+
+def qlora_fewtok_poll_limit(polls: int):
+    lib().qlora_fewtok_poll_limit(int(polls))
 
 
 def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1=None, dL2=None,

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <vector>
 
 #include "common.hpp"
@@ -37,6 +38,12 @@ hipError_t gemm_nt_timed(const uint16_t* A0, const uint16_t* B0, int64_t lda0, i
 }
 
 thread_local int g_last_hip_error = 0;
+
+// Tag of a work-list launch (1 .. 255): arrival words in the counter header carry it, so words left behind by
+// another call are told from this call's own.  Consecutive calls get different tags.
+std::atomic<unsigned> g_nonce{0};
+inline unsigned next_nonce() { return 1u + g_nonce.fetch_add(1u, std::memory_order_relaxed) % 255u; }
+std::atomic<int> g_poll_limit{64};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -212,6 +219,38 @@ MultiPlan plan_fwd_multi(void* ws, int64_t M, int32_t n, int64_t h, const int64_
   return p;
 }
 
+// A list of independent layers at a few tokens: one persistent launch; every layer with its own partial buffers.
+// At more tokens the layers run one after the other through the single-layer path, sharing one workspace.
+static_assert(QLORA_LIST_MAX == qlora::kListMax, "the header's limit is the kernel's");
+struct ListWs {
+  qlora::ListPlan plan;
+  float* part[qlora::kListMax];
+  float* lpart[qlora::kListMax];
+  bool few;
+  size_t bytes;
+};
+ListWs plan_list(void* ws, bool bwd, int64_t M, int32_t n, const int64_t* h, const int64_t* o, const int32_t* r) {
+  ListWs p{};
+  int hi[qlora::kListMax], oi[qlora::kListMax];
+  for (int l = 0; l < n; ++l) { hi[l] = (int)h[l]; oi[l] = (int)o[l]; }
+  if (M <= qlora::kFewTokens) p.plan = qlora::fewlist_plan(bwd, (int)M, n, hi, oi, r);
+  p.few = p.plan.ok;
+  if (p.few) {
+    Carver c(ws);
+    for (int l = 0; l < n; ++l) {
+      p.part[l] = c.take<float>(p.plan.part_floats[l]);
+      p.lpart[l] = c.take<float>(p.plan.lpart_floats[l]);
+    }
+    p.bytes = c.off;
+  } else {
+    for (int l = 0; l < n; ++l) {
+      const size_t b = bwd ? plan_bwd(nullptr, M, h[l], o[l], r[l]).bytes : plan_fwd(nullptr, M, h[l], o[l], r[l]).bytes;
+      if (b > p.bytes) p.bytes = b;
+    }
+  }
+  return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -225,6 +264,7 @@ const char* qlora_status_string(qlora_status st) {
     case QLORA_ERR_WORKSPACE: return "QLORA_ERR_WORKSPACE: workspace or scratch too small";
     case QLORA_ERR_ALIGN: return "QLORA_ERR_ALIGN: pointer not 16-byte aligned";
     case QLORA_ERR_HIP: return "QLORA_ERR_HIP: kernel launch failed";
+    case QLORA_ERR_STATE: return "QLORA_ERR_STATE: the workspace's counter header was not zero when a few-token kernel used it";
     default: return "QLORA: unknown status";
   }
 }
@@ -564,5 +604,97 @@ qlora_status qlora_linear_bwd_dropout(const uint16_t* dY, const uint16_t* X, con
   return linear_bwd_impl(dY, X, Wq, L1, L2, r > 0 ? dropout_scale(s, p) : s, M, r, r > 0 ? keep_mask : nullptr, T_saved,
                          dX, dL1, dL2, dL1_acc, dL2_acc, workspace, workspace_bytes, hip_stream);
 }
+
+}  // extern "C"
+
+// --- lists of layers at a few tokens ------------------------------------------------------------------
+namespace {
+qlora_status list_impl(bool bwd, int32_t n, const uint16_t* const* In, const qlora_nf4_view* Wq, const uint16_t* const* L1,
+                       const uint16_t* const* L2, const float* s, int64_t M, const int32_t* r, uint16_t* const* Out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!In || !Wq || !s || !r || !Out || !workspace) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_LIST_MAX) return QLORA_ERR_SHAPE;
+  int64_t h[QLORA_LIST_MAX], o[QLORA_LIST_MAX];
+  for (int l = 0; l < n; ++l) {
+    if (qlora_status st = check_view(&Wq[l])) return st;
+    h[l] = Wq[l].rows; o[l] = Wq[l].cols;
+    if (qlora_status st = check_linear(M, h[l], o[l], r[l])) return st;
+    if (!In[l] || !Out[l]) return QLORA_ERR_NULL;
+    if (r[l] > 0 && (!L1 || !L2 || !L1[l] || !L2[l])) return QLORA_ERR_NULL;
+    if (!aligned16(In[l]) || !aligned16(Out[l]) || (r[l] > 0 && (!aligned16(L1[l]) || !aligned16(L2[l])))) return QLORA_ERR_ALIGN;
+  }
+  if (!aligned16(workspace)) return QLORA_ERR_ALIGN;
+  if (M <= qlora::kFewTokens)
+    for (int l = 0; l < n; ++l)
+      if (!streams_few(&Wq[l]) || Wq[l].dtype != Wq[0].dtype) return QLORA_ERR_UNSUPPORTED;   // one decode table per launch
+  const ListWs p = plan_list(workspace, bwd, M, n, h, o, r);
+  if (M <= qlora::kFewTokens && !p.few) return QLORA_ERR_UNSUPPORTED;
+  if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
+  if (!p.few) {
+    for (int l = 0; l < n; ++l) {
+      const uint16_t* l1 = r[l] > 0 ? L1[l] : nullptr;
+      const uint16_t* l2 = r[l] > 0 ? L2[l] : nullptr;
+      const qlora_status st =
+          bwd ? qlora_linear_bwd(In[l], nullptr, &Wq[l], l1, l2, s[l], M, r[l], nullptr, Out[l], nullptr, nullptr, workspace,
+                                 workspace_bytes, hip_stream)
+              : qlora_linear_fwd(In[l], &Wq[l], l1, l2, s[l], M, r[l], Out[l], nullptr, workspace, workspace_bytes, hip_stream);
+      if (st) return st;
+    }
+    return QLORA_OK;
+  }
+  qlora::ListLayerDesc layers[QLORA_LIST_MAX];
+  for (int l = 0; l < n; ++l)
+    layers[l] = qlora::ListLayerDesc{to_dev(&Wq[l]), In[l], r[l] > 0 ? L1[l] : nullptr, r[l] > 0 ? L2[l] : nullptr, r[l], s[l],
+                                     p.part[l], p.lpart[l], Out[l], nullptr};
+  QL_TRY(qlora::launch_fewlist(bwd, (int)M, n, layers, p.plan, (unsigned*)workspace, next_nonce(),
+                               g_poll_limit.load(std::memory_order_relaxed), (hipStream_t)hip_stream));
+  return QLORA_OK;
+}
+
+qlora_status list_sizes_impl(bool bwd, int64_t M, int32_t n, const int64_t* h, const int64_t* o, const int32_t* r,
+                             size_t* workspace_bytes) {
+  if (!h || !o || !r || !workspace_bytes) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_LIST_MAX) return QLORA_ERR_SHAPE;
+  for (int l = 0; l < n; ++l)
+    if (qlora_status st = check_linear(M, h[l], o[l], r[l])) return st;
+  const ListWs p = plan_list(nullptr, bwd, M, n, h, o, r);
+  if (M <= qlora::kFewTokens && !p.few) return QLORA_ERR_UNSUPPORTED;
+  *workspace_bytes = p.bytes;
+  return QLORA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+qlora_status qlora_linear_fwd_list_sizes(int64_t M, int32_t n, const int64_t* h, const int64_t* o, const int32_t* r,
+                                         size_t* workspace_bytes) {
+  return list_sizes_impl(false, M, n, h, o, r, workspace_bytes);
+}
+qlora_status qlora_linear_bwd_list_sizes(int64_t M, int32_t n, const int64_t* h, const int64_t* o, const int32_t* r,
+                                         size_t* workspace_bytes) {
+  return list_sizes_impl(true, M, n, h, o, r, workspace_bytes);
+}
+
+qlora_status qlora_linear_fwd_list(int32_t n, const uint16_t* const* X, const qlora_nf4_view* Wq, const uint16_t* const* L1,
+                                   const uint16_t* const* L2, const float* s, int64_t M, const int32_t* r,
+                                   uint16_t* const* Y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return list_impl(false, n, X, Wq, L1, L2, s, M, r, Y, workspace, workspace_bytes, hip_stream);
+}
+qlora_status qlora_linear_bwd_list(int32_t n, const uint16_t* const* dY, const qlora_nf4_view* Wq, const uint16_t* const* L1,
+                                   const uint16_t* const* L2, const float* s, int64_t M, const int32_t* r,
+                                   uint16_t* const* dX, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return list_impl(true, n, dY, Wq, L1, L2, s, M, r, dX, workspace, workspace_bytes, hip_stream);
+}
+
+qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace) return QLORA_ERR_NULL;
+  if (workspace_bytes < qlora::kWorkspaceHeaderBytes) return QLORA_ERR_WORKSPACE;
+  unsigned status = 0;
+  QL_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+  QL_TRY(hipMemcpy(&status, (const unsigned*)workspace + qlora::kHeaderStatusWord, sizeof(status), hipMemcpyDeviceToHost));
+  return status ? QLORA_ERR_STATE : QLORA_OK;
+}
+
+void qlora_fewtok_poll_limit(int32_t polls) { g_poll_limit.store(polls < 0 ? 0 : polls, std::memory_order_relaxed); }
 
 }  // extern "C"

@@ -63,6 +63,7 @@ hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int
 constexpr int kFewTokens = 16;
 constexpr size_t kWorkspaceHeaderBytes = 16384;
 constexpr int kFewMaxSlabs = 2047;
+constexpr int kHeaderStatusWord = 2047;     // sticky status word of the counter header (work-list kernels)
 int fewtok_fwd_splits(int h, int o);
 int fewtok_bwd_splits(int h, int o);
 int fewtok_fwd_slabs(int o);
@@ -92,5 +93,45 @@ int fewtok_multi_splits(int n, int h, const int* o, int r_max);
 hipError_t launch_fewtok_fwd_multi(const uint16_t* X, int M, int n, const FewLayer* layers, int splits, unsigned* ctr,
                                    hipStream_t st);
 hipError_t launch_workspace_init(void* workspace, hipStream_t st);
+
+// fewlist.hip: the same two products for a LIST of independent layers (each with its own token rows) in one
+// persistent launch.  The work of all layers is one line of units (forward: 16 weight rows x 256 columns; backward:
+// 256 rows x 128 columns) and workgroup rho of `grid` takes units [list_start(rho), list_start(rho + 1)); the
+// first n_adapter workgroups also compute one partial of an adapter's inner product each and get `credit` fewer
+// units for it.  Host (sizes, launch) and device evaluate the same two functions.
+constexpr int kListMax = 8;
+constexpr int kListLoraChunk = 1024;         // contraction elements per adapter item (more when a layer would need over 23 items)
+struct ListPart { long long cost_total; int grid, credit, n_adapter; };
+__host__ __device__ inline int list_start(const ListPart& q, int rho) {
+  const int a = rho < q.n_adapter ? rho : q.n_adapter;
+  return (int)(((long long)rho * q.cost_total) / q.grid - (long long)q.credit * a);
+}
+// the workgroup whose range holds unit u (0 <= u < total units); ranges are non-empty and ascending by construction
+__host__ __device__ inline int list_rho_of(const ListPart& q, int u) {
+  int rho = (int)(((long long)u * q.grid) / q.cost_total);   // start(rho) <= rho * cost / grid <= u
+  while (rho + 1 < q.grid && list_start(q, rho + 1) <= u) ++rho;
+  return rho;
+}
+struct ListPlan {
+  bool ok;                                   // false: not a few-token list (too many tokens, layers or slabs)
+  ListPart part;
+  int total_units, total_slabs;
+  int n_slabs[kListMax], ups[kListMax], unit0[kListMax], a0[kListMax], ctr0[kListMax];
+  int n_lparts[kListMax], lora_chunk[kListMax], max_contrib[kListMax];
+  size_t part_floats[kListMax], lpart_floats[kListMax];      // sizes of the two partial buffers of every layer
+};
+ListPlan fewlist_plan(bool bwd, int M, int n, const int* h, const int* o, const int* r);
+struct ListLayerDesc {
+  NF4Dev w;
+  const uint16_t* X;                         // forward: X (M x h); backward: dY (M x o)
+  const uint16_t* L1; const uint16_t* L2; int r; float scale;
+  float* part; float* lpart;                 // part_floats / lpart_floats of the plan
+  uint16_t* out;                             // forward: Y (M x o); backward: dX (M x h)
+  uint16_t* hl;                              // M x 2r [hi | lo] pair of X L1 (forward) or dY L2^T (backward), or NULL
+};
+//   hdr: the workspace's counter header; nonce: 1 .. 255, different for consecutive calls on one header;
+//   spin_limit: polls of a slab's last contributor for the adapter's partials (0: never wait)
+hipError_t launch_fewlist(bool bwd, int M, int n, const ListLayerDesc* layers, const ListPlan& plan, unsigned* hdr,
+                          unsigned nonce, int spin_limit, hipStream_t st);
 
 }  // namespace qlora

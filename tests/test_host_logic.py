@@ -21,3 +21,22 @@ def test_nf4_index_schemes_agree(tmp_path):
     out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout
     assert out.startswith("OK "), out
     assert int(out.split()[1]) > 30_000_000
+
+
+def test_list_partition_tiles_the_work(tmp_path):
+    """The range formula of the few-token list kernels (evaluated alike by the size queries, the launcher and the
+    kernels): exact tiling, inverse map, contributor counts against brute force, for thousands of shape lists."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    from paper_2305_14314_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(verbose=False)
+    exe = str(tmp_path / "list_partition_check")
+    src = os.path.join(ROOT, "tests", "host_checks", "list_partition_check.cpp")
+    pkg = os.path.dirname(binding.LIB_PATH)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-x", "hip", "-I", CSRC, src, "-o", exe,
+                    "-L", pkg, "-lqlora_hip", "-Wl,-rpath," + pkg], check=True, capture_output=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout
+    assert out.startswith("OK "), out
+    assert int(out.split()[1]) > 2000
