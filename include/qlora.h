@@ -160,6 +160,18 @@ qlora_status qlora_nf4_quantize(const float* W, int64_t rows, int64_t cols,
                                 uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
                                 void* scratch, size_t scratch_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory and have no scratch buffer to pass (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): qlora_nf4_quantize with its scratch in a device array that
+ * the library itself holds (16 MiB + 2 KiB on every device it runs on, until the process ends).  Same arguments,
+ * same results bit for bit, no allocation on the way; tensors of at most QLORA_STATIC_QUANT_MAX_WEIGHTS weights,
+ * QLORA_ERR_WORKSPACE beyond that.  All calls on one device share the array: two calls that overlap there (on
+ * different streams or threads) race; calls on one stream are ordered and fine. */
+#define QLORA_STATIC_QUANT_MAX_WEIGHTS ((int64_t)1 << 28)
+qlora_status qlora_nf4_quantize_static(const float* W, int64_t rows, int64_t cols,
+                                       int32_t blocksize, int32_t dq_blocksize,
+                                       uint8_t* packed, uint8_t* c2_code, float* c1, float* c2_mean,
+                                       void* hip_stream);
+
 /* The same with one of the other table data types (Section 4's 4-bit ones, QLORA_NF3, QLORA_NF2); dtype = QLORA_NF4
  * is qlora_nf4_quantize.  The
  * buffers, their sizes and the Double Quantization of the constants do not depend on the data type. */

@@ -23,7 +23,7 @@ EXPORTS = [
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
-    "qlora_workspace_check", "qlora_fewtok_poll_limit",
+    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_nf4_quantize_static",
 ]
 
 
@@ -57,6 +57,7 @@ def lib():
     L.qlora_last_hip_error.restype = ctypes.c_int
     L.qlora_nf4_sizes.argtypes = [c_int64, c_int64, c_int32, c_int32, sp, sp, sp, sp]
     L.qlora_nf4_quantize.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
+    L.qlora_nf4_quantize_static.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, vp, vp, vp, vp, vp]
     L.qlora_quantize_4bit.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, c_int32, vp, vp, vp, vp, vp, c_size_t, vp]
     L.qlora_codebook_4bit.argtypes = [c_int32, vp]
     L.qlora_quant_sizes.argtypes = [c_int64, c_int64, c_int32, c_int32, c_int32, sp, sp, sp, sp]
@@ -223,6 +224,20 @@ def qlora_nf4_quantize(W, blocksize=64, dq_blocksize=256, scratch=None, stream=N
                                          _ptr(code), _ptr(c1), _ptr(mean), _ptr(scratch), scratch.numel(),
                                          _stream(stream)))
     out.dtype = int(dtype)
+    return out
+
+
+STATIC_QUANT_MAX_WEIGHTS = 1 << 28
+
+
+def qlora_nf4_quantize_static(W, out: NF4Weight, stream=None) -> NF4Weight:
+    """qlora_nf4_quantize into the caller's buffers `out`, with the scratch in the library's own device array:
+    nothing is allocated here or below."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
+    rows, cols = W.shape
+    assert (out.rows, out.cols, out.dtype) == (rows, cols, NF4)
+    _check(lib().qlora_nf4_quantize_static(_ptr(W), rows, cols, out.blocksize, out.dq_blocksize, _ptr(out.packed),
+                                           _ptr(out.code), _ptr(out.c1), _ptr(out.mean), _stream(stream)))
     return out
 
 

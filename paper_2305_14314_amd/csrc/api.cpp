@@ -222,6 +222,7 @@ MultiPlan plan_fwd_multi(void* ws, int64_t M, int32_t n, int64_t h, const int64_
 // A list of independent layers at a few tokens: one persistent launch; every layer with its own partial buffers.
 // At more tokens the layers run one after the other through the single-layer path, sharing one workspace.
 static_assert(QLORA_LIST_MAX == qlora::kListMax, "the header's limit is the kernel's");
+static_assert(QLORA_STATIC_QUANT_MAX_WEIGHTS == qlora::kStaticQuantBlocks * 64, "the header's limit is the kernel's");
 struct ListWs {
   qlora::ListPlan plan;
   float* part[qlora::kListMax];
@@ -344,6 +345,20 @@ qlora_status qlora_quantize_4bit(const float* W, int64_t rows, int64_t cols,
     return QLORA_ERR_ALIGN;
   return hip_status(qlora::launch_quantize(W, rows, cols, packed, c2_code, c1, c2_mean, scratch,
                                            (hipStream_t)hip_stream, dtype, dq));
+}
+
+qlora_status qlora_nf4_quantize_static(const float* W, int64_t rows, int64_t cols, int32_t blocksize,
+                                       int32_t dq_blocksize, uint8_t* packed, uint8_t* c2_code, float* c1,
+                                       float* c2_mean, void* hip_stream) {
+  const bool dq = dq_blocksize != 0;
+  if (!W || !packed || !c1 || (dq && (!c2_code || !c2_mean))) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(rows, cols, blocksize, dq_blocksize)) return st;
+  if (rows * cols > (int64_t)QLORA_STATIC_QUANT_MAX_WEIGHTS) return QLORA_ERR_WORKSPACE;
+  if (!aligned16(W) || !aligned16(packed) || !aligned16(c1) ||
+      (dq && (!aligned16(c2_code) || ((uintptr_t)c2_mean & 3u))))
+    return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_quantize_static(W, rows, cols, packed, c2_code, c1, c2_mean,
+                                                  (hipStream_t)hip_stream, QLORA_NF4, dq));
 }
 
 qlora_status qlora_quantize_int8(const float* W, int64_t rows, int64_t cols,

@@ -23,6 +23,11 @@ constexpr size_t kQuantBinsBytes = 256 * sizeof(unsigned long long);
 //   dq = false: no Double Quantization; the fp32 constants c2 go to `c1` (rows * cols / 64 floats), code and mean untouched.
 hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code, float* c1,
                            float* mean, void* scratch, hipStream_t st, int dtype = 0, bool dq = true);
+// The same with the scratch in a device array of the library itself (no allocation anywhere on the way): tensors of
+// up to kStaticQuantBlocks blocks.  Calls on one device share the array: calls that overlap there race.
+constexpr size_t kStaticQuantBlocks = (size_t)4 << 20;
+hipError_t launch_quantize_static(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code,
+                                  float* c1, float* mean, hipStream_t st, int dtype = 0, bool dq = true);
 
 // dequant.hip
 hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);

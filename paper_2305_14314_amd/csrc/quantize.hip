@@ -11,6 +11,8 @@
 // The mean is exact and independent of summation order: every fp32 constant is
 // mantissa * 2^(exponent), the mantissas are summed per exponent in 64-bit integers
 // (integer atomics commute), and the bins are combined in multi-word integer arithmetic.
+#include <mutex>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -230,6 +232,40 @@ hipError_t launch_quantize(const float* W, int64_t rows, int64_t cols, uint8_t* 
   hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)n1), dim3(kDqBlock), 0, st, c2, n, mean, code, c1,
                      (uint32_t)rows, (uint32_t)(cols / kBlock));
   return hipGetLastError();
+}
+
+// ---- the variant for callers that cannot allocate ---------------------------------------------------------------
+// Its scratch (the exponent bins and the fp32 constants c2 of up to kStaticQuantBlocks blocks) is this array; every
+// device the library runs on holds its own copy at its own address, found once per device.
+static __device__ __align__(256) unsigned char scratch[kQuantBinsBytes + kStaticQuantBlocks * sizeof(float)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+hipError_t quantize_static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipError_t e = hipGetDevice(&dev)) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+hipError_t launch_quantize_static(const float* W, int64_t rows, int64_t cols, uint8_t* packed, uint8_t* code,
+                                  float* c1, float* mean, hipStream_t st, int dtype, bool dq) {
+  if (rows * cols / kBlock > (int64_t)kStaticQuantBlocks) return hipErrorInvalidValue;
+  void* ptr = nullptr;
+  if (hipError_t e = quantize_static_scratch(&ptr)) return e;
+  return launch_quantize(W, rows, cols, packed, code, c1, mean, ptr, st, dtype, dq);
 }
 
 }  // namespace qlora
