@@ -29,6 +29,34 @@
 
 #include "fewtok_common.hpp"
 
+// Launch shapes (threads per workgroup, ring depth of the load pipeline) of the three kernels.  The load cursor of the
+// next segment costs registers: with 1024 threads (128 registers a lane) the forward kernel for up to 8 tokens spilled
+// 61 and the backward kernel 103 registers to scratch, which showed as 40 and 97 MiB of HBM writes per launch.  With
+// 512 threads nothing spills.  Measured on the seven linears of a 65B-shaped block, 1 / 4 / 16 tokens, microseconds
+// per launch: backward 1024 threads, depth 2: 207 / 217 / 245; 512 threads, depth 3: 177 / 182 / 209 (depth 4 spills
+// again).  Forward, up to 8 tokens: 1024 threads, depth 3: 174 / 177; 512 threads, depth 4: 175 / 178, depth 6:
+// 179 / 183.  Forward, 16 tokens (512 threads): depth 3, 4, 5: 204, 203, 205.
+#ifndef QL_LIST_FWD8_NT
+#define QL_LIST_FWD8_NT 512
+#endif
+#ifndef QL_LIST_FWD8_DEPTH
+#define QL_LIST_FWD8_DEPTH 4
+#endif
+#ifndef QL_LIST_FWD16_DEPTH
+#define QL_LIST_FWD16_DEPTH 3
+#endif
+#ifndef QL_LIST_BWD_NCW
+#define QL_LIST_BWD_NCW 2
+#endif
+#ifndef QL_LIST_BWD_DEPTH
+#define QL_LIST_BWD_DEPTH 3
+#endif
+// An adapter item is charged its bytes in streaming units, times this factor.  Measured (same block, 1 token, forward /
+// backward microseconds): factor 0: 181 / 182; 0.5: 177 / 176; 1: 175 / 177; 2: 179 / 182; 3: 186 / 188; 4: 192 / 194.
+#ifndef QL_LIST_CREDIT_X
+#define QL_LIST_CREDIT_X 1
+#endif
+
 namespace qlora {
 
 namespace {
@@ -340,10 +368,9 @@ __device__ __forceinline__ int seg_steps(const Seg& s, int w, int nw) {
 // See the one-layer forward kernel for the lane layout of a step (16 weight rows x 256 columns per wave and step).
 struct LFwd { uint32_t pk[8]; u32x4 x; uint32_t code; float c1; float mean; };   // raw loads only
 
-template <int MT, int NT>
+template <int MT, int NT, int kDepth>
 __global__ __launch_bounds__(NT) void fewlist_fwd_kernel(const ListArgs A) {
   constexpr int NA = MT / 8;                                 // accumulator sets (and MFMAs per column phase)
-  constexpr int kDepth = 3;
   constexpr int NW = NT / 64, HW = NW / 2;
   constexpr int kTile = MT * 256;                            // floats of one wave's [MT][256] tile
   static_assert(HW * kTile * 4 <= 64 * 1024, "half of the waves' tiles fit the sum area");
@@ -548,11 +575,13 @@ __global__ __launch_bounds__(NT) void fewlist_fwd_kernel(const ListArgs A) {
 
 // ---- backward -------------------------------------------------------------------------------------
 // See the one-layer backward kernel for the lane layout: wave (rg = wave % 4, cw = wave / 4) owns weight rows
-// 64 rg .. +63 of the slab and takes the 128-column steps cw, cw + 4, ... of a segment.
+// 64 rg .. +63 of the slab and takes the 128-column steps cw, cw + NCW, ... of a segment (NCW waves per row group).
 struct LBwd { u32x4 w[4]; u32x4 y[4]; uint32_t code[4]; float c1[4]; float mean; };   // raw loads only
 
-__global__ __launch_bounds__(kFewThreads) void fewlist_bwd_kernel(const ListArgs A) {
-  constexpr int NT = kFewThreads, kDepth = kBwdDepth;
+template <int NCW, int kDepth>
+__global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A) {
+  constexpr int NT = 256 * NCW;
+  static_assert(NCW == 2 || NCW == 4, "two or four waves per row group");
   __shared__ __attribute__((aligned(256))) char smem[kListSmem];
   __shared__ int flag;
   f32x2* lut2 = (f32x2*)smem;
@@ -597,7 +626,7 @@ __global__ __launch_bounds__(kFewThreads) void fewlist_bwd_kernel(const ListArgs
     y_off = (uint32_t)((y_row_ok ? i : 0) * y.o);
   };
   setup_load();
-  int ln = seg_steps(ls, cw, 4), lit = (ln + kDepth - 1) / kDepth * kDepth, li = 0;
+  int ln = seg_steps(ls, cw, NCW), lit = (ln + kDepth - 1) / kDepth * kDepth, li = 0;
   bool l_done = false;
   int kb_last = ls.s0 * 128;
   auto skip_empty = [&]() {
@@ -605,14 +634,14 @@ __global__ __launch_bounds__(kFewThreads) void fewlist_bwd_kernel(const ListArgs
       if (ls.u_end >= u1) { l_done = true; break; }
       ls = seg_at(A, ls.u_end, u1);
       setup_load();
-      ln = seg_steps(ls, cw, 4); lit = (ln + kDepth - 1) / kDepth * kDepth; li = 0;
+      ln = seg_steps(ls, cw, NCW); lit = (ln + kDepth - 1) / kDepth * kDepth; li = 0;
       kb_last = ls.s0 * 128;
     }
   };
   skip_empty();
   auto next_load = [&](LBwd& s) {                            // see the forward kernel
     const bool valid = !l_done && li < ln;
-    const int kb = valid ? (ls.s0 + cw + 4 * li) * 128 : kb_last;
+    const int kb = valid ? (ls.s0 + cw + NCW * li) * 128 : kb_last;
     kb_last = kb;
     int col = kb + 32 * g;                                   // per lane
     if (col >= l_o) col = l_o - 64 + 32 * (g & 1);           // the half-empty last step: any valid column (masked at compute)
@@ -667,7 +696,7 @@ __global__ __launch_bounds__(kFewThreads) void fewlist_bwd_kernel(const ListArgs
   };
 
   for (Seg cs = seg_at(A, u0, u1);; cs = seg_at(A, cs.u_end, u1)) {
-    const int cn = seg_steps(cs, cw, 4), cit = (cn + kDepth - 1) / kDepth * kDepth;
+    const int cn = seg_steps(cs, cw, NCW), cit = (cn + kDepth - 1) / kDepth * kDepth;
     const int o_cs = A.L[cs.l].o;
     for (int it = 0; it < cit;) {
       const int room = l_done ? cit - it : lit - li;
@@ -675,14 +704,14 @@ __global__ __launch_bounds__(kFewThreads) void fewlist_bwd_kernel(const ListArgs
       for (; it < it_end; it += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
-          if (it + d < cn) compute(buf[d], y_row_ok && (cs.s0 + cw + 4 * (it + d)) * 128 + 32 * g < o_cs);
+          if (it + d < cn) compute(buf[d], y_row_ok && (cs.s0 + cw + NCW * (it + d)) * 128 + 32 * g < o_cs);
           next_load(buf[d]);
         }
       }
       skip_empty();
     }
     // D layout: column slot = lane % 16 = weight row within the 16-row group, token rows 4 * (lane / 16) + v.
-    // Every wave stores its 16 x 64 tile; the 4 tiles of a row group are summed.
+    // Every wave stores its 16 x 64 tile; the NCW tiles of a row group are summed.
     float* my = red + wave16 * (16 * 64);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -699,7 +728,7 @@ __global__ __launch_bounds__(kFewThreads) void fewlist_bwd_kernel(const ListArgs
       const float* src = red + (rr >> 6) * (16 * 64) + m * 64 + (rr & 63);
       float t = 0.0f;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) t += src[q * 4 * 16 * 64];
+      for (int q = 0; q < NCW; ++q) t += src[q * 4 * 16 * 64];
       __hip_atomic_store(out + idx, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (arrive_mask(p, p.ctr + cs.slab, cb.j, cb.total, &flag))
@@ -751,7 +780,7 @@ ListPlan fewlist_plan(bool bwd, int M, int n, const int* h, const int* o, const 
     ListPart q{};
     q.grid = grid;
     q.n_adapter = adapters;
-    int credit = adapters > 0 ? (int)(adapter_bytes / adapters / unit_bytes) : 0;
+    int credit = adapters > 0 ? (int)(QL_LIST_CREDIT_X * (double)(adapter_bytes / adapters / unit_bytes)) : 0;
     if (adapters > grid || (units + (int64_t)credit * adapters) / grid < credit + 1) credit = 0;
     q.credit = credit;
     q.cost_total = units + (int64_t)credit * adapters;
@@ -796,9 +825,10 @@ hipError_t launch_fewlist(bool bwd, int M, int n, const ListLayerDesc* layers, c
   }
   for (int l = n; l < kListMax; ++l) { A.L[l] = A.L[n - 1]; A.L[l].unit0 = 0x7fffffff; A.L[l].a0 = 0x7fffffff; }
   const dim3 grid((unsigned)P.part.grid);
-  if (bwd) hipLaunchKernelGGL(fewlist_bwd_kernel, grid, dim3(kFewThreads), 0, st, A);
-  else if (M <= 8) hipLaunchKernelGGL((fewlist_fwd_kernel<8, 1024>), grid, dim3(1024), 0, st, A);
-  else hipLaunchKernelGGL((fewlist_fwd_kernel<16, 512>), grid, dim3(512), 0, st, A);
+  if (bwd) hipLaunchKernelGGL((fewlist_bwd_kernel<QL_LIST_BWD_NCW, QL_LIST_BWD_DEPTH>), grid, dim3(256 * QL_LIST_BWD_NCW), 0, st, A);
+  else if (M <= 8)
+    hipLaunchKernelGGL((fewlist_fwd_kernel<8, QL_LIST_FWD8_NT, QL_LIST_FWD8_DEPTH>), grid, dim3(QL_LIST_FWD8_NT), 0, st, A);
+  else hipLaunchKernelGGL((fewlist_fwd_kernel<16, 512, QL_LIST_FWD16_DEPTH>), grid, dim3(512), 0, st, A);
   return hipGetLastError();
 }
 
