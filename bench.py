@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 PEAK_HBM_GBS = 8000.0
-SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes")
+SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam")
 
 
 def _ensure_built():
@@ -303,6 +303,27 @@ def main():
                             "frac_hbm": round(el * 2.5159 / (t * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                             "bytes_per_element": 2.5159}
         del outb
+    if want("adam"):
+        # optimizer step on the adapters of 8 blocks (80 M parameters in one flat buffer): global-norm pass over the
+        # gradient, then Adam with clipping, the bf16 copy and the cleared gradient: 4 + 34 bytes per parameter
+        n_par = 8 * sum(h * r + r * o for h, o in linears)
+        pa = [torch.zeros(n_par, dtype=torch.float32, device=dev) for _ in range(3)]
+        ga = torch.randn(n_par, dtype=torch.float32, device=dev) * 1e-3
+        pb = torch.empty(n_par, dtype=torch.bfloat16, device=dev)
+        acc = torch.zeros(1, dtype=torch.float64, device=dev)
+        tstep = [0]
+
+        def adam():
+            tstep[0] += 1
+            acc.zero_()
+            ql.qlora_grad_sqnorm(ga, acc)
+            ql.qlora_adam_step(pa[0], pa[1], pa[2], ga, tstep[0], 1e-4, 0.9, 0.999, 1e-8, grad_scale=1.0 / 16,
+                               max_grad_norm=0.3, sqnorm=acc, param_bf16=pb, zero_grad=True)
+        t = _time_ms(torch, adam, 10)
+        extra["adam"] = {"params": n_par, "us": round(t * 1e3, 1), "bytes_per_param": 38,
+                         "GBps": round(n_par * 38 / (t * 1e-3) * 1e-9, 1),
+                         "frac_hbm": round(n_par * 38 / (t * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4)}
+        del pa, ga, pb
     if want("types"):
         # the data types of the paper's comparison (Section 4) on one 8192 x 8192 N(0, 0.02) tensor: round-trip error
         # of quantise + doubleDequant in units of sigma (NF4 is the smallest), and the rate of the quantise pass

@@ -341,6 +341,44 @@ qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes
  * exercised).  Process-wide; affects the few-token list kernels only; results are the same bits either way. */
 void qlora_fewtok_poll_limit(int32_t polls);
 
+/* ---- optimizer step of the LoRA parameters ---------------------------------------------------------------------
+ * The paper trains the adapters with Adam, beta2 = 0.999, a maximum gradient norm of 0.3 and a constant learning rate
+ * of 2e-4 (7B, 13B) or 1e-4 (33B, 65B) (hyperparameter appendix), and keeps the optimizer state in memory that can be
+ * paged (Section 3, "Paged Optimizers").  The paging is not built; the state lives in device buffers of the caller.
+ * The paper does not print the update rule: this is the published algorithm (Kingma & Ba 2015, Algorithm 1) with bias
+ * correction.  All buffers are device memory; the fp32 ones 16-byte aligned, param_bf16 8-byte aligned. */
+typedef struct {
+  double lr;            /* learning rate                                                             */
+  double beta1;         /* 0.9 unless the caller says otherwise                                      */
+  double beta2;         /* 0.999 (hyperparameter appendix)                                           */
+  double eps;           /* 1e-8                                                                      */
+  double weight_decay;  /* decoupled: p <- p - lr * weight_decay * p before the step; 0 = none       */
+  double grad_scale;    /* the accumulators hold a sum over micro-batches: 1 / their number          */
+  double max_grad_norm; /* 0.3 in the paper; <= 0 or sqnorm = NULL: no clipping                      */
+  int64_t step;         /* 1 for the first step (bias correction 1 - beta^step)                      */
+  int32_t zero_grad;    /* != 0: the gradient buffer is cleared after use                            */
+  int32_t reserved;     /* 0 */
+} qlora_adam_config;
+
+/* *sqnorm_accum += sum of grad[i]^2 in double precision (order of the additions unspecified).  The caller clears the
+ * device double once, calls this for every gradient buffer of the model (the fp32 accumulators that
+ * qlora_linear_bwd_acc adds to), and passes the same pointer to every qlora_adam_step of the step. */
+qlora_status qlora_grad_sqnorm(const float* grad, int64_t n, double* sqnorm_accum, void* hip_stream);
+
+/* One Adam step on n parameters, per element in fp32, each operation rounded separately, in this order:
+ *   g' = coef * g      coef = fl32(grad_scale * min(1, max_grad_norm / (|grad_scale| * sqrt(*sqnorm))))
+ *   m  = beta1 * m + (1 - beta1) * g'
+ *   v  = beta2 * v + (1 - beta2) * (g' * g')
+ *   p  = p - (lr * weight_decay) * p                      (only when weight_decay != 0)
+ *   p  = p - lr * ((m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps))
+ * (the scalars 1 - beta, 1 - beta^step, lr * weight_decay are computed in double precision on the host and rounded
+ * once).  param, m, v are read and written; grad is read (and cleared when zero_grad is set); param_bf16 (may be NULL)
+ * receives the round-to-nearest-even bf16 copy of the new parameters, which is what qlora_linear_fwd / _bwd read as
+ * L1 / L2.  All LoRA parameters of a model can sit in one flat buffer and take one call.  sqnorm: NULL, or the device
+ * double that qlora_grad_sqnorm filled for ALL gradients of this step.  n = 0 is accepted and does nothing. */
+qlora_status qlora_adam_step(float* param, float* m, float* v, float* grad, uint16_t* param_bf16, int64_t n,
+                             const qlora_adam_config* cfg, const double* sqnorm, void* hip_stream);
+
 /* Measurement aid for the benchmark (not part of the method): while enabled, every launch of the
  * main MFMA GEMM kernel made by qlora_linear_fwd / qlora_linear_bwd is bracketed by a pair of HIP
  * events recorded on the call's stream.  qlora_profile_gemm_read waits for those events, returns

@@ -24,7 +24,14 @@ EXPORTS = [
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
     "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_nf4_quantize_static",
+    "qlora_grad_sqnorm", "qlora_adam_step",
 ]
+
+
+class qlora_adam_config(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double), ("grad_scale", ctypes.c_double),
+                ("max_grad_norm", ctypes.c_double), ("step", c_int64), ("zero_grad", c_int32), ("reserved", c_int32)]
 
 
 class QloraError(RuntimeError):
@@ -85,6 +92,8 @@ def lib():
     L.qlora_linear_bwd_list.argtypes = list(L.qlora_linear_fwd_list.argtypes)
     L.qlora_workspace_check.argtypes = [vp, c_size_t, vp]
     L.qlora_fewtok_poll_limit.argtypes = [c_int32]
+    L.qlora_grad_sqnorm.argtypes = [vp, c_int64, vp, vp]
+    L.qlora_adam_step.argtypes = [vp, vp, vp, vp, vp, c_int64, POINTER(qlora_adam_config), vp, vp]
     L.qlora_fewtok_poll_limit.restype = None
     L.qlora_profile_gemm.argtypes = [ctypes.c_int]
     L.qlora_profile_gemm.restype = None
@@ -480,6 +489,32 @@ def qlora_linear_bwd_dropout(dY, X, Wq: NF4Weight, L1, L2, s, keep_mask, p, T_sa
                                           _ptr(dL1_acc), _ptr(dL2_acc), _ptr(workspace), workspace.numel(),
                                           _stream(stream)))
     return dX, dL1, dL2
+
+
+def qlora_grad_sqnorm(grad, accum, stream=None):
+    """accum (device float64 tensor with one element) += sum of squares of grad (fp32 device tensor)."""
+    assert grad.is_cuda and grad.dtype == torch.float32 and grad.is_contiguous()
+    assert accum.is_cuda and accum.dtype == torch.float64 and accum.numel() == 1
+    _check(lib().qlora_grad_sqnorm(_ptr(grad), grad.numel(), _ptr(accum), _stream(stream)))
+    return accum
+
+
+def qlora_adam_step(param, m, v, grad, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0,
+                    max_grad_norm=0.0, sqnorm=None, param_bf16=None, zero_grad=False, stream=None):
+    """One Adam step in place on the fp32 device tensors param, m, v (grad is cleared when zero_grad is set);
+    param_bf16 receives the bf16 copy of the new parameters."""
+    n = param.numel()
+    for t in (param, m, v, grad):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n
+    if param_bf16 is not None:
+        assert param_bf16.is_cuda and param_bf16.dtype == torch.bfloat16 and param_bf16.is_contiguous()
+        assert param_bf16.numel() == n
+    if sqnorm is not None:
+        assert sqnorm.is_cuda and sqnorm.dtype == torch.float64 and sqnorm.numel() == 1
+    cfg = qlora_adam_config(lr, beta1, beta2, eps, weight_decay, grad_scale, max_grad_norm, int(step),
+                            1 if zero_grad else 0, 0)
+    _check(lib().qlora_adam_step(_ptr(param), _ptr(m), _ptr(v), _ptr(grad), _ptr(param_bf16), n, ctypes.byref(cfg),
+                                 _ptr(sqnorm), _stream(stream)))
 
 
 def qlora_profile_gemm(enable: bool):

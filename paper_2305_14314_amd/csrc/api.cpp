@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cmath>
 #include <vector>
 
 #include "common.hpp"
@@ -708,6 +709,40 @@ qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes
   QL_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
   QL_TRY(hipMemcpy(&status, (const unsigned*)workspace + qlora::kHeaderStatusWord, sizeof(status), hipMemcpyDeviceToHost));
   return status ? QLORA_ERR_STATE : QLORA_OK;
+}
+
+qlora_status qlora_grad_sqnorm(const float* grad, int64_t n, double* sqnorm_accum, void* hip_stream) {
+  if (n < 0) return QLORA_ERR_SHAPE;
+  if (n == 0) return QLORA_OK;                               // an empty buffer adds nothing
+  if (!grad || !sqnorm_accum) return QLORA_ERR_NULL;
+  if (!aligned16(grad) || ((uintptr_t)sqnorm_accum & 7u)) return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_grad_sqnorm(grad, n, sqnorm_accum, (hipStream_t)hip_stream));
+}
+
+qlora_status qlora_adam_step(float* param, float* m, float* v, float* grad, uint16_t* param_bf16, int64_t n,
+                             const qlora_adam_config* cfg, const double* sqnorm, void* hip_stream) {
+  if (!cfg) return QLORA_ERR_NULL;
+  if (n < 0 || cfg->step < 1) return QLORA_ERR_SHAPE;
+  if (!(cfg->beta1 >= 0.0 && cfg->beta1 < 1.0) || !(cfg->beta2 >= 0.0 && cfg->beta2 < 1.0) || !(cfg->eps >= 0.0) ||
+      !(cfg->lr == cfg->lr) || !(cfg->weight_decay == cfg->weight_decay) || !(cfg->grad_scale == cfg->grad_scale) ||
+      cfg->reserved != 0)
+    return QLORA_ERR_UNSUPPORTED;
+  if (n == 0) return QLORA_OK;                               // no parameters: nothing to do
+  if (!param || !m || !v || !grad) return QLORA_ERR_NULL;
+  if (!aligned16(param) || !aligned16(m) || !aligned16(v) || !aligned16(grad) || ((uintptr_t)param_bf16 & 7u) ||
+      ((uintptr_t)sqnorm & 7u))
+    return QLORA_ERR_ALIGN;
+  qlora::AdamConsts c{};
+  c.b1 = (float)cfg->beta1; c.b2 = (float)cfg->beta2;
+  c.omb1 = (float)(1.0 - cfg->beta1); c.omb2 = (float)(1.0 - cfg->beta2);
+  c.bc1 = (float)(1.0 - std::pow(cfg->beta1, (double)cfg->step));
+  c.bc2 = (float)(1.0 - std::pow(cfg->beta2, (double)cfg->step));
+  c.eps = (float)cfg->eps; c.lr = (float)cfg->lr;
+  c.lrwd = cfg->weight_decay != 0.0 ? (float)(cfg->lr * cfg->weight_decay) : 0.0f;
+  c.zero_grad = cfg->zero_grad != 0;
+  c.grad_scale = cfg->grad_scale; c.max_norm = cfg->max_grad_norm;
+  c.sqnorm = cfg->max_grad_norm > 0.0 ? sqnorm : nullptr;
+  return hip_status(qlora::launch_adam(param, m, v, grad, param_bf16, n, c, (hipStream_t)hip_stream));
 }
 
 void qlora_fewtok_poll_limit(int32_t polls) { g_poll_limit.store(polls < 0 ? 0 : polls, std::memory_order_relaxed); }

@@ -139,4 +139,18 @@ struct ListLayerDesc {
 hipError_t launch_fewlist(bool bwd, int M, int n, const ListLayerDesc* layers, const ListPlan& plan, unsigned* hdr,
                           unsigned nonce, int spin_limit, hipStream_t st);
 
+// adam.hip: optimizer step of the LoRA parameters.  Scalars derived from the hyperparameters are computed by the
+// caller in double precision and rounded once to fp32.
+struct AdamConsts {
+  float b1, b2, omb1, omb2;                  // beta, 1 - beta
+  float bc1, bc2;                            // 1 - beta^t
+  float eps, lr, lrwd;                       // lrwd = lr * weight_decay (0: no decay)
+  int zero_grad;                             // clear the gradient after it has been used
+  double grad_scale, max_norm;               // gradient coefficient = grad_scale * min(1, max_norm / (|grad_scale| sqrt(*sqnorm)))
+  const double* sqnorm;                      // device; NULL or max_norm <= 0: no clipping
+};
+hipError_t launch_grad_sqnorm(const float* g, int64_t n, double* accum, hipStream_t st);
+hipError_t launch_adam(float* p, float* m, float* v, float* g, uint16_t* p_bf16, int64_t n, const AdamConsts& c,
+                       hipStream_t st);
+
 }  // namespace qlora

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_status_strings(L):
-    for st in range(-6, 1):
+    for st in range(-7, 1):
         assert L.qlora_status_string(st).startswith(b"QLORA_")
 
 
@@ -286,3 +286,68 @@ def test_header_is_plain_c_and_the_library_links_from_c(L, tmp_path):
     P = 8192 * 22016
     assert out[:7] == ["0", str(P // 2), str(P // 64), str(4 * P // (64 * 256)), "0", "0.015625", "1"]
     assert out[7].startswith("QLORA_ERR_ALIGN")
+
+
+def test_list_and_header_arguments_are_rejected_on_the_host(L):
+    """The persistent list calls, the header check and the poll limit validate before any HIP call."""
+    from paper_2305_14314_amd import QloraError, qlora_linear_list_sizes
+    from paper_2305_14314_amd.binding import LIST_MAX, WORKSPACE_HEADER_BYTES, qlora_nf4_view
+    assert LIST_MAX == 8
+    assert qlora_linear_list_sizes(4, [64, 128], [64, 64], [0, 16]) > WORKSPACE_HEADER_BYTES
+    assert qlora_linear_list_sizes(4, [64, 128], [64, 64], [0, 16], backward=True) > WORKSPACE_HEADER_BYTES
+    for args, st in [((4, [], [], []), -2), ((4, [64] * 9, [64] * 9, [0] * 9), -2), ((4, [64], [96], [0]), -3),
+                     ((0, [64], [64], [0]), -2), ((4, [64], [64], [8]), -3)]:
+        with pytest.raises(QloraError) as e:
+            qlora_linear_list_sizes(*args)
+        assert e.value.status == st, args
+    fake, big, n = ctypes.c_void_p(0x1000), 1 << 30, 2
+    views = (qlora_nf4_view * n)(qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256),
+                                 qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 64, 128, 64, 256))
+    ptrs = lambda *v: (ctypes.c_void_p * n)(*v)
+    s, r0, r16 = (ctypes.c_float * n)(1.0, 1.0), (ctypes.c_int32 * n)(0, 0), (ctypes.c_int32 * n)(0, 16)
+    ok = ptrs(0x1000, 0x1000)
+    for f in (L.qlora_linear_fwd_list, L.qlora_linear_bwd_list):
+        assert f(n, None, views, None, None, s, 4, r0, ok, fake, big, None) == -1                      # inputs
+        assert f(n, ptrs(0x1000, None), views, None, None, s, 4, r0, ok, fake, big, None) == -1        # input 1
+        assert f(n, ok, views, None, None, s, 4, r0, ptrs(None, 0x1000), fake, big, None) == -1        # output 0
+        assert f(n, ok, views, None, None, s, 4, r16, ok, fake, big, None) == -1                       # adapter of layer 1
+        assert f(n, ok, views, None, None, s, 4, r0, ok, None, big, None) == -1                        # workspace
+        assert f(0, ok, views, None, None, s, 4, r0, ok, fake, big, None) == -2
+        assert f(9, ok, views, None, None, s, 4, r0, ok, fake, big, None) == -2
+        assert f(n, ok, views, None, None, s, 0, r0, ok, fake, big, None) == -2
+        assert f(n, ok, views, None, None, s, 4, r0, ok, fake, 64, None) == -4                         # too small
+        assert f(n, ok, views, None, None, s, 4, r0, ptrs(0x1000, 0x1008), fake, big, None) == -5
+    # the header check: arguments first (it would synchronise the stream and read the status word otherwise)
+    assert L.qlora_workspace_check(None, big, None) == -1
+    assert L.qlora_workspace_check(fake, WORKSPACE_HEADER_BYTES - 1, None) == -4
+    assert L.qlora_status_string(-7).startswith(b"QLORA_ERR_STATE")
+    L.qlora_fewtok_poll_limit(-5)                              # clamped, no error path
+    L.qlora_fewtok_poll_limit(64)
+
+
+def test_optimizer_arguments_are_rejected_on_the_host(L):
+    from paper_2305_14314_amd.binding import qlora_adam_config
+    fake = ctypes.c_void_p(0x1000)
+    cfg = qlora_adam_config(1e-4, 0.9, 0.999, 1e-8, 0.0, 1.0, 0.3, 1, 0, 0)
+    f = L.qlora_adam_step
+    assert f(fake, fake, fake, fake, None, 64, None, None, None) == -1                                  # no config
+    assert f(None, fake, fake, fake, None, 64, ctypes.byref(cfg), None, None) == -1
+    assert f(fake, fake, fake, None, None, 64, ctypes.byref(cfg), None, None) == -1
+    assert f(fake, fake, fake, fake, None, -1, ctypes.byref(cfg), None, None) == -2
+    assert f(ctypes.c_void_p(0x1004), fake, fake, fake, None, 64, ctypes.byref(cfg), None, None) == -5
+    assert f(fake, fake, fake, fake, ctypes.c_void_p(0x1004), 64, ctypes.byref(cfg), None, None) == -5  # bf16 copy
+    assert f(fake, fake, fake, fake, None, 64, ctypes.byref(cfg), ctypes.c_void_p(0x1004), None) == -5  # norm
+    assert f(None, None, None, None, None, 0, ctypes.byref(cfg), None, None) == 0                       # empty: nothing to do
+    for field, bad in (("step", 0), ("beta1", 1.0), ("beta2", -0.1), ("eps", -1.0), ("lr", float("nan")), ("reserved", 1)):
+        c = qlora_adam_config(1e-4, 0.9, 0.999, 1e-8, 0.0, 1.0, 0.3, 1, 0, 0)
+        setattr(c, field, bad)
+        assert f(fake, fake, fake, fake, None, 64, ctypes.byref(c), None, None) in (-2, -3), field
+    g = L.qlora_grad_sqnorm
+    assert g(None, 64, fake, None) == -1 and g(fake, 64, None, None) == -1
+    assert g(fake, -1, fake, None) == -2 and g(None, 0, None, None) == 0
+    assert g(ctypes.c_void_p(0x1004), 64, fake, None) == -5 and g(fake, 64, ctypes.c_void_p(0x1004), None) == -5
+    # the static-scratch quantiser: its size limit is checked before anything else touches the device
+    q = L.qlora_nf4_quantize_static
+    assert q(fake, 1 << 15, (1 << 13) + 64, 64, 256, fake, fake, fake, fake, None) == -4
+    assert q(None, 64, 64, 64, 256, fake, fake, fake, fake, None) == -1
+    assert q(fake, 64, 96, 64, 256, fake, fake, fake, fake, None) in (-2, -3)
