@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 PEAK_HBM_GBS = 8000.0
-SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam")
+SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam", "stacked")
 
 
 def _ensure_built():
@@ -303,6 +303,35 @@ def main():
                             "frac_hbm": round(el * 2.5159 / (t * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
                             "bytes_per_element": 2.5159}
         del outb
+    if want("stacked"):
+        # the layers of a block that read one input, forward only: one call per layer against one stacked call
+        # (one matrix product over all outputs, adapters block-diagonal in the second contraction segment)
+        st = {}
+        for name, idx in (("qkv", [0, 1, 2]), ("gate_up", [4, 5])):
+            n = len(idx)
+            outs = [linears[i][1] for i in idx]
+            Ys = [torch.empty((M, o_), dtype=torch.bfloat16, device=dev) for o_ in outs]
+            Yst = torch.empty((M, sum(outs)), dtype=torch.bfloat16, device=dev)
+            ws_st = ql.workspace_alloc(ql.qlora_linear_fwd_stacked_sizes(M, d, outs, [r] * n), dev)
+            k = [0]
+
+            def separate():
+                blk = pool[k[0] % len(pool)]
+                k[0] += 1
+                for j, i in enumerate(idx):
+                    ql.qlora_linear_fwd(X[d], blk[i], L1[i], L2[i], s, Y=Ys[j], workspace=ws)
+
+            def stacked():
+                blk = pool[k[0] % len(pool)]
+                k[0] += 1
+                ql.qlora_linear_fwd_stacked(X[d], [blk[i] for i in idx], [L1[i] for i in idx],
+                                            [L2[i] for i in idx], [s] * n, Y=Yst, workspace=ws_st)
+            t_sep = _time_ms(torch, separate, 12)
+            t_st = _time_ms(torch, stacked, 12)
+            st[name] = {"separate_us": round(t_sep * 1e3, 1), "stacked_us": round(t_st * 1e3, 1),
+                        "stacked_over_separate": round(t_st / t_sep, 4)}
+            del Ys, Yst, ws_st
+        extra["stacked"] = st
     if want("adam"):
         # optimizer step on the adapters of 8 blocks (80 M parameters in one flat buffer): global-norm pass over the
         # gradient, then Adam with clipping, the bf16 copy and the cleared gradient: 4 + 34 bytes per parameter

@@ -301,6 +301,21 @@ qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf
                                     int64_t M, const int32_t* r, uint16_t* const* Y,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same layers at training token counts with ONE matrix product for all of them (Eq. 5 per layer): the
+ * dequantised weights are stacked along the output dimension, the adapters share the second contraction segment
+ * block-diagonally (layer l's s[l] * X * L1[l] meets only layer l's L2[l]), and the outputs come out side by side:
+ *   Y is M x (o[0] + ... + o[n-1]), row-major; layer l's output is the column range starting at o[0] + ... + o[l-1].
+ * T_save: NULL, or a host array of n device pointers (entries may be NULL): T_save[l] receives X * L1[l] as the
+ * M x 2 r[l] [hi | lo] pair qlora_linear_bwd takes.  Any M >= 1 (few tokens take the same path).  Workspace: the size
+ * qlora_linear_fwd_stacked_sizes reports, (sum o) * (h + sum of the ranks rounded up to 64) bf16 values and a few
+ * small buffers; same rules otherwise.  Each layer's output meets the tolerance of qlora_linear_fwd. */
+qlora_status qlora_linear_fwd_stacked_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
+                                            size_t* workspace_bytes);
+qlora_status qlora_linear_fwd_stacked(const uint16_t* X, int32_t n, const qlora_nf4_view* Wq,
+                                      const uint16_t* const* L1, const uint16_t* const* L2, const float* s,
+                                      int64_t M, const int32_t* r, uint16_t* Y, uint16_t* const* T_save,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Forward of a LIST of independent QLoRA linear layers at a few tokens in ONE launch (Eq. 5 applied per layer; the
  * adapter sits on every linear layer of a decoder block -- Section 5 and the hyperparameter appendix):
  *   Y[l] = X[l] * doubleDequant(Wq[l]) + s[l] * (X[l] * L1[l]) * L2[l],   l = 0 .. n-1,  1 <= n <= QLORA_LIST_MAX.

@@ -24,7 +24,7 @@ EXPORTS = [
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
     "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_nf4_quantize_static",
-    "qlora_grad_sqnorm", "qlora_adam_step",
+    "qlora_grad_sqnorm", "qlora_adam_step", "qlora_linear_fwd_stacked_sizes", "qlora_linear_fwd_stacked",
 ]
 
 
@@ -80,6 +80,9 @@ def lib():
     L.qlora_linear_fwd_multi_sizes.argtypes = [c_int64, c_int32, c_int64, POINTER(c_int64), POINTER(c_int32), sp]
     L.qlora_linear_fwd_multi.argtypes = [vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
                                          c_int64, POINTER(c_int32), POINTER(vp), vp, c_size_t, vp]
+    L.qlora_linear_fwd_stacked_sizes.argtypes = list(L.qlora_linear_fwd_multi_sizes.argtypes)
+    L.qlora_linear_fwd_stacked.argtypes = [vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
+                                           c_int64, POINTER(c_int32), vp, POINTER(vp), vp, c_size_t, vp]
     L.qlora_linear_dropout_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp, sp]
     L.qlora_linear_fwd_dropout.argtypes = [vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp, c_float,
                                            vp, vp, vp, c_size_t, vp]
@@ -339,6 +342,33 @@ def qlora_linear_fwd_multi(X, Wqs, L1s, L2s, ss, Ys=None, workspace=None, stream
                                         M, (c_int32 * n)(*rs), ptrs(Ys), _ptr(workspace), workspace.numel(),
                                         _stream(stream)))
     return Ys
+
+
+def qlora_linear_fwd_stacked_sizes(M, h, os_, rs) -> int:
+    n = len(os_)
+    out = c_size_t()
+    _check(lib().qlora_linear_fwd_stacked_sizes(M, n, h, (c_int64 * n)(*os_), (c_int32 * n)(*rs), ctypes.byref(out)))
+    return int(out.value)
+
+
+def qlora_linear_fwd_stacked(X, Wqs, L1s, L2s, ss, Y=None, T_saves=None, workspace=None, stream=None):
+    """The layers of qlora_linear_fwd_multi with one matrix product: returns Y (M, sum o), layer l in the column range
+    that starts at o[0] + ... + o[l-1].  T_saves: None or a list of (M, 2 r) bf16 tensors / None per layer."""
+    n = len(Wqs)
+    M, h = X.shape
+    rs = [0 if L1s[l] is None else L1s[l].shape[1] for l in range(n)]
+    N = sum(w.cols for w in Wqs)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    assert Y.shape == (M, N) and Y.is_contiguous()
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_fwd_stacked_sizes(M, h, [w.cols for w in Wqs], rs), X.device, stream)
+    views = (qlora_nf4_view * n)(*[w.view() for w in Wqs])
+    ptrs = lambda ts: (c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
+    _check(lib().qlora_linear_fwd_stacked(_ptr(X), n, views, ptrs(L1s), ptrs(L2s), (c_float * n)(*[float(s) for s in ss]),
+                                          M, (c_int32 * n)(*rs), _ptr(Y), None if T_saves is None else ptrs(T_saves),
+                                          _ptr(workspace), workspace.numel(), _stream(stream)))
+    return Y
 
 
 LIST_MAX = 8

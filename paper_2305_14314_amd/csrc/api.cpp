@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <vector>
@@ -525,6 +526,91 @@ qlora_status qlora_linear_fwd_multi(const uint16_t* X, int32_t n, const qlora_nf
     layers[l] = qlora::FewLayer{to_dev(&Wq[l]), r[l] > 0 ? L1[l] : nullptr, r[l] > 0 ? L2[l] : nullptr, r[l], s[l],
                                 p.fpart[l], p.lpart[l], Y[l]};
   QL_TRY(qlora::launch_fewtok_fwd_multi(X, (int)M, n, layers, p.splits, (unsigned*)workspace, (hipStream_t)hip_stream));
+  return QLORA_OK;
+}
+
+// Several layers on one X at training token counts: the dequantised weights stacked along n, the adapters
+// block-diagonal in the second K segment, one product for all outputs.
+namespace {
+struct StackPlan {
+  uint16_t* Wt;      // (sum o) x (h + Rp): row n of layer l = What_l^T[n], then L2_l^T[n] in the layer's rank columns
+  uint16_t* Ts;      // M x Rp: [s_0 X L1_0 | s_1 X L1_1 | ...], every layer's rank zero-padded to a multiple of 64
+  float* part;       // split-K partials of one X L1 at a time
+  int Rp, off[QLORA_MULTI_MAX], rp[QLORA_MULTI_MAX], splits[QLORA_MULTI_MAX];
+  int64_t N;
+  size_t bytes;
+};
+StackPlan plan_fwd_stacked(void* ws, int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r) {
+  StackPlan p{};
+  Carver c(ws);
+  size_t pe = 0;
+  for (int l = 0; l < n; ++l) {
+    p.N += o[l];
+    p.off[l] = p.Rp;
+    p.rp[l] = r[l] > 0 ? (r[l] + 63) / 64 * 64 : 0;
+    p.Rp += p.rp[l];
+    if (r[l] > 0) {
+      p.splits[l] = qlora::small_gemm_splits((int)M, r[l], (int)h);
+      pe = std::max(pe, (size_t)p.splits[l] * M * r[l]);
+    }
+  }
+  p.Wt = c.take<uint16_t>((size_t)(h + p.Rp) * p.N);
+  if (p.Rp > 0) {
+    p.Ts = c.take<uint16_t>((size_t)M * p.Rp);
+    p.part = c.take<float>(pe);
+  }
+  p.bytes = c.off;
+  return p;
+}
+}  // namespace
+
+qlora_status qlora_linear_fwd_stacked_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
+                                            size_t* workspace_bytes) {
+  if (!o || !r || !workspace_bytes) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_MULTI_MAX) return QLORA_ERR_SHAPE;
+  for (int l = 0; l < n; ++l)
+    if (qlora_status st = check_linear(M, h, o[l], r[l])) return st;
+  *workspace_bytes = plan_fwd_stacked(nullptr, M, n, h, o, r).bytes;
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_fwd_stacked(const uint16_t* X, int32_t n, const qlora_nf4_view* Wq, const uint16_t* const* L1,
+                                      const uint16_t* const* L2, const float* s, int64_t M, const int32_t* r,
+                                      uint16_t* Y, uint16_t* const* T_save, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+  if (!X || !Wq || !s || !r || !Y || !workspace) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_MULTI_MAX) return QLORA_ERR_SHAPE;
+  int64_t o[QLORA_MULTI_MAX];
+  const int64_t h = Wq[0].rows;
+  for (int l = 0; l < n; ++l) {
+    if (qlora_status st = check_view(&Wq[l])) return st;
+    if (Wq[l].rows != h) return QLORA_ERR_SHAPE;              // every layer reads the same X
+    o[l] = Wq[l].cols;
+    if (qlora_status st = check_linear(M, h, o[l], r[l])) return st;
+    if (r[l] > 0 && (!L1 || !L2 || !L1[l] || !L2[l])) return QLORA_ERR_NULL;
+    if (r[l] > 0 && (!aligned16(L1[l]) || !aligned16(L2[l]))) return QLORA_ERR_ALIGN;
+    if (T_save && !aligned16(T_save[l])) return QLORA_ERR_ALIGN;
+  }
+  if (!aligned16(X) || !aligned16(Y) || !aligned16(workspace)) return QLORA_ERR_ALIGN;
+  const StackPlan p = plan_fwd_stacked(workspace, M, n, h, o, r);
+  if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t ldw = h + p.Rp;
+  int64_t n0 = 0;
+  for (int l = 0; l < n; ++l) {
+    if (r[l] > 0) {
+      // T_l = X L1_l (Eq. 3), scaled and rounded into its rank columns of Ts
+      QL_TRY(qlora::launch_small_gemm(X, h, false, L1[l], r[l], true, 0, 0, (int)M, r[l], (int)h, p.part, p.splits[l], st,
+                                      nullptr));
+      QL_TRY(qlora::launch_small_finalize(p.part, p.splits[l], (int)M, r[l], p.Ts + p.off[l], p.Rp, p.rp[l], s[l],
+                                          T_save ? T_save[l] : nullptr, nullptr, st));
+    }
+    QL_TRY(qlora::launch_dequant_t(to_dev(&Wq[l]), p.Wt + n0 * ldw, ldw, st, r[l] > 0 ? L2[l] : nullptr, r[l], p.Rp,
+                                   p.off[l]));
+    n0 += o[l];
+  }
+  // Y[:, layer l's columns] = X What_l + s_l (X L1_l) L2_l (Eq. 5 per layer)
+  QL_TRY(gemm_nt_timed(X, p.Wt, h, ldw, (int)h, p.Ts, p.Wt + h, p.Rp, ldw, p.Rp, Y, p.N, (int)M, (int)p.N, st));
   return QLORA_OK;
 }
 

@@ -84,14 +84,15 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
 // form 128-byte runs along k.  No LDS staging of data.
 //
 // Workgroup rows beyond the weight's (blockIdx.y >= ceil(h / 64)) transpose the adapter's L2 (r x o, bf16) the same
-// way into columns h .. h + rp - 1 of `out` (rows t >= r are written as zeros), so that one buffer of row stride
-// ld_out >= h + rp holds both K segments of the forward product's weight-side operand and no launch of its own is
-// spent on a 1 MB transpose.
+// way into columns h + col0 .. h + col0 + r - 1 of `out` and write zeros to the rest of columns h .. h + rp - 1, so
+// that one buffer of row stride ld_out >= h + rp holds both K segments of the forward product's weight-side operand
+// and no launch of its own is spent on a 1 MB transpose.  (col0 > 0: several layers stacked along n share the adapter
+// segment block-diagonally: a layer's rows hold its own L2^T in its own columns and zeros in the others'.)
 template <bool DQ, bool I8>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     const void* __restrict__ packed_v, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint16_t* __restrict__ out, int h, int o, int64_t ld_out, const int dtype,
-    const Table4 tab, const uint16_t* __restrict__ L2, int r) {
+    const Table4 tab, const uint16_t* __restrict__ L2, int r, int col0) {
   constexpr bool dq = DQ;
   const uint32_t* __restrict__ packed = (const uint32_t*)packed_v;
   const int w_rows = (h + 63) >> 6;                          // workgroup rows of the weight
@@ -105,8 +106,8 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
     uint4 row[8];                                            // row[j] = L2[t_base + j][n_first .. n_first + 7]
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int t = t_base + j;
-      row[j] = (t < r) ? *(const uint4*)(L2 + (int64_t)t * o + n_first) : uint4{0u, 0u, 0u, 0u};
+      const int t = t_base + j - col0;                        // row of L2 that belongs into column h + t_base + j
+      row[j] = (t >= 0 && t < r) ? *(const uint4*)(L2 + (int64_t)t * o + n_first) : uint4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -175,15 +176,15 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_t_kernel(
 }
 
 hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st, const uint16_t* L2, int r,
-                            int rp) {
+                            int rp, int col0) {
   const int h = (int)w.rows, o = (int)w.cols;
-  if (L2 == nullptr) { r = 0; rp = 0; }
-  if (rp % 64 != 0 || r > rp || ld_out < h + rp || ld_out % 8 != 0) return hipErrorInvalidValue;
+  if (L2 == nullptr) { r = 0; col0 = 0; }                    // rp > 0 without an adapter: the segment is all zeros
+  if (rp % 64 != 0 || col0 < 0 || col0 + r > rp || ld_out < h + rp || ld_out % 8 != 0) return hipErrorInvalidValue;
   dim3 grid((unsigned)((o + 255) / 256), (unsigned)((h + 63) / 64 + rp / 64));
   const bool i8 = w.dtype == kTypeInt8;
 #define QL_DEQ_T(DQ, I8)                                                                                        \
   hipLaunchKernelGGL((dequant_nf4_t_kernel<DQ, I8>), grid, dim3(kDeqThreads), 0, st, (const void*)w.packed, w.code, \
-                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype), L2, r)
+                     w.c1, w.mean, out, h, o, ld_out, w.dtype, table4_host(w.dtype), L2, r, col0)
   if (w.dq) { if (i8) QL_DEQ_T(true, true); else QL_DEQ_T(true, false); }
   else      { if (i8) QL_DEQ_T(false, true); else QL_DEQ_T(false, false); }
 #undef QL_DEQ_T

@@ -32,10 +32,10 @@ hipError_t launch_quantize_static(const float* W, int64_t rows, int64_t cols, ui
 // dequant.hip
 hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);
 // out[n][k] = dequant(W)[k][n] with row stride ld_out (elements); requires h % 8 == 0.
-// L2 != NULL (r x o bf16, rp = r rounded up to a multiple of 64, ld_out >= h + rp): the same launch also writes
-// out[n][h + t] = L2[t][n] for t < r and zeros for r <= t < rp.
+// rp > 0 (a multiple of 64, ld_out >= h + rp): the same launch also writes the adapter segment, columns h .. h + rp - 1:
+// out[n][h + col0 + t] = L2[t][n] for t < r (L2: r x o bf16, col0 + r <= rp; NULL: none) and zeros elsewhere.
 hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipStream_t st,
-                            const uint16_t* L2 = nullptr, int r = 0, int rp = 0);
+                            const uint16_t* L2 = nullptr, int r = 0, int rp = 0, int col0 = 0);
 
 // gemm.hip: C[M x N] = A0 B0^T + A1 B1^T, all operands K-contiguous bf16, K0 and K1 multiples of 64.
 hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
