@@ -86,7 +86,7 @@ int qlora_last_hip_error(void);
  * parameter, 4.5 bit in all): `c1` holds the n fp32 first-level constants c2 themselves, in flattened block order,
  * and c2_code / c2_mean are not read (may be NULL).  Such a weight is accepted by quantise, dequantise and the
  * linear-layer calls, which then take the large-GEMM path at any M -- the few-token streaming kernels read
- * double-quantised constants; size the workspaces with qlora_linear_dropout_sizes -- and refused with
+ * double-quantised constants; the sizes qlora_linear_fwd_sizes / _bwd_sizes report cover that plan -- and refused with
  * QLORA_ERR_UNSUPPORTED by qlora_linear_fwd_multi at M <= 16.
  *
  * 8-bit integers (dtype = QLORA_INT8; Eq. 1 and Eq. 2 as printed): `packed` holds one signed byte per weight,
@@ -206,7 +206,10 @@ qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void*
 qlora_status qlora_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Workspace (bytes) qlora_linear_fwd / qlora_linear_bwd need for this shape
- * (header included). */
+ * (header included), whatever the weight's data type: at M <= 16 a 4-bit
+ * double-quantised weight takes the streaming kernels and any other weight
+ * (QLORA_INT8, dq_blocksize = 0) the dequantise + GEMM plan; the larger of
+ * the two sizes is reported. */
 qlora_status qlora_linear_fwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes);
 qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes);
 

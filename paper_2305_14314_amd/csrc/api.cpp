@@ -391,14 +391,16 @@ qlora_status qlora_nf4_dequant(const qlora_nf4_view* Wq, uint16_t* W_bf16, void*
 qlora_status qlora_linear_fwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes) {
   if (qlora_status st = check_linear(M, h, o, r)) return st;
   if (!workspace_bytes) return QLORA_ERR_NULL;
-  *workspace_bytes = plan_fwd(nullptr, M, h, o, r).bytes;
+  // no view here: few tokens stream 4-bit, double-quantised weights, every other weight takes the dequantise + GEMM
+  // plan at any M, so the size that serves both is reported
+  *workspace_bytes = std::max(plan_fwd(nullptr, M, h, o, r, true).bytes, plan_fwd(nullptr, M, h, o, r, false).bytes);
   return QLORA_OK;
 }
 
 qlora_status qlora_linear_bwd_sizes(int64_t M, int64_t h, int64_t o, int32_t r, size_t* workspace_bytes) {
   if (qlora_status st = check_linear(M, h, o, r)) return st;
   if (!workspace_bytes) return QLORA_ERR_NULL;
-  *workspace_bytes = plan_bwd(nullptr, M, h, o, r).bytes;
+  *workspace_bytes = std::max(plan_bwd(nullptr, M, h, o, r, true).bytes, plan_bwd(nullptr, M, h, o, r, false).bytes);
   return QLORA_OK;
 }
 

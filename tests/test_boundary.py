@@ -151,14 +151,18 @@ def test_dropout_arguments_are_rejected_on_the_host(L):
     assert b(fake, fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, None, 0.1, None, fake, None, None, None, None, fake, big, None) == -1
     assert b(fake, None, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 0.1, None, fake, fake, None, None, None, fake, big, None) == -1  # dL1 needs X
     assert b(fake, fake, ctypes.byref(v), fake, fake, 1.0, 4, 16, fake, 0.1, None, fake, None, None, None, None, fake, 64, None) == -4
-    # 4 tokens: the plain calls would stream (small workspace), the dropout calls dequantise the whole weight
+    # 4 tokens: the plain calls would stream (small workspace), the dropout calls dequantise the whole weight; the
+    # plain size queries know no data type and report a size that serves both plans (an 8-bit or not double-quantised
+    # weight takes the dequantise plan at any M)
     fb, bb = qlora_linear_dropout_sizes(4, 1024, 1024, 16)
     assert fb >= 2 * 1024 * 1024 and bb >= 2 * 1024 * 1024
-    assert fb > qlora_linear_fwd_sizes(4, 1024, 1024, 16) and bb > qlora_linear_bwd_sizes(4, 1024, 1024, 16)
+    assert qlora_linear_fwd_sizes(4, 1024, 1024, 16) >= fb and qlora_linear_bwd_sizes(4, 1024, 1024, 16) >= bb
     assert qlora_linear_dropout_sizes(300, 1024, 1024, 16) == (qlora_linear_fwd_sizes(300, 1024, 1024, 16),
                                                                 qlora_linear_bwd_sizes(300, 1024, 1024, 16))
-    assert qlora_linear_dropout_sizes(4, 1024, 1024, 0) == (qlora_linear_fwd_sizes(4, 1024, 1024, 0),
-                                                             qlora_linear_bwd_sizes(4, 1024, 1024, 0))
+    # no adapter, nothing to drop: the dropout calls are the plain ones, streaming kernels included (small workspace)
+    f0, b0 = qlora_linear_dropout_sizes(4, 1024, 1024, 0)
+    assert f0 < 1024 * 1024 and b0 < 1024 * 1024
+    assert f0 <= qlora_linear_fwd_sizes(4, 1024, 1024, 0) and b0 <= qlora_linear_bwd_sizes(4, 1024, 1024, 0)
 
 
 def test_data_type_tables_and_their_validation(L, oracle):
