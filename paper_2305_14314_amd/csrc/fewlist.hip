@@ -784,6 +784,7 @@ ListPlan fewlist_plan(bool bwd, int M, int n, const int* h, const int* o, const 
     if (adapters > grid || (units + (int64_t)credit * adapters) / grid < credit + 1) credit = 0;
     q.credit = credit;
     q.cost_total = units + (int64_t)credit * adapters;
+    q.q = (int)(q.cost_total / grid); q.rem = (int)(q.cost_total % grid);   // q >= 1: grid <= units
     int worst = 1;
     for (int l = 0; l < n; ++l) {
       int mc = 1;

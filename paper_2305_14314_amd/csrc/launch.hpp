@@ -106,15 +106,22 @@ hipError_t launch_workspace_init(void* workspace, hipStream_t st);
 // units for it.  Host (sizes, launch) and device evaluate the same two functions.
 constexpr int kListMax = 8;
 constexpr int kListLoraChunk = 1024;         // contraction elements per adapter item (more when a layer would need over 23 items)
-struct ListPart { long long cost_total; int grid, credit, n_adapter; };
-__host__ __device__ inline int list_start(const ListPart& q, int rho) {
-  const int a = rho < q.n_adapter ? rho : q.n_adapter;
-  return (int)(((long long)rho * q.cost_total) / q.grid - (long long)q.credit * a);
+struct ListPart {
+  long long cost_total; int grid, credit, n_adapter;
+  int q, rem;                                // cost_total / grid and cost_total % grid: the kernels divide 32-bit numbers only
+};
+// floor(rho * cost_total / grid) - credit * min(rho, n_adapter), for 0 <= rho <= grid <= 256
+__host__ __device__ inline int list_start(const ListPart& p, int rho) {
+  const int a = rho < p.n_adapter ? rho : p.n_adapter;
+  return rho * p.q + (int)((unsigned)(rho * p.rem) / (unsigned)p.grid) - p.credit * a;
 }
-// the workgroup whose range holds unit u (0 <= u < total units); ranges are non-empty and ascending by construction
-__host__ __device__ inline int list_rho_of(const ListPart& q, int u) {
-  int rho = (int)(((long long)u * q.grid) / q.cost_total);   // start(rho) <= rho * cost / grid <= u
-  while (rho + 1 < q.grid && list_start(q, rho + 1) <= u) ++rho;
+// the workgroup whose range holds unit u (0 <= u < total units); ranges are non-empty and ascending by construction.
+// The first guess only sets how often the two loops run: the result is exact whatever it is.
+__host__ __device__ inline int list_rho_of(const ListPart& p, int u) {
+  int rho = (int)((float)u / (float)p.q);
+  if (rho > p.grid - 1) rho = p.grid - 1;
+  while (rho > 0 && list_start(p, rho) > u) --rho;
+  while (rho + 1 < p.grid && list_start(p, rho + 1) <= u) ++rho;
   return rho;
 }
 struct ListPlan {

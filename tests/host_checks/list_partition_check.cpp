@@ -22,6 +22,14 @@ static int check(bool bwd, int M, int n, const int* h, const int* o, const int* 
   const ListPart& q = P.part;
   if (q.grid < 1 || q.grid > 256) return fail("grid", q.grid, 0, 0);
   if (list_start(q, 0) != 0 || list_start(q, q.grid) != P.total_units) return fail("ends", list_start(q, q.grid), P.total_units, 0);
+  for (int rho = 0; rho <= q.grid; ++rho) {                  // the 32-bit form the kernels evaluate against the definition
+    const long long want = (long long)rho * q.cost_total / q.grid - (long long)q.credit * (rho < q.n_adapter ? rho : q.n_adapter);
+    if (list_start(q, rho) != want) return fail("list_start differs from its definition", rho, list_start(q, rho), (int)want);
+  }
+  for (int u = 0; u < P.total_units; u += 1 + P.total_units / 997) {   // inverse map on a sample of all units
+    const int rho = list_rho_of(q, u);
+    if (rho < 0 || rho >= q.grid || list_start(q, rho) > u || list_start(q, rho + 1) <= u) return fail("rho_of(u)", u, rho, 0);
+  }
   for (int rho = 0; rho < q.grid; ++rho) {
     const int a = list_start(q, rho), b = list_start(q, rho + 1);
     if (b <= a) return fail("empty or descending range", rho, a, b);
