@@ -109,6 +109,36 @@ def test_list_65b_block(oracle, synth, M):
         del What
 
 
+@pytest.mark.parametrize("config,M", [(1, 4), (2, 16)])
+def test_list_7b_13b_blocks(oracle, synth, config, M):
+    """The seven linears of the 7B- and 13B-shaped blocks (d = 4096 / 5120, ffn = 11008 / 13824: 43 and 54 slabs, the
+    contraction of `down` ragged against the 1024-element adapter chunks) as one list, forward and input gradient, every
+    output element."""
+    import paper_2305_14314_amd as ql
+    cfg = synth.CONFIGS[config]
+    r, s = cfg["r"], cfg["alpha"] / cfg["r"]
+    layers = []
+    for l, (h, o) in enumerate(cfg["linears"]):
+        Wd = synth.normal_f32_device((h, o), synth.SIGMA_W, synth.tensor_seed(config, l, "W") + 55)
+        Wq = ql.qlora_nf4_quantize(Wd)
+        del Wd
+        hL1 = synth.normal_bf16((h, r), cfg["sigma_l"], synth.tensor_seed(config, l, "L1") + 55)
+        hL2 = synth.normal_bf16((r, o), cfg["sigma_l"], synth.tensor_seed(config, l, "L2") + 55)
+        hX = synth.normal_bf16((M, h), 1.0, synth.tensor_seed(config, l, "X") + 55 + M)
+        hdY = synth.normal_bf16((M, o), 1.0, synth.tensor_seed(config, l, "dY") + 55 + M)
+        layers.append(dict(h=h, o=o, r=r, Wq=Wq, What=None, hL1=hL1, hL2=hL2, hX=hX, hdY=hdY, L1=dev_bf16(hL1),
+                           L2=dev_bf16(hL2), X=dev_bf16(hX), dY=dev_bf16(hdY), s=s))
+    print(f"case list {cfg['name']} M={M}", flush=True)
+    Ys = _run_list(ql, layers, False)
+    dXs = _run_list(ql, layers, True)
+    torch.cuda.synchronize()
+    for l, y in enumerate(layers):
+        What = oracle.nf4_dequant(download_quant(y["Wq"]))
+        _check(host_bits(Ys[l]), oracle.linear_fwd(y["hX"], What, y["hL1"], y["hL2"], s), f"{cfg['name']} M={M} layer {l} Y")
+        _check(host_bits(dXs[l]), oracle.linear_bwd_dx(y["hdY"], What, y["hL1"], y["hL2"], s), f"{cfg['name']} M={M} layer {l} dX")
+        del What
+
+
 @pytest.mark.parametrize("backward", [False, True])
 def test_list_output_stage_handed_to_the_adapter(oracle, synth, backward):
     """Poll limit 0: a slab's last contributor never waits for the adapter's partial sums, so wherever they are not in
