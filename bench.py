@@ -331,6 +331,36 @@ def main():
             st[name] = {"separate_us": round(t_sep * 1e3, 1), "stacked_us": round(t_st * 1e3, 1),
                         "stacked_over_separate": round(t_st / t_sep, 4)}
             del Ys, Yst, ws_st
+            # backward (input gradient and adapter gradients): one call per layer, whose input gradients a block then
+            # has to add up (two or one elementwise sums of M x h), against one stacked call that writes the sum
+            dYst = B.rnd(M, sum(outs))
+            dYs = [dYst[:, j * outs[0]:(j + 1) * outs[0]].contiguous() for j in range(n)]
+            dXs = [torch.empty((M, d), dtype=torch.bfloat16, device=dev) for _ in range(n)]
+            dXst = torch.empty((M, d), dtype=torch.bfloat16, device=dev)
+            ws_sb = ql.workspace_alloc(ql.qlora_linear_bwd_stacked_sizes(M, d, outs, [r] * n), dev)
+
+            def separate_bwd(add=True):
+                blk = pool[k[0] % len(pool)]
+                k[0] += 1
+                for j, i in enumerate(idx):
+                    ql.qlora_linear_bwd(dYs[j], X[d], blk[i], L1[i], L2[i], s, T_saved=T[i], dX=dXs[j], dL1=B.dL1[i],
+                                        dL2=B.dL2[i], workspace=ws)
+                if add:
+                    for j in range(1, n):
+                        dXs[0].add_(dXs[j])
+
+            def stacked_bwd():
+                blk = pool[k[0] % len(pool)]
+                k[0] += 1
+                ql.qlora_linear_bwd_stacked(dYst, X[d], [blk[i] for i in idx], [L1[i] for i in idx], [L2[i] for i in idx],
+                                            [s] * n, T_saveds=[T[i] for i in idx], dX=dXst, workspace=ws_sb,
+                                            dL1s=[B.dL1[i] for i in idx], dL2s=[B.dL2[i] for i in idx])
+            t_sep = _time_ms(torch, separate_bwd, 12)
+            t_sep0 = _time_ms(torch, lambda: separate_bwd(False), 12)
+            t_st = _time_ms(torch, stacked_bwd, 12)
+            st[name + "_bwd"] = {"separate_with_sums_us": round(t_sep * 1e3, 1), "separate_without_sums_us": round(t_sep0 * 1e3, 1),
+                                 "stacked_us": round(t_st * 1e3, 1), "stacked_over_separate_with_sums": round(t_st / t_sep, 4)}
+            del dYst, dYs, dXs, dXst, ws_sb
         extra["stacked"] = st
     if want("adam"):
         # optimizer step on the adapters of 8 blocks (80 M parameters in one flat buffer): global-norm pass over the

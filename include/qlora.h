@@ -319,6 +319,24 @@ qlora_status qlora_linear_fwd_stacked(const uint16_t* X, int32_t n, const qlora_
                                       int64_t M, const int32_t* r, uint16_t* Y, uint16_t* const* T_save,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The backward of the same group of layers.  Layers that read one input have ONE input gradient, the sum of theirs
+ * (Section 3 after Eq. 6, per layer; the sum is the chain rule at the shared input):
+ *   dX = sum over l of  dY_l * doubleDequant(Wq[l])^T + s[l] * (dY_l * L2[l]^T) * L1[l]^T,
+ * computed as one matrix product whose contraction runs over all layers' outputs and then over all layers' ranks, so
+ * no per-layer gradients are written and added afterwards.  dY is M x (o[0] + ... + o[n-1]) in the layout
+ * qlora_linear_fwd_stacked writes; dX is M x h.  dL1 / dL2: NULL, or host arrays of n device pointers (entries may be
+ * NULL): dL1[l] (h x r[l]) and dL2[l] (r[l] x o[l]) receive layer l's adapter gradients as bf16, exactly as
+ * qlora_linear_bwd computes them; X (M x h) is needed only for those.  T_saved: NULL, or n pointers to the pairs
+ * qlora_linear_fwd_stacked saved (a NULL entry: X * L1[l] is recomputed).  Any M >= 1.  Workspace:
+ * qlora_linear_bwd_stacked_sizes, h * (sum o) bf16 values and a few small buffers; same rules otherwise. */
+qlora_status qlora_linear_bwd_stacked_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
+                                            size_t* workspace_bytes);
+qlora_status qlora_linear_bwd_stacked(const uint16_t* dY, const uint16_t* X, int32_t n, const qlora_nf4_view* Wq,
+                                      const uint16_t* const* L1, const uint16_t* const* L2, const float* s,
+                                      int64_t M, const int32_t* r, const uint16_t* const* T_saved, uint16_t* dX,
+                                      uint16_t* const* dL1, uint16_t* const* dL2,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Forward of a LIST of independent QLoRA linear layers at a few tokens in ONE launch (Eq. 5 applied per layer; the
  * adapter sits on every linear layer of a decoder block -- Section 5 and the hyperparameter appendix):
  *   Y[l] = X[l] * doubleDequant(Wq[l]) + s[l] * (X[l] * L1[l]) * L2[l],   l = 0 .. n-1,  1 <= n <= QLORA_LIST_MAX.

@@ -25,6 +25,7 @@ EXPORTS = [
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
     "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_nf4_quantize_static",
     "qlora_grad_sqnorm", "qlora_adam_step", "qlora_linear_fwd_stacked_sizes", "qlora_linear_fwd_stacked",
+    "qlora_linear_bwd_stacked_sizes", "qlora_linear_bwd_stacked",
 ]
 
 
@@ -83,6 +84,10 @@ def lib():
     L.qlora_linear_fwd_stacked_sizes.argtypes = list(L.qlora_linear_fwd_multi_sizes.argtypes)
     L.qlora_linear_fwd_stacked.argtypes = [vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
                                            c_int64, POINTER(c_int32), vp, POINTER(vp), vp, c_size_t, vp]
+    L.qlora_linear_bwd_stacked_sizes.argtypes = list(L.qlora_linear_fwd_multi_sizes.argtypes)
+    L.qlora_linear_bwd_stacked.argtypes = [vp, vp, c_int32, POINTER(qlora_nf4_view), POINTER(vp), POINTER(vp), POINTER(c_float),
+                                           c_int64, POINTER(c_int32), POINTER(vp), vp, POINTER(vp), POINTER(vp), vp,
+                                           c_size_t, vp]
     L.qlora_linear_dropout_sizes.argtypes = [c_int64, c_int64, c_int64, c_int32, sp, sp]
     L.qlora_linear_fwd_dropout.argtypes = [vp, POINTER(qlora_nf4_view), vp, vp, c_float, c_int64, c_int32, vp, c_float,
                                            vp, vp, vp, c_size_t, vp]
@@ -369,6 +374,41 @@ def qlora_linear_fwd_stacked(X, Wqs, L1s, L2s, ss, Y=None, T_saves=None, workspa
                                           M, (c_int32 * n)(*rs), _ptr(Y), None if T_saves is None else ptrs(T_saves),
                                           _ptr(workspace), workspace.numel(), _stream(stream)))
     return Y
+
+
+def qlora_linear_bwd_stacked_sizes(M, h, os_, rs) -> int:
+    n = len(os_)
+    out = c_size_t()
+    _check(lib().qlora_linear_bwd_stacked_sizes(M, n, h, (c_int64 * n)(*os_), (c_int32 * n)(*rs), ctypes.byref(out)))
+    return int(out.value)
+
+
+def qlora_linear_bwd_stacked(dY, X, Wqs, L1s, L2s, ss, T_saveds=None, dX=None, need_dL=True, workspace=None, stream=None,
+                             dL1s=None, dL2s=None):
+    """dY: (M, sum o) in the stacked layout.  Returns (dX (M, h) = the sum of the layers' input gradients, dL1s, dL2s);
+    the adapter gradients are lists with None for layers without an adapter (or all None with need_dL=False)."""
+    n = len(Wqs)
+    M = dY.shape[0]
+    h = Wqs[0].rows
+    rs = [0 if L1s[l] is None else L1s[l].shape[1] for l in range(n)]
+    assert dY.shape == (M, sum(w.cols for w in Wqs)) and dY.is_contiguous()
+    dev = dY.device
+    if dX is None:
+        dX = torch.empty((M, h), dtype=torch.bfloat16, device=dev)
+    if dL1s is None:
+        dL1s = [torch.empty((h, rs[l]), dtype=torch.bfloat16, device=dev) if need_dL and rs[l] else None for l in range(n)]
+    if dL2s is None:
+        dL2s = [torch.empty((rs[l], Wqs[l].cols), dtype=torch.bfloat16, device=dev) if need_dL and rs[l] else None
+                for l in range(n)]
+    if workspace is None:
+        workspace = workspace_alloc(qlora_linear_bwd_stacked_sizes(M, h, [w.cols for w in Wqs], rs), dev, stream)
+    views = (qlora_nf4_view * n)(*[w.view() for w in Wqs])
+    ptrs = lambda ts: (c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
+    _check(lib().qlora_linear_bwd_stacked(_ptr(dY), _ptr(X), n, views, ptrs(L1s), ptrs(L2s),
+                                          (c_float * n)(*[float(s) for s in ss]), M, (c_int32 * n)(*rs),
+                                          None if T_saveds is None else ptrs(T_saveds), _ptr(dX), ptrs(dL1s), ptrs(dL2s),
+                                          _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dX, dL1s, dL2s
 
 
 LIST_MAX = 8

@@ -709,6 +709,125 @@ qlora_status qlora_linear_bwd_dropout(const uint16_t* dY, const uint16_t* X, con
                          dX, dL1, dL2, dL1_acc, dL2_acc, workspace, workspace_bytes, hip_stream);
 }
 
+// The input gradient of several layers that read one input is the SUM of their input gradients; with the outputs
+// side by side (the layout qlora_linear_fwd_stacked writes) that sum is one product whose contraction runs over all
+// layers' outputs, then over all layers' ranks:  dX = [dY_0 | dY_1 ...] [What_0 | What_1 ...]^T + [Us_0 | ...] [L1_0 | ...]^T.
+namespace {
+struct StackBwdPlan {
+  uint16_t* Wd;      // h x (sum o): the dequantised weights side by side
+  uint16_t* L1s;     // h x Rp: the layers' L1, every rank zero-padded to a multiple of 64
+  uint16_t* Us;      // M x Rp: bf16(s_l dY_l L2_l^T) in layer l's rank columns
+  uint16_t* Uhl;     // M x 2 r_max: one layer's dY L2^T as a [hi | lo] pair, for its dL1
+  uint16_t* Thl;     // M x 2 r_max: one layer's X L1, recomputed when the caller saved none
+  float* part;       // split-K partials, reused by every skinny product
+  int Rp, off[QLORA_MULTI_MAX], rp[QLORA_MULTI_MAX];
+  int64_t N;
+  size_t bytes;
+};
+StackBwdPlan plan_bwd_stacked(void* ws, int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r) {
+  StackBwdPlan p{};
+  Carver c(ws);
+  size_t pe = 0;
+  int r_max = 0;
+  for (int l = 0; l < n; ++l) {
+    p.N += o[l];
+    p.off[l] = p.Rp;
+    p.rp[l] = r[l] > 0 ? (r[l] + 63) / 64 * 64 : 0;
+    p.Rp += p.rp[l];
+    r_max = std::max(r_max, (int)r[l]);
+    if (r[l] > 0) {
+      pe = std::max(pe, (size_t)qlora::small_gemm_splits((int)M, r[l], (int)o[l]) * M * r[l]);
+      pe = std::max(pe, (size_t)qlora::small_gemm_splits((int)M, r[l], (int)h) * M * r[l]);
+      pe = std::max(pe, (size_t)qlora::small_gemm_splits((int)h, r[l], (int)M) * h * r[l]);
+      pe = std::max(pe, (size_t)qlora::small_gemm_splits(r[l], (int)o[l], (int)M) * r[l] * o[l]);
+    }
+  }
+  p.Wd = c.take<uint16_t>((size_t)h * p.N);
+  if (p.Rp > 0) {
+    p.L1s = c.take<uint16_t>((size_t)h * p.Rp);
+    p.Us = c.take<uint16_t>((size_t)M * p.Rp);
+    p.Uhl = c.take<uint16_t>((size_t)M * 2 * r_max);
+    p.Thl = c.take<uint16_t>((size_t)M * 2 * r_max);
+    p.part = c.take<float>(pe);
+  }
+  p.bytes = c.off;
+  return p;
+}
+}  // namespace
+
+qlora_status qlora_linear_bwd_stacked_sizes(int64_t M, int32_t n, int64_t h, const int64_t* o, const int32_t* r,
+                                            size_t* workspace_bytes) {
+  if (!o || !r || !workspace_bytes) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_MULTI_MAX) return QLORA_ERR_SHAPE;
+  for (int l = 0; l < n; ++l)
+    if (qlora_status st = check_linear(M, h, o[l], r[l])) return st;
+  *workspace_bytes = plan_bwd_stacked(nullptr, M, n, h, o, r).bytes;
+  return QLORA_OK;
+}
+
+qlora_status qlora_linear_bwd_stacked(const uint16_t* dY, const uint16_t* X, int32_t n, const qlora_nf4_view* Wq,
+                                      const uint16_t* const* L1, const uint16_t* const* L2, const float* s, int64_t M,
+                                      const int32_t* r, const uint16_t* const* T_saved, uint16_t* dX,
+                                      uint16_t* const* dL1, uint16_t* const* dL2, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  if (!dY || !Wq || !s || !r || !dX || !workspace) return QLORA_ERR_NULL;
+  if (n < 1 || n > QLORA_MULTI_MAX) return QLORA_ERR_SHAPE;
+  int64_t o[QLORA_MULTI_MAX];
+  const int64_t h = Wq[0].rows;
+  bool want_dl = false;
+  for (int l = 0; l < n; ++l) {
+    if (qlora_status st = check_view(&Wq[l])) return st;
+    if (Wq[l].rows != h) return QLORA_ERR_SHAPE;              // one input, one input gradient
+    o[l] = Wq[l].cols;
+    if (qlora_status st = check_linear(M, h, o[l], r[l])) return st;
+    if (r[l] > 0 && (!L1 || !L2 || !L1[l] || !L2[l])) return QLORA_ERR_NULL;
+    if (r[l] > 0 && (!aligned16(L1[l]) || !aligned16(L2[l]))) return QLORA_ERR_ALIGN;
+    if ((T_saved && !aligned16(T_saved[l])) || (dL1 && !aligned16(dL1[l])) || (dL2 && !aligned16(dL2[l])))
+      return QLORA_ERR_ALIGN;
+    if (r[l] > 0 && ((dL1 && dL1[l]) || (dL2 && dL2[l]))) want_dl = true;
+  }
+  if (want_dl && !X) return QLORA_ERR_NULL;
+  if (!aligned16(dY) || !aligned16(X) || !aligned16(dX) || !aligned16(workspace)) return QLORA_ERR_ALIGN;
+  const StackBwdPlan p = plan_bwd_stacked(workspace, M, n, h, o, r);
+  if (workspace_bytes < p.bytes) return QLORA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t N = p.N;
+  int64_t n0 = 0;
+  for (int l = 0; l < n; ++l) {
+    const uint16_t* dYl = dY + n0;                           // layer l's columns of dY, row stride N
+    const int rl = r[l];
+    if (rl > 0) {
+      // U_l = dY_l L2_l^T: bf16(s_l U_l) into the layer's rank columns of Us, the [hi | lo] pair for dL1
+      const int sU = qlora::small_gemm_splits((int)M, rl, (int)o[l]);
+      QL_TRY(qlora::launch_small_gemm(dYl, N, false, L2[l], o[l], false, 0, 0, (int)M, rl, (int)o[l], p.part, sU, st));
+      QL_TRY(qlora::launch_small_finalize(p.part, sU, (int)M, rl, p.Us + p.off[l], p.Rp, p.rp[l], s[l], p.Uhl, nullptr, st));
+      QL_TRY(qlora::launch_copy_pad(L1[l], (int)h, rl, p.L1s + p.off[l], p.rp[l], st, p.Rp));
+      if (dL1 && dL1[l]) {                                   // dL1_l = s_l X^T U_l
+        const int sL1 = qlora::small_gemm_splits((int)h, rl, (int)M);
+        QL_TRY(qlora::launch_small_gemm(X, h, true, p.Uhl, 2 * rl, true, 2, rl, (int)h, rl, (int)M, p.part, sL1, st));
+        QL_TRY(qlora::launch_small_finalize(p.part, sL1, (int)h, rl, dL1[l], rl, rl, s[l], nullptr, nullptr, st));
+      }
+      if (dL2 && dL2[l]) {                                   // dL2_l = s_l T_l^T dY_l
+        const uint16_t* T = T_saved ? T_saved[l] : nullptr;
+        if (!T) {
+          const int sT = qlora::small_gemm_splits((int)M, rl, (int)h);
+          QL_TRY(qlora::launch_small_gemm(X, h, false, L1[l], rl, true, 0, 0, (int)M, rl, (int)h, p.part, sT, st));
+          QL_TRY(qlora::launch_small_finalize(p.part, sT, (int)M, rl, nullptr, 0, 0, 0.0f, p.Thl, nullptr, st));
+          T = p.Thl;
+        }
+        const int sL2 = qlora::small_gemm_splits(rl, (int)o[l], (int)M);
+        QL_TRY(qlora::launch_small_gemm(T, 2 * rl, true, dYl, N, true, 1, rl, rl, (int)o[l], (int)M, p.part, sL2, st));
+        QL_TRY(qlora::launch_small_finalize(p.part, sL2, rl, (int)o[l], dL2[l], o[l], (int)o[l], s[l], nullptr, nullptr, st));
+      }
+    }
+    QL_TRY(qlora::launch_dequant(to_dev(&Wq[l]), p.Wd + n0, st, N));
+    n0 += o[l];
+  }
+  // dX = sum over the layers of dY_l What_l^T + Us_l L1_l^T: one product, contraction over all outputs, then all ranks
+  QL_TRY(gemm_nt_timed(dY, p.Wd, N, N, (int)N, p.Us, p.L1s, p.Rp, p.Rp, p.Rp, dX, h, (int)M, (int)h, st));
+  return QLORA_OK;
+}
+
 }  // extern "C"
 
 // --- lists of layers at a few tokens ------------------------------------------------------------------

@@ -31,7 +31,8 @@ template <bool DQ, bool I8>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
     const void* __restrict__ packed_v, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr,
-    const int dtype, const Table4 tab) {
+    const int dtype, const Table4 tab, const int64_t row_gap) {
+  // row_gap: 16-byte groups between the end of an output row and the start of the next (0: rows back to back)
   constexpr bool dq = DQ;                                    // Double Quantization, or the fp32 constants as they are
   const uint32_t* __restrict__ packed = (const uint32_t*)packed_v;
   __shared__ float lut[16];
@@ -73,7 +74,8 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
       o.z = pack_bf16x2(__fmul_rn(lut[(p >> 16) & 15u], c2), __fmul_rn(lut[(p >> 20) & 15u], c2));
       o.w = pack_bf16x2(__fmul_rn(lut[(p >> 24) & 15u], c2), __fmul_rn(lut[p >> 28], c2));
     }
-    out[d] = o;
+    if (row_gap == 0) out[d] = o;
+    else out[d + (int64_t)(blk / bpr) * row_gap] = o;        // a wider buffer: several weights side by side
   }
 }
 
@@ -191,7 +193,9 @@ hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipS
   return hipGetLastError();
 }
 
-hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
+hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st, int64_t ld_out) {
+  if (ld_out == 0) ld_out = w.cols;
+  if (ld_out < w.cols || ld_out % 8 != 0) return hipErrorInvalidValue;
   const int64_t n_dwords = w.rows * w.cols / 8;
   int64_t blocks = (n_dwords + kDeqThreads - 1) / kDeqThreads;
   const int64_t cap = 256 * 32;
@@ -200,7 +204,7 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st) {
 #define QL_DEQ(DQ, I8)                                                                                      \
   hipLaunchKernelGGL((dequant_nf4_kernel<DQ, I8>), dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,        \
                      (const void*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,  \
-                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype))
+                     (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype), (ld_out - w.cols) / 8)
   if (w.dq) { if (i8) QL_DEQ(true, true); else QL_DEQ(true, false); }
   else      { if (i8) QL_DEQ(false, true); else QL_DEQ(false, false); }
 #undef QL_DEQ

@@ -30,7 +30,8 @@ hipError_t launch_quantize_static(const float* W, int64_t rows, int64_t cols, ui
                                   float* c1, float* mean, hipStream_t st, int dtype = 0, bool dq = true);
 
 // dequant.hip
-hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st);
+//   out[k][n] = dequant(W)[k][n] with row stride ld_out elements (0: cols; else >= cols and a multiple of 8)
+hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st, int64_t ld_out = 0);
 // out[n][k] = dequant(W)[k][n] with row stride ld_out (elements); requires h % 8 == 0.
 // rp > 0 (a multiple of 64, ld_out >= h + rp): the same launch also writes the adapter segment, columns h .. h + rp - 1:
 // out[n][h + col0 + t] = L2[t][n] for t < r (L2: r x o bf16, col0 + r <= rp; NULL: none) and zeros elsewhere.
@@ -60,7 +61,8 @@ hipError_t launch_dropout_dx_fix(uint16_t* dX, int M, int h, const uint8_t* mask
 //   hl = [bf16(sum) | bf16(sum - bf16(sum))] (row stride 2 J) and/or adds scale0 * sum to the fp32 matrix acc (I x J).
 hipError_t launch_small_finalize(const float* part, int splits, int I, int J, uint16_t* out0, int64_t ld0, int w0,
                                  float scale0, uint16_t* hl, float* acc, hipStream_t st);
-hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st);
+//   dst[row][0 .. Cp) = src[row][0 .. C) then zeros; dst rows ld_dst elements apart (0: Cp)
+hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st, int64_t ld_dst = 0);
 
 // fewtok.hip: few-token (M <= 16) streaming path, one launch per call: fp32 split partials of the frozen product,
 // partials of the adapter's inner product, and the output written by the last workgroup to arrive at each slab

@@ -224,11 +224,12 @@ __global__ void small_finalize_kernel(const float* __restrict__ part, int splits
 }
 
 // dst[row][0..Cp) = src[row][0..C) followed by zeros
-__global__ void copy_pad_kernel(const uint16_t* __restrict__ src, int R, int C, uint16_t* __restrict__ dst, int Cp) {
+__global__ void copy_pad_kernel(const uint16_t* __restrict__ src, int R, int C, uint16_t* __restrict__ dst, int Cp,
+                                int64_t ld_dst) {
   const int64_t total = (int64_t)R * Cp;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
     const int row = (int)(e / Cp), c = (int)(e % Cp);
-    dst[e] = (c < C) ? src[(int64_t)row * C + c] : (uint16_t)0;
+    dst[(int64_t)row * ld_dst + c] = (c < C) ? src[(int64_t)row * C + c] : (uint16_t)0;
   }
 }
 
@@ -368,10 +369,12 @@ hipError_t launch_dropout_dx_fix(uint16_t* dX, int M, int h, const uint8_t* mask
   return hipGetLastError();
 }
 
-hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st) {
+hipError_t launch_copy_pad(const uint16_t* src, int R, int C, uint16_t* dst, int Cp, hipStream_t st, int64_t ld_dst) {
+  if (ld_dst == 0) ld_dst = Cp;
+  if (ld_dst < Cp) return hipErrorInvalidValue;
   int64_t blocks = ((int64_t)R * Cp + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(copy_pad_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, R, C, dst, Cp);
+  hipLaunchKernelGGL(copy_pad_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, R, C, dst, Cp, ld_dst);
   return hipGetLastError();
 }
 

@@ -355,3 +355,46 @@ def test_optimizer_arguments_are_rejected_on_the_host(L):
     assert q(fake, 1 << 15, (1 << 13) + 64, 64, 256, fake, fake, fake, fake, None) == -4
     assert q(None, 64, 64, 64, 256, fake, fake, fake, fake, None) == -1
     assert q(fake, 64, 96, 64, 256, fake, fake, fake, fake, None) in (-2, -3)
+
+
+def test_stacked_arguments_are_rejected_on_the_host(L):
+    """One matrix product for the layers that share an input, forward and backward: validation before any HIP call."""
+    from paper_2305_14314_amd import (QloraError, qlora_linear_bwd_stacked_sizes, qlora_linear_fwd_sizes,
+                                      qlora_linear_fwd_stacked_sizes)
+    from paper_2305_14314_amd.binding import qlora_nf4_view
+    for fn in (qlora_linear_fwd_stacked_sizes, qlora_linear_bwd_stacked_sizes):
+        for args, st in [((4, 64, [], []), -2), ((4, 64, [64] * 5, [0] * 5), -2), ((4, 64, [64, 96], [0, 0]), -3),
+                         ((4, 64, [64, 64], [0, 8]), -3), ((0, 64, [64], [0]), -2)]:
+            with pytest.raises(QloraError) as e:
+                fn(*args)
+            assert e.value.status == st
+    # the stacked weight: (sum o) x (h + sum of padded ranks) bf16 values, plus the small buffers
+    M, h, outs, ranks = 300, 1024, [1024, 512], [16, 80]
+    assert qlora_linear_fwd_stacked_sizes(M, h, outs, ranks) >= 2 * sum(outs) * (h + 64 + 128)
+    assert qlora_linear_bwd_stacked_sizes(M, h, outs, ranks) >= 2 * sum(outs) * h + 2 * h * (64 + 128)
+    assert qlora_linear_fwd_stacked_sizes(M, h, [1024], [16]) <= qlora_linear_fwd_sizes(M, h, 1024, 16) + 4096
+    fake, big, n = ctypes.c_void_p(0x1000), 1 << 34, 2
+    views = (qlora_nf4_view * n)(qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 128, 64, 256),
+                                 qlora_nf4_view(0x1000, 0x1000, 0x1000, 0x1000, 128, 64, 64, 256))
+    ptrs = lambda *v: (ctypes.c_void_p * n)(*v)
+    s, r0, r16 = (ctypes.c_float * n)(1.0, 1.0), (ctypes.c_int32 * n)(0, 0), (ctypes.c_int32 * n)(0, 16)
+    f = L.qlora_linear_fwd_stacked
+    assert f(None, n, views, None, None, s, 4, r0, fake, None, fake, big, None) == -1                       # X
+    assert f(fake, n, views, None, None, s, 4, r0, None, None, fake, big, None) == -1                       # Y
+    assert f(fake, n, views, None, None, s, 4, r16, fake, None, fake, big, None) == -1                      # L1 with r > 0
+    assert f(fake, 0, views, None, None, s, 4, r0, fake, None, fake, big, None) == -2
+    assert f(fake, 5, views, None, None, s, 4, r0, fake, None, fake, big, None) == -2
+    assert f(fake, n, views, None, None, s, 4, r0, fake, None, fake, 64, None) == -4
+    assert f(fake, n, views, None, None, s, 4, r0, ctypes.c_void_p(0x1008), None, fake, big, None) == -5
+    assert f(fake, n, views, None, None, s, 4, r0, fake, ptrs(0x1000, 0x1008), fake, big, None) == -5       # T_save[1]
+    b = L.qlora_linear_bwd_stacked
+    assert b(None, fake, n, views, None, None, s, 4, r0, None, fake, None, None, fake, big, None) == -1     # dY
+    assert b(fake, fake, n, views, None, None, s, 4, r0, None, None, None, None, fake, big, None) == -1     # dX
+    assert b(fake, None, n, views, ptrs(None, 0x1000), ptrs(None, 0x1000), s, 4, r16, None, fake,
+             ptrs(None, 0x1000), None, fake, big, None) == -1                                               # dL1 needs X
+    assert b(fake, None, n, views, ptrs(None, 0x1000), ptrs(None, 0x1000), s, 4, r16, None, fake, None, None, fake, 64,
+             None) == -4
+    assert b(fake, fake, n, views, None, None, s, 4, r0, None, ctypes.c_void_p(0x1004), None, None, fake, big, None) == -5
+    views[1].rows = 192                                                                                     # another h
+    assert f(fake, n, views, None, None, s, 4, r0, fake, None, fake, big, None) == -2
+    assert b(fake, fake, n, views, None, None, s, 4, r0, None, fake, None, None, fake, big, None) == -2
