@@ -124,6 +124,20 @@ enum { QLORA_NF4 = 0, QLORA_FP4_E2M1 = 1, QLORA_FP4_E3M0 = 2, QLORA_INT4 = 3, QL
  * codes sit in the same 4-bit containers (codes >= 2^k are never produced), so they show the error of fewer levels,
  * not a smaller footprint. */
 
+/* A real k-bit footprint for QLORA_NF3 and QLORA_NF2 (k = 3, 2): at rest the codes of such a weight are one dense bit
+ * stream over the flattened weight -- code i in bits [k*i, k*i + k), bit b of the stream = bit b % 8 of byte b / 8 --
+ * of rows*cols*k/8 bytes (3.127 and 2.127 bits per parameter with the constants, which do not change).  The paper gives
+ * the k-bit construction (Section 3) and no memory format; this one is the library's.  qlora_kbit_pack writes the stream
+ * from the 4-bit container qlora_quantize_4bit fills (codes above 2^k - 1, which those data types never produce, would
+ * lose their upper bits); qlora_kbit_unpack restores the container, which every other call reads -- a transient buffer
+ * of rows*cols/2 bytes, like the dequantised weight of the GEMM path.  Device pointers, 16-byte aligned; shapes as for
+ * quantisation; k other than 2 or 3: QLORA_ERR_UNSUPPORTED. */
+qlora_status qlora_kbit_sizes(int64_t rows, int64_t cols, int32_t k, size_t* stream_bytes);
+qlora_status qlora_kbit_pack(const uint8_t* packed4, int64_t rows, int64_t cols, int32_t k, uint8_t* stream,
+                             void* hip_stream);
+qlora_status qlora_kbit_unpack(const uint8_t* stream, int64_t rows, int64_t cols, int32_t k, uint8_t* packed4,
+                               void* hip_stream);
+
 /* The 16 values of a table data type (the 4-bit ones, QLORA_NF3, QLORA_NF2), ascending, as fp32 (host array).
  * QLORA_ERR_UNSUPPORTED for an unknown type and for QLORA_INT8, which has no table. */
 qlora_status qlora_codebook_4bit(int32_t dtype, float* values16);

@@ -26,6 +26,7 @@ EXPORTS = [
     "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_nf4_quantize_static",
     "qlora_grad_sqnorm", "qlora_adam_step", "qlora_linear_fwd_stacked_sizes", "qlora_linear_fwd_stacked",
     "qlora_linear_bwd_stacked_sizes", "qlora_linear_bwd_stacked",
+    "qlora_kbit_sizes", "qlora_kbit_pack", "qlora_kbit_unpack",
 ]
 
 
@@ -101,6 +102,9 @@ def lib():
     L.qlora_workspace_check.argtypes = [vp, c_size_t, vp]
     L.qlora_fewtok_poll_limit.argtypes = [c_int32]
     L.qlora_grad_sqnorm.argtypes = [vp, c_int64, vp, vp]
+    L.qlora_kbit_sizes.argtypes = [c_int64, c_int64, c_int32, sp]
+    L.qlora_kbit_pack.argtypes = [vp, c_int64, c_int64, c_int32, vp, vp]
+    L.qlora_kbit_unpack.argtypes = [vp, c_int64, c_int64, c_int32, vp, vp]
     L.qlora_adam_step.argtypes = [vp, vp, vp, vp, vp, c_int64, POINTER(qlora_adam_config), vp, vp]
     L.qlora_fewtok_poll_limit.restype = None
     L.qlora_profile_gemm.argtypes = [ctypes.c_int]
@@ -559,6 +563,30 @@ def qlora_linear_bwd_dropout(dY, X, Wq: NF4Weight, L1, L2, s, keep_mask, p, T_sa
                                           _ptr(dL1_acc), _ptr(dL2_acc), _ptr(workspace), workspace.numel(),
                                           _stream(stream)))
     return dX, dL1, dL2
+
+
+def qlora_kbit_sizes(rows, cols, k) -> int:
+    out = c_size_t()
+    _check(lib().qlora_kbit_sizes(rows, cols, k, ctypes.byref(out)))
+    return int(out.value)
+
+
+def qlora_kbit_pack(Wq: NF4Weight, out=None, stream=None):
+    """The dense k-bit stream (uint8 tensor) of an NF3 / NF2 weight's codes; the constants stay as they are."""
+    k = {NF3: 3, NF2: 2}[Wq.dtype]
+    if out is None:
+        out = torch.empty(qlora_kbit_sizes(Wq.rows, Wq.cols, k), dtype=torch.uint8, device=Wq.packed.device)
+    _check(lib().qlora_kbit_pack(_ptr(Wq.packed), Wq.rows, Wq.cols, k, _ptr(out), _stream(stream)))
+    return out
+
+
+def qlora_kbit_unpack(stream_bytes, Wq: NF4Weight, stream=None) -> NF4Weight:
+    """Restores the 4-bit container `Wq.packed` of an NF3 / NF2 weight from its k-bit stream."""
+    k = {NF3: 3, NF2: 2}[Wq.dtype]
+    assert stream_bytes.is_cuda and stream_bytes.dtype == torch.uint8
+    assert stream_bytes.numel() == qlora_kbit_sizes(Wq.rows, Wq.cols, k)
+    _check(lib().qlora_kbit_unpack(_ptr(stream_bytes), Wq.rows, Wq.cols, k, _ptr(Wq.packed), _stream(stream)))
+    return Wq
 
 
 def qlora_grad_sqnorm(grad, accum, stream=None):

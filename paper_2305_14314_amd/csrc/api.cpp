@@ -918,6 +918,32 @@ qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes
   return status ? QLORA_ERR_STATE : QLORA_OK;
 }
 
+qlora_status qlora_kbit_sizes(int64_t rows, int64_t cols, int32_t k, size_t* stream_bytes) {
+  if (!stream_bytes) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(rows, cols, 64, 256)) return st;
+  if (k != 2 && k != 3) return QLORA_ERR_UNSUPPORTED;
+  *stream_bytes = (size_t)(rows * cols / 8 * k);
+  return QLORA_OK;
+}
+
+qlora_status qlora_kbit_pack(const uint8_t* packed4, int64_t rows, int64_t cols, int32_t k, uint8_t* stream,
+                             void* hip_stream) {
+  if (!packed4 || !stream) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(rows, cols, 64, 256)) return st;
+  if (k != 2 && k != 3) return QLORA_ERR_UNSUPPORTED;
+  if (!aligned16(packed4) || !aligned16(stream)) return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_kbit_pack(packed4, rows * cols, k, stream, (hipStream_t)hip_stream));
+}
+
+qlora_status qlora_kbit_unpack(const uint8_t* stream, int64_t rows, int64_t cols, int32_t k, uint8_t* packed4,
+                               void* hip_stream) {
+  if (!packed4 || !stream) return QLORA_ERR_NULL;
+  if (qlora_status st = check_quant_shape(rows, cols, 64, 256)) return st;
+  if (k != 2 && k != 3) return QLORA_ERR_UNSUPPORTED;
+  if (!aligned16(packed4) || !aligned16(stream)) return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_kbit_unpack(stream, rows * cols, k, packed4, (hipStream_t)hip_stream));
+}
+
 qlora_status qlora_grad_sqnorm(const float* grad, int64_t n, double* sqnorm_accum, void* hip_stream) {
   if (n < 0) return QLORA_ERR_SHAPE;
   if (n == 0) return QLORA_OK;                               // an empty buffer adds nothing

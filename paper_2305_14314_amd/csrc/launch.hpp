@@ -148,6 +148,11 @@ struct ListLayerDesc {
 hipError_t launch_fewlist(bool bwd, int M, int n, const ListLayerDesc* layers, const ListPlan& plan, unsigned* hdr,
                           unsigned nonce, int spin_limit, hipStream_t st);
 
+// kbit.hip: between the 4-bit container (elems / 2 bytes) and the k-bit stream (elems * k / 8 bytes), k = 2 or 3,
+// elems a multiple of 32; codes above 2^k - 1 lose their upper bits when packed.
+hipError_t launch_kbit_pack(const uint8_t* packed4, int64_t elems, int k, uint8_t* stream, hipStream_t st);
+hipError_t launch_kbit_unpack(const uint8_t* stream, int64_t elems, int k, uint8_t* packed4, hipStream_t st);
+
 // adam.hip: optimizer step of the LoRA parameters.  Scalars derived from the hyperparameters are computed by the
 // caller in double precision and rounded once to fp32.
 struct AdamConsts {
