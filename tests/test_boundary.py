@@ -398,3 +398,22 @@ def test_stacked_arguments_are_rejected_on_the_host(L):
     views[1].rows = 192                                                                                     # another h
     assert f(fake, n, views, None, None, s, 4, r0, fake, None, fake, big, None) == -2
     assert b(fake, fake, n, views, None, None, s, 4, r0, None, fake, None, None, fake, big, None) == -2
+
+
+def test_kbit_arguments_are_rejected_on_the_host(L):
+    from paper_2305_14314_amd import qlora_kbit_sizes
+    assert qlora_kbit_sizes(8192, 22016, 3) == 8192 * 22016 * 3 // 8
+    assert qlora_kbit_sizes(64, 64, 2) == 1024
+    # with the constants: 3.127 and 2.127 bits per parameter (Section 3's formula with k in place of 4)
+    P = 8192 * 22016
+    assert (qlora_kbit_sizes(8192, 22016, 3) + P // 64 + 4 * P // (64 * 256)) * 8 / P == 3 + 8 / 64 + 32 / (64 * 256)
+    fake = ctypes.c_void_p(0x1000)
+    out = ctypes.c_size_t()
+    assert L.qlora_kbit_sizes(64, 64, 4, ctypes.byref(out)) == -3
+    assert L.qlora_kbit_sizes(64, 64, 3, None) == -1
+    assert L.qlora_kbit_sizes(64, 96, 3, ctypes.byref(out)) == -2
+    for f in (L.qlora_kbit_pack, L.qlora_kbit_unpack):
+        assert f(None, 64, 64, 3, fake, None) == -1 and f(fake, 64, 64, 3, None, None) == -1
+        assert f(fake, 64, 64, 1, fake, None) == -3 and f(fake, 0, 64, 3, fake, None) == -2
+        assert f(ctypes.c_void_p(0x1008), 64, 64, 3, fake, None) == -5
+        assert f(fake, 64, 64, 2, ctypes.c_void_p(0x1004), None) == -5
