@@ -359,8 +359,20 @@ __device__ __forceinline__ Seg seg_at(const ListArgs& A, int u, int u1) {
   return s;
 }
 // steps of a segment that fall to lane-group `w` of `nw` (they interleave), and that count rounded up to the ring depth
+// QL_LIST_ROTATE: in round i lane-group w takes step nw i + (w + i) % nw instead of nw i + w, so that a wave does not
+// keep to one residue class of rows (nw is a power of two).
+#ifndef QL_LIST_ROTATE
+#define QL_LIST_ROTATE 0
+#endif
+__device__ __forceinline__ int step_of(int w, int i, int nw) {
+  return QL_LIST_ROTATE ? nw * i + ((w + i) & (nw - 1)) : nw * i + w;
+}
 __device__ __forceinline__ int seg_steps(const Seg& s, int w, int nw) {
   const int len = s.s1 - s.s0;
+  if (QL_LIST_ROTATE) {
+    const int full = len / nw, rem = len - full * nw;
+    return full + ((((w + full) & (nw - 1)) < rem) ? 1 : 0);
+  }
   return len > w ? (len - w + nw - 1) / nw : 0;
 }
 
@@ -441,7 +453,7 @@ __global__ __launch_bounds__(NT) void fewlist_fwd_kernel(const ListArgs A) {
   // innermost loop: a rarely taken path that rejoins there makes the compiler wait for every load in flight
   auto next_load = [&](LFwd& s) {
     const bool valid = !l_done && li < ln;
-    const int kc = valid ? (ls.s0 + wave + NW * li) * 16 : kc_last;
+    const int kc = valid ? (ls.s0 + step_of(wave, li, NW)) * 16 : kc_last;
     kc_last = kc;
     const char* wbase = l_packed + (int64_t)kc * l_rowb;
 #pragma unroll
@@ -483,14 +495,27 @@ __global__ __launch_bounds__(NT) void fewlist_fwd_kernel(const ListArgs A) {
       xa[0] = __builtin_bit_cast(bf16x8, (x_ok && !(g & 1)) ? s.x : zero);
       xa[NA - 1] = __builtin_bit_cast(bf16x8, (x_ok && (g & 1)) ? s.x : zero);
     }
+    // The table lookups of byte b + 1 are issued before the arithmetic of byte b and the scheduler is told not to move
+    // anything across that point: left alone it puts every lookup right in front of its first use, and each then costs
+    // the wave a full LDS round trip (32 of them per step).
+    f32x2 qn[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) qn[j] = pair_lookup_b(lut2, s.pk[j], lane_off, 0);
 #pragma unroll
     for (int b = 0; b < 4; ++b) {                            // byte b of every row: columns 2b, 2b + 1 of the dword
+      f32x2 q[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) q[j] = qn[j];
+      if (b < 3) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) qn[j] = pair_lookup_b(lut2, s.pk[j], lane_off, b + 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       float lo[8], hi[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const f32x2 q = pair_lookup_b(lut2, s.pk[j], lane_off, b);
-        lo[j] = __fmul_rn(q[0], c2[j]);
-        hi[j] = __fmul_rn(q[1], c2[j]);
+        lo[j] = __fmul_rn(q[j][0], c2[j]);
+        hi[j] = __fmul_rn(q[j][1], c2[j]);
       }
       u32x4 w;
 #pragma unroll
@@ -641,7 +666,7 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
   skip_empty();
   auto next_load = [&](LBwd& s) {                            // see the forward kernel
     const bool valid = !l_done && li < ln;
-    const int kb = valid ? (ls.s0 + cw + NCW * li) * 128 : kb_last;
+    const int kb = valid ? (ls.s0 + step_of(cw, li, NCW)) * 128 : kb_last;
     kb_last = kb;
     int col = kb + 32 * g;                                   // per lane
     if (col >= l_o) col = l_o - 64 + 32 * (g & 1);           // the half-empty last step: any valid column (masked at compute)
@@ -704,7 +729,7 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
       for (; it < it_end; it += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
-          if (it + d < cn) compute(buf[d], y_row_ok && (cs.s0 + cw + NCW * (it + d)) * 128 + 32 * g < o_cs);
+          if (it + d < cn) compute(buf[d], y_row_ok && (cs.s0 + step_of(cw, it + d, NCW)) * 128 + 32 * g < o_cs);
           next_load(buf[d]);
         }
       }
