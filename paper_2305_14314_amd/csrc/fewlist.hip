@@ -703,18 +703,34 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
     float c2v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) c2v[u] = __fadd_rn(__fmul_rn(unit[s.code[u]], s.c1[u]), s.mean);
+    // 8 groups of 8 lookups: dword t of weight-row groups 2 uh, 2 uh + 1; the lookups of the next group are issued
+    // before the arithmetic of this one (see the forward kernel)
+    auto lookups = [&](f32x2 (&q)[2][4], int grp) {
+      const int t = grp >> 1, uh = grp & 1;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+      for (int v = 0; v < 2; ++v)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) q[v][b] = pair_lookup_b(lut2, s.w[2 * uh + v][t], lane_off, b);
+    };
+    f32x2 qn[2][4];
+    lookups(qn, 0);
+#pragma unroll
+    for (int grp = 0; grp < 8; ++grp) {
+      const int t = grp >> 1, uh = grp & 1;
+      f32x2 q[2][4];
+#pragma unroll
+      for (int v = 0; v < 2; ++v)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) q[v][b] = qn[v][b];
+      if (grp < 7) lookups(qn, grp + 1);
+      __builtin_amdgcn_sched_barrier(0);
       const bf16x8 ya = __builtin_bit_cast(bf16x8, y_ok ? s.y[t] : u32x4{0u, 0u, 0u, 0u});
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t d = s.w[u][t];
+      for (int v = 0; v < 2; ++v) {
+        const int u = 2 * uh + v;
         u32x4 w;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const f32x2 q = pair_lookup_b(lut2, d, lane_off, b);
-          w[b] = pack_bf16x2(__fmul_rn(q[0], c2v[u]), __fmul_rn(q[1], c2v[u]));
-        }
+        for (int b = 0; b < 4; ++b) w[b] = pack_bf16x2(__fmul_rn(q[v][b][0], c2v[u]), __fmul_rn(q[v][b][1], c2v[u]));
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ya, __builtin_bit_cast(bf16x8, w), acc[u], 0, 0, 0);
       }
     }
