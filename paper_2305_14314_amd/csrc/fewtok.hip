@@ -367,14 +367,37 @@ __device__ __forceinline__ void fewtok_fwd_body(const FewArgs& p, const int work
       xa[0] = __builtin_bit_cast(bf16x8, (x_ok && !(g & 1)) ? s.x : zero);
       xa[NA - 1] = __builtin_bit_cast(bf16x8, (x_ok && (g & 1)) ? s.x : zero);
     }
+    // The table lookups of byte b + 1 are issued before the arithmetic of byte b and the scheduler is told not to move
+    // anything across that point: left alone it puts every lookup right in front of its first use, and each then costs
+    // the wave a full LDS round trip (32 of them per step).
+    // (With 1024 threads there are no registers for the batch ahead: the 8 lookups of a byte are issued together and
+    // waited for, 4 round trips per step.)
+    constexpr bool kAhead = NT <= 512;
+    f32x2 qn[8];
+    if (kAhead) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qn[j] = pair_lookup_b(lut2, s.pk[j], lane_off, 0);
+    }
 #pragma unroll
     for (int b = 0; b < 4; ++b) {                            // byte b of every row: columns 2b, 2b + 1 of the dword
+      f32x2 q[8];
+      if (kAhead) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = qn[j];
+        if (b < 3) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) qn[j] = pair_lookup_b(lut2, s.pk[j], lane_off, b + 1);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = pair_lookup_b(lut2, s.pk[j], lane_off, b);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       float lo[8], hi[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const f32x2 q = pair_lookup_b(lut2, s.pk[j], lane_off, b);
-        lo[j] = __fmul_rn(q[0], c2[j]);
-        hi[j] = __fmul_rn(q[1], c2[j]);
+        lo[j] = __fmul_rn(q[j][0], c2[j]);
+        hi[j] = __fmul_rn(q[j][1], c2[j]);
       }
       u32x4 w;
 #pragma unroll
@@ -544,18 +567,21 @@ __global__ __launch_bounds__(kFewThreads) void fewtok_bwd_kernel(const FewArgs p
     float c2v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) c2v[u] = __fadd_rn(__fmul_rn(unit[s.code[u]], s.c1[u]), mean);
+    // the 4 lookups of a dword are issued together, then waited for (left alone the scheduler puts every lookup right
+    // in front of its first use: 64 LDS round trips per step instead of 16; 1024 threads leave no registers for more)
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const bf16x8 ya = __builtin_bit_cast(bf16x8, y_ok ? s.y[t] : u32x4{0u, 0u, 0u, 0u});
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const uint32_t d = s.w[u][t];
+        f32x2 q[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) q[b] = pair_lookup_b(lut2, d, lane_off, b);
+        __builtin_amdgcn_sched_barrier(0);
         u32x4 w;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const f32x2 q = pair_lookup_b(lut2, d, lane_off, b);
-          w[b] = pack_bf16x2(__fmul_rn(q[0], c2v[u]), __fmul_rn(q[1], c2v[u]));
-        }
+        for (int b = 0; b < 4; ++b) w[b] = pack_bf16x2(__fmul_rn(q[b][0], c2v[u]), __fmul_rn(q[b][1], c2v[u]));
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ya, __builtin_bit_cast(bf16x8, w), acc[u], 0, 0, 0);
       }
     }
