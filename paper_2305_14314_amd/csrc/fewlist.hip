@@ -26,6 +26,7 @@
 // kernel raises the header's sticky status word, which qlora_workspace_check reports.  Every wait is a bounded
 // poll, so all waves exit whatever the header held.
 #include <algorithm>
+#include <vector>
 
 #include "fewtok_common.hpp"
 
@@ -51,10 +52,32 @@
 #ifndef QL_LIST_BWD_DEPTH
 #define QL_LIST_BWD_DEPTH 3
 #endif
-// An adapter item is charged its bytes in streaming units, times this factor.  Measured (same block, 1 token, forward /
-// backward microseconds): factor 0: 181 / 182; 0.5: 177 / 176; 1: 175 / 177; 2: 179 / 182; 3: 186 / 188; 4: 192 / 194.
-#ifndef QL_LIST_CREDIT_X
-#define QL_LIST_CREDIT_X 1
+// Cost model of the partition, in units of streaming one unit (forward 2 KB, backward 16 KB): what the end of a
+// segment costs, what a slab's output stage costs, what an adapter item costs.  From the timing probe of a debug build
+// (forward, one token, 65B block: a unit 0.12 us; reduction + partial store + arrival about 6 us; an output stage about
+// 12 us; an adapter item about 20 us, part of it overlapped; backward units are 8 times larger), then chosen by
+// measurement on the same block (1 / 4 / 16 tokens, us per launch; forward as tail, stage, item): 50, 100, 100: 136 /
+// 146 / 164; 40, 130, 150: 137 / 140 / 166; 60, 160, 100: 136 / 139 / 163; 70, 200, 120: 137 / 138 / 159; 60, 240, 100:
+// 138 / 140 / 161; 30, 100, 60: 141 / 144 / 166 (equal units with a credit of 64 per item, the previous rule: 148 / 154 /
+// 178).  Backward: 6, 12, 12: 170 / 178 / 214; 0, 0, 8: 167 / 174 / 208; 3, 6, 8: 161 / 169 / 204; 2, 4, 6: 161 / 167 / 199;
+// 4, 8, 8: 164 / 170 / 203; 10, 20, 16: 173 / 178 / 210.
+#ifndef QL_LIST_TAIL_FWD
+#define QL_LIST_TAIL_FWD 70
+#endif
+#ifndef QL_LIST_FIN_FWD
+#define QL_LIST_FIN_FWD 200
+#endif
+#ifndef QL_LIST_ITEM_FWD
+#define QL_LIST_ITEM_FWD 120
+#endif
+#ifndef QL_LIST_TAIL_BWD
+#define QL_LIST_TAIL_BWD 2
+#endif
+#ifndef QL_LIST_FIN_BWD
+#define QL_LIST_FIN_BWD 4
+#endif
+#ifndef QL_LIST_ITEM_BWD
+#define QL_LIST_ITEM_BWD 6
 #endif
 
 namespace qlora {
@@ -100,6 +123,7 @@ struct ListArgs {
   Table4 tab;
   ListLayer L[kListMax];
 };
+static_assert(sizeof(ListArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 __device__ __forceinline__ FewArgs layer_args(const ListArgs& A, const ListLayer& y) {
   FewArgs p;
@@ -791,7 +815,6 @@ ListPlan fewlist_plan(bool bwd, int M, int n, const int* h, const int* o, const 
   if (n < 1 || n > kListMax || M < 1 || M > kFewTokens) return P;
   int64_t units = 0;
   int adapters = 0, slabs = 0, ups_max = 1;
-  int64_t adapter_bytes = 0;
   for (int l = 0; l < n; ++l) {
     const int outs = bwd ? h[l] : o[l], contr = bwd ? o[l] : h[l];
     P.n_slabs[l] = (outs + 255) / 256;
@@ -807,25 +830,59 @@ ListPlan fewlist_plan(bool bwd, int M, int n, const int* h, const int* o, const 
     P.n_lparts[l] = r[l] > 0 ? (contr + chunk - 1) / chunk : 0;
     P.a0[l] = adapters;
     adapters += P.n_lparts[l];
-    adapter_bytes += (int64_t)contr * r[l] * 2;
     P.ctr0[l] = slabs;
     slabs += P.n_slabs[l];
   }
   if (slabs > kFewMaxSlabs - 1) return P;                    // the last word of the slab range is the status word
   P.total_units = (int)units;
   P.total_slabs = slabs;
-  const int unit_bytes = bwd ? 16384 : 2048;
+  // Estimated time of a workgroup in units of streaming one unit: its units, plus kTail for every segment (a run of
+  // units within one slab: reduction, partial store, arrival), plus kFin for every slab that begins inside its range
+  // (of the workgroups that share a slab the one with the slab's first units gets there last, at the end of its own
+  // range, and runs the slab's output stage), plus kItem for every adapter item it computes first.  Boundaries: the
+  // smallest bound T for which a greedy walk (every workgroup takes what fits under T) covers the line with `grid`
+  // workgroups.
+  const int kTail = bwd ? QL_LIST_TAIL_BWD : QL_LIST_TAIL_FWD, kFin = bwd ? QL_LIST_FIN_BWD : QL_LIST_FIN_FWD;
+  const int kItem = bwd ? QL_LIST_ITEM_BWD : QL_LIST_ITEM_FWD;
+  std::vector<int> slab_end;                                 // ascending unit index where each slab ends
+  for (int l = 0; l < n; ++l)
+    for (int sidx = 0; sidx < P.n_slabs[l]; ++sidx) slab_end.push_back(P.unit0[l] + (sidx + 1) * P.ups[l]);
+  auto walk = [&](int grid, int64_t T, int* start) -> bool { // fills start[0 .. grid] when it returns true
+    int u = 0, next_end = 0;                                 // next_end: index of the first slab that ends after u
+    for (int rho = 0; rho < grid; ++rho) {
+      if (start) start[rho] = u;
+      const int items = rho < adapters ? (adapters - rho + grid - 1) / grid : 0;
+      int64_t budget = T - (int64_t)kItem * items;
+      bool took = false;
+      while (u < (int)units && budget > 0) {
+        while (slab_end[next_end] <= u) ++next_end;
+        const int s_begin = next_end == 0 ? 0 : slab_end[next_end - 1];
+        const int64_t overhead = kTail + (u == s_begin ? kFin : 0);
+        if (budget <= overhead) {                            // not worth another segment; but nobody with a budget leaves empty-handed
+          if (!took) { ++u; took = true; }
+          break;
+        }
+        const int64_t room = budget - overhead;
+        const int to_end = slab_end[next_end] - u;
+        const int take = room >= to_end ? to_end : (int)room;
+        u += take; budget -= overhead + take; took = true;
+      }
+    }
+    if (start) start[grid] = (int)units;
+    return u >= (int)units;
+  };
   // fewer workgroups than compute units when there is less than one unit each, or when a slab would otherwise be
   // shared by more workgroups than an arrival word has bits for
-  for (int grid = (int)std::min<int64_t>(256, units); grid >= 1; grid = grid > 32 ? grid - 32 : grid - 1) {
+  for (int grid = (int)std::min<int64_t>(kListGridMax, units); grid >= 1; grid = grid > 32 ? grid - 32 : grid - 1) {
     ListPart q{};
     q.grid = grid;
     q.n_adapter = adapters;
-    int credit = adapters > 0 ? (int)(QL_LIST_CREDIT_X * (double)(adapter_bytes / adapters / unit_bytes)) : 0;
-    if (adapters > grid || (units + (int64_t)credit * adapters) / grid < credit + 1) credit = 0;
-    q.credit = credit;
-    q.cost_total = units + (int64_t)credit * adapters;
-    q.q = (int)(q.cost_total / grid); q.rem = (int)(q.cost_total % grid);   // q >= 1: grid <= units
+    int64_t lo = 0, hi = units + (int64_t)(kTail + kFin) * slabs + (int64_t)kItem * adapters + 1;   // walk(hi) succeeds with one workgroup
+    while (hi - lo > 1) {
+      const int64_t mid = (lo + hi) / 2;
+      if (walk(grid, mid, nullptr)) hi = mid; else lo = mid;
+    }
+    walk(grid, hi, q.start);
     int worst = 1;
     for (int l = 0; l < n; ++l) {
       int mc = 1;

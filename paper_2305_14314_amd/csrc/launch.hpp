@@ -103,28 +103,26 @@ hipError_t launch_workspace_init(void* workspace, hipStream_t st);
 
 // fewlist.hip: the same two products for a LIST of independent layers (each with its own token rows) in one
 // persistent launch.  The work of all layers is one line of units (forward: 16 weight rows x 256 columns; backward:
-// 256 rows x 128 columns) and workgroup rho of `grid` takes units [list_start(rho), list_start(rho + 1)); the
-// first n_adapter workgroups also compute one partial of an adapter's inner product each and get `credit` fewer
-// units for it.  Host (sizes, launch) and device evaluate the same two functions.
+// 256 rows x 128 columns) and workgroup rho of `grid` takes units [start[rho], start[rho + 1]); the first n_adapter
+// workgroups also compute one partial of an adapter's inner product each.  The host chooses the boundaries so that
+// the workgroups' estimated times are equal (a range that crosses slab boundaries pays for the ends of its segments);
+// the table travels in the kernel arguments, and host and device read it through the same two functions.
 constexpr int kListMax = 8;
+constexpr int kListGridMax = 256;
 constexpr int kListLoraChunk = 1024;         // contraction elements per adapter item (more when a layer would need over 23 items)
 struct ListPart {
-  long long cost_total; int grid, credit, n_adapter;
-  int q, rem;                                // cost_total / grid and cost_total % grid: the kernels divide 32-bit numbers only
+  int grid, n_adapter;
+  int start[kListGridMax + 1];               // ascending, start[0] = 0, start[grid] = total units; equal neighbours: an empty range
 };
-// floor(rho * cost_total / grid) - credit * min(rho, n_adapter), for 0 <= rho <= grid <= 256
-__host__ __device__ inline int list_start(const ListPart& p, int rho) {
-  const int a = rho < p.n_adapter ? rho : p.n_adapter;
-  return rho * p.q + (int)((unsigned)(rho * p.rem) / (unsigned)p.grid) - p.credit * a;
-}
-// the workgroup whose range holds unit u (0 <= u < total units); ranges are non-empty and ascending by construction.
-// The first guess only sets how often the two loops run: the result is exact whatever it is.
+__host__ __device__ inline int list_start(const ListPart& p, int rho) { return p.start[rho]; }
+// the workgroup whose range holds unit u (0 <= u < total units): the last rho with start[rho] <= u
 __host__ __device__ inline int list_rho_of(const ListPart& p, int u) {
-  int rho = (int)((float)u / (float)p.q);
-  if (rho > p.grid - 1) rho = p.grid - 1;
-  while (rho > 0 && list_start(p, rho) > u) --rho;
-  while (rho + 1 < p.grid && list_start(p, rho + 1) <= u) ++rho;
-  return rho;
+  int lo = 0, hi = p.grid;                   // invariant: start[lo] <= u < start[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (p.start[mid] <= u) lo = mid; else hi = mid;
+  }
+  return lo;
 }
 struct ListPlan {
   bool ok;                                   // false: not a few-token list (too many tokens, layers or slabs)
