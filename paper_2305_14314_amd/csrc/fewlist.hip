@@ -388,6 +388,25 @@ __device__ __forceinline__ Seg seg_at(const ListArgs& A, int u, int u1) {
 #ifndef QL_LIST_ROTATE
 #define QL_LIST_ROTATE 0
 #endif
+// QL_LIST_BWD_GROUP (backward only): a wave takes its 128-column steps in runs of this many adjacent ones -- steps
+// G (nw j + w) .. + G - 1 -- so that the 64-byte pieces of a weight row that share a 128-byte line (and, with 4, the
+// neighbouring line) are asked for by the same wave, one ring position apart.  Measured on the 65B block (1 / 4 / 16
+// tokens, us per launch): 1: 161 / 167 / 199; 2: 155 / 162 / 194; 4: 157 / 164 / 195; 8: 158 / 165 / 194.
+#ifndef QL_LIST_BWD_GROUP
+#define QL_LIST_BWD_GROUP 2
+#endif
+__device__ __forceinline__ int group_step_of(int w, int i, int nw) {
+  constexpr int G = QL_LIST_BWD_GROUP;
+  return G * (nw * (i / G) + w) + (i % G);
+}
+__device__ __forceinline__ int group_seg_steps(int len, int w, int nw) {
+  constexpr int G = QL_LIST_BWD_GROUP;
+  const int groups = (len + G - 1) / G;                      // the last group may be short
+  if (groups <= w) return 0;
+  const int mine = (groups - w + nw - 1) / nw;               // groups w, w + nw, ...
+  const int last = w + nw * (mine - 1);
+  return G * mine - (last == groups - 1 ? groups * G - len : 0);
+}
 __device__ __forceinline__ int step_of(int w, int i, int nw) {
   return QL_LIST_ROTATE ? nw * i + ((w + i) & (nw - 1)) : nw * i + w;
 }
@@ -652,6 +671,8 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
   if (u0 >= u1) return;
 
   const int rg = wave16 & 3, cw = wave16 >> 2;
+  auto bwd_steps = [&](const Seg& sg, int w) { return group_seg_steps(sg.s1 - sg.s0, w, NCW); };
+  auto bwd_step = [&](int w, int i) { return group_step_of(w, i, NCW); };
   const int i = lane & 15, g = lane >> 4;
   const uint32_t lane_off = 8u * (uint32_t)(lane & (kLutCopies - 1));
   const bool y_row_ok = i < A.M;
@@ -675,7 +696,7 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
     y_off = (uint32_t)((y_row_ok ? i : 0) * y.o);
   };
   setup_load();
-  int ln = seg_steps(ls, cw, NCW), lit = (ln + kDepth - 1) / kDepth * kDepth, li = 0;
+  int ln = bwd_steps(ls, cw), lit = (ln + kDepth - 1) / kDepth * kDepth, li = 0;
   bool l_done = false;
   int kb_last = ls.s0 * 128;
   auto skip_empty = [&]() {
@@ -683,14 +704,14 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
       if (ls.u_end >= u1) { l_done = true; break; }
       ls = seg_at(A, ls.u_end, u1);
       setup_load();
-      ln = seg_steps(ls, cw, NCW); lit = (ln + kDepth - 1) / kDepth * kDepth; li = 0;
+      ln = bwd_steps(ls, cw); lit = (ln + kDepth - 1) / kDepth * kDepth; li = 0;
       kb_last = ls.s0 * 128;
     }
   };
   skip_empty();
   auto next_load = [&](LBwd& s) {                            // see the forward kernel
     const bool valid = !l_done && li < ln;
-    const int kb = valid ? (ls.s0 + step_of(cw, li, NCW)) * 128 : kb_last;
+    const int kb = valid ? (ls.s0 + bwd_step(cw, li)) * 128 : kb_last;
     kb_last = kb;
     int col = kb + 32 * g;                                   // per lane
     if (col >= l_o) col = l_o - 64 + 32 * (g & 1);           // the half-empty last step: any valid column (masked at compute)
@@ -761,7 +782,7 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
   };
 
   for (Seg cs = seg_at(A, u0, u1);; cs = seg_at(A, cs.u_end, u1)) {
-    const int cn = seg_steps(cs, cw, NCW), cit = (cn + kDepth - 1) / kDepth * kDepth;
+    const int cn = bwd_steps(cs, cw), cit = (cn + kDepth - 1) / kDepth * kDepth;
     const int o_cs = A.L[cs.l].o;
     for (int it = 0; it < cit;) {
       const int room = l_done ? cit - it : lit - li;
@@ -769,7 +790,7 @@ __global__ __launch_bounds__(256 * NCW) void fewlist_bwd_kernel(const ListArgs A
       for (; it < it_end; it += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
-          if (it + d < cn) compute(buf[d], y_row_ok && (cs.s0 + step_of(cw, it + d, NCW)) * 128 + 32 * g < o_cs);
+          if (it + d < cn) compute(buf[d], y_row_ok && (cs.s0 + bwd_step(cw, it + d)) * 128 + 32 * g < o_cs);
           next_load(buf[d]);
         }
       }
