@@ -27,34 +27,34 @@ constexpr int kStripOff = kUnitOff + 1024;                   // float[kWaves][2]
 constexpr int kSmemBytes = kStripOff + kWaves * 256;
 static_assert(kLutBytes <= kRedBytes && kSmemBytes <= 160 * 1024, "LDS map");
 
-// dtype 0: NF4 from constants.  Another 4-bit data type (Section 4): its 16 values come with the arguments and are
-// staged in LDS by one thread first (`stage`, 16 floats) -- a lane-indexed read of a by-value argument would go
-// through scratch memory.
+// The 16 values (NF4's from constants, another data type's from the arguments: Section 4) are staged in LDS by 16
+// threads first (`stage`, 16 floats) -- a lane-indexed read of a constant array or of a by-value argument is a memory
+// load per element.  Entry e = 32 b + copy of the table belongs to byte b = e / 32; thread t writes entries t, t + NT,
+// ...: their low nibble (t / 32) % 16 is the same for all of them and their high nibble advances by NT / 512 per entry,
+// so a thread reads the stage once for the low value and at compile-time positions for the high ones.
 template <int NT>
 __device__ __forceinline__ void init_pair_lut(f32x2* lut2 /* [256][32] */, float* unit /* [256] */, int dtype,
                                               const Table4& tab, float* stage) {
-  if (dtype == 0) {
+  static_assert(NT == 512 || NT == 1024, "entries per thread and their nibbles are worked out for these two");
+  if (threadIdx.x < 16) {
     constexpr float t[16] = {QLORA_NF4_VALUES};
-    for (int e = threadIdx.x; e < 256 * kLutCopies; e += NT) {
-      const int b = e / kLutCopies;
-      f32x2 v;
-      v[0] = t[b & 15];
-      v[1] = t[b >> 4];
-      lut2[e] = v;
-    }
-  } else {
-    if (threadIdx.x == 0) {
+    float v = t[threadIdx.x];
+    if (dtype != 0) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) stage[i] = tab.v[i];
+      for (int i = 0; i < 16; ++i) v = (int)threadIdx.x == i ? tab.v[i] : v;
     }
-    __syncthreads();
-    for (int e = threadIdx.x; e < 256 * kLutCopies; e += NT) {
-      const int b = e / kLutCopies;
-      f32x2 v;
-      v[0] = stage[b & 15];
-      v[1] = stage[b >> 4];
-      lut2[e] = v;
-    }
+    stage[threadIdx.x] = v;
+  }
+  __syncthreads();
+  const int b0 = threadIdx.x / kLutCopies;                   // byte of this thread's first entry: < NT / 32
+  const float lo = stage[b0 & 15];
+#pragma unroll
+  for (int k = 0; k < 256 * kLutCopies / NT; ++k) {
+    const int hi_nibble = (NT == 512) ? k : 2 * k + (b0 >> 4);
+    f32x2 v;
+    v[0] = lo;
+    v[1] = stage[hi_nibble];
+    lut2[threadIdx.x + NT * k] = v;
   }
   if (threadIdx.x < 256) unit[threadIdx.x] = e4m3_unit(threadIdx.x);
 }
