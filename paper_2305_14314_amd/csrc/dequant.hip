@@ -27,12 +27,12 @@ __device__ __forceinline__ float s8_to_f32(uint32_t p, int j) { return (float)((
 
 // I8: 8-bit integers, Eq. 2 as printed: w = q * absmax / 127, as bf16(fl32(q * fl32(c2 / 127))).  A lane then reads
 // 8 bytes instead of 4; `packed` and `n_dwords` count in lane-sized units (8 weights) either way.
-template <bool DQ, bool I8>
+template <bool DQ, bool I8, bool GAP>
 __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
     const void* __restrict__ packed_v, const uint8_t* __restrict__ code, const float* __restrict__ c1,
     const float* __restrict__ mean_ptr, uint4* __restrict__ out, int64_t n_dwords, uint32_t rows, uint32_t bpr,
     const int dtype, const Table4 tab, const int64_t row_gap) {
-  // row_gap: 16-byte groups between the end of an output row and the start of the next (0: rows back to back)
+  // GAP: the output rows are row_gap 16-byte groups apart (a wider buffer: several weights side by side); else back to back
   constexpr bool dq = DQ;                                    // Double Quantization, or the fp32 constants as they are
   const uint32_t* __restrict__ packed = (const uint32_t*)packed_v;
   __shared__ float lut[16];
@@ -74,8 +74,8 @@ __global__ __launch_bounds__(kDeqThreads) void dequant_nf4_kernel(
       o.z = pack_bf16x2(__fmul_rn(lut[(p >> 16) & 15u], c2), __fmul_rn(lut[(p >> 20) & 15u], c2));
       o.w = pack_bf16x2(__fmul_rn(lut[(p >> 24) & 15u], c2), __fmul_rn(lut[p >> 28], c2));
     }
-    if (row_gap == 0) out[d] = o;
-    else out[d + (int64_t)(blk / bpr) * row_gap] = o;        // a wider buffer: several weights side by side
+    if constexpr (GAP) out[d + (int64_t)(blk / bpr) * row_gap] = o;
+    else out[d] = o;
   }
 }
 
@@ -201,12 +201,17 @@ hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st, int64_
   const int64_t cap = 256 * 32;
   if (blocks > cap) blocks = cap;
   const bool i8 = w.dtype == kTypeInt8;
-#define QL_DEQ(DQ, I8)                                                                                      \
-  hipLaunchKernelGGL((dequant_nf4_kernel<DQ, I8>), dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,        \
+#define QL_DEQ(DQ, I8, GAP)                                                                                 \
+  hipLaunchKernelGGL((dequant_nf4_kernel<DQ, I8, GAP>), dim3((unsigned)blocks), dim3(kDeqThreads), 0, st,   \
                      (const void*)w.packed, w.code, w.c1, w.mean, (uint4*)out, n_dwords, (uint32_t)w.rows,  \
                      (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype), (ld_out - w.cols) / 8)
-  if (w.dq) { if (i8) QL_DEQ(true, true); else QL_DEQ(true, false); }
-  else      { if (i8) QL_DEQ(false, true); else QL_DEQ(false, false); }
+  if (ld_out != w.cols) {
+    if (w.dq) { if (i8) QL_DEQ(true, true, true); else QL_DEQ(true, false, true); }
+    else      { if (i8) QL_DEQ(false, true, true); else QL_DEQ(false, false, true); }
+  } else {
+    if (w.dq) { if (i8) QL_DEQ(true, true, false); else QL_DEQ(true, false, false); }
+    else      { if (i8) QL_DEQ(false, true, false); else QL_DEQ(false, false, false); }
+  }
 #undef QL_DEQ
   return hipGetLastError();
 }
