@@ -29,7 +29,8 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 PEAK_HBM_GBS = 8000.0
-SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam", "stacked")
+SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam", "stacked",
+            "fused_bwd")
 
 
 def _ensure_built():
@@ -362,6 +363,29 @@ def main():
                                  "stacked_us": round(t_st * 1e3, 1), "stacked_over_separate_with_sums": round(t_st / t_sep, 4)}
             del dYst, dYs, dXs, dXst, ws_sb
         extra["stacked"] = st
+    if want("fused_bwd"):
+        # the input gradient of one layer in its two forms: dequantise into the workspace, then multiply (what the step
+        # runs), against the product that decodes the weight's tiles itself (the bf16 weight is never in HBM)
+        fb = {}
+        for i in (0, 6):                                       # a square layer and the down projection
+            h_, o_ = linears[i]
+            dX_ = torch.empty((M, h_), dtype=torch.bfloat16, device=dev)
+            k = [0]
+
+            def dx_only():
+                blk = pool[k[0] % len(pool)]
+                k[0] += 1
+                ql.qlora_linear_bwd(dY[o_], None, blk[i], L1[i], L2[i], s, dX=dX_, need_dL=False, workspace=ws)
+            t = {}
+            for mode in (0, 1, 0, 1):
+                prev = ql.qlora_bwd_fused_dequant(mode)
+                tm = _time_ms(torch, dx_only, 8)
+                ql.qlora_bwd_fused_dequant(prev)
+                t[mode] = min(t.get(mode, tm), tm)
+            fb[f"{h_}x{o_}"] = {"dequant_then_gemm_us": round(t[0] * 1e3, 1), "fused_us": round(t[1] * 1e3, 1),
+                               "fused_over_two_kernels": round(t[1] / t[0], 4)}
+            del dX_
+        extra["fused_bwd"] = fb
     if want("adam"):
         # optimizer step on the adapters of 8 blocks (80 M parameters in one flat buffer): global-norm pass over the
         # gradient, then Adam with clipping, the bf16 copy and the cleared gradient: 4 + 34 bytes per parameter

@@ -386,6 +386,14 @@ qlora_status qlora_linear_bwd_list(int32_t n, const uint16_t* const* dY, const q
  * QLORA_OK otherwise.  qlora_workspace_init clears it. */
 qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Which of two forms of the large-token backward product runs (arXiv 2305.14314, Eq. 5-6 and the backward through the
+ * dequantised weight): mode 0 dequantises the weight into the workspace and multiplies; mode 1 decodes the weight's
+ * tiles inside the product (codes and block constants go from HBM to the matrix cores' LDS tiles, the bf16 weight is
+ * never in HBM).  The decoded tiles are the same bits either way; the adapter term is added first instead of last in
+ * mode 1, so outputs may differ in the last bf16 bit.  Mode 1 applies to 4-bit types with cols % 64 == 0 and r <= 64
+ * and falls back to mode 0 otherwise.  mode < 0 only queries.  Returns the previous mode.  Process-wide. */
+int32_t qlora_bwd_fused_dequant(int32_t mode);
+
 /* Testing aid: how many times a slab's last contributor polls for the adapter's partial sums before it hands the
  * slab's output stage to the adapter's workgroups (default 64; 0 = never wait, so that hand-over path can be
  * exercised).  Process-wide; affects the few-token list kernels only; results are the same bits either way. */

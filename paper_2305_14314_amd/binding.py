@@ -23,7 +23,7 @@ EXPORTS = [
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
-    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_nf4_quantize_static",
+    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_bwd_fused_dequant", "qlora_nf4_quantize_static",
     "qlora_grad_sqnorm", "qlora_adam_step", "qlora_linear_fwd_stacked_sizes", "qlora_linear_fwd_stacked",
     "qlora_linear_bwd_stacked_sizes", "qlora_linear_bwd_stacked",
     "qlora_kbit_sizes", "qlora_kbit_pack", "qlora_kbit_unpack",
@@ -101,6 +101,7 @@ def lib():
     L.qlora_linear_bwd_list.argtypes = list(L.qlora_linear_fwd_list.argtypes)
     L.qlora_workspace_check.argtypes = [vp, c_size_t, vp]
     L.qlora_fewtok_poll_limit.argtypes = [c_int32]
+    L.qlora_bwd_fused_dequant.argtypes = [c_int32]
     L.qlora_grad_sqnorm.argtypes = [vp, c_int64, vp, vp]
     L.qlora_kbit_sizes.argtypes = [c_int64, c_int64, c_int32, sp]
     L.qlora_kbit_pack.argtypes = [vp, c_int64, c_int64, c_int32, vp, vp]
@@ -464,6 +465,11 @@ def qlora_workspace_check(workspace, stream=None) -> bool:
 
 def qlora_fewtok_poll_limit(polls: int):
     lib().qlora_fewtok_poll_limit(int(polls))
+
+
+def qlora_bwd_fused_dequant(mode: int) -> int:
+    """0: dequantise, then multiply; 1: decode the weight's tiles inside the backward product; < 0: query.  Returns the previous mode."""
+    return int(lib().qlora_bwd_fused_dequant(int(mode)))
 
 
 def qlora_linear_bwd(dY, X, Wq: NF4Weight, L1, L2, s, T_saved=None, dX=None, dL1=None, dL2=None,

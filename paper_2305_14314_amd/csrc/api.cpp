@@ -41,6 +41,26 @@ hipError_t gemm_nt_timed(const uint16_t* A0, const uint16_t* B0, int64_t lda0, i
 
 thread_local int g_last_hip_error = 0;
 
+// Whether the large-token backward decodes the weight inside the product (qlora_bwd_fused_dequant).
+std::atomic<int> g_bwd_fused{0};
+
+// The fused form of gemm_nt_timed's product (weight-side operand of segment 0 as codes + constants), timed alike.
+hipError_t gemm_nt_fused_timed(const uint16_t* A0, const uint8_t* Bq, const float* Bc, const float* tab16, int64_t lda0,
+                               int K0, const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
+                               uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
+  if (!g_prof.enabled)
+    return qlora::launch_gemm_nt_fused(A0, Bq, Bc, tab16, lda0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
+  GemmProfile::Rec r{};
+  if (hipError_t e = hipEventCreateWithFlags(&r.start, hipEventDisableSystemFence)) return e;
+  if (hipError_t e = hipEventCreateWithFlags(&r.stop, hipEventDisableSystemFence)) { (void)hipEventDestroy(r.start); return e; }
+  r.flops = 2.0 * (double)M * (double)N * (double)(K0 + K1);
+  (void)hipEventRecord(r.start, st);
+  const hipError_t e = qlora::launch_gemm_nt_fused(A0, Bq, Bc, tab16, lda0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
+  (void)hipEventRecord(r.stop, st);
+  g_prof.recs.push_back(r);
+  return e;
+}
+
 // Tag of a work-list launch (1 .. 255): arrival words in the counter header carry it, so words left behind by
 // another call are told from this call's own.  Consecutive calls get different tags.
 std::atomic<unsigned> g_nonce{0};
@@ -653,10 +673,21 @@ qlora_status linear_bwd_impl(const uint16_t* dY, const uint16_t* X, const qlora_
   if (!p.few && dX) {
     const uint16_t* B1 = L1;
     if (r > 0 && p.L1p) { QL_TRY(qlora::launch_copy_pad(L1, (int)h, r, p.L1p, p.rp, st)); B1 = p.L1p; }
-    QL_TRY(qlora::launch_dequant(W, p.Wd, st));
-    // dX = dY What^T + Us L1^T
-    QL_TRY(gemm_nt_timed(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, r > 0 ? p.rp : 0, dX, h, (int)M, (int)h,
-                                 st));
+    const int K1 = r > 0 ? p.rp : 0;
+    if (g_bwd_fused.load(std::memory_order_relaxed) && W.dtype != qlora::kTypeInt8 && o % 64 == 0 &&
+        qlora::gemm_nt_fused_fits((int)o, K1, (int)h)) {
+      // dX = Us L1^T + dY What^T with What decoded tile by tile inside the product: the workspace that would hold
+      // What takes the h x o / 64 block constants and the 16 values of the data type instead
+      float* consts = (float*)p.Wd;
+      float* tab16 = consts + ((size_t)h * (o / 64) + 15) / 16 * 16;
+      QL_TRY(qlora::launch_block_consts(W, consts, tab16, st));
+      QL_TRY(gemm_nt_fused_timed(dY, W.packed, W.dq ? consts : W.c1, tab16, o, (int)o, p.Us, B1, p.rp, p.rp, K1, dX, h,
+                                 (int)M, (int)h, st));
+    } else {
+      QL_TRY(qlora::launch_dequant(W, p.Wd, st));
+      // dX = dY What^T + Us L1^T
+      QL_TRY(gemm_nt_timed(dY, p.Wd, o, o, (int)o, p.Us, B1, p.rp, p.rp, K1, dX, h, (int)M, (int)h, st));
+    }
     // LoRA dropout: a dropped input element gets no gradient through the adapter
     if (r > 0 && keep_mask) QL_TRY(qlora::launch_dropout_dx_fix(dX, (int)M, (int)h, keep_mask, p.Us, p.rp, L1, r, st));
   }
@@ -976,6 +1007,11 @@ qlora_status qlora_adam_step(float* param, float* m, float* v, float* grad, uint
   c.grad_scale = cfg->grad_scale; c.max_norm = cfg->max_grad_norm;
   c.sqnorm = cfg->max_grad_norm > 0.0 ? sqnorm : nullptr;
   return hip_status(qlora::launch_adam(param, m, v, grad, param_bf16, n, c, (hipStream_t)hip_stream));
+}
+
+int32_t qlora_bwd_fused_dequant(int32_t mode) {
+  if (mode < 0) return g_bwd_fused.load(std::memory_order_relaxed);
+  return g_bwd_fused.exchange(mode != 0 ? 1 : 0, std::memory_order_relaxed);
 }
 
 void qlora_fewtok_poll_limit(int32_t polls) { g_poll_limit.store(polls < 0 ? 0 : polls, std::memory_order_relaxed); }

@@ -193,6 +193,42 @@ hipError_t launch_dequant_t(const NF4Dev& w, uint16_t* out, int64_t ld_out, hipS
   return hipGetLastError();
 }
 
+// What the fused backward GEMM reads beside the packed codes: the data type's 16 values, and (with Double
+// Quantization) the fp32 constant of every 64-block in flat order, dequant(c1, c2) of Eq. 6 with the two roundings of
+// the kernels above.  0.0625 bytes written per weight.
+__global__ __launch_bounds__(kDeqThreads) void block_consts_kernel(const uint8_t* __restrict__ code,
+                                                                   const float* __restrict__ c1,
+                                                                   const float* __restrict__ mean_ptr,
+                                                                   float* __restrict__ out, int64_t n_blocks,
+                                                                   uint32_t rows, uint32_t bpr, const int dtype,
+                                                                   const Table4 tab, float* __restrict__ tab_out,
+                                                                   const bool dq) {
+  __shared__ float lut[16];
+  __shared__ float unit[256];
+  init_lut16(lut, dtype, tab);
+  unit[threadIdx.x] = e4m3_unit(threadIdx.x);
+  __syncthreads();
+  if (blockIdx.x == 0 && threadIdx.x < 16) tab_out[threadIdx.x] = lut[threadIdx.x];
+  if (!dq) return;
+  const float mean = *mean_ptr;
+  const int64_t stride = (int64_t)gridDim.x * kDeqThreads;
+  for (int64_t b = (int64_t)blockIdx.x * kDeqThreads + threadIdx.x; b < n_blocks; b += stride) {
+    const uint32_t row = (uint32_t)(b / bpr);
+    const uint8_t cd = code[code_pos(rows, (int)bpr, row, (int)(b - (int64_t)row * bpr))];
+    out[b] = __fadd_rn(__fmul_rn(unit[cd], c1[b >> 8]), mean);
+  }
+}
+
+hipError_t launch_block_consts(const NF4Dev& w, float* consts, float* tab16, hipStream_t st) {
+  if (w.dtype == kTypeInt8 || w.cols % 64 != 0) return hipErrorInvalidValue;
+  const int64_t n_blocks = w.rows * (w.cols / 64);
+  int64_t blocks = w.dq ? (n_blocks + kDeqThreads - 1) / kDeqThreads : 1;
+  if (blocks > 256 * 8) blocks = 256 * 8;
+  hipLaunchKernelGGL(block_consts_kernel, dim3((unsigned)blocks), dim3(kDeqThreads), 0, st, w.code, w.c1, w.mean, consts,
+                     n_blocks, (uint32_t)w.rows, (uint32_t)(w.cols / 64), w.dtype, table4_host(w.dtype), tab16, w.dq);
+  return hipGetLastError();
+}
+
 hipError_t launch_dequant(const NF4Dev& w, uint16_t* out, hipStream_t st, int64_t ld_out) {
   if (ld_out == 0) ld_out = w.cols;
   if (ld_out < w.cols || ld_out % 8 != 0) return hipErrorInvalidValue;

@@ -43,6 +43,17 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
                           const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                           uint16_t* C, int64_t ldc, int M, int N, hipStream_t st);
 
+// The same product with the weight-side operand of segment 0 decoded inside the kernel: Bq = N rows of K0 / 2 bytes of
+// 4-bit codes, Bc = N x K0 / 64 fp32 block constants, tab16 = the data type's 16 values (all device memory).  The
+// weight tiles are bit-identical to launch_dequant's; the adapter segment (K1 = 0 or 64) is accumulated first.
+bool gemm_nt_fused_fits(int K0, int K1, int N);
+hipError_t launch_gemm_nt_fused(const uint16_t* A0, const uint8_t* Bq, const float* Bc, const float* tab16, int64_t lda0,
+                                int K0, const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
+                                uint16_t* C, int64_t ldc, int M, int N, hipStream_t st);
+// dequant.hip: the block constants (Double Quantization only; else w.c1 holds them already) and the value table the
+// fused product reads.  4-bit types with cols % 64 == 0.
+hipError_t launch_block_consts(const NF4Dev& w, float* consts, float* tab16, hipStream_t st);
+
 // small.hip: skinny GEMMs of the LoRA branch with split-K fp32 partials, and layout helpers.
 //   part[split][I x J] = A(i,k) B(k,j);  ta: A stored [k][i] instead of [i][k];  tb: B stored [k][j] instead of [j][k].
 //   hl = 1 / 2: A / B is a [hi | lo] pair (the lo half hl_off elements behind the hi half) and enters as hi + lo;
