@@ -441,8 +441,10 @@ qlora_status qlora_adam_step(float* param, float* m, float* v, float* grad, uint
  * main MFMA GEMM kernel made by qlora_linear_fwd / qlora_linear_bwd is bracketed by a pair of HIP
  * events recorded on the call's stream.  qlora_profile_gemm_read waits for those events, returns
  * the summed kernel time in milliseconds, the number of launches and the summed algorithmic FLOPs
- * (2*M*N*K per launch, adapter segment included), and clears the record.  Not thread-safe; the
- * events are the only objects the library ever creates. */
+ * (2*M*N*K per launch, adapter segment included), and clears the record.  The event pairs (at most
+ * 4096 between two reads; launches beyond that run unbracketed) are created on first use and kept for
+ * reuse: they are the only objects the library ever creates, and only while this aid is enabled.
+ * Safe to call from several host threads. */
 void qlora_profile_gemm(int enable);
 qlora_status qlora_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops);
 

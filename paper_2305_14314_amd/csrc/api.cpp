@@ -8,7 +8,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cmath>
-#include <vector>
+#include <mutex>
 
 #include "common.hpp"
 #include "launch.hpp"
@@ -16,27 +16,49 @@
 namespace {
 
 // ---- optional event bracket around the main GEMM launches (benchmark aid) ----
+// A fixed pool of event pairs, created on first use while the aid is enabled and reused after every read; a mutex
+// makes enabling, recording and reading safe from several host threads.  Launches beyond the pool's capacity between
+// two reads run unbracketed and are counted as dropped.
 struct GemmProfile {
-  bool enabled = false;
+  static constexpr int kCap = 4096;
   struct Rec { hipEvent_t start, stop; double flops; };
-  std::vector<Rec> recs;
+  std::mutex mu;
+  bool enabled = false;
+  int created = 0, used = 0;
+  int64_t dropped = 0;
+  Rec recs[kCap];
 } g_prof;
+
+template <class Launch>
+hipError_t timed_launch(double flops, hipStream_t st, Launch&& launch) {
+  GemmProfile::Rec* r = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.enabled) {
+      if (g_prof.used == g_prof.created && g_prof.created < GemmProfile::kCap) {
+        GemmProfile::Rec n{};
+        // timing-only events: no system-scope fence (and the cache write-back it implies) when they complete
+        if (hipError_t e = hipEventCreateWithFlags(&n.start, hipEventDisableSystemFence)) return e;
+        if (hipError_t e = hipEventCreateWithFlags(&n.stop, hipEventDisableSystemFence)) { (void)hipEventDestroy(n.start); return e; }
+        g_prof.recs[g_prof.created++] = n;
+      }
+      if (g_prof.used < g_prof.created) { r = &g_prof.recs[g_prof.used++]; r->flops = flops; }
+      else ++g_prof.dropped;
+    }
+  }
+  if (!r) return launch();
+  (void)hipEventRecord(r->start, st);
+  const hipError_t e = launch();
+  (void)hipEventRecord(r->stop, st);
+  return e;
+}
 
 hipError_t gemm_nt_timed(const uint16_t* A0, const uint16_t* B0, int64_t lda0, int64_t ldb0, int K0,
                          const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                          uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
-  if (!g_prof.enabled)
+  return timed_launch(2.0 * (double)M * (double)N * (double)(K0 + K1), st, [&] {
     return qlora::launch_gemm_nt(A0, B0, lda0, ldb0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
-  GemmProfile::Rec r{};
-  // timing-only events: no system-scope fence (and the cache write-back it implies) when they complete
-  if (hipError_t e = hipEventCreateWithFlags(&r.start, hipEventDisableSystemFence)) return e;
-  if (hipError_t e = hipEventCreateWithFlags(&r.stop, hipEventDisableSystemFence)) { (void)hipEventDestroy(r.start); return e; }
-  r.flops = 2.0 * (double)M * (double)N * (double)(K0 + K1);
-  (void)hipEventRecord(r.start, st);
-  const hipError_t e = qlora::launch_gemm_nt(A0, B0, lda0, ldb0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
-  (void)hipEventRecord(r.stop, st);
-  g_prof.recs.push_back(r);
-  return e;
+  });
 }
 
 thread_local int g_last_hip_error = 0;
@@ -48,17 +70,9 @@ std::atomic<int> g_bwd_fused{0};
 hipError_t gemm_nt_fused_timed(const uint16_t* A0, const uint8_t* Bq, const float* Bc, const float* tab16, int64_t lda0,
                                int K0, const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                                uint16_t* C, int64_t ldc, int M, int N, hipStream_t st) {
-  if (!g_prof.enabled)
+  return timed_launch(2.0 * (double)M * (double)N * (double)(K0 + K1), st, [&] {
     return qlora::launch_gemm_nt_fused(A0, Bq, Bc, tab16, lda0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
-  GemmProfile::Rec r{};
-  if (hipError_t e = hipEventCreateWithFlags(&r.start, hipEventDisableSystemFence)) return e;
-  if (hipError_t e = hipEventCreateWithFlags(&r.stop, hipEventDisableSystemFence)) { (void)hipEventDestroy(r.start); return e; }
-  r.flops = 2.0 * (double)M * (double)N * (double)(K0 + K1);
-  (void)hipEventRecord(r.start, st);
-  const hipError_t e = qlora::launch_gemm_nt_fused(A0, Bq, Bc, tab16, lda0, K0, A1, B1, lda1, ldb1, K1, C, ldc, M, N, st);
-  (void)hipEventRecord(r.stop, st);
-  g_prof.recs.push_back(r);
-  return e;
+  });
 }
 
 // Tag of a work-list launch (1 .. 255): arrival words in the counter header carry it, so words left behind by
@@ -294,23 +308,27 @@ const char* qlora_status_string(qlora_status st) {
 
 int qlora_last_hip_error(void) { return g_last_hip_error; }
 
-void qlora_profile_gemm(int enable) { g_prof.enabled = enable != 0; }
+void qlora_profile_gemm(int enable) {
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  g_prof.enabled = enable != 0;
+}
 
 qlora_status qlora_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops) {
   if (!total_ms || !launches || !total_flops) return QLORA_ERR_NULL;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   double ms = 0.0, fl = 0.0;
   hipError_t bad = hipSuccess;
-  for (auto& r : g_prof.recs) {
+  for (int i = 0; i < g_prof.used; ++i) {
+    GemmProfile::Rec& r = g_prof.recs[i];
     float t = 0.0f;
     hipError_t e = hipEventSynchronize(r.stop);
     if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
     if (e != hipSuccess) bad = e;
     ms += t; fl += r.flops;
-    (void)hipEventDestroy(r.start);
-    (void)hipEventDestroy(r.stop);
   }
-  *total_ms = ms; *launches = (int64_t)g_prof.recs.size(); *total_flops = fl;
-  g_prof.recs.clear();
+  *total_ms = ms; *launches = (int64_t)g_prof.used; *total_flops = fl;
+  g_prof.used = 0;                                           // the events stay for the next measurement
+  g_prof.dropped = 0;
   return hip_status(bad);
 }
 
