@@ -248,17 +248,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs p) {
   float tabv = 0.0f;
   uint32_t wbase[3] = {0u, 0u, 0u};
   if constexpr (FUSED) {
-    const int rc = (n0 + tid < p.N) ? n0 + tid : p.N - 1;
+    const int rc = fused_row(n0, tid, p.N);
     q_rsrc = raw_rsrc(p.Bq, (uint32_t)p.N * (uint32_t)p.KT0 * 32u);
     c_rsrc = raw_rsrc(p.Bc, (uint32_t)p.N * (uint32_t)p.KT0 * 4u);
-    q_voff = rc * p.KT0 * 32;
-    c_voff = rc * p.KT0 * 4;
+    q_voff = (int)fused_code_offset(rc, 0, p.KT0);           // a step adds 32 (codes) / 4 (constant) bytes: the scalar offset
+    c_voff = (int)fused_const_offset(rc, 0, p.KT0);
     tabv = p.tab[lane & 15];
 #pragma unroll
     for (int w = 0; w < 3; ++w) wbase[w] = lds0 + w * 65536 + tid * 128 + ((tid >> 1) & 7) * 16;
   }
   // step of segment 0 behind tile t of the fused order (t >= KT1), clamped to the last
-  auto seg0_step = [&](int t) { return (t < KT ? t : KT - 1) - p.KT1; };
+  auto seg0_step = [&](int t) { return fused_seg0_step(t, KT, p.KT1); };
   uint32_t baseA[2][3], baseB[2][3];
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk)

@@ -47,6 +47,15 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
 // 4-bit codes, Bc = N x K0 / 64 fp32 block constants, tab16 = the data type's 16 values (all device memory).  The
 // weight tiles are bit-identical to launch_dequant's; the adapter segment (K1 = 0 or 64) is accumulated first.
 bool gemm_nt_fused_fits(int K0, int K1, int N);
+// Index arithmetic of the fused kernel's row loads, shared with the host-side check.  Tiles are numbered in the order
+// the kernel consumes them: KT1 adapter tiles (0 or 1) first, then the KT0 steps of segment 0; KT = KT0 + KT1.
+//   step of segment 0 behind tile t (t >= KT1); tiles past the end repeat the last step (their rows are never used)
+__host__ __device__ inline int fused_seg0_step(int t, int KT, int KT1) { return (t < KT ? t : KT - 1) - KT1; }
+//   weight row that thread `tid` (0 .. 255) of the workgroup at output column n0 decodes, clamped to the matrix
+__host__ __device__ inline int fused_row(int n0, int tid, int N) { return n0 + tid < N ? n0 + tid : N - 1; }
+//   byte offsets of that row's 32 bytes of codes and of its fp32 constant for one step (K0 = 64 KT0)
+__host__ __device__ inline int64_t fused_code_offset(int row, int step, int KT0) { return ((int64_t)row * KT0 + step) * 32; }
+__host__ __device__ inline int64_t fused_const_offset(int row, int step, int KT0) { return ((int64_t)row * KT0 + step) * 4; }
 hipError_t launch_gemm_nt_fused(const uint16_t* A0, const uint8_t* Bq, const float* Bc, const float* tab16, int64_t lda0,
                                 int K0, const uint16_t* A1, const uint16_t* B1, int64_t lda1, int64_t ldb1, int K1,
                                 uint16_t* C, int64_t ldc, int M, int N, hipStream_t st);

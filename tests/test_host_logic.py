@@ -40,3 +40,22 @@ def test_list_partition_tiles_the_work(tmp_path):
     out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout
     assert out.startswith("OK "), out
     assert int(out.split()[1]) > 2000
+
+
+def test_fused_gemm_row_loads_stay_inside_the_weight(tmp_path):
+    """The fused backward GEMM loads a weight row's codes and block constant per K-step: every load its schedule asks
+    for lies inside the buffers, for ragged N, K shorter and longer than the prefetch ring, with and without an adapter."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    from paper_2305_14314_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(verbose=False)
+    exe = str(tmp_path / "fused_gemm_index_check")
+    src = os.path.join(ROOT, "tests", "host_checks", "fused_gemm_index_check.cpp")
+    pkg = os.path.dirname(binding.LIB_PATH)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-x", "hip", "-I", CSRC, src, "-o", exe,
+                    "-L", pkg, "-lqlora_hip", "-Wl,-rpath," + pkg], check=True, capture_output=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout
+    assert out.startswith("OK "), out
+    assert int(out.split()[1]) > 500
