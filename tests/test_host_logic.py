@@ -59,3 +59,29 @@ def test_fused_gemm_row_loads_stay_inside_the_weight(tmp_path):
     out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=300).stdout
     assert out.startswith("OK "), out
     assert int(out.split()[1]) > 500
+
+
+def test_fused_gemm_reads_no_register_in_flight(tmp_path):
+    """The fused GEMM kernel's hand-placed asynchronous loads and lookups: in the compiled kernel no instruction touches
+    a register between its asynchronous write and the wait that covers it (the compiler is free to schedule or copy
+    such registers early: this checks what it actually did).  With the main loop's vmcnt waits deleted from the same
+    text the check must fail, which shows that it sees the loads."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("async_register_check",
+                                                  os.path.join(ROOT, "tests", "host_checks", "async_register_check.py"))
+    chk = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(chk)
+    from paper_2305_14314_amd import build
+    asm = str(tmp_path / "gemm.s")
+    subprocess.run([hipcc, *build.FLAGS, "-x", "hip", "--cuda-device-only",
+                    "-S", os.path.join(CSRC, "gemm.hip"), "-o", asm], check=True, capture_output=True)
+    text = open(asm).read()
+    bad, seen = chk.check(text)
+    assert seen >= 5 and not bad, (seen, bad[:5])
+    broken = text.replace("s_waitcnt vmcnt(8)", "s_nop 0")
+    assert broken != text
+    bad, _ = chk.check(broken)
+    assert bad
