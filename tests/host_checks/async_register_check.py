@@ -21,8 +21,8 @@ def regs(tok):
     return {int(m.group(1))} if m else set()
 
 
-def check(text):
-    start = [m.start() for m in re.finditer(r"^_ZN\S*" + KERNEL + r"\S*:", text, re.M)]
+def check(text, kernel=KERNEL):
+    start = [m.start() for m in re.finditer(r"^_ZN\S*" + kernel + r"\S*:", text, re.M)]
     if not start:
         return ["kernel not found"], 0
     body = text[start[0]:text.index("s_endpgm", start[0])]
@@ -38,8 +38,6 @@ def check(text):
     bad, seen = [], 0
     for name, b in blocks:
         if not any(x.startswith("v_mfma") for x in b):
-            continue
-        if not any(x.startswith("buffer_load_dwordx2") or x.startswith("ds_bpermute") for x in b):
             continue
         seen += 1
         # the hardware's two counters, as queues of the destination registers of the operations in flight: memory

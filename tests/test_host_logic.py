@@ -81,6 +81,9 @@ def test_fused_gemm_reads_no_register_in_flight(tmp_path):
     text = open(asm).read()
     bad, seen = chk.check(text)
     assert seen >= 5 and not bad, (seen, bad[:5])
+    for plain in ("gemm_nt_kernelILi256ELi4ELb0EE", "gemm_nt_kernelILi128ELi4ELb0EE"):   # their fragment reads alike
+        bad, seen = chk.check(text, plain)
+        assert seen >= 5 and not bad, (plain, seen, bad[:5])
     broken = text.replace("s_waitcnt vmcnt(8)", "s_nop 0")
     assert broken != text
     bad, _ = chk.check(broken)
