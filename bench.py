@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 PEAK_HBM_GBS = 8000.0
 SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam", "stacked",
-            "fused_bwd")
+            "fused_bwd", "mfma_ceiling")
 
 
 def _ensure_built():
@@ -363,6 +363,24 @@ def main():
                                  "stacked_us": round(t_st * 1e3, 1), "stacked_over_separate_with_sums": round(t_st / t_sep, 4)}
             del dYst, dYs, dXs, dXst, ws_sb
         extra["stacked"] = st
+    if want("mfma_ceiling"):
+        # what the matrix cores sustain on this board under its power limit: a register-only loop of the GEMM's MFMA on
+        # Gaussian operands, one wave per SIMD, without and with the LDS fragment-read traffic of the GEMM's wave tile
+        outp = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+        cz = {}
+        for name, reads in (("registers_only", False), ("with_fragment_reads", True), ("registers_only", False),
+                            ("with_fragment_reads", True)):
+            fl = [0.0]
+
+            def probe():
+                fl[0] = ql.qlora_mfma_probe(reads, 200000, out=outp)   # ~25 ms a call: long enough for the power limit to act
+            t = _time_ms(torch, probe, 3)
+            cz[name + "_TFLOPs"] = max(cz.get(name + "_TFLOPs", 0.0), round(fl[0] / (t * 1e-3) * 1e-12, 1))
+        cz["gemm_over_ceiling_with_reads"] = round(achieved / cz["with_fragment_reads_TFLOPs"], 4)
+        cz["note"] = ("16x16x32 bf16 MFMAs on N(0,1) operands in registers, 256 CUs x 4 waves; the board's power limit sets "
+                      "these rates, and they depend on the operand values")
+        extra["mfma_ceiling"] = cz
+        del outp
     if want("fused_bwd"):
         # the input gradient of one layer in its two forms: dequantise into the workspace, then multiply (what the step
         # runs), against the product that decodes the weight's tiles itself (the bf16 weight is never in HBM)

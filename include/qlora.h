@@ -386,6 +386,14 @@ qlora_status qlora_linear_bwd_list(int32_t n, const uint16_t* const* dY, const q
  * QLORA_OK otherwise.  qlora_workspace_init clears it. */
 qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid for the benchmark (not part of the method): the rate the matrix cores sustain on this board, to
+ * read the main GEMM's rate against.  One wave per SIMD on all 256 CUs runs `iters` x 16 independent 16x16x32 bf16
+ * MFMAs on Gaussian operands held in registers -- no memory traffic (with_lds_reads = 0), or with the LDS
+ * fragment-read traffic of the main kernel's wave tile, one 16-byte read per lane and four MFMAs (with_lds_reads = 1).
+ * Flops of one call: 256 * 4 * iters * 16 * 16384.  out: at least 256 * 256 floats of device memory (written so that
+ * the loop is not optimised away).  iters in 1 .. 2^20. */
+qlora_status qlora_mfma_probe(int32_t with_lds_reads, int32_t iters, float* out, size_t out_bytes, void* hip_stream);
+
 /* Which of two forms of the large-token backward product runs (arXiv 2305.14314, Eq. 5-6 and the backward through the
  * dequantised weight): mode 0 dequantises the weight into the workspace and multiplies; mode 1 decodes the weight's
  * tiles inside the product (codes and block constants go from HBM to the matrix cores' LDS tiles, the bf16 weight is

@@ -23,7 +23,7 @@ EXPORTS = [
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
-    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_bwd_fused_dequant", "qlora_nf4_quantize_static",
+    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_bwd_fused_dequant", "qlora_mfma_probe", "qlora_nf4_quantize_static",
     "qlora_grad_sqnorm", "qlora_adam_step", "qlora_linear_fwd_stacked_sizes", "qlora_linear_fwd_stacked",
     "qlora_linear_bwd_stacked_sizes", "qlora_linear_bwd_stacked",
     "qlora_kbit_sizes", "qlora_kbit_pack", "qlora_kbit_unpack",
@@ -102,6 +102,7 @@ def lib():
     L.qlora_workspace_check.argtypes = [vp, c_size_t, vp]
     L.qlora_fewtok_poll_limit.argtypes = [c_int32]
     L.qlora_bwd_fused_dequant.argtypes = [c_int32]
+    L.qlora_mfma_probe.argtypes = [c_int32, c_int32, vp, c_size_t, vp]
     L.qlora_grad_sqnorm.argtypes = [vp, c_int64, vp, vp]
     L.qlora_kbit_sizes.argtypes = [c_int64, c_int64, c_int32, sp]
     L.qlora_kbit_pack.argtypes = [vp, c_int64, c_int64, c_int32, vp, vp]
@@ -465,6 +466,14 @@ def qlora_workspace_check(workspace, stream=None) -> bool:
 
 def qlora_fewtok_poll_limit(polls: int):
     lib().qlora_fewtok_poll_limit(int(polls))
+
+
+def qlora_mfma_probe(with_lds_reads: bool, iters: int, out=None, stream=None) -> float:
+    """Enqueues the register-only MFMA loop; returns the flops of the call (time it with events around the call)."""
+    if out is None:
+        out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    _check(lib().qlora_mfma_probe(1 if with_lds_reads else 0, int(iters), _ptr(out), out.numel() * 4, _stream(stream)))
+    return 256.0 * 4 * int(iters) * 16 * 16384
 
 
 def qlora_bwd_fused_dequant(mode: int) -> int:

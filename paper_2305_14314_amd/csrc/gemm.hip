@@ -559,6 +559,61 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
   return hipGetLastError();
 }
 
+// ---- measurement aid: what the matrix pipes sustain on this board --------------------------------------------------
+// One wave per SIMD on every CU runs independent 16x16x32 bf16 MFMAs on Gaussian operands held in registers, with no
+// memory traffic at all (READS = false) or with the LDS fragment-read traffic of the main kernel's 128 x 128 wave tile
+// (one ds_read_b128 per four MFMAs).  The board's power limit, not the issue rate, sets the result, and it depends on
+// the operands' values: this is the ceiling the main GEMM's rate is to be read against.
+namespace {
+__device__ __forceinline__ float probe_gauss(uint32_t s) {
+  auto pcg = [](uint32_t x) { x = x * 747796405u + 2891336453u; uint32_t w = ((x >> ((x >> 28) + 4)) ^ x) * 277803737u; return (w >> 22) ^ w; };
+  const uint32_t a = pcg(s), b = pcg(a);
+  return __builtin_sqrtf(-2.0f * __builtin_logf(((float)a + 1.0f) * 0x1p-32f)) * __builtin_cosf(6.2831853f * ((float)b * 0x1p-32f));
+}
+template <bool READS>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters) {
+  __shared__ float lds[4096];
+  for (int i = threadIdx.x; i < 4096; i += 256) lds[i] = probe_gauss(i * 7u + blockIdx.x);
+  __syncthreads();
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[j][i] = (__bf16)probe_gauss(threadIdx.x * 64u + j * 8u + i);
+      b[j][i] = (__bf16)probe_gauss(threadIdx.x * 64u + j * 8u + i + 99991u);
+    }
+  const uint32_t raddr = (uint32_t)(uintptr_t)lds + (threadIdx.x & 63) * 16u;
+  f32x4 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 16; ++i) asm volatile("s_nop 3" : "+a"(acc[i]));
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      QL_MFMA(acc[i], a[i & 3], b[i >> 2]);
+      if (READS && (i & 3) == 3) QL_LDS_READ(a[(i >> 2) & 3], raddr, 0);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+a"(acc[i]));
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += acc[i][0];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+}  // namespace
+
+// 256 workgroups x 4 waves x iters x 16 MFMAs of 2 * 16 * 16 * 32 flops; `out`: 256 * 256 floats of device memory.
+hipError_t launch_mfma_probe(bool with_reads, int iters, float* out, hipStream_t st) {
+  if (iters <= 0 || iters > (1 << 20) || !out) return hipErrorInvalidValue;
+  if (with_reads) hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3(256), dim3(256), 0, st, out, iters);
+  else hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(256), dim3(256), 0, st, out, iters);
+  return hipGetLastError();
+}
+
 bool gemm_nt_fused_fits(int K0, int K1, int N) {
   return K0 > 0 && K0 % BK == 0 && (K1 == 0 || K1 == BK) && N > 0 && (int64_t)N * (K0 / 2) < (1ll << 31);
 }
