@@ -82,3 +82,30 @@ def test_fused_backward_other_types_and_plain_constants(oracle, synth, fused, dt
         a0 = _dx(ql, 0, dY, X, Wq, None, None, 0.0)
         b0 = _dx(ql, 1, dY, X, Wq, None, None, 0.0)
         assert torch.equal(a0, b0)
+
+
+def test_fused_backward_under_dropout_and_accumulation(synth, fused):
+    """The other callers of the backward product: LoRA dropout (the input-gradient fix-up runs behind either form) and
+    fp32 gradient accumulation; both forms against each other."""
+    ql = fused
+    M, h, o, r = 200, 384, 512, 32
+    L = synth.make_layer(0, 0, M=M, h=h, o=o, r=r)
+    Wq = ql.qlora_nf4_quantize(torch.from_numpy(L["W"]).cuda())
+    X, dY, L1, L2 = dev_bf16(L["X"]), dev_bf16(L["dY"]), dev_bf16(L["L1"]), dev_bf16(L["L2"])
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    mask = ql.pack_keep_mask(torch.rand((M, h), device="cuda", generator=gen) >= 0.1)
+    res = {}
+    for mode in (0, 1):
+        ql.qlora_bwd_fused_dequant(mode)
+        dX, dL1, dL2 = ql.qlora_linear_bwd_dropout(dY, X, Wq, L1, L2, L["s"], mask, 0.1)
+        a1 = torch.zeros((h, r), dtype=torch.float32, device="cuda")
+        a2 = torch.zeros((r, o), dtype=torch.float32, device="cuda")
+        dXa = ql.qlora_linear_bwd_acc(dY, X, Wq, L1, L2, L["s"], dL1_acc=a1, dL2_acc=a2)
+        torch.cuda.synchronize()
+        res[mode] = (dX, dL1, dL2, dXa, a1, a2)
+    for k in (1, 2, 4, 5):                                    # the adapter gradients do not pass through the product
+        assert torch.equal(res[0][k], res[1][k])
+    for k in (0, 3):
+        ga, gb = bits_f64(host_bits(res[0][k])), bits_f64(host_bits(res[1][k]))
+        assert np.all(np.abs(ga - gb) <= 2.0 ** -7 * np.abs(ga) + 1e-4 * np.sqrt((ga ** 2).mean()))
