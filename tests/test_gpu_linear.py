@@ -196,6 +196,20 @@ def test_full_size_sampled(oracle, synth, config, layer):
         r1, r2 = oracle.linear_bwd_dl(hdY, hX, hL1, hL2, s)
         _check(host_bits(dL1), r1, "dL1")
         _check(host_bits(dL2), r2, "dL2")
+    # the same input gradient with the weight decoded inside the product: same oracle rows and columns, and without
+    # the adapter the same bits as the two-kernel form (the decoded tiles are identical)
+    prev = ql.qlora_bwd_fused_dequant(1)
+    try:
+        dXf = ql.qlora_linear_bwd(dY, X, Wq, L1, L2, s, T_saved=T, need_dL=False)[0]
+        dXf0 = ql.qlora_linear_bwd(dY, None, Wq, None, None, 0.0, need_dL=False)[0]
+        ql.qlora_bwd_fused_dequant(0)
+        dX0 = ql.qlora_linear_bwd(dY, None, Wq, None, None, 0.0, need_dL=False)[0]
+        torch.cuda.synchronize()
+    finally:
+        ql.qlora_bwd_fused_dequant(prev)
+    _check(host_bits(dXf)[rows], oracle.linear_bwd_dx(hdY, What, hL1, hL2, s, rows=rows), "dX rows (fused)")
+    _check(host_bits(dXf)[:, xcols], oracle.linear_bwd_dx(hdY, What, hL1, hL2, s, cols=xcols), "dX cols (fused)")
+    assert torch.equal(dXf0, dX0)
 
 
 def _random_shapes(n, seed):
