@@ -114,7 +114,6 @@ struct Codes { uint64_t q[4]; float c; };
                : "=&v"((dst).q[0]), "=&v"((dst).q[1]), "=&v"((dst).q[2]), "=&v"((dst).q[3])                  \
                : "v"(q_voff), "s"(q_rsrc), "s"((kstep) * 32));                                               \
   asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=&v"((dst).c) : "v"(c_voff), "s"(c_rsrc), "s"((kstep) * 4))
-constexpr int kCodeLoads = 5;                                // vector-memory instructions of one QL_LOAD_CODES
 // to = from, for a `from` whose loads an earlier s_waitcnt has covered; `to` is then an ordinary value
 #define QL_TAKE_CODES(to, from)                                                                              \
   asm volatile("v_mov_b64 %0, %5\n\tv_mov_b64 %1, %6\n\tv_mov_b64 %2, %7\n\tv_mov_b64 %3, %8\n\tv_mov_b32 %4, %9" \
