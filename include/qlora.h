@@ -388,11 +388,12 @@ qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes
 
 /* Measurement aid for the benchmark (not part of the method): the rate the matrix cores sustain on this board, to
  * read the main GEMM's rate against.  One wave per SIMD on all 256 CUs runs `iters` x 16 independent 16x16x32 bf16
- * MFMAs on Gaussian operands held in registers -- no memory traffic (with_lds_reads = 0), or with the LDS
- * fragment-read traffic of the main kernel's wave tile, one 16-byte read per lane and four MFMAs (with_lds_reads = 1).
+ * MFMAs on Gaussian operands held in registers -- with no memory traffic (lds_traffic = 0), with the LDS
+ * fragment-read traffic of the main kernel's wave tile, one 16-byte read per lane and four MFMAs (1), or with that and
+ * the LDS writes of the operand tiles that land per K-step, one 16-byte write per lane and eight MFMAs (2).
  * Flops of one call: 256 * 4 * iters * 16 * 16384.  out: at least 256 * 256 floats of device memory (written so that
  * the loop is not optimised away).  iters in 1 .. 2^20. */
-qlora_status qlora_mfma_probe(int32_t with_lds_reads, int32_t iters, float* out, size_t out_bytes, void* hip_stream);
+qlora_status qlora_mfma_probe(int32_t lds_traffic, int32_t iters, float* out, size_t out_bytes, void* hip_stream);
 
 /* Which of two forms of the large-token backward product runs (arXiv 2305.14314, Eq. 5-6 and the backward through the
  * dequantised weight): mode 0 dequantises the weight into the workspace and multiplies; mode 1 decodes the weight's

@@ -468,11 +468,12 @@ def qlora_fewtok_poll_limit(polls: int):
     lib().qlora_fewtok_poll_limit(int(polls))
 
 
-def qlora_mfma_probe(with_lds_reads: bool, iters: int, out=None, stream=None) -> float:
-    """Enqueues the register-only MFMA loop; returns the flops of the call (time it with events around the call)."""
+def qlora_mfma_probe(lds_traffic: int, iters: int, out=None, stream=None) -> float:
+    """Enqueues the register-only MFMA loop (lds_traffic 0: none, 1: fragment reads, 2: and tile writes); returns the
+    flops of the call (time it with events around the call)."""
     if out is None:
         out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
-    _check(lib().qlora_mfma_probe(1 if with_lds_reads else 0, int(iters), _ptr(out), out.numel() * 4, _stream(stream)))
+    _check(lib().qlora_mfma_probe(int(lds_traffic), int(iters), _ptr(out), out.numel() * 4, _stream(stream)))
     return 256.0 * 4 * int(iters) * 16 * 16384
 
 

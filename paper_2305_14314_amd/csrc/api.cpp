@@ -1027,10 +1027,12 @@ qlora_status qlora_adam_step(float* param, float* m, float* v, float* grad, uint
   return hip_status(qlora::launch_adam(param, m, v, grad, param_bf16, n, c, (hipStream_t)hip_stream));
 }
 
-qlora_status qlora_mfma_probe(int32_t with_lds_reads, int32_t iters, float* out, size_t out_bytes, void* hip_stream) {
+qlora_status qlora_mfma_probe(int32_t lds_traffic, int32_t iters, float* out, size_t out_bytes, void* hip_stream) {
   if (!out) return QLORA_ERR_NULL;
-  if (iters <= 0 || iters > (1 << 20) || out_bytes < (size_t)256 * 256 * sizeof(float)) return QLORA_ERR_SHAPE;
-  return hip_status(qlora::launch_mfma_probe(with_lds_reads != 0, iters, out, (hipStream_t)hip_stream));
+  if (lds_traffic < 0 || lds_traffic > 2 || iters <= 0 || iters > (1 << 20) ||
+      out_bytes < (size_t)256 * 256 * sizeof(float))
+    return QLORA_ERR_SHAPE;
+  return hip_status(qlora::launch_mfma_probe(lds_traffic, iters, out, (hipStream_t)hip_stream));
 }
 
 int32_t qlora_bwd_fused_dequant(int32_t mode) {

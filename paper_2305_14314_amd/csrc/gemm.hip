@@ -560,18 +560,21 @@ hipError_t launch_gemm_nt(const uint16_t* A0, const uint16_t* B0, int64_t lda0, 
 
 // ---- measurement aid: what the matrix pipes sustain on this board --------------------------------------------------
 // One wave per SIMD on every CU runs independent 16x16x32 bf16 MFMAs on Gaussian operands held in registers, with no
-// memory traffic at all (READS = false) or with the LDS fragment-read traffic of the main kernel's 128 x 128 wave tile
-// (one ds_read_b128 per four MFMAs).  The board's power limit, not the issue rate, sets the result, and it depends on
-// the operands' values: this is the ceiling the main GEMM's rate is to be read against.
+// memory traffic at all (MODE 0), with the LDS fragment-read traffic of the main kernel's 128 x 128 wave tile (MODE 1:
+// one ds_read_b128 per four MFMAs), or with that and the LDS write traffic of the operand tiles landing (MODE 2: one
+// 16-byte write per lane and eight MFMAs, what the DMA of a 256 x 256 x 64 step puts into LDS per wave).  The board's
+// power limit, not the issue rate, sets the result, and it depends on the operands' values: this is the ceiling the
+// main GEMM's rate is to be read against.
 namespace {
 __device__ __forceinline__ float probe_gauss(uint32_t s) {
   auto pcg = [](uint32_t x) { x = x * 747796405u + 2891336453u; uint32_t w = ((x >> ((x >> 28) + 4)) ^ x) * 277803737u; return (w >> 22) ^ w; };
   const uint32_t a = pcg(s), b = pcg(a);
   return __builtin_sqrtf(-2.0f * __builtin_logf(((float)a + 1.0f) * 0x1p-32f)) * __builtin_cosf(6.2831853f * ((float)b * 0x1p-32f));
 }
-template <bool READS>
+template <int MODE>
 __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters) {
-  __shared__ float lds[4096];
+  constexpr bool READS = MODE >= 1, WRITES = MODE >= 2;
+  __shared__ float lds[8192];
   for (int i = threadIdx.x; i < 4096; i += 256) lds[i] = probe_gauss(i * 7u + blockIdx.x);
   __syncthreads();
   bf16x8 a[4], b[4];
@@ -593,6 +596,7 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters) 
     for (int i = 0; i < 16; ++i) {
       QL_MFMA(acc[i], a[i & 3], b[i >> 2]);
       if (READS && (i & 3) == 3) QL_LDS_READ(a[(i >> 2) & 3], raddr, 0);
+      if (WRITES && (i & 7) == 5) asm volatile("ds_write_b128 %0, %1 offset:16384" ::"v"(raddr), "v"(b[3]));
     }
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
   }
@@ -606,10 +610,11 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters) 
 }  // namespace
 
 // 256 workgroups x 4 waves x iters x 16 MFMAs of 2 * 16 * 16 * 32 flops; `out`: 256 * 256 floats of device memory.
-hipError_t launch_mfma_probe(bool with_reads, int iters, float* out, hipStream_t st) {
-  if (iters <= 0 || iters > (1 << 20) || !out) return hipErrorInvalidValue;
-  if (with_reads) hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3(256), dim3(256), 0, st, out, iters);
-  else hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(256), dim3(256), 0, st, out, iters);
+hipError_t launch_mfma_probe(int mode, int iters, float* out, hipStream_t st) {
+  if (iters <= 0 || iters > (1 << 20) || !out || mode < 0 || mode > 2) return hipErrorInvalidValue;
+  if (mode == 2) hipLaunchKernelGGL(mfma_probe_kernel<2>, dim3(256), dim3(256), 0, st, out, iters);
+  else if (mode == 1) hipLaunchKernelGGL(mfma_probe_kernel<1>, dim3(256), dim3(256), 0, st, out, iters);
+  else hipLaunchKernelGGL(mfma_probe_kernel<0>, dim3(256), dim3(256), 0, st, out, iters);
   return hipGetLastError();
 }
 

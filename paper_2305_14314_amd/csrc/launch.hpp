@@ -63,9 +63,9 @@ hipError_t launch_gemm_nt_fused(const uint16_t* A0, const uint8_t* Bq, const flo
 // fused product reads.  4-bit types with cols % 64 == 0.
 hipError_t launch_block_consts(const NF4Dev& w, float* consts, float* tab16, hipStream_t st);
 
-// Measurement aid: register-only MFMA loop on Gaussian operands, optionally with the main kernel's LDS fragment-read
-// traffic; 256 * 4 * iters * 16 MFMAs of 16384 flops.  out: 256 * 256 floats.
-hipError_t launch_mfma_probe(bool with_reads, int iters, float* out, hipStream_t st);
+// Measurement aid: register-only MFMA loop on Gaussian operands; mode 1 adds the main kernel's LDS fragment-read
+// traffic, mode 2 also the LDS writes of its operand tiles; 256 * 4 * iters * 16 MFMAs of 16384 flops.  out: 256 * 256 floats.
+hipError_t launch_mfma_probe(int mode, int iters, float* out, hipStream_t st);
 
 // small.hip: skinny GEMMs of the LoRA branch with split-K fp32 partials, and layout helpers.
 //   part[split][I x J] = A(i,k) B(k,j);  ta: A stored [k][i] instead of [i][k];  tb: B stored [k][j] instead of [j][k].
