@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 PEAK_HBM_GBS = 8000.0
 SECTIONS = ("plain", "quantize", "dequant", "types", "dropout", "configs", "gemv", "gemm_shapes", "adam", "stacked",
-            "fused_bwd", "mfma_ceiling")
+            "fused_bwd", "mfma_ceiling", "hbm_ceiling")
 
 
 def _ensure_built():
@@ -382,6 +382,23 @@ def main():
                       "these rates, and they depend on the operand values")
         extra["mfma_ceiling"] = cz
         del outp
+    if want("hbm_ceiling"):
+        # what plain streams reach on this board: 1 GiB read, written, and copied, by the library's probe kernel
+        a_ = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        b_ = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        hz = {}
+        for name, mode, nbuf in (("read", 0, 1), ("write", 1, 1), ("copy_read_plus_write", 2, 2)):
+            best = 0.0
+            for wgs in (4, 8, 16):
+                t = _time_ms(torch, lambda: ql.qlora_hbm_probe(mode, a_ if mode != 1 else None, b_ if mode != 0 else None,
+                                                                 sink, wgs), 6)
+                best = max(best, nbuf * (1 << 30) / (t * 1e-3) * 1e-9)
+            hz[name + "_GBps"] = round(best, 1)
+            hz[name + "_frac_hbm"] = round(best / PEAK_HBM_GBS, 4)
+        hz["note"] = "16-byte accesses, four in flight per lane, 4 / 8 / 16 workgroups of 256 threads per CU (best of the three)"
+        extra["hbm_ceiling"] = hz
+        del a_, b_, sink
     if want("fused_bwd"):
         # the input gradient of one layer in its two forms: dequantise into the workspace, then multiply (what the step
         # runs), against the product that decodes the weight's tiles itself (the bf16 weight is never in HBM)

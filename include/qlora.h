@@ -395,6 +395,14 @@ qlora_status qlora_workspace_check(const void* workspace, size_t workspace_bytes
  * the loop is not optimised away).  iters in 1 .. 2^20. */
 qlora_status qlora_mfma_probe(int32_t lds_traffic, int32_t iters, float* out, size_t out_bytes, void* hip_stream);
 
+/* Measurement aid for the benchmark (not part of the method): what a plain stream reaches on this board, to read the
+ * bandwidth-bound kernels' rates against.  mode 0 reads `bytes` bytes at src (16-byte loads; sink: one device word that
+ * keeps the loads alive and is practically never written), mode 1 writes them at dst, mode 2 copies src to dst.
+ * bytes: a positive multiple of 16; src / dst 16-byte aligned device memory; wgs_per_cu in 1 .. 64 workgroups of 256
+ * threads per compute unit, each lane with four 16-byte accesses in flight. */
+qlora_status qlora_hbm_probe(int32_t mode, const void* src, void* dst, int64_t bytes, uint32_t* sink, int32_t wgs_per_cu,
+                             void* hip_stream);
+
 /* Which of two forms of the large-token backward product runs (arXiv 2305.14314, Eq. 5-6 and the backward through the
  * dequantised weight): mode 0 dequantises the weight into the workspace and multiplies; mode 1 decodes the weight's
  * tiles inside the product (codes and block constants go from HBM to the matrix cores' LDS tiles, the bf16 weight is

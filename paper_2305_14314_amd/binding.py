@@ -23,7 +23,7 @@ EXPORTS = [
     "qlora_linear_dropout_sizes", "qlora_linear_fwd_dropout", "qlora_linear_bwd_dropout",
     "qlora_codebook_4bit", "qlora_quantize_4bit", "qlora_quant_sizes", "qlora_quantize_int8",
     "qlora_linear_fwd_list_sizes", "qlora_linear_bwd_list_sizes", "qlora_linear_fwd_list", "qlora_linear_bwd_list",
-    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_bwd_fused_dequant", "qlora_mfma_probe", "qlora_nf4_quantize_static",
+    "qlora_workspace_check", "qlora_fewtok_poll_limit", "qlora_bwd_fused_dequant", "qlora_mfma_probe", "qlora_hbm_probe", "qlora_nf4_quantize_static",
     "qlora_grad_sqnorm", "qlora_adam_step", "qlora_linear_fwd_stacked_sizes", "qlora_linear_fwd_stacked",
     "qlora_linear_bwd_stacked_sizes", "qlora_linear_bwd_stacked",
     "qlora_kbit_sizes", "qlora_kbit_pack", "qlora_kbit_unpack",
@@ -103,6 +103,7 @@ def lib():
     L.qlora_fewtok_poll_limit.argtypes = [c_int32]
     L.qlora_bwd_fused_dequant.argtypes = [c_int32]
     L.qlora_mfma_probe.argtypes = [c_int32, c_int32, vp, c_size_t, vp]
+    L.qlora_hbm_probe.argtypes = [c_int32, vp, vp, c_int64, vp, c_int32, vp]
     L.qlora_grad_sqnorm.argtypes = [vp, c_int64, vp, vp]
     L.qlora_kbit_sizes.argtypes = [c_int64, c_int64, c_int32, sp]
     L.qlora_kbit_pack.argtypes = [vp, c_int64, c_int64, c_int32, vp, vp]
@@ -466,6 +467,14 @@ def qlora_workspace_check(workspace, stream=None) -> bool:
 
 def qlora_fewtok_poll_limit(polls: int):
     lib().qlora_fewtok_poll_limit(int(polls))
+
+
+def qlora_hbm_probe(mode: int, src, dst, sink, wgs_per_cu: int = 8, stream=None) -> int:
+    """Enqueues a plain stream (0: read src, 1: write dst, 2: copy src to dst); returns the bytes one buffer holds."""
+    buf = src if src is not None else dst
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib().qlora_hbm_probe(int(mode), _ptr(src), _ptr(dst), nbytes, _ptr(sink), int(wgs_per_cu), _stream(stream)))
+    return nbytes
 
 
 def qlora_mfma_probe(lds_traffic: int, iters: int, out=None, stream=None) -> float:

@@ -107,6 +107,44 @@ unsigned stream_grid(int64_t n) {
 
 }  // namespace
 
+// ---- measurement aid: what plain streams reach on this board ------------------------------------------------------
+// mode 0 reads n16 16-byte words (their XOR goes to `sink`, so the loads stay), mode 1 writes them, mode 2 copies
+// src to dst.  256 threads, a grid-stride loop with `unroll` independent 16-byte accesses per lane in flight.
+template <int MODE>
+__global__ __launch_bounds__(256) void hbm_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16,
+                                                        uint32_t* __restrict__ sink) {
+  constexpr int U = 4;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  uint4 x = {0u, 0u, 0u, 0u};
+  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < n16; i0 += U * stride) {
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = i0 + u * stride;
+      if (MODE != 1) v[u] = src[i < n16 ? i : i0];
+      else v[u] = uint4{(uint32_t)i, 1u, 2u, 3u};
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = i0 + u * stride;
+      if (MODE == 0) { x.x ^= v[u].x; x.y ^= v[u].y; x.z ^= v[u].z; x.w ^= v[u].w; }
+      else if (i < n16) dst[i] = v[u];
+    }
+  }
+  if (MODE == 0 && (x.x ^ x.y ^ x.z ^ x.w) == 0x9e3779b9u) *sink = 1u;   // practically never true: keeps the loads alive
+}
+
+hipError_t launch_hbm_probe(int mode, const void* src, void* dst, int64_t bytes, uint32_t* sink, int wgs_per_cu,
+                            hipStream_t st) {
+  if (mode < 0 || mode > 2 || bytes <= 0 || bytes % 16 != 0 || wgs_per_cu < 1 || wgs_per_cu > 64) return hipErrorInvalidValue;
+  const int64_t n16 = bytes / 16;
+  const dim3 grid((unsigned)(256 * wgs_per_cu));
+  if (mode == 0) hipLaunchKernelGGL(hbm_probe_kernel<0>, grid, dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n16, sink);
+  else if (mode == 1) hipLaunchKernelGGL(hbm_probe_kernel<1>, grid, dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n16, sink);
+  else hipLaunchKernelGGL(hbm_probe_kernel<2>, grid, dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n16, sink);
+  return hipGetLastError();
+}
+
 hipError_t launch_grad_sqnorm(const float* g, int64_t n, double* accum, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(sqnorm_kernel, dim3(stream_grid(n)), dim3(kAdamThreads), 0, st, g, n, accum);

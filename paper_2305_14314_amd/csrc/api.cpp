@@ -1027,6 +1027,14 @@ qlora_status qlora_adam_step(float* param, float* m, float* v, float* grad, uint
   return hip_status(qlora::launch_adam(param, m, v, grad, param_bf16, n, c, (hipStream_t)hip_stream));
 }
 
+qlora_status qlora_hbm_probe(int32_t mode, const void* src, void* dst, int64_t bytes, uint32_t* sink, int32_t wgs_per_cu,
+                             void* hip_stream) {
+  if (mode < 0 || mode > 2 || bytes <= 0 || bytes % 16 != 0 || wgs_per_cu < 1 || wgs_per_cu > 64) return QLORA_ERR_SHAPE;
+  if ((mode != 1 && !src) || (mode != 0 && !dst) || (mode == 0 && !sink)) return QLORA_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst)) return QLORA_ERR_ALIGN;
+  return hip_status(qlora::launch_hbm_probe(mode, src, dst, bytes, sink, wgs_per_cu, (hipStream_t)hip_stream));
+}
+
 qlora_status qlora_mfma_probe(int32_t lds_traffic, int32_t iters, float* out, size_t out_bytes, void* hip_stream) {
   if (!out) return QLORA_ERR_NULL;
   if (lds_traffic < 0 || lds_traffic > 2 || iters <= 0 || iters > (1 << 20) ||

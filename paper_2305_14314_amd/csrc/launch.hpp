@@ -67,6 +67,12 @@ hipError_t launch_block_consts(const NF4Dev& w, float* consts, float* tab16, hip
 // traffic, mode 2 also the LDS writes of its operand tiles; 256 * 4 * iters * 16 MFMAs of 16384 flops.  out: 256 * 256 floats.
 hipError_t launch_mfma_probe(int mode, int iters, float* out, hipStream_t st);
 
+// Measurement aid (adam.hip): a plain stream over `bytes` bytes (a multiple of 16): mode 0 reads src, 1 writes dst, 2 copies
+// src to dst; sink: one device word (written only in the practically impossible case that the XOR of the data equals a
+// constant, which keeps the loads alive).
+hipError_t launch_hbm_probe(int mode, const void* src, void* dst, int64_t bytes, uint32_t* sink, int wgs_per_cu,
+                            hipStream_t st);
+
 // small.hip: skinny GEMMs of the LoRA branch with split-K fp32 partials, and layout helpers.
 //   part[split][I x J] = A(i,k) B(k,j);  ta: A stored [k][i] instead of [i][k];  tb: B stored [k][j] instead of [j][k].
 //   hl = 1 / 2: A / B is a [hi | lo] pair (the lo half hl_off elements behind the hi half) and enters as hi + lo;
